@@ -1,0 +1,154 @@
+/*
+ * a2sf.h - C ABI of the MI355X (gfx950) A2SF hot path.
+ *
+ * A2SF = Accumulative Attention Score with Forgetting Factor (arxiv 2407.20485).
+ * The library computes, for G independent heads (one head = one (layer, batch, head)
+ * triple; the paper keeps a separate score per layer and per head, Section 2.2 and
+ * Section 3.1 Eq.2):
+ *
+ *   prompt phase      masked self-attention (Section 1, Section 3.1 Eq.3), the forgotten
+ *                     accumulated score of every prompt token (Section 3.3 Eq.5/Eq.6)
+ *                     S_j = sum_{i>=j} alpha^(n-1-i) * softmax(Q K^T / sqrt(d))[i, j],
+ *                     and one selection of the budgeted token set into a KV cache;
+ *   generation step   attention of one new query over the retained tokens only
+ *                     (Section 2.2: pruning changes the softmax denominator), the update
+ *                     S <- alpha * S + a_t on every retained token (abstract, Section 3.3),
+ *                     and eviction of the lowest-score tokens so that the budget holds
+ *                     (Section 2.2, Section 3.1 after Eq.2, Section 4.1 for the split of
+ *                     the budget into a score-selected and a most-recent part).
+ *
+ * Conventions shared by every call
+ *  - All data pointers are DEVICE pointers owned by the caller; the library never
+ *    allocates, frees or keeps them.  a2sf_cache itself is a small HOST struct.
+ *  - Every call only enqueues work on `hip_stream` (a hipStream_t passed as void*;
+ *    NULL = the default stream) and never synchronises.  Results are valid once the
+ *    stream reaches the end of the enqueued work.
+ *  - Arguments are validated on the host before anything is launched; an argument
+ *    error returns its status and launches nothing (so it is testable without a GPU).
+ *    A failed launch returns A2SF_EHIP.
+ *  - Row-major everywhere, head dimension d contiguous.  d is 64 or 128.  dtype is
+ *    fp32 or bf16 for Q/K/V/O; scores are always fp32, positions int32.
+ *  - Data pointers must be 16-byte aligned.
+ *  - 0 <= alpha <= 1 and finite.  The paper states 0 < alpha < 1 (Section 3.3) but
+ *    evaluates alpha = 0 (Section 4.4) and alpha = 1 is the plain accumulated score of
+ *    Section 3.1 Eq.4; both ends are accepted, with 0^0 = 1.
+ *  - Budget B = select + recent >= 1.  recent = 0 is the paper's own A2SF setting and
+ *    select = 0 is its local-attention baseline (Section 4.1).
+ *  - "Position" is the 0-based index of a token in the sequence.  Ties between equal
+ *    scores are resolved in favour of the lower position (the higher one is evicted).
+ *  - Original positions stored in a cache must be distinct and >= 0.
+ */
+#ifndef A2SF_H
+#define A2SF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  A2SF_OK = 0,
+  A2SF_EINVAL = 1,     /* null pointer, misaligned pointer, alpha outside [0,1] or not finite,
+                          negative count, unknown mode */
+  A2SF_ESHAPE = 2,     /* d not in {64,128}, n < 1, G < 1, L < 1 ... */
+  A2SF_EDTYPE = 3,     /* dtype not A2SF_F32 / A2SF_BF16 */
+  A2SF_ECAPACITY = 4,  /* cache capacity too small for budget + 1, or above the supported maximum */
+  A2SF_EWORKSPACE = 5, /* workspace missing or smaller than a2sf_workspace_bytes() */
+  A2SF_EHIP = 6        /* the HIP runtime reported an error at launch */
+} a2sf_status;
+
+typedef enum { A2SF_F32 = 0, A2SF_BF16 = 1 } a2sf_dtype;
+
+/* How a generation step makes the cache dense again after an eviction. */
+typedef enum {
+  A2SF_EVICT_FAST = 0,   /* the new token's row is written into the evicted slot: no row
+                            moves; slot order becomes arbitrary, the set of (pos, K, V, S)
+                            tuples is what is defined */
+  A2SF_EVICT_STABLE = 1  /* slots stay in ascending position (select + in-place compaction) */
+} a2sf_evict_mode;
+
+/* Section 4.1: the cache ratio is split into a score-selected and a most-recent part. */
+typedef struct {
+  int32_t select; /* tokens kept for their score, >= 0 */
+  int32_t recent; /* newest tokens always kept, >= 0 */
+} a2sf_budget;
+
+/* The KV cache of G heads plus the A2SF bookkeeping (host struct, device pointers). */
+typedef struct {
+  void* k;        /* [G, capacity, d] dtype */
+  void* v;        /* [G, capacity, d] dtype */
+  float* scores;  /* [G, capacity] accumulated score of each slot */
+  int32_t* pos;   /* [G, capacity] original position of each slot */
+  int32_t* len;   /* [G] number of valid slots of each head */
+  int32_t G;
+  int32_t capacity; /* slots per head; needs >= select + recent + 1; at most A2SF_MAX_CAPACITY */
+  int32_t d;
+  int32_t dtype;  /* a2sf_dtype */
+} a2sf_cache;
+
+#define A2SF_MAX_CAPACITY 12288
+
+/* Bytes of device workspace that any of the calls below may need for these sizes
+ * (n_max = longest prompt, 0 if a2sf_prefill is not used; capacity as in a2sf_cache).
+ * Returns 0 on invalid arguments.  The content of the workspace need not be preserved
+ * between calls; calls that share a workspace must not overlap in time. */
+size_t a2sf_workspace_bytes(int32_t G, int32_t n_max, int32_t capacity, int32_t d,
+                            int32_t dtype, a2sf_budget budget);
+
+/* Prompt phase (Section 3.1 Eq.3, Section 3.3 Eq.5, one selection as in Section 2.2).
+ *   q, k, v      [G, n, d] dtype, read only.
+ *   cache        out: for every head the min(n, B) surviving tokens in ascending
+ *                position: K, V rows, their Eq.5 score, their position; len = min(n, B).
+ *                Survivors: the `recent` last positions, plus of the others the `select`
+ *                with the largest score (tie -> lower position).
+ *   o            out [G, n, d] dtype: attention output rows; may be NULL (then no P*V
+ *                work is done).
+ *   scores_full  out [G, n] fp32: the Eq.5 score of every prompt token; may be NULL.
+ * The n x n probability matrix is never written to memory. */
+a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n, float alpha,
+                         a2sf_budget budget, const a2sf_cache* cache, void* o,
+                         float* scores_full, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/* One generation step (abstract; Section 2.2; Section 3.3).
+ *   q, k_new, v_new  [G, d] dtype: the new token's query, key and value.
+ *   t_pos            original position of the new token (larger than every cached one).
+ *   cache            in/out.  Requires len[g] + 1 <= capacity.  The new token joins with
+ *                    score 0; a = softmax(K_c q / sqrt(d)) over the len+1 cached tokens;
+ *                    o = a^T V_c; every score becomes alpha*S + a; then, if len+1 > B,
+ *                    the len+1-B lowest-score tokens outside the `recent` newest
+ *                    positions are evicted (tie -> the higher position goes) and
+ *                    len = B; else len = len+1.
+ *   mode             a2sf_evict_mode.
+ *   o                out [G, d] dtype. */
+a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                             const a2sf_cache* cache, float alpha, a2sf_budget budget,
+                             int32_t mode, void* o, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+
+/* Selection alone (Section 2.2, Section 4.1): which of the L tokens of each head survive.
+ *   scores    [G, stride] fp32 (no NaN);  pos [G, stride] int32 or NULL (position = slot).
+ *   len       [G] device, valid slots per head (<= L), or NULL: every head has L.
+ *   keep_idx  out [G, B]: surviving slot indices in ascending slot order, first n_keep[g]
+ *             entries valid;  n_keep out [G] = min(len, B).
+ * Survivors: the `recent` largest positions plus the `select` best scores of the rest
+ * (tie -> lower position); everything if len <= B. */
+a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* len, int32_t G,
+                        int32_t L, int32_t stride, a2sf_budget budget, int32_t* keep_idx,
+                        int32_t* n_keep, void* hip_stream);
+
+/* In-place stable compaction of a cache: for every head, row keep_idx[g][r] of K, V,
+ * scores and pos moves to row r for r < n_keep[g], and len[g] = n_keep[g].
+ *   keep_idx  [G, keep_stride] strictly ascending slot indices (as a2sf_select writes).
+ *   n_keep    [G] device. */
+a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32_t keep_stride,
+                         const int32_t* n_keep, void* hip_stream);
+
+const char* a2sf_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2SF_H */

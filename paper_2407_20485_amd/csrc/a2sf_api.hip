@@ -1,0 +1,180 @@
+// C-ABI entry points: argument validation on the host, workspace carving, launches.
+// Nothing here allocates, synchronises or falls back to the CPU.
+#include <math.h>
+#include <stdint.h>
+
+#include "a2sf_internal.h"
+
+using namespace a2sf;
+
+namespace {
+
+inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+struct WsLayout {
+  size_t lse2, s_full, keep_idx, n_keep, split, total;
+};
+
+// One layout serves every call: the regions a call does not use are simply not touched.
+WsLayout ws_layout(int G, int n_max, int capacity, int d, a2sf_budget b) {
+  WsLayout w;
+  size_t off = 0;
+  const size_t Gn = (size_t)G * (size_t)(n_max > 0 ? n_max : 0);
+  w.lse2 = off;     off += align_up(Gn * sizeof(float));
+  w.s_full = off;   off += align_up(Gn * sizeof(float));
+  w.keep_idx = off; off += align_up((size_t)G * (size_t)(b.select + b.recent) * sizeof(int32_t));
+  w.n_keep = off;   off += align_up((size_t)G * sizeof(int32_t));
+  w.split = off;    off += align_up(capacity > 0 ? plan_decode(G, capacity, d).ws_bytes : 0);
+  w.total = off;
+  return w;
+}
+
+a2sf_status check_budget(a2sf_budget b) {
+  if (b.select < 0 || b.recent < 0) return A2SF_EINVAL;
+  if ((long long)b.select + (long long)b.recent < 1) return A2SF_EINVAL;
+  if ((long long)b.select + (long long)b.recent > 0x3FFFFFFF) return A2SF_EINVAL;
+  return A2SF_OK;
+}
+
+a2sf_status check_alpha(float alpha) {
+  if (!(alpha >= 0.0f && alpha <= 1.0f)) return A2SF_EINVAL;  // also rejects NaN
+  return A2SF_OK;
+}
+
+a2sf_status check_cache(const a2sf_cache* c, a2sf_budget b) {
+  if (!c) return A2SF_EINVAL;
+  if (c->dtype != A2SF_F32 && c->dtype != A2SF_BF16) return A2SF_EDTYPE;
+  if (c->d != 64 && c->d != 128) return A2SF_ESHAPE;
+  if (c->G < 1) return A2SF_ESHAPE;
+  if (!c->k || !c->v || !c->scores || !c->pos || !c->len) return A2SF_EINVAL;
+  if (misaligned(c->k) || misaligned(c->v) || misaligned(c->scores) || misaligned(c->pos))
+    return A2SF_EINVAL;
+  if (c->capacity < 1 || c->capacity > A2SF_MAX_CAPACITY) return A2SF_ECAPACITY;
+  if ((long long)c->capacity < (long long)b.select + b.recent + 1) return A2SF_ECAPACITY;
+  return A2SF_OK;
+}
+
+inline a2sf_status launch_status() {
+  return hipGetLastError() == hipSuccess ? A2SF_OK : A2SF_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t a2sf_workspace_bytes(int32_t G, int32_t n_max, int32_t capacity, int32_t d, int32_t dtype,
+                            a2sf_budget budget) {
+  if (G < 1 || n_max < 0 || capacity < 0 || (d != 64 && d != 128)) return 0;
+  if (dtype != A2SF_F32 && dtype != A2SF_BF16) return 0;
+  if (check_budget(budget) != A2SF_OK) return 0;
+  if (capacity > A2SF_MAX_CAPACITY) return 0;
+  return ws_layout(G, n_max, capacity, d, budget).total;
+}
+
+a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n, float alpha,
+                         a2sf_budget budget, const a2sf_cache* cache, void* o,
+                         float* scores_full, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_alpha(alpha)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (!q || !k || !v) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(scores_full))
+    return A2SF_EINVAL;
+  if (n < 1) return A2SF_ESHAPE;
+  if ((long long)cache->G * n > 0x7FFFFFFFLL) return A2SF_ESHAPE;
+  const WsLayout w = ws_layout(cache->G, n, 0, cache->d, budget);
+  if (!workspace || misaligned(workspace) || workspace_bytes < w.total) return A2SF_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  float* lse2 = (float*)(ws + w.lse2);
+  float* s_full = scores_full ? scores_full : (float*)(ws + w.s_full);
+  int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
+  int32_t* n_keep = (int32_t*)(ws + w.n_keep);
+  const int G = cache->G, d = cache->d;
+  const int B = budget.select + budget.recent;
+
+  if (cache->dtype == A2SF_F32) {
+    launch_prefill_f32((const float*)q, (const float*)k, (const float*)v, G, n, d, (float*)o, lse2, st);
+    launch_scores_f32((const float*)q, (const float*)k, lse2, G, n, d, alpha, s_full, st);
+  } else {
+    launch_prefill_bf16(q, k, v, G, n, d, o, lse2, st);
+    launch_scores_bf16(q, k, lse2, G, n, d, alpha, s_full, st);
+  }
+  launch_select(s_full, nullptr, nullptr, G, n, n, budget.select, budget.recent, keep_idx, n_keep, st);
+  launch_gather_prompt(k, v, s_full, n, keep_idx, B, n_keep, *cache, st);
+  return launch_status();
+}
+
+a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                             const a2sf_cache* cache, float alpha, a2sf_budget budget,
+                             int32_t mode, void* o, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_alpha(alpha)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (!q || !k_new || !v_new || !o) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(o)) return A2SF_EINVAL;
+  if (t_pos < 0) return A2SF_EINVAL;
+  if (mode != A2SF_EVICT_FAST && mode != A2SF_EVICT_STABLE) return A2SF_EINVAL;
+  const WsLayout w = ws_layout(cache->G, 0, cache->capacity, cache->d, budget);
+  const DecodePlan plan = plan_decode(cache->G, cache->capacity, cache->d);
+  const bool needs_ws = plan.ws_bytes > 0 || mode == A2SF_EVICT_STABLE;
+  if (needs_ws && (!workspace || misaligned(workspace) || workspace_bytes < w.total))
+    return A2SF_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  launch_decode(q, k_new, v_new, t_pos, *cache, alpha, budget.select, budget.recent,
+                mode == A2SF_EVICT_FAST, o, ws ? ws + w.split : nullptr, plan, st);
+  if (mode == A2SF_EVICT_STABLE) {
+    int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
+    int32_t* n_keep = (int32_t*)(ws + w.n_keep);
+    launch_select(cache->scores, cache->pos, cache->len, cache->G, cache->capacity,
+                  cache->capacity, budget.select, budget.recent, keep_idx, n_keep, st);
+    launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
+  }
+  return launch_status();
+}
+
+a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* len, int32_t G,
+                        int32_t L, int32_t stride, a2sf_budget budget, int32_t* keep_idx,
+                        int32_t* n_keep, void* hip_stream) {
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if (!scores || !keep_idx || !n_keep) return A2SF_EINVAL;
+  if (G < 1 || L < 1 || stride < L) return A2SF_ESHAPE;
+  launch_select(scores, pos, len, G, L, stride, budget.select, budget.recent, keep_idx, n_keep,
+                (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32_t keep_stride,
+                         const int32_t* n_keep, void* hip_stream) {
+  a2sf_budget any = {1, 0};
+  a2sf_status s;
+  if ((s = check_cache(cache, any)) != A2SF_OK) return s;
+  if (!keep_idx || !n_keep) return A2SF_EINVAL;
+  if (keep_stride < 1) return A2SF_ESHAPE;
+  launch_compact(*cache, keep_idx, keep_stride, n_keep, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+const char* a2sf_status_string(int32_t status) {
+  switch (status) {
+    case A2SF_OK: return "ok";
+    case A2SF_EINVAL: return "invalid argument";
+    case A2SF_ESHAPE: return "unsupported shape";
+    case A2SF_EDTYPE: return "unsupported dtype";
+    case A2SF_ECAPACITY: return "cache capacity too small or too large";
+    case A2SF_EWORKSPACE: return "workspace missing or too small";
+    case A2SF_EHIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

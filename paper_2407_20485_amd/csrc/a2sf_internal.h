@@ -1,0 +1,50 @@
+// Host-side launch functions of the kernel files, called by the C-ABI entry points.
+// Every launcher only enqueues on `st`; shapes have been validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/a2sf.h"
+
+namespace a2sf {
+
+// select_compact.hip
+void launch_select(const float* scores, const int32_t* pos, const int32_t* len, int G, int L,
+                   int stride, int select, int recent, int32_t* keep_idx, int32_t* n_keep,
+                   hipStream_t st);
+void launch_compact(const a2sf_cache& c, const int32_t* keep_idx, int keep_stride,
+                    const int32_t* n_keep, hipStream_t st);
+// Out-of-place gather of the prompt's surviving rows into the cache.
+void launch_gather_prompt(const void* k, const void* v, const float* scores_full, int n,
+                          const int32_t* keep_idx, int keep_stride, const int32_t* n_keep,
+                          const a2sf_cache& c, hipStream_t st);
+
+// decode.hip
+struct DecodePlan {
+  int nsplit;          // workgroups per head (1 = single fused kernel)
+  int rows_per_split;  // multiple of 64
+  size_t ws_bytes;     // split-K scratch
+};
+DecodePlan plan_decode(int G, int capacity, int d);
+void launch_decode(const void* q, const void* k_new, const void* v_new, int t_pos,
+                   const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
+                   void* o, void* ws, const DecodePlan& plan, hipStream_t st);
+
+// prefill_f32.hip / prefill_bf16.hip
+// lse2[g][i] = log2(sum_j exp(s_ij)) of the masked row i (s already scaled by 1/sqrt(d)).
+void launch_prefill_f32(const float* q, const float* k, const float* v, int G, int n, int d,
+                        float* o, float* lse2, hipStream_t st);
+void launch_scores_f32(const float* q, const float* k, const float* lse2, int G, int n, int d,
+                       float alpha, float* scores, hipStream_t st);
+void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
+                         void* o, float* lse2, hipStream_t st);
+void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
+                        float alpha, float* scores, hipStream_t st);
+
+// Rows i < first_row contribute exactly 0 to every fp32 score (their weight alpha^(n-1-i)
+// is below the smallest fp32 subnormal while P <= 1), so the score kernels skip them.
+// Also returns log2(alpha) as used in the exponent (0 for alpha == 0, whose only row is n-1).
+int first_contributing_row(int n, float alpha, float* log2_alpha);
+
+}  // namespace a2sf

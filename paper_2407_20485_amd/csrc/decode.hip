@@ -1,0 +1,449 @@
+// Fused generation step: attention of one query over the retained tokens, the forgetting
+// update S <- alpha*S + a (abstract and Section 3.3 of the paper) and eviction of the
+// lowest-score token (Section 2.2, Section 3.1), one head per workgroup.
+//
+// The step is bound by the stream of cached K and V rows (Section 1: loading the KV cache
+// is the memory-bandwidth bottleneck), so there is no matrix-core work here: every lane
+// loads 16 bytes of a row, rows are spread over the lanes of the four waves, the logits
+// and probabilities of the head live in LDS and the softmax maximum / sum go through
+// wavefront shuffles.  Bytes read per head: 2*L*d*e (K and V once) + 8*L (scores).
+//
+// Eviction without row moves: the new token's K/V row is not written at the end of the
+// cache but straight into the slot of the evicted token, so a steady-state step writes two
+// rows per head.  "Recent" is decided by stored position, not by slot order.
+//
+// With few heads (G small) the tokens of a head are split over several workgroups
+// (partial kernel writes logits, per-split max / sum / unnormalised output) and a combine
+// kernel per head finishes the softmax, the score update and the eviction.
+#include <math.h>
+
+#include "a2sf_dev.h"
+#include "a2sf_internal.h"
+
+namespace a2sf {
+namespace {
+
+constexpr int kUnroll = 4;  // 16-byte loads in flight per lane in the K and V sweeps
+
+template <typename T, int D>
+struct RowGeom {
+  static constexpr int EPL = Elem<T>::kPerLane;   // elements per lane
+  static constexpr int LPR = D / EPL;             // lanes per row
+  static constexpr int RPW = kWave / LPR;         // rows per wave-wide load
+  static constexpr int ROWS_PER_ITER = kWaves * RPW * kUnroll;
+};
+
+struct StepSmem {
+  float part[kWaves][128];          // per-wave partial outputs
+  unsigned long long red64[8];
+  float redf[8];
+  int redi[8];
+  int victim;
+};
+
+// logits z[r] (log2 units) of rows [row_begin, row_end) into LDS z[r - z_base].
+template <typename T, int D>
+__device__ __forceinline__ void sweep_k(const T* __restrict__ Kg, const T* __restrict__ knew,
+                                        int n_old, int row_begin, int row_end,
+                                        const float* qv, float* z, int z_base) {
+  using Gm = RowGeom<T, D>;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+  for (int base = row_begin; base < row_end; base += Gm::ROWS_PER_ITER) {
+    uint4 x[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      const T* p = (r == n_old) ? knew : Kg + (size_t)(r < row_end ? r : row_begin) * D;
+      x[u] = load16(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[e], f[e], dot);
+#pragma unroll
+      for (int o = Gm::LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      if (sub == 0 && r < row_end) z[r - z_base] = dot;
+    }
+  }
+}
+
+// acc[e] += sum_r w[r] * V[r][sub*EPL + e] over rows [row_begin, row_end); then reduced over
+// the workgroup into sm.part[0][0..D) (valid after the function returns, for all threads).
+template <typename T, int D>
+__device__ __forceinline__ void sweep_v(const T* __restrict__ Vg, const T* __restrict__ vnew,
+                                        int n_old, int row_begin, int row_end, const float* w,
+                                        int w_base, StepSmem& sm) {
+  using Gm = RowGeom<T, D>;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+  float acc[Gm::EPL];
+#pragma unroll
+  for (int e = 0; e < Gm::EPL; ++e) acc[e] = 0.f;
+  for (int base = row_begin; base < row_end; base += Gm::ROWS_PER_ITER) {
+    uint4 x[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      const T* p = (r == n_old) ? vnew : Vg + (size_t)(r < row_end ? r : row_begin) * D;
+      x[u] = load16(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      const float wr = r < row_end ? w[r - w_base] : 0.f;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int e = 0; e < Gm::EPL; ++e) acc[e] = fmaf(wr, f[e], acc[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < Gm::EPL; ++e) {
+#pragma unroll
+    for (int o = Gm::LPR; o < kWave; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+  }
+  __syncthreads();
+  if (rgrp == 0) {
+#pragma unroll
+    for (int e = 0; e < Gm::EPL; ++e) sm.part[wave][sub * Gm::EPL + e] = acc[e];
+  }
+  __syncthreads();
+  if (threadIdx.x < D) {
+    const int c = threadIdx.x;
+    sm.part[0][c] = (sm.part[0][c] + sm.part[1][c]) + (sm.part[2][c] + sm.part[3][c]);
+  }
+  __syncthreads();
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void copy_row(T* dst, const T* src) {
+  using Gm = RowGeom<T, D>;
+  if (threadIdx.x < Gm::LPR) store16(dst + threadIdx.x * Gm::EPL, load16(src + threadIdx.x * Gm::EPL));
+}
+
+// Score update and eviction of one head.  On entry a[0..L) in LDS holds the probabilities
+// of the L = n_old+1 tokens (slot n_old = the new token, not yet stored in the cache).
+// All 256 threads call this.  a[] is overwritten with the updated scores.
+template <typename T, int D>
+__device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, int32_t* Pg,
+                                 int32_t* len_g, const T* knew, const T* vnew, int t_pos,
+                                 float alpha, int select, int recent, bool evict_here,
+                                 StepSmem& sm) {
+  const int tid = threadIdx.x;
+  const int L = n_old + 1;
+  const int excess = evict_here ? L - (select + recent) : 0;
+
+  // forgetting update into LDS
+  for (int j = tid; j < n_old; j += kThreads) a[j] = fmaf(alpha, Sg[j], a[j]);
+  __syncthreads();
+
+  if (excess <= 0) {  // room left: plain append
+    for (int j = tid; j < L; j += kThreads) Sg[j] = a[j];
+    if (tid == 0) { Pg[n_old] = t_pos; *len_g = L; }
+    copy_row<T, D>(Kg + (size_t)n_old * D, knew);
+    if (tid >= 64) {
+      using Gm = RowGeom<T, D>;
+      const int t = tid - 64;
+      if (t < Gm::LPR) store16(Vg + (size_t)n_old * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
+    }
+    return;
+  }
+
+  // Recent window by position: in a cache that always kept its newest `recent` tokens the
+  // window is exactly pos > t_pos - recent.  Verify by counting; otherwise rank by position.
+  const int thr = t_pos - recent;
+  int cnt = 0;
+  unsigned long long best = ~0ull;
+  for (int j = tid; j < L; j += kThreads) {
+    const int p = j < n_old ? Pg[j] : t_pos;
+    if (p > thr) {
+      ++cnt;
+    } else {
+      const unsigned long long key =
+          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - p);
+      best = key < best ? key : best;
+    }
+  }
+  cnt = block_sum_i(cnt, sm.redi);
+
+  if (excess == 1 && cnt == recent) {
+    // ---- steady state: one eviction, no row moves
+    if (tid == 0) sm.victim = n_old;  // overwritten below by the owner of the minimum
+    const unsigned long long win = block_min_u64(best, sm.red64);
+    for (int j = tid; j < L; j += kThreads) {
+      const int p = j < n_old ? Pg[j] : t_pos;
+      if (p <= thr) {
+        const unsigned long long key =
+            ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - p);
+        if (key == win) sm.victim = j;
+      }
+    }
+    __syncthreads();
+    const int v = sm.victim;
+    for (int j = tid; j < n_old; j += kThreads)
+      if (j != v) Sg[j] = a[j];
+    if (v != n_old) {
+      if (tid == 0) { Sg[v] = a[n_old]; Pg[v] = t_pos; }
+      copy_row<T, D>(Kg + (size_t)v * D, knew);
+      if (tid >= 64) {
+        using Gm = RowGeom<T, D>;
+        const int t = tid - 64;
+        if (t < Gm::LPR) store16(Vg + (size_t)v * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
+      }
+    }
+    if (tid == 0) *len_g = n_old;  // = select + recent
+    return;
+  }
+
+  // ---- general case (several evictions, or a cache whose newest positions have gaps):
+  // make the new token physical, mark the `recent` largest positions, then evict one token
+  // at a time, moving the last live row into the hole.
+  for (int j = tid; j < L; j += kThreads) Sg[j] = a[j];
+  if (tid == 0) Pg[n_old] = t_pos;
+  copy_row<T, D>(Kg + (size_t)n_old * D, knew);
+  if (tid >= 64) {
+    using Gm = RowGeom<T, D>;
+    const int t = tid - 64;
+    if (t < Gm::LPR) store16(Vg + (size_t)n_old * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
+  }
+  __threadfence_block();
+  __syncthreads();
+  // protected tokens get score +inf in LDS (their real score is already in Sg)
+  for (int j = tid; j < L; j += kThreads) {
+    const int pj = Pg[j];
+    int newer = 0;
+    for (int i = 0; i < L; ++i) newer += Pg[i] > pj;
+    if (newer < recent) a[j] = INFINITY;
+  }
+  __syncthreads();
+  int live = L;
+  for (int it = 0; it < excess; ++it) {
+    unsigned long long b = ~0ull;
+    for (int j = tid; j < live; j += kThreads) {
+      const unsigned long long key =
+          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - Pg[j]);
+      b = key < b ? key : b;
+    }
+    if (tid == 0) sm.victim = live - 1;
+    const unsigned long long win = block_min_u64(b, sm.red64);
+    for (int j = tid; j < live; j += kThreads) {
+      const unsigned long long key =
+          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - Pg[j]);
+      if (key == win) sm.victim = j;
+    }
+    __syncthreads();
+    const int v = sm.victim, last = live - 1;
+    if (v != last) {
+      copy_row<T, D>(Kg + (size_t)v * D, Kg + (size_t)last * D);
+      if (tid >= 64) {
+        using Gm = RowGeom<T, D>;
+        const int t = tid - 64;
+        if (t < Gm::LPR)
+          store16(Vg + (size_t)v * D + t * Gm::EPL, load16(Vg + (size_t)last * D + t * Gm::EPL));
+      }
+      if (tid == 0) { Sg[v] = Sg[last]; Pg[v] = Pg[last]; a[v] = a[last]; }
+    }
+    --live;
+    __threadfence_block();
+    __syncthreads();
+  }
+  if (tid == 0) *len_g = live;
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void load_query(const T* qg, float scale_log2e, float* qv) {
+  using Gm = RowGeom<T, D>;
+  const int sub = (threadIdx.x & 63) % Gm::LPR;
+  Elem<T>::unpack(load16(qg + sub * Gm::EPL), qv);
+#pragma unroll
+  for (int e = 0; e < Gm::EPL; ++e) qv[e] *= scale_log2e;
+}
+
+// ---- one workgroup per head ---------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_fused_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int capacity, float alpha, int select,
+    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+  extern __shared__ float a[];  // [capacity]
+  __shared__ StepSmem sm;
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) return;  // precondition len+1 <= capacity violated
+  const int L = n_old + 1;
+  T* Kg = K + (size_t)g * capacity * D;
+  T* Vg = V + (size_t)g * capacity * D;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+
+  float qv[RowGeom<T, D>::EPL];
+  load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
+  sweep_k<T, D>(Kg, knew, n_old, 0, L, qv, a, 0);
+  __syncthreads();
+
+  float mx = -INFINITY;
+  for (int j = tid; j < L; j += kThreads) mx = fmaxf(mx, a[j]);
+  mx = block_max(mx, sm.redf);
+  float sum = 0.f;
+  for (int j = tid; j < L; j += kThreads) {
+    const float p = exp2f(a[j] - mx);
+    a[j] = p;
+    sum += p;
+  }
+  sum = block_sum(sum, sm.redf);
+  const float inv = 1.0f / sum;
+  for (int j = tid; j < L; j += kThreads) a[j] *= inv;
+  __syncthreads();
+
+  sweep_v<T, D>(Vg, vnew, n_old, 0, L, a, 0, sm);
+  if (tid < D) Elem<T>::store(o + (size_t)g * D + tid, sm.part[0][tid]);
+
+  update_and_evict<T, D>(a, n_old, Kg, Vg, S + (size_t)g * capacity, P + (size_t)g * capacity,
+                         len + g, knew, vnew, t_pos, alpha, select, recent, evict_here != 0, sm);
+}
+
+// ---- split over tokens ----------------------------------------------------------------
+// workspace layout (floats): z[G][capacity] | ml[G][nsplit][2] | po[G][nsplit][D]
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_partial_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new,
+    const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ len, int capacity,
+    int nsplit, int rows_per_split, float* __restrict__ zbuf, float* __restrict__ ml,
+    float* __restrict__ po, float scale_log2e) {
+  extern __shared__ float z[];  // [rows_per_split]
+  __shared__ StepSmem sm;
+  const int g = blockIdx.x / nsplit, c = blockIdx.x % nsplit, tid = threadIdx.x;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) return;
+  const int L = n_old + 1;
+  const int r0 = c * rows_per_split;
+  const int r1 = min(L, r0 + rows_per_split);
+  float* mlo = ml + ((size_t)g * nsplit + c) * 2;
+  float* poo = po + ((size_t)g * nsplit + c) * D;
+  if (r0 >= r1) {
+    if (tid == 0) { mlo[0] = -INFINITY; mlo[1] = 0.f; }
+    if (tid < D) poo[tid] = 0.f;
+    return;
+  }
+  const T* Kg = K + (size_t)g * capacity * D;
+  const T* Vg = V + (size_t)g * capacity * D;
+  float qv[RowGeom<T, D>::EPL];
+  load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
+  sweep_k<T, D>(Kg, k_new + (size_t)g * D, n_old, r0, r1, qv, z, r0);
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = r0 + tid; j < r1; j += kThreads) {
+    const float zz = z[j - r0];
+    zbuf[(size_t)g * capacity + j] = zz;
+    mx = fmaxf(mx, zz);
+  }
+  mx = block_max(mx, sm.redf);
+  float sum = 0.f;
+  for (int j = r0 + tid; j < r1; j += kThreads) {
+    const float p = exp2f(z[j - r0] - mx);
+    z[j - r0] = p;
+    sum += p;
+  }
+  sum = block_sum(sum, sm.redf);
+  sweep_v<T, D>(Vg, v_new + (size_t)g * D, n_old, r0, r1, z, r0, sm);
+  if (tid == 0) { mlo[0] = mx; mlo[1] = sum; }
+  if (tid < D) poo[tid] = sm.part[0][tid];
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_combine_kernel(
+    const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos, T* K, T* V, float* S,
+    int32_t* P, int32_t* len, int capacity, int nsplit, const float* __restrict__ zbuf,
+    const float* __restrict__ ml, const float* __restrict__ po, float alpha, int select,
+    int recent, int evict_here, T* __restrict__ o) {
+  extern __shared__ float a[];  // [capacity]
+  __shared__ StepSmem sm;
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) return;
+  const int L = n_old + 1;
+  const float* mlg = ml + (size_t)g * nsplit * 2;
+  float mx = -INFINITY;
+  for (int c = 0; c < nsplit; ++c) mx = fmaxf(mx, mlg[2 * c]);
+  float sum = 0.f;
+  for (int c = 0; c < nsplit; ++c) sum += mlg[2 * c + 1] * exp2f(mlg[2 * c] - mx);
+  const float inv = 1.0f / sum;
+  if (tid < D) {
+    float acc = 0.f;
+    for (int c = 0; c < nsplit; ++c)
+      acc += po[((size_t)g * nsplit + c) * D + tid] * exp2f(mlg[2 * c] - mx);
+    Elem<T>::store(o + (size_t)g * D + tid, acc * inv);
+  }
+  for (int j = tid; j < L; j += kThreads) a[j] = exp2f(zbuf[(size_t)g * capacity + j] - mx) * inv;
+  __syncthreads();
+  update_and_evict<T, D>(a, n_old, K + (size_t)g * capacity * D, V + (size_t)g * capacity * D,
+                         S + (size_t)g * capacity, P + (size_t)g * capacity, len + g,
+                         k_new + (size_t)g * D, v_new + (size_t)g * D, t_pos, alpha, select,
+                         recent, evict_here != 0, sm);
+}
+
+template <typename T, int D>
+void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos,
+                  const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
+                  void* o, void* ws, const DecodePlan& plan, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  if (plan.nsplit <= 1) {
+    hipLaunchKernelGGL((decode_fused_kernel<T, D>), dim3(c.G), dim3(kThreads),
+                       (size_t)c.capacity * sizeof(float), st, (const T*)q, (const T*)k_new,
+                       (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                       c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+    return;
+  }
+  float* zbuf = (float*)ws;
+  float* ml = zbuf + (size_t)c.G * c.capacity;
+  float* po = ml + (size_t)c.G * plan.nsplit * 2;
+  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3((unsigned)c.G * plan.nsplit),
+                     dim3(kThreads), (size_t)plan.rows_per_split * sizeof(float), st,
+                     (const T*)q, (const T*)k_new, (const T*)v_new, (const T*)c.k,
+                     (const T*)c.v, c.len, c.capacity, plan.nsplit, plan.rows_per_split, zbuf, ml,
+                     po, scale_log2e);
+  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(c.G), dim3(kThreads),
+                     (size_t)c.capacity * sizeof(float), st, (const T*)k_new, (const T*)v_new,
+                     t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len, c.capacity, plan.nsplit,
+                     zbuf, ml, po, alpha, select, recent, (int)evict_here, (T*)o);
+}
+
+}  // namespace
+
+DecodePlan plan_decode(int G, int capacity, int d) {
+  DecodePlan p;
+  // Enough workgroups to cover the 256 compute units a few times over; a split never
+  // gets fewer than 64 rows.
+  int want = (1024 + G - 1) / G;
+  int max_split = (capacity + 63) / 64;
+  int ns = want < max_split ? want : max_split;
+  if (ns < 1) ns = 1;
+  if (ns > 64) ns = 64;
+  int rows = (capacity + ns - 1) / ns;
+  rows = (rows + 63) / 64 * 64;
+  ns = (capacity + rows - 1) / rows;
+  p.nsplit = ns;
+  p.rows_per_split = rows;
+  p.ws_bytes = ns <= 1 ? 0
+                       : sizeof(float) * ((size_t)G * capacity + (size_t)G * ns * 2 + (size_t)G * ns * d);
+  return p;
+}
+
+void launch_decode(const void* q, const void* k_new, const void* v_new, int t_pos,
+                   const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
+                   void* o, void* ws, const DecodePlan& plan, hipStream_t st) {
+  if (c.dtype == A2SF_F32) {
+    if (c.d == 64) launch_typed<float, 64>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+    else launch_typed<float, 128>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+  } else {
+    if (c.d == 64) launch_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+    else launch_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+  }
+}
+
+}  // namespace a2sf

@@ -1,0 +1,440 @@
+// bf16 prompt phase on the gfx950 matrix cores.
+//
+//  attn_fwd   masked attention rows (Section 1; Section 3.1 Eq.3 of the paper): for a block
+//             of query rows, K/V tiles of 64 keys stream through LDS, S^T = K Q^T and
+//             O^T = V^T P^T run on v_mfma_f32_32x32x16_bf16 with an online softmax.
+//             Writes O (optional) and the base-2 log-sum-exp of every row.
+//  col_scores forgotten accumulated score of every key (Section 3.3 Eq.5):
+//             S_j = sum_{i>=j} alpha^(n-1-i) * P[i, j].  A block of key columns stays in
+//             registers, Q tiles stream through LDS, the logit tile is recomputed on the
+//             matrix cores, exp2(s - lse_i + (n-1-i) log2 alpha) is formed per element (the
+//             forgetting weight is folded into the exponent) and summed down the tile's
+//             rows.  The n x n probability matrix is never written.
+//
+// Both kernels compute the TRANSPOSED logit tile (keys = M, queries = N).  In the 32x32
+// accumulator layout a lane then owns one query (column l%32) and 16 keys
+// (rows 8*(i/4) + 4*(l/32) + i%4, i = 0..15), so
+//   - row statistics of the softmax are per-lane scalars (one exchange with lane^32),
+//   - P^T is already in the B-operand layout of the second product (no LDS round trip),
+//   - the column sums of col_scores accumulate per lane and are reduced across lanes once.
+#include <math.h>
+
+#include "a2sf_dev.h"
+#include "a2sf_internal.h"
+
+namespace a2sf {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTile = 64;  // keys (attn_fwd) or query rows (col_scores) per LDS tile
+
+__device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, const f32x16& c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- LDS layouts ----------------------------------------------------------------------
+// Row tile [64][D] bf16 in 16-byte chunks, chunk index XOR-swizzled by the row so that the
+// 16 lanes of a quarter-wave reading one chunk column of 16 consecutive rows hit 16
+// different bank groups, and the 16 lanes writing one row do too.
+template <int D>
+__device__ __forceinline__ int row_tile_unit(int row, int chunk) {
+  constexpr int CPR = D / 8;
+  const int swz = (CPR == 16) ? (row & 15) : ((row >> 1) & 7);
+  return row * CPR + (chunk ^ swz);
+}
+// Transposed V tile [D][64 keys] bf16, 128 bytes per d-row = 8 chunks of 8 keys.  Inside
+// each group of 16 keys the keys are stored in the order the matrix-core operand wants:
+// key kappa sits at 8*((kappa>>2)&1) + (kappa&3) + 4*(kappa>>3).
+__device__ __forceinline__ int vt_swizzle(int d) { return ((d >> 1) ^ (d >> 4)) & 7; }
+
+template <int D>
+struct Stage {
+  static constexpr int CPR = D / 8;
+  static constexpr int KU = kTile * CPR / kThreads;        // K units (16 B) per thread
+  static constexpr int VTASKS = 16 * CPR;                  // (key quad, d chunk) tasks
+  uint4 kreg[KU];
+  uint4 vreg[4];
+
+  template <bool WITH_V>
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ Kg, const bf16_t* __restrict__ Vg,
+                                       int row0, int n) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      const int unit = tid + u * kThreads;
+      int r = row0 + unit / CPR;
+      r = r < n ? r : n - 1;
+      kreg[u] = load16(Kg + (size_t)r * D + (unit % CPR) * 8);
+    }
+    if (WITH_V && tid < VTASKS) {
+      const int dc = tid % CPR, kq = tid / CPR;
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        int r = row0 + 4 * kq + rr;
+        r = r < n ? r : n - 1;
+        vreg[rr] = load16(Vg + (size_t)r * D + dc * 8);
+      }
+    }
+  }
+  template <bool WITH_V>
+  __device__ __forceinline__ void store(uint4* ks, char* vt) const {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < KU; ++u) {
+      const int unit = tid + u * kThreads;
+      ks[row_tile_unit<D>(unit / CPR, unit % CPR)] = kreg[u];
+    }
+    if (WITH_V && tid < VTASKS) {
+      const int dc = tid % CPR, kq = tid / CPR;
+      const int chunk = 2 * (kq >> 2) + (kq & 1), half = (kq & 3) >> 1;
+      const uint32_t* x0 = reinterpret_cast<const uint32_t*>(&vreg[0]);
+      const uint32_t* x1 = reinterpret_cast<const uint32_t*>(&vreg[1]);
+      const uint32_t* x2 = reinterpret_cast<const uint32_t*>(&vreg[2]);
+      const uint32_t* x3 = reinterpret_cast<const uint32_t*>(&vreg[3]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int w = i >> 1, d = dc * 8 + i;
+        uint2 out;
+        if (i & 1) {
+          out.x = (x0[w] >> 16) | (x1[w] & 0xFFFF0000u);
+          out.y = (x2[w] >> 16) | (x3[w] & 0xFFFF0000u);
+        } else {
+          out.x = (x0[w] & 0xFFFFu) | (x1[w] << 16);
+          out.y = (x2[w] & 0xFFFFu) | (x3[w] << 16);
+        }
+        *reinterpret_cast<uint2*>(vt + d * 128 + ((chunk ^ vt_swizzle(d)) << 4) + half * 8) = out;
+      }
+    }
+  }
+};
+
+// Workgroup id -> flat work id such that each of the 8 accelerator dies (which receive
+// consecutive workgroup ids round-robin) works on a contiguous range of work ids, i.e. on
+// whole heads whose K/V stay in that die's L2.
+__device__ __forceinline__ long long xcd_contiguous_id(long long total) {
+  const long long per = (total + 7) / 8;
+  return (long long)(blockIdx.x % 8) * per + blockIdx.x / 8;
+}
+
+// ---------------------------------------------------------------------------------------
+template <int D, int NB, bool WITH_O>
+__global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+  constexpr int BM = kWaves * 32 * NB;
+  constexpr int CPR = D / 8;
+  constexpr int KK = D / 16;   // k-steps of the first product
+  constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
+  __shared__ uint4 ks[2][kTile * CPR];
+  __shared__ __attribute__((aligned(16))) char vt[WITH_O ? 2 : 1][WITH_O ? D * 128 : 16];
+
+  const long long total = (long long)G * nqb;
+  const long long vid = xcd_contiguous_id(total);
+  if (vid >= total) return;
+  const int g = (int)(vid / nqb);
+  const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * n * D;
+  const bf16_t* Vg = V + (size_t)g * n * D;
+  const int row0 = qb * BM;
+  const int wrow0 = row0 + wave * 32 * NB;  // first query row of this wave
+
+  // Q fragments (B operand): lane (query l32, half h) holds Q[query][16kk + 8h .. +7]
+  uint4 qf[NB][KK];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int r = wrow0 + nb * 32 + l32;
+    r = r < n ? r : n - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[nb][kk] = load16(Qg + (size_t)r * D + kk * 16 + h * 8);
+  }
+
+  f32x16 oacc[NB][DB];
+  float m[NB], lsum[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    m[nb] = -INFINITY;
+    lsum[nb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[nb][db][i] = 0.f;
+  }
+
+  const int last_row = min(n, row0 + BM) - 1;
+  const int ntiles = last_row / kTile + 1;
+  Stage<D> stg;
+  stg.template load<WITH_O>(Kg, Vg, 0, n);
+  stg.template store<WITH_O>(ks[0], vt[0]);
+  __syncthreads();
+
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < ntiles) stg.template load<WITH_O>(Kg, Vg, (t + 1) * kTile, n);
+    const int key0 = t * kTile;
+    if (key0 <= wrow0 + 32 * NB - 1) {  // some key of the tile is visible to this wave
+      // ---- S^T = K Q^T
+      f32x16 sacc[NB][2];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[nb][kb][i] = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const uint4 a = ks[buf][row_tile_unit<D>(kb * 32 + l32, 2 * kk + h)];
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) sacc[nb][kb] = mfma_bf16(a, qf[nb][kk], sacc[nb][kb]);
+        }
+      const bool diag = key0 + kTile - 1 > wrow0;  // tile reaches past the wave's first row
+      uint4 pf[NB][2][2];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int qrow = wrow0 + nb * 32 + l32;
+        if (diag) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+              if (key > qrow) sacc[nb][kb][i] = -INFINITY;
+            }
+        }
+        float mx = sacc[nb][0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // rows past the end of a ragged block can be fully masked in a tile: keep m finite
+        const float m_new = fmaxf(m[nb], fmaxf(mx * scale_log2e, -1e30f));
+        if (__any(m_new > m[nb])) {
+          const float corr = fast_exp2(m[nb] - m_new);
+          lsum[nb] *= corr;
+          if (WITH_O) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) oacc[nb][db][i] *= corr;
+          }
+          m[nb] = m_new;
+        }
+        float rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            p[i] = fast_exp2(fmaf(sacc[nb][kb][i], scale_log2e, -m[nb]));
+            rs += p[i];
+          }
+          if (WITH_O) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+              uint4 w;
+              w.x = pack_bf16(p[8 * tt + 0], p[8 * tt + 1]);
+              w.y = pack_bf16(p[8 * tt + 2], p[8 * tt + 3]);
+              w.z = pack_bf16(p[8 * tt + 4], p[8 * tt + 5]);
+              w.w = pack_bf16(p[8 * tt + 6], p[8 * tt + 7]);
+              pf[nb][kb][tt] = w;
+            }
+          }
+        }
+        lsum[nb] += rs;
+      }
+      // ---- O^T += V^T P^T
+      if (WITH_O) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const int d = db * 32 + l32;
+          const char* vrow = vt[buf] + d * 128;
+          const int sw = vt_swizzle(d);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+              const uint4 a = *reinterpret_cast<const uint4*>(vrow + (((4 * kb + 2 * tt + h) ^ sw) << 4));
+#pragma unroll
+              for (int nb = 0; nb < NB; ++nb) oacc[nb][db] = mfma_bf16(a, pf[nb][kb][tt], oacc[nb][db]);
+            }
+        }
+      }
+    }
+    if (t + 1 < ntiles) stg.template store<WITH_O>(ks[buf ^ 1], vt[WITH_O ? (buf ^ 1) : 0]);
+    __syncthreads();
+  }
+
+  // ---- epilogue
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int qrow = wrow0 + nb * 32 + l32;
+    const float l = lsum[nb] + __shfl_xor(lsum[nb], 32, 64);
+    if (qrow < n) {
+      if (h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
+      if (WITH_O) {
+        const float inv = 1.0f / l;
+        bf16_t* orow = O + ((size_t)g * n + qrow) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            uint2 w;
+            w.x = pack_bf16(oacc[nb][db][4 * i4 + 0] * inv, oacc[nb][db][4 * i4 + 1] * inv);
+            w.y = pack_bf16(oacc[nb][db][4 * i4 + 2] * inv, oacc[nb][db][4 * i4 + 3] * inv);
+            *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i4 + 4 * h) = w;
+          }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
+    float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
+    float scale_log2e) {
+  constexpr int BC = kWaves * 32;  // key columns per workgroup
+  constexpr int CPR = D / 8;
+  constexpr int KK = D / 16;
+  __shared__ uint4 qs[2][kTile * CPR];
+
+  const long long total = (long long)G * ncb;
+  const long long vid = xcd_contiguous_id(total);
+  if (vid >= total) return;
+  const int g = (int)(vid / ncb);
+  const int cb = (int)(vid % ncb);  // column block 0 has the most rows: first
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * n * D;
+  const float* lse = LSE2 + (size_t)g * n;
+  const int c0 = cb * BC;
+  const int wc0 = c0 + wave * 32;  // first key of this wave
+
+  // K fragments (A operand): lane (key l32, half h) holds K[key][16kk + 8h .. +7]
+  uint4 kf[KK];
+  {
+    int r = wc0 + l32;
+    r = r < n ? r : n - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+  }
+  float acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+
+  const int t_begin = max(c0, first_row) / kTile;
+  const int t_end = (n + kTile - 1) / kTile;
+  Stage<D> stg;
+  stg.template load<false>(Qg, nullptr, t_begin * kTile, n);
+  stg.template store<false>(qs[0], nullptr);
+  __syncthreads();
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int buf = (t - t_begin) & 1;
+    if (t + 1 < t_end) stg.template load<false>(Qg, nullptr, (t + 1) * kTile, n);
+    const int row0 = t * kTile;
+    if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const uint4 b = qs[buf][row_tile_unit<D>(qb * 32 + l32, 2 * kk + h)];
+          sacc = mfma_bf16(kf[kk], b, sacc);
+        }
+        const int r = row0 + qb * 32 + l32;
+        // exponent offset of row r: -lse_r + (n-1-r) log2(alpha); rows past the end, and rows
+        // whose weight is exactly 0 in fp32 (before first_row), add nothing
+        const float bias = (r < n && r >= first_row)
+                               ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+        const bool diag = row0 + qb * 32 < wc0 + 31;  // block reaches above the diagonal
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
+          float p = fast_exp2(fmaf(sacc[i], scale_log2e, -bias));
+          if (diag && key > r) p = 0.f;
+          acc[i] += p;
+        }
+      }
+    }
+    if (t + 1 < t_end) stg.template store<false>(qs[buf ^ 1], nullptr);
+    __syncthreads();
+  }
+  // sum over the 32 queries (lanes with the same half)
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) acc[i] += __shfl_xor(acc[i], o, 64);
+  }
+  if (l32 == 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
+      if (key < n) S[(size_t)g * n + key] = acc[i];
+    }
+  }
+}
+
+template <int D>
+void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
+                hipStream_t st) {
+  constexpr int NB = 1;
+  constexpr int BM = kWaves * 32 * NB;
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  const int nqb = (n + BM - 1) / BM;
+  const long long total = (long long)G * nqb;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+  if (o)
+    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
+                       G, nqb, scale_log2e);
+  else
+    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, false>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
+                       lse2, n, G, nqb, scale_log2e);
+}
+
+template <int D>
+void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, float alpha,
+                 float* scores, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  float l2a;
+  const int first = first_contributing_row(n, alpha, &l2a);
+  const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
+  const long long total = (long long)G * ncb;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+  hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st,
+                     (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
+                     scale_log2e);
+}
+
+}  // namespace
+
+void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
+                         void* o, float* lse2, hipStream_t st) {
+  if (d == 64) launch_fwd<64>(q, k, v, G, n, o, lse2, st);
+  else launch_fwd<128>(q, k, v, G, n, o, lse2, st);
+}
+
+void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
+                        float alpha, float* scores, hipStream_t st) {
+  if (d == 64) launch_cols<64>(q, k, lse2, G, n, alpha, scores, st);
+  else launch_cols<128>(q, k, lse2, G, n, alpha, scores, st);
+}
+
+}  // namespace a2sf

@@ -1,0 +1,110 @@
+"""CPU-only checks of the boundary: the shared library loads, exports every function that
+include/a2sf.h declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2407_20485_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "a2sf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(a2sf_[a-z_]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree():
+    assert declared_functions() == sorted(B.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    for name in declared_functions():
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    assert B.a2sf_status_string(B.A2SF_OK) == "ok"
+    assert "workspace" in B.a2sf_status_string(B.A2SF_EWORKSPACE)
+    assert B.a2sf_status_string(99) == "unknown status"
+
+
+def test_workspace_bytes():
+    w = B.a2sf_workspace_bytes(4, 256, 65, 64, B.A2SF_F32, 32, 32)
+    assert w >= 2 * 4 * 256 * 4 + 4 * 64 * 4
+    assert B.a2sf_workspace_bytes(4, 256, 65, 96, B.A2SF_F32, 32, 32) == 0      # bad d
+    assert B.a2sf_workspace_bytes(4, 256, 65, 64, 7, 32, 32) == 0               # bad dtype
+    assert B.a2sf_workspace_bytes(4, 256, 65, 64, B.A2SF_F32, 0, 0) == 0        # empty budget
+    assert B.a2sf_workspace_bytes(0, 256, 65, 64, B.A2SF_F32, 1, 1) == 0
+
+
+FAKE = 0x10000  # a 16-byte aligned non-null "device pointer"; never dereferenced on these paths
+
+
+def fake_cache(G=2, capacity=9, d=64, dtype=B.A2SF_F32, **over):
+    f = dict(k=FAKE, v=FAKE, scores=FAKE, pos=FAKE, len=FAKE, G=G, capacity=capacity, d=d, dtype=dtype)
+    f.update(over)
+    return B.CacheStruct(**f)
+
+
+def prefill_status(cache, n=16, alpha=0.3, select=4, recent=4, q=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    return B.lib().a2sf_prefill(q, FAKE, FAKE, n, alpha, B.Budget(select, recent), ctypes.byref(cache),
+                                None, None, ws, ws_bytes, None)
+
+
+def decode_status(cache, alpha=0.3, select=4, recent=4, mode=0, t_pos=5, o=FAKE, ws=FAKE, ws_bytes=1 << 30):
+    return B.lib().a2sf_decode_step(FAKE, FAKE, FAKE, t_pos, ctypes.byref(cache), alpha,
+                                    B.Budget(select, recent), mode, o, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("alpha", [-0.1, 1.5, float("nan"), float("inf")])
+def test_alpha_domain(alpha):
+    assert prefill_status(fake_cache(), alpha=alpha) == B.A2SF_EINVAL
+    assert decode_status(fake_cache(), alpha=alpha) == B.A2SF_EINVAL
+
+
+def test_prefill_argument_errors():
+    assert prefill_status(fake_cache(), q=None) == B.A2SF_EINVAL
+    assert prefill_status(fake_cache(), q=FAKE + 4) == B.A2SF_EINVAL            # misaligned
+    assert prefill_status(fake_cache(), n=0) == B.A2SF_ESHAPE
+    assert prefill_status(fake_cache(d=96)) == B.A2SF_ESHAPE
+    assert prefill_status(fake_cache(dtype=5)) == B.A2SF_EDTYPE
+    assert prefill_status(fake_cache(capacity=8)) == B.A2SF_ECAPACITY           # needs B+1 = 9
+    assert prefill_status(fake_cache(capacity=B.A2SF_MAX_CAPACITY + 1)) == B.A2SF_ECAPACITY
+    assert prefill_status(fake_cache(), select=0, recent=0) == B.A2SF_EINVAL
+    assert prefill_status(fake_cache(), select=-1, recent=4) == B.A2SF_EINVAL
+    assert prefill_status(fake_cache(), ws=None) == B.A2SF_EWORKSPACE
+    assert prefill_status(fake_cache(), ws_bytes=16) == B.A2SF_EWORKSPACE
+    assert prefill_status(fake_cache(k=None)) == B.A2SF_EINVAL
+
+
+def test_decode_argument_errors():
+    assert decode_status(fake_cache(), o=None) == B.A2SF_EINVAL
+    assert decode_status(fake_cache(), mode=3) == B.A2SF_EINVAL
+    assert decode_status(fake_cache(), t_pos=-1) == B.A2SF_EINVAL
+    assert decode_status(fake_cache(capacity=8)) == B.A2SF_ECAPACITY
+    # few heads => split over tokens => needs the workspace; stable mode always does
+    assert decode_status(fake_cache(G=2, capacity=200, select=50, recent=50), select=50, recent=50,
+                         ws=None) == B.A2SF_EWORKSPACE
+    assert decode_status(fake_cache(G=4096), mode=1, ws=None) == B.A2SF_EWORKSPACE
+
+
+def test_select_and_compact_argument_errors():
+    lib = B.lib()
+    assert lib.a2sf_select(None, None, None, 1, 8, 8, B.Budget(2, 2), FAKE, FAKE, None) == B.A2SF_EINVAL
+    assert lib.a2sf_select(FAKE, None, None, 1, 8, 4, B.Budget(2, 2), FAKE, FAKE, None) == B.A2SF_ESHAPE
+    assert lib.a2sf_select(FAKE, None, None, 1, 8, 8, B.Budget(0, 0), FAKE, FAKE, None) == B.A2SF_EINVAL
+    c = fake_cache()
+    assert lib.a2sf_compact(ctypes.byref(c), None, 8, FAKE, None) == B.A2SF_EINVAL
+    assert lib.a2sf_compact(ctypes.byref(c), FAKE, 0, FAKE, None) == B.A2SF_ESHAPE
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liba2sf.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()
