@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the A2SF hot path on one MI355X.
+
+One "step" of this benchmark is one pass of the whole path over one batch of synthetic
+input: the prompt phase (masked attention + forgotten scores + selection + gather into the
+cache) followed by the workload's T generation steps (attention over the retained tokens,
+score update, eviction).  Inputs are resident in HBM before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2]
+
+Prints ONE JSON line.  `value` is generation steps per second (one generation step = one
+a2sf_decode_step call covering all G heads), measured with HIP events on the launch stream
+over every generation step of the K timed passes.  The roofline objects relate the two
+heavy kernels to the machine: the fused decode kernel to the HBM peak, the prompt-phase
+attention to the dense bf16 matrix-core peak.  `cpu_baseline` is the float64 oracle timed
+on the host cores of this machine on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for _p in (ROOT, os.path.join(ROOT, "tests")):
+    if _p not in sys.path:
+        sys.path.insert(0, _p)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def decode_bytes_per_step(G, L, d, e):
+    """Algorithmic bytes of one generation step: K and V rows read once, scores read and
+    written, q read, o written, the new k/v rows written."""
+    return G * (2 * L * d * e + 8 * L + 4 * d * e)
+
+
+def prefill_model_flops(G, n, d, with_o=True):
+    """One causal QK^T sweep (2 flop per MAC over the lower triangle incl. diagonal), plus one
+    PV sweep when outputs are requested.  The score kernel's recomputation is not counted."""
+    one = d * n * (n + 1)
+    return G * one * (2 if with_o else 1)
+
+
+def read_traffic(name):
+    """HBM bytes per launch measured with rocprofv3 --pmc (see profiles/), if recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == name:
+            return float(parts[1])
+    return None
+
+
+def cpu_baseline(w, budget_s=12.0):
+    """The oracle, as it stands, on this machine's host cores: prompt phase of two heads, then
+    generation steps head by head until about `budget_s` seconds have been spent."""
+    import numpy as np
+
+    from oracle import a2sf_oracle as orc
+    from paper_2407_20485_amd import synth
+
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:  # pragma: no cover
+        blas_threads = 1
+    alpha = w.alpha
+    heads = [0, w.G // 2]
+    caches, data = [], []
+    t0 = time.perf_counter()
+    for g in heads:
+        Q, K, V = (x.astype(np.float64) for x in synth.head_arrays(w, g))
+        data.append((Q, K, V))
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for Q, K, V in data:
+        if w.n <= 8192:
+            _, _, c = orc.prefill(Q[:w.n], K[:w.n], V[:w.n], alpha, w.select, w.recent)
+        else:
+            S, _ = orc.forgotten_scores_streamed(Q[:w.n], K[:w.n], [alpha], V=V[:w.n])
+            keep = orc.select_keep(S[float(alpha)], np.arange(w.n), w.select, w.recent)
+            c = orc.HeadCache(K[keep], V[keep], S[float(alpha)][keep], keep)
+        caches.append(c)
+    t_prefill = (time.perf_counter() - t0) / len(heads)
+    head_steps, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < budget_s:
+        for (Q, K, V), c0 in zip(data, caches):
+            c = c0.copy()
+            for t in range(w.T):
+                r = w.n + t
+                orc.decode_step(c, Q[r], K[r], V[r], r, alpha, w.select, w.recent)
+            head_steps += w.T
+    t_dec = time.perf_counter() - t0
+    per_head_step = t_dec / head_steps
+    return {
+        "value": 1.0 / (per_head_step * w.G), "unit": "steps/s", "cores": int(blas_threads),
+        "kind": "oracle",
+        "sample": (f"{len(heads)} of {w.G} heads: float64 prompt phase {t_prefill:.3f} s/head, then "
+                   f"{head_steps} head-steps of the generation loop in {t_dec:.1f} s "
+                   f"({per_head_step * 1e6:.1f} us per head-step); value = 1/(G * that), i.e. "
+                   f"extrapolated linearly to all {w.G} heads; the per-head Python loop is serial, "
+                   f"BLAS may use up to {blas_threads} threads"),
+        "prefill_s_per_head": t_prefill,
+        "prefill_s_all_heads_extrapolated": t_prefill * w.G,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-o", action="store_true", help="prompt phase without attention outputs")
+    ap.add_argument("--mode", choices=["fast", "stable"], default="fast")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU only (every head is an independent problem; "
+            "see DESIGN.md for how the path would shard). Run with --gpus 1.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2407_20485_amd as a2sf
+    from paper_2407_20485_amd import synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback.")
+        sys.exit(3)
+    w = synth.CONFIGS[args.config]
+    alpha = w.alpha
+    G, n, d, T = w.G, w.n, w.d, w.T
+    e = 4 if w.dtype == "f32" else 2
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    mode = a2sf.A2SF_EVICT_FAST if args.mode == "fast" else a2sf.A2SF_EVICT_STABLE
+
+    log(f"[bench] generating config {w.cfg_id} ({w.name}): G={G} n={n} d={d} {w.dtype} T={T} "
+        f"budget={w.select}+{w.recent} alpha={alpha}")
+    t0 = time.perf_counter()
+    data = synth.generate(w, progress=lambda c, H: log(f"[bench]   {c}/{H} heads"))
+    dev = {}
+    for k, v in data.items():
+        t = torch.from_numpy(v)
+        if w.dtype == "bf16":
+            t = t.view(torch.int16).view(torch.bfloat16)
+        dev[k] = t.cuda()
+    del data
+    log(f"[bench] inputs resident in HBM after {time.perf_counter() - t0:.1f} s")
+
+    capacity = w.budget + 1
+    cache = a2sf.Cache(G, capacity, d, tdt)
+    code = a2sf.A2SF_F32 if w.dtype == "f32" else a2sf.A2SF_BF16
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, n, capacity, d, code, w.select, w.recent),
+                     dtype=torch.uint8, device="cuda")
+    o_pre = None if args.no_o else torch.empty((G, n, d), dtype=tdt, device="cuda")
+    o_dec = torch.empty((G, d), dtype=tdt, device="cuda")
+
+    def one_pass(ev=None):
+        if ev:
+            ev[0].record()
+        a2sf.a2sf_prefill(dev["q"], dev["k"], dev["v"], n, alpha, w.select, w.recent, cache,
+                          o=o_pre, scores_full=None, workspace=ws)
+        if ev:
+            ev[1].record()
+        for t in range(T):
+            a2sf.a2sf_decode_step(dev["qd"][t], dev["kd"][t], dev["vd"][t], n + t, cache, alpha,
+                                  w.select, w.recent, o_dec, mode=mode, workspace=ws)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_pass(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    prefill_ms = [ev[0].elapsed_time(ev[1]) for ev in events]
+    decode_ms = [ev[1].elapsed_time(ev[2]) for ev in events]
+    dec_s_per_step = sum(decode_ms) / 1e3 / (args.steps * T)
+    pre_s = sum(prefill_ms) / 1e3 / args.steps
+    lens = cache.len.cpu().numpy()
+    assert np.all(lens == min(n + T, w.budget)), "cache lengths wrong after the timed passes"
+
+    L = min(n, w.budget) + 1     # tokens a steady-state generation step reads
+    dbytes = decode_bytes_per_step(G, L, d, e)
+    flops = prefill_model_flops(G, n, d, with_o=not args.no_o)
+    dec_gbs = dbytes / dec_s_per_step / 1e9
+    pre_tflops = flops / pre_s / 1e12
+    nsplit_note = "one fused kernel per step" if G >= 1024 else "token-split partial + combine kernels per step"
+
+    out = {
+        "metric": "decode steps/s (fused attn+A2SF+evict) & HBM GB/s; prefill score TFLOP/s",
+        "value": 1.0 / dec_s_per_step,
+        "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n, "head_dim": d,
+                   "decode_steps": T, "budget": f"{w.select}+{w.recent}", "alpha": alpha,
+                   "evict_mode": args.mode, "prefill_outputs": not args.no_o,
+                   "pass": "prefill + T decode steps"},
+        "decode_us_per_step": dec_s_per_step * 1e6,
+        "decode_hbm_gbs_algorithmic": dec_gbs,
+        "prefill_ms": pre_s * 1e3,
+        "prefill_tflops_model": pre_tflops,
+        "roofline": {"kernel": f"decode step ({nsplit_note})", "bound": "hbm", "achieved": dec_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
+                     "bytes_per_launch": dbytes, "avg_launch_us": dec_s_per_step * 1e6,
+                     "traffic": read_traffic(f"decode_cfg{w.cfg_id}")},
+        "roofline_prefill": {"kernel": "a2sf_prefill (attention fwd + column scores + select + gather)",
+                             "bound": "mfma", "achieved": pre_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                             "unit": "TFLOP/s", "frac": pre_tflops / MFMA_BF16_PEAK_TFLOPS,
+                             "flops_per_launch": flops, "avg_launch_ms": pre_s * 1e3,
+                             "flop_convention": "model flops: one causal QK^T sweep + one PV sweep; "
+                                                "the score kernel's recomputed QK^T is not counted",
+                             "traffic": read_traffic(f"prefill_cfg{w.cfg_id}")},
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the float64 oracle on the host cores ...")
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
