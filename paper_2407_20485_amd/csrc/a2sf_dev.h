@@ -49,6 +49,34 @@ template <> struct Elem<bf16_t> {
   __device__ static __forceinline__ void store(bf16_t* p, float x) { *p = (bf16_t)f32_to_bf16(x); }
 };
 
+// 16 bytes of packed elements from EPL floats (inverse of Elem<T>::unpack)
+__device__ __forceinline__ uint4 pack16(const float* f, float) {
+  return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+__device__ __forceinline__ uint4 pack16(const float* f, bf16_t) {
+  return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+}
+
+// Sum over aligned groups of N consecutive lanes (N = 8, 16, 32 or 64); every lane of a
+// group gets the group's total.  The first four halvings are DPP lane permutations folded
+// into the adds (quad swaps, then mirrors inside half rows and rows of 16 lanes: a mirror
+// pairs each lane with one holding the other half's partial sum); only the steps across
+// rows of 16 go through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_move<0xB1>(v);                  // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);                  // quad_perm [2,3,0,1]
+  if (N >= 8) v += dpp_move<0x141>(v);     // row_half_mirror
+  if (N >= 16) v += dpp_move<0x140>(v);    // row_mirror
+  if (N >= 32) v += __shfl_xor(v, 16, 64);
+  if (N >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 // ---- ordering ---------------------------------------------------------------------------
 // Monotone map float -> uint32 (larger float = larger key); -0 is folded onto +0.
 __device__ __forceinline__ uint32_t ordered_key(float s) {

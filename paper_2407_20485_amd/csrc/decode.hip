@@ -23,78 +23,105 @@
 namespace a2sf {
 namespace {
 
-constexpr int kUnroll = 4;  // 16-byte loads in flight per lane in the K and V sweeps
-
 template <typename T, int D>
 struct RowGeom {
   static constexpr int EPL = Elem<T>::kPerLane;   // elements per lane
   static constexpr int LPR = D / EPL;             // lanes per row
   static constexpr int RPW = kWave / LPR;         // rows per wave-wide load
-  static constexpr int ROWS_PER_ITER = kWaves * RPW * kUnroll;
 };
 
 struct StepSmem {
-  float part[kWaves][128];          // per-wave partial outputs
   unsigned long long red64[8];
   float redf[8];
   int redi[8];
   int victim;
 };
 
+// The threads that cooperate on one head: a whole workgroup, or a single wave.
+struct BlockGroup {
+  static constexpr int kSize = kThreads, kNW = kWaves;
+  __device__ static __forceinline__ int tid() { return threadIdx.x; }
+  __device__ static __forceinline__ int wave() { return threadIdx.x >> 6; }
+  __device__ static __forceinline__ void sync() { __syncthreads(); }
+  __device__ static __forceinline__ float max(float v, StepSmem& sm) { return block_max(v, sm.redf); }
+  __device__ static __forceinline__ float sum(float v, StepSmem& sm) { return block_sum(v, sm.redf); }
+  __device__ static __forceinline__ int sum_i(int v, StepSmem& sm) { return block_sum_i(v, sm.redi); }
+  __device__ static __forceinline__ unsigned long long min_u64(unsigned long long v, StepSmem& sm) {
+    return block_min_u64(v, sm.red64);
+  }
+};
+struct WaveGroup {
+  static constexpr int kSize = kWave, kNW = 1;
+  __device__ static __forceinline__ int tid() { return threadIdx.x & 63; }
+  __device__ static __forceinline__ int wave() { return 0; }
+  // LDS and global accesses of one wave, made visible to its other lanes
+  __device__ static __forceinline__ void sync() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+  }
+  __device__ static __forceinline__ float max(float v, StepSmem&) { return wave_max(v); }
+  __device__ static __forceinline__ float sum(float v, StepSmem&) { return wave_sum(v); }
+  __device__ static __forceinline__ int sum_i(int v, StepSmem&) { return wave_sum_i(v); }
+  __device__ static __forceinline__ unsigned long long min_u64(unsigned long long v, StepSmem&) {
+    return wave_min_u64(v);
+  }
+};
+
 // logits z[r] (log2 units) of rows [row_begin, row_end) into LDS z[r - z_base].
-template <typename T, int D>
+// U = 16-byte loads in flight per lane.
+template <typename Grp, int U, typename T, int D>
 __device__ __forceinline__ void sweep_k(const T* __restrict__ Kg, const T* __restrict__ knew,
                                         int n_old, int row_begin, int row_end,
                                         const float* qv, float* z, int z_base) {
   using Gm = RowGeom<T, D>;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int ROWS_PER_ITER = Grp::kNW * Gm::RPW * U;
+  const int lane = threadIdx.x & 63, wave = Grp::wave();
   const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
-  for (int base = row_begin; base < row_end; base += Gm::ROWS_PER_ITER) {
-    uint4 x[kUnroll];
+  for (int base = row_begin; base < row_end; base += ROWS_PER_ITER) {
+    uint4 x[U];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+    for (int u = 0; u < U; ++u) {
+      const int r = base + (u * Grp::kNW + wave) * Gm::RPW + rgrp;
       const T* p = (r == n_old) ? knew : Kg + (size_t)(r < row_end ? r : row_begin) * D;
       x[u] = load16(p + sub * Gm::EPL);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+    for (int u = 0; u < U; ++u) {
+      const int r = base + (u * Grp::kNW + wave) * Gm::RPW + rgrp;
       float f[Gm::EPL];
       Elem<T>::unpack(x[u], f);
       float dot = 0.f;
 #pragma unroll
       for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[e], f[e], dot);
-#pragma unroll
-      for (int o = Gm::LPR / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      dot = group_sum<Gm::LPR>(dot);
       if (sub == 0 && r < row_end) z[r - z_base] = dot;
     }
   }
 }
 
-// acc[e] += sum_r w[r] * V[r][sub*EPL + e] over rows [row_begin, row_end); then reduced over
-// the workgroup into sm.part[0][0..D) (valid after the function returns, for all threads).
-template <typename T, int D>
+// acc[e] = sum_r w[r] * V[r][sub*EPL + e] over this wave's share of rows [row_begin, row_end),
+// summed over the row groups of the wave: valid in the lanes with rgrp == 0.
+template <typename Grp, int U, typename T, int D>
 __device__ __forceinline__ void sweep_v(const T* __restrict__ Vg, const T* __restrict__ vnew,
                                         int n_old, int row_begin, int row_end, const float* w,
-                                        int w_base, StepSmem& sm) {
+                                        int w_base, float* acc) {
   using Gm = RowGeom<T, D>;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr int ROWS_PER_ITER = Grp::kNW * Gm::RPW * U;
+  const int lane = threadIdx.x & 63, wave = Grp::wave();
   const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
-  float acc[Gm::EPL];
 #pragma unroll
   for (int e = 0; e < Gm::EPL; ++e) acc[e] = 0.f;
-  for (int base = row_begin; base < row_end; base += Gm::ROWS_PER_ITER) {
-    uint4 x[kUnroll];
+  for (int base = row_begin; base < row_end; base += ROWS_PER_ITER) {
+    uint4 x[U];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+    for (int u = 0; u < U; ++u) {
+      const int r = base + (u * Grp::kNW + wave) * Gm::RPW + rgrp;
       const T* p = (r == n_old) ? vnew : Vg + (size_t)(r < row_end ? r : row_begin) * D;
       x[u] = load16(p + sub * Gm::EPL);
     }
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int r = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+    for (int u = 0; u < U; ++u) {
+      const int r = base + (u * Grp::kNW + wave) * Gm::RPW + rgrp;
       const float wr = r < row_end ? w[r - w_base] : 0.f;
       float f[Gm::EPL];
       Elem<T>::unpack(x[u], f);
@@ -107,33 +134,100 @@ __device__ __forceinline__ void sweep_v(const T* __restrict__ Vg, const T* __res
 #pragma unroll
     for (int o = Gm::LPR; o < kWave; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
   }
+}
+
+// Workgroup-wide sum of the per-wave partial outputs; result in part[0][0..D).
+template <typename T, int D>
+__device__ __forceinline__ void reduce_output(const float* acc, float (*part)[128]) {
+  using Gm = RowGeom<T, D>;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
   __syncthreads();
   if (rgrp == 0) {
 #pragma unroll
-    for (int e = 0; e < Gm::EPL; ++e) sm.part[wave][sub * Gm::EPL + e] = acc[e];
+    for (int e = 0; e < Gm::EPL; ++e) part[wave][sub * Gm::EPL + e] = acc[e];
   }
   __syncthreads();
   if (threadIdx.x < D) {
     const int c = threadIdx.x;
-    sm.part[0][c] = (sm.part[0][c] + sm.part[1][c]) + (sm.part[2][c] + sm.part[3][c]);
+    part[0][c] = (part[0][c] + part[1][c]) + (part[2][c] + part[3][c]);
   }
   __syncthreads();
 }
 
-template <typename T, int D>
-__device__ __forceinline__ void copy_row(T* dst, const T* src) {
+// K and V row `src` -> row `dst` (pointers to the rows), by the first lanes of the group.
+template <typename Grp, typename T, int D>
+__device__ __forceinline__ void copy_kv_row(T* kdst, const T* ksrc, T* vdst, const T* vsrc) {
   using Gm = RowGeom<T, D>;
-  if (threadIdx.x < Gm::LPR) store16(dst + threadIdx.x * Gm::EPL, load16(src + threadIdx.x * Gm::EPL));
+  const int t = Grp::tid();
+  if (t < Gm::LPR) store16(kdst + t * Gm::EPL, load16(ksrc + t * Gm::EPL));
+  else if (t < 2 * Gm::LPR)
+    store16(vdst + (t - Gm::LPR) * Gm::EPL, load16(vsrc + (t - Gm::LPR) * Gm::EPL));
 }
 
-// Score update and eviction of one head.  On entry a[0..L) in LDS holds the probabilities
-// of the L = n_old+1 tokens (slot n_old = the new token, not yet stored in the cache).
-// All 256 threads call this.  a[] is overwritten with the updated scores.
+__device__ __forceinline__ unsigned long long evict_key(float score, int pos) {
+  // smallest key = lowest score; among equal scores the highest position
+  return ((unsigned long long)ordered_key(score) << 32) | (unsigned)(0x7FFFFFFF - pos);
+}
+
+// General eviction (several tokens at once, or a cache whose newest positions have gaps).
+// On entry a[0..L) in LDS holds the UPDATED scores of the L = n_old+1 tokens; slot n_old is
+// the new token, not yet stored.  Makes the new token physical, marks the `recent` largest
+// positions, then evicts one token at a time, moving the last live row into the hole.
+template <typename Grp, typename T, int D>
+__device__ void evict_general(float* a, int n_old, int excess, T* Kg, T* Vg, float* Sg,
+                              int32_t* Pg, int32_t* len_g, const T* knew, const T* vnew,
+                              int t_pos, int recent, StepSmem& sm) {
+  const int tid = Grp::tid();
+  const int L = n_old + 1;
+  for (int j = tid; j < L; j += Grp::kSize) Sg[j] = a[j];
+  if (tid == 0) Pg[n_old] = t_pos;
+  copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
+  __threadfence_block();
+  Grp::sync();
+  // protected tokens get score +inf in LDS (their real score is already in Sg)
+  for (int j = tid; j < L; j += Grp::kSize) {
+    const int pj = Pg[j];
+    int newer = 0;
+    for (int i = 0; i < L; ++i) newer += Pg[i] > pj;
+    if (newer < recent) a[j] = INFINITY;
+  }
+  Grp::sync();
+  int live = L;
+  for (int it = 0; it < excess; ++it) {
+    unsigned long long b = ~0ull;
+    for (int j = tid; j < live; j += Grp::kSize) {
+      const unsigned long long key = evict_key(a[j], Pg[j]);
+      b = key < b ? key : b;
+    }
+    if (tid == 0) sm.victim = live - 1;
+    Grp::sync();
+    const unsigned long long win = Grp::min_u64(b, sm);
+    for (int j = tid; j < live; j += Grp::kSize)
+      if (evict_key(a[j], Pg[j]) == win) sm.victim = j;
+    Grp::sync();
+    const int v = sm.victim, last = live - 1;
+    if (v != last) {
+      copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, Kg + (size_t)last * D, Vg + (size_t)v * D,
+                             Vg + (size_t)last * D);
+      if (tid == Grp::kSize - 1) { Sg[v] = Sg[last]; Pg[v] = Pg[last]; a[v] = a[last]; }
+    }
+    --live;
+    __threadfence_block();
+    Grp::sync();
+  }
+  if (tid == 0) *len_g = live;
+}
+
+// Score update and eviction of one head by a whole workgroup.  On entry a[0..L) in LDS holds
+// the probabilities of the L = n_old+1 tokens (slot n_old = the new token, not yet stored in
+// the cache).  All 256 threads call this.  a[] is overwritten with the updated scores.
 template <typename T, int D>
 __device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, int32_t* Pg,
                                  int32_t* len_g, const T* knew, const T* vnew, int t_pos,
                                  float alpha, int select, int recent, bool evict_here,
                                  StepSmem& sm) {
+  using Grp = BlockGroup;
   const int tid = threadIdx.x;
   const int L = n_old + 1;
   const int excess = evict_here ? L - (select + recent) : 0;
@@ -145,12 +239,7 @@ __device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, i
   if (excess <= 0) {  // room left: plain append
     for (int j = tid; j < L; j += kThreads) Sg[j] = a[j];
     if (tid == 0) { Pg[n_old] = t_pos; *len_g = L; }
-    copy_row<T, D>(Kg + (size_t)n_old * D, knew);
-    if (tid >= 64) {
-      using Gm = RowGeom<T, D>;
-      const int t = tid - 64;
-      if (t < Gm::LPR) store16(Vg + (size_t)n_old * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
-    }
+    copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
     return;
   }
 
@@ -164,8 +253,7 @@ __device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, i
     if (p > thr) {
       ++cnt;
     } else {
-      const unsigned long long key =
-          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - p);
+      const unsigned long long key = evict_key(a[j], p);
       best = key < best ? key : best;
     }
   }
@@ -177,82 +265,20 @@ __device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, i
     const unsigned long long win = block_min_u64(best, sm.red64);
     for (int j = tid; j < L; j += kThreads) {
       const int p = j < n_old ? Pg[j] : t_pos;
-      if (p <= thr) {
-        const unsigned long long key =
-            ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - p);
-        if (key == win) sm.victim = j;
-      }
+      if (p <= thr && evict_key(a[j], p) == win) sm.victim = j;
     }
     __syncthreads();
     const int v = sm.victim;
     for (int j = tid; j < n_old; j += kThreads)
       if (j != v) Sg[j] = a[j];
     if (v != n_old) {
-      if (tid == 0) { Sg[v] = a[n_old]; Pg[v] = t_pos; }
-      copy_row<T, D>(Kg + (size_t)v * D, knew);
-      if (tid >= 64) {
-        using Gm = RowGeom<T, D>;
-        const int t = tid - 64;
-        if (t < Gm::LPR) store16(Vg + (size_t)v * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
-      }
+      if (tid == kThreads - 1) { Sg[v] = a[n_old]; Pg[v] = t_pos; }
+      copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, knew, Vg + (size_t)v * D, vnew);
     }
     if (tid == 0) *len_g = n_old;  // = select + recent
     return;
   }
-
-  // ---- general case (several evictions, or a cache whose newest positions have gaps):
-  // make the new token physical, mark the `recent` largest positions, then evict one token
-  // at a time, moving the last live row into the hole.
-  for (int j = tid; j < L; j += kThreads) Sg[j] = a[j];
-  if (tid == 0) Pg[n_old] = t_pos;
-  copy_row<T, D>(Kg + (size_t)n_old * D, knew);
-  if (tid >= 64) {
-    using Gm = RowGeom<T, D>;
-    const int t = tid - 64;
-    if (t < Gm::LPR) store16(Vg + (size_t)n_old * D + t * Gm::EPL, load16(vnew + t * Gm::EPL));
-  }
-  __threadfence_block();
-  __syncthreads();
-  // protected tokens get score +inf in LDS (their real score is already in Sg)
-  for (int j = tid; j < L; j += kThreads) {
-    const int pj = Pg[j];
-    int newer = 0;
-    for (int i = 0; i < L; ++i) newer += Pg[i] > pj;
-    if (newer < recent) a[j] = INFINITY;
-  }
-  __syncthreads();
-  int live = L;
-  for (int it = 0; it < excess; ++it) {
-    unsigned long long b = ~0ull;
-    for (int j = tid; j < live; j += kThreads) {
-      const unsigned long long key =
-          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - Pg[j]);
-      b = key < b ? key : b;
-    }
-    if (tid == 0) sm.victim = live - 1;
-    const unsigned long long win = block_min_u64(b, sm.red64);
-    for (int j = tid; j < live; j += kThreads) {
-      const unsigned long long key =
-          ((unsigned long long)ordered_key(a[j]) << 32) | (unsigned)(0x7FFFFFFF - Pg[j]);
-      if (key == win) sm.victim = j;
-    }
-    __syncthreads();
-    const int v = sm.victim, last = live - 1;
-    if (v != last) {
-      copy_row<T, D>(Kg + (size_t)v * D, Kg + (size_t)last * D);
-      if (tid >= 64) {
-        using Gm = RowGeom<T, D>;
-        const int t = tid - 64;
-        if (t < Gm::LPR)
-          store16(Vg + (size_t)v * D + t * Gm::EPL, load16(Vg + (size_t)last * D + t * Gm::EPL));
-      }
-      if (tid == 0) { Sg[v] = Sg[last]; Pg[v] = Pg[last]; a[v] = a[last]; }
-    }
-    --live;
-    __threadfence_block();
-    __syncthreads();
-  }
-  if (tid == 0) *len_g = live;
+  evict_general<Grp, T, D>(a, n_old, excess, Kg, Vg, Sg, Pg, len_g, knew, vnew, t_pos, recent, sm);
 }
 
 template <typename T, int D>
@@ -264,6 +290,9 @@ __device__ __forceinline__ void load_query(const T* qg, float scale_log2e, float
   for (int e = 0; e < Gm::EPL; ++e) qv[e] *= scale_log2e;
 }
 
+constexpr int kBlockUnroll = 4;  // loads in flight per lane, workgroup-per-head kernels
+constexpr int kWaveUnroll = 8;   // loads in flight per lane, wave-per-head kernel
+
 // ---- one workgroup per head ---------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
@@ -272,6 +301,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
     int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
   extern __shared__ float a[];  // [capacity]
   __shared__ StepSmem sm;
+  __shared__ float part[kWaves][128];
   const int g = blockIdx.x, tid = threadIdx.x;
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;  // precondition len+1 <= capacity violated
@@ -283,7 +313,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
 
   float qv[RowGeom<T, D>::EPL];
   load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
-  sweep_k<T, D>(Kg, knew, n_old, 0, L, qv, a, 0);
+  sweep_k<BlockGroup, kBlockUnroll, T, D>(Kg, knew, n_old, 0, L, qv, a, 0);
   __syncthreads();
 
   float mx = -INFINITY;
@@ -300,11 +330,158 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
   for (int j = tid; j < L; j += kThreads) a[j] *= inv;
   __syncthreads();
 
-  sweep_v<T, D>(Vg, vnew, n_old, 0, L, a, 0, sm);
-  if (tid < D) Elem<T>::store(o + (size_t)g * D + tid, sm.part[0][tid]);
+  float acc[RowGeom<T, D>::EPL];
+  sweep_v<BlockGroup, kBlockUnroll, T, D>(Vg, vnew, n_old, 0, L, a, 0, acc);
+  reduce_output<T, D>(acc, part);
+  if (tid < D) Elem<T>::store(o + (size_t)g * D + tid, part[0][tid]);
 
   update_and_evict<T, D>(a, n_old, Kg, Vg, S + (size_t)g * capacity, P + (size_t)g * capacity,
                          len + g, knew, vnew, t_pos, alpha, select, recent, evict_here != 0, sm);
+}
+
+// ---- one wave per head ----------------------------------------------------------------
+// For many heads with short caches (capacity <= 64*NJ).  No workgroup barrier anywhere: a
+// wave streams its head's K rows, keeps logits / probabilities in its own LDS strip, the
+// scores and positions of its head in registers (slot j = lane + 64k), and finishes the
+// softmax, the score update and the single eviction with wave shuffles only, so the four
+// heads of a workgroup never wait for each other and loads of different heads overlap.
+template <typename T, int D, int NJ>
+__global__ __launch_bounds__(kThreads) void decode_wave_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha, int select,
+    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+  using Gm = RowGeom<T, D>;
+  using Grp = WaveGroup;
+  __shared__ float zs[kWaves][NJ * 64];
+  __shared__ StepSmem sms[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.x * kWaves + wave;
+  if (g >= G) return;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) return;
+  const int L = n_old + 1;
+  float* z = zs[wave];
+  StepSmem& sm = sms[wave];
+  T* Kg = K + (size_t)g * capacity * D;
+  T* Vg = V + (size_t)g * capacity * D;
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+
+  // bookkeeping of the head, fetched up front so that it is in registers when needed
+  float s_old[NJ];
+  int pos[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    s_old[k] = j < n_old ? Sg[j] : 0.f;
+    pos[k] = j < n_old ? Pg[j] : t_pos;
+  }
+  float qv[Gm::EPL];
+  load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
+  sweep_k<Grp, kWaveUnroll, T, D>(Kg, knew, n_old, 0, L, qv, z, 0);
+  Grp::sync();
+
+  float zr[NJ];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    zr[k] = j < L ? z[j] : -INFINITY;
+    mx = fmaxf(mx, zr[k]);
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    zr[k] = exp2f(zr[k] - mx);  // 0 for j >= L
+    sum += zr[k];
+  }
+  sum = wave_sum(sum);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    zr[k] *= inv;
+    const int j = lane + 64 * k;
+    if (j < L) z[j] = zr[k];
+  }
+  Grp::sync();
+
+  float acc[Gm::EPL];
+  sweep_v<Grp, kWaveUnroll, T, D>(Vg, vnew, n_old, 0, L, z, 0, acc);
+  if (rgrp == 0) store16(o + (size_t)g * D + sub * Gm::EPL, pack16(acc, T()));
+
+  // ---- S <- alpha*S + a, in registers
+  float s_new[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], zr[k]);
+  const int excess = evict_here ? L - (select + recent) : 0;
+  if (excess <= 0) {  // room left: plain append
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < L) Sg[j] = s_new[k];
+    }
+    if (lane == 0) { Pg[n_old] = t_pos; len[g] = L; }
+    copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
+    return;
+  }
+  const int thr = t_pos - recent;
+  int cnt = 0;
+  unsigned long long best = ~0ull;
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    if (j < L) {
+      if (pos[k] > thr) {
+        ++cnt;
+      } else {
+        const unsigned long long key = evict_key(s_new[k], pos[k]);
+        best = key < best ? key : best;
+      }
+    }
+  }
+  cnt = wave_sum_i(cnt);
+  if (excess == 1 && cnt == recent) {
+    const unsigned long long win = wave_min_u64(best);
+    int v = -1;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
+    if (v < 0) v = n_old;  // cannot happen for valid input: drop the new token rather than write out of range
+    // the new token's updated score (= its probability) sits with lane n_old%64, slot n_old/64
+    float s_tok = 0.f;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k)
+      if (k == n_old / 64) s_tok = s_new[k];
+    s_tok = __shfl(s_tok, n_old & 63, 64);
+    // one contiguous store of the scores; the victim's slot receives the new token's
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < n_old) Sg[j] = (j == v) ? s_tok : s_new[k];
+    }
+    if (v != n_old) {
+      if (lane == 63) Pg[v] = t_pos;
+      copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, knew, Vg + (size_t)v * D, vnew);
+    }
+    // len stays n_old (= select + recent): nothing to write
+    return;
+  }
+  // rare: several evictions or gaps in the newest positions
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    if (j < L) z[j] = s_new[k];
+  }
+  Grp::sync();
+  evict_general<Grp, T, D>(z, n_old, excess, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos, recent, sm);
 }
 
 // ---- split over tokens ----------------------------------------------------------------
@@ -317,6 +494,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     float* __restrict__ po, float scale_log2e) {
   extern __shared__ float z[];  // [rows_per_split]
   __shared__ StepSmem sm;
+  __shared__ float part[kWaves][128];
   const int g = blockIdx.x / nsplit, c = blockIdx.x % nsplit, tid = threadIdx.x;
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;
@@ -334,7 +512,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   const T* Vg = V + (size_t)g * capacity * D;
   float qv[RowGeom<T, D>::EPL];
   load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
-  sweep_k<T, D>(Kg, k_new + (size_t)g * D, n_old, r0, r1, qv, z, r0);
+  sweep_k<BlockGroup, kBlockUnroll, T, D>(Kg, k_new + (size_t)g * D, n_old, r0, r1, qv, z, r0);
   __syncthreads();
   float mx = -INFINITY;
   for (int j = r0 + tid; j < r1; j += kThreads) {
@@ -350,9 +528,11 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
     sum += p;
   }
   sum = block_sum(sum, sm.redf);
-  sweep_v<T, D>(Vg, v_new + (size_t)g * D, n_old, r0, r1, z, r0, sm);
+  float acc[RowGeom<T, D>::EPL];
+  sweep_v<BlockGroup, kBlockUnroll, T, D>(Vg, v_new + (size_t)g * D, n_old, r0, r1, z, r0, acc);
+  reduce_output<T, D>(acc, part);
   if (tid == 0) { mlo[0] = mx; mlo[1] = sum; }
-  if (tid < D) poo[tid] = sm.part[0][tid];
+  if (tid < D) poo[tid] = part[0][tid];
 }
 
 template <typename T, int D>
@@ -392,6 +572,19 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                   const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
                   void* o, void* ws, const DecodePlan& plan, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  if (plan.nsplit <= 1 && plan.wave_slots > 0) {
+    const dim3 grid((c.G + kWaves - 1) / kWaves);
+#define A2SF_WAVE(NJ)                                                                            \
+  hipLaunchKernelGGL((decode_wave_kernel<T, D, NJ>), grid, dim3(kThreads), 0, st, (const T*)q,   \
+                     (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, \
+                     c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o,      \
+                     scale_log2e)
+    if (plan.wave_slots == 2) A2SF_WAVE(2);
+    else if (plan.wave_slots == 4) A2SF_WAVE(4);
+    else A2SF_WAVE(8);
+#undef A2SF_WAVE
+    return;
+  }
   if (plan.nsplit <= 1) {
     hipLaunchKernelGGL((decode_fused_kernel<T, D>), dim3(c.G), dim3(kThreads),
                        (size_t)c.capacity * sizeof(float), st, (const T*)q, (const T*)k_new,
@@ -429,6 +622,9 @@ DecodePlan plan_decode(int G, int capacity, int d) {
   ns = (capacity + rows - 1) / rows;
   p.nsplit = ns;
   p.rows_per_split = rows;
+  // Many heads with short caches: one wave per head (slots held as 64 * wave_slots registers).
+  p.wave_slots = 0;
+  if (ns == 1 && G >= 4096 && capacity <= 512) p.wave_slots = capacity <= 128 ? 2 : (capacity <= 256 ? 4 : 8);
   p.ws_bytes = ns <= 1 ? 0
                        : sizeof(float) * ((size_t)G * capacity + (size_t)G * ns * 2 + (size_t)G * ns * d);
   return p;

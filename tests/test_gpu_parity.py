@@ -136,13 +136,24 @@ def test_small_fp32(d, say):
     run_lockstep(w, 0.5, mode=a2sf.A2SF_EVICT_STABLE, say=say)
 
 
+@pytest.mark.parametrize("G", [1100, 4200])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_many_heads_single_workgroup_decode(dtype, say):
-    """G >= 1024 heads: the decode step runs as one fused kernel per head (no token split)."""
-    w = variant(1, heads=1100, d=128 if dtype == "bf16" else 64, dtype=dtype, n=96, T=12,
-                select=12, recent=12, name=f"many heads {dtype}")
-    run_lockstep(w, 0.3, sample=list(range(0, 1100, 53)), say=say)
-    run_lockstep(w, 0.3, sample=list(range(7, 1100, 211)), mode=a2sf.A2SF_EVICT_STABLE, say=say)
+def test_many_heads_decode(dtype, G, say):
+    """G >= 1024 heads: one workgroup per head (no token split); G >= 4096 heads with a short
+    cache: one wave per head."""
+    w = variant(1, heads=G, d=128 if dtype == "bf16" else 64, dtype=dtype, n=96, T=12,
+                select=12, recent=12, name=f"{G} heads {dtype}")
+    run_lockstep(w, 0.3, sample=list(range(0, G, G // 20)), say=say)
+    run_lockstep(w, 0.3, sample=list(range(7, G, G // 5)), mode=a2sf.A2SF_EVICT_STABLE, say=say)
+
+
+@pytest.mark.parametrize("select,recent,d,dtype", [(150, 151, 128, "bf16"), (100, 100, 64, "bf16"),
+                                                   (90, 90, 128, "f32"), (20, 20, 128, "bf16")])
+def test_wave_per_head_slot_counts(select, recent, d, dtype, say):
+    """The wave-per-head decode kernel holds 128 / 256 / 512 slots per head in registers."""
+    w = variant(1, heads=4100, d=d, dtype=dtype, n=select + recent + 30, T=5, select=select,
+                recent=recent, name=f"wave slots B={select + recent} d{d} {dtype}")
+    run_lockstep(w, 0.5, sample=[0, 1, 2, 3, 2049, 4099], say=say)
 
 
 @pytest.mark.parametrize("select,recent", [(10, 0), (0, 10), (1, 0), (0, 1), (200, 200)])
@@ -151,12 +162,13 @@ def test_budget_shapes(select, recent, say):
     and a budget larger than prompt + steps (the cache only grows)."""
     w = variant(1, heads=4, n=120, T=10, select=select, recent=recent, name=f"budget {select}+{recent}")
     run_lockstep(w, 0.3, say=say)
-    w2 = variant(1, heads=1030, n=70, T=6, d=64, select=select, recent=recent,
-                 name=f"budget {select}+{recent} fused")
-    run_lockstep(w2, 0.3, sample=[0, 500, 1029], say=say)
+    for G in (1030, 4100):
+        w2 = variant(1, heads=G, n=70, T=6, d=64, select=select, recent=recent,
+                     name=f"budget {select}+{recent} G={G}")
+        run_lockstep(w2, 0.3, sample=[0, 500, G - 1], say=say)
 
 
-@pytest.mark.parametrize("G", [3, 1040])
+@pytest.mark.parametrize("G", [3, 1040, 4100])
 def test_budget_lowered_between_steps(G, say):
     """A step that must evict several tokens at once, and a recent window larger than the one
     the cache was built with (its newest positions then have gaps)."""
