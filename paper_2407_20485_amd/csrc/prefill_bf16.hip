@@ -29,6 +29,17 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 64;  // keys (attn_fwd) or query rows (col_scores) per LDS tile
+constexpr float kLazyRescale = 8.0f;  // log2 units
+#ifndef A2SF_FWD_PREFETCH
+#define A2SF_FWD_PREFETCH 4
+#endif
+constexpr int kPrefetch = A2SF_FWD_PREFETCH;  // LDS fragment reads in flight ahead of their matrix op
+#ifndef A2SF_FWD_NB
+#define A2SF_FWD_NB 1      // 32-row query blocks per wave in attn_fwd
+#endif
+#ifndef A2SF_FWD_OCC
+#define A2SF_FWD_OCC 2     // workgroups per compute unit the register budget is sized for
+#endif
 
 __device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, const f32x16& c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
@@ -122,7 +133,7 @@ __device__ __forceinline__ long long xcd_contiguous_id(long long total) {
 
 // ---------------------------------------------------------------------------------------
 template <int D, int NB, bool WITH_O>
-__global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
+__global__ __launch_bounds__(kThreads, A2SF_FWD_OCC) void attn_fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
   constexpr int BM = kWaves * 32 * NB;
@@ -188,14 +199,26 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) sacc[nb][kb][i] = 0.f;
+      {
+        // fragment i = (kk, kb): the two key blocks alternate so that consecutive matrix
+        // instructions never depend on each other; LDS reads run kPrefetch fragments ahead.
+        constexpr int NF = 2 * KK;
+        uint4 fr[NF];
+        auto kfrag = [&](int i) {
+          return ks[buf][row_tile_unit<D>((i & 1) * 32 + l32, 2 * (i >> 1) + h)];
+        };
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int i = 0; i < kPrefetch && i < NF; ++i) fr[i] = kfrag(i);
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const uint4 a = ks[buf][row_tile_unit<D>(kb * 32 + l32, 2 * kk + h)];
+        for (int i = 0; i < NF; ++i) {
+          if (i + kPrefetch < NF) fr[i + kPrefetch] = kfrag(i + kPrefetch);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) sacc[nb][kb] = mfma_bf16(a, qf[nb][kk], sacc[nb][kb]);
+          for (int nb = 0; nb < NB; ++nb)
+            sacc[nb][i & 1] = mfma_bf16(fr[i], qf[nb][i >> 1], sacc[nb][i & 1]);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+          __builtin_amdgcn_sched_group_barrier(0x008, NB, 0); // then this step's matrix ops
         }
+      }
       const bool diag = key0 + kTile - 1 > wrow0;  // tile reaches past the wave's first row
       uint4 pf[NB][2][2];
 #pragma unroll
@@ -216,9 +239,14 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
 #pragma unroll
           for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        // rows past the end of a ragged block can be fully masked in a tile: keep m finite
-        const float m_new = fmaxf(m[nb], fmaxf(mx * scale_log2e, -1e30f));
-        if (__any(m_new > m[nb])) {
+        // The running maximum only has to bound the exponents, not equal the true maximum:
+        // it is raised (and the accumulators rescaled) only when some row of the wave
+        // exceeds it by more than 2^kLazyRescale, so probabilities stay below that factor
+        // and the rescale, which costs a multiply per accumulator register, becomes rare.
+        // (Rows past the end of a ragged block can be fully masked: keep m finite.)
+        const float mxs = fmaxf(mx * scale_log2e, -1e30f);
+        if (__any(mxs > m[nb] + kLazyRescale)) {
+          const float m_new = fmaxf(m[nb], mxs);
           const float corr = fast_exp2(m[nb] - m_new);
           lsum[nb] *= corr;
           if (WITH_O) {
@@ -254,19 +282,25 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_bf16_kernel(
       }
       // ---- O^T += V^T P^T
       if (WITH_O) {
+        // fragment i = (kb, tt, db): the head-dimension block is the fastest index, so that
+        // consecutive matrix instructions go to different accumulators (a dependent
+        // back-to-back pair costs 48 instead of 32 cycles).
+        constexpr int NF = DB * 4;
+        uint4 fr[NF];
+        auto vfrag = [&](int i) {
+          const int d = (i % DB) * 32 + l32;
+          return *reinterpret_cast<const uint4*>(vt[buf] + d * 128 + ((((i / DB) * 2 + h) ^ vt_swizzle(d)) << 4));
+        };
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const int d = db * 32 + l32;
-          const char* vrow = vt[buf] + d * 128;
-          const int sw = vt_swizzle(d);
+        for (int i = 0; i < kPrefetch && i < NF; ++i) fr[i] = vfrag(i);
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
+        for (int i = 0; i < NF; ++i) {
+          if (i + kPrefetch < NF) fr[i + kPrefetch] = vfrag(i + kPrefetch);
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-              const uint4 a = *reinterpret_cast<const uint4*>(vrow + (((4 * kb + 2 * tt + h) ^ sw) << 4));
-#pragma unroll
-              for (int nb = 0; nb < NB; ++nb) oacc[nb][db] = mfma_bf16(a, pf[nb][kb][tt], oacc[nb][db]);
-            }
+          for (int nb = 0; nb < NB; ++nb)
+            oacc[nb][i % DB] = mfma_bf16(fr[i], pf[nb][(i / DB) >> 1][(i / DB) & 1], oacc[nb][i % DB]);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
         }
       }
     }
@@ -393,7 +427,7 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
 template <int D>
 void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
                 hipStream_t st) {
-  constexpr int NB = 1;
+  constexpr int NB = A2SF_FWD_NB;
   constexpr int BM = kWaves * 32 * NB;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const int nqb = (n + BM - 1) / BM;
