@@ -333,6 +333,241 @@ __global__ __launch_bounds__(kThreads, A2SF_FWD_OCC) void attn_fwd_bf16_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// d = 128 variant built on two gfx950 features:
+//  * K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per
+//    lane, a wave fills 1 KB = 4 rows per instruction; lane l's data lands at base + 16 l,
+//    so the swizzle is applied by choosing which global chunk each lane fetches).  No
+//    staging registers, no LDS store instructions.
+//  * V stays row-major [key][d] in LDS; the V^T operand of O^T = V^T P^T is read with
+//    ds_read_b64_tr_b16, which transposes 4x4 blocks of 16-bit elements across the 16
+//    lanes of a group: output lane i, element r  <-  source lane 4r + i/4, element i%4.
+//    Source lane (r, q) therefore points at V[key_r][d0 + 4q ..+3] and output lane i
+//    receives V[key_0..3][d0 + i]: exactly the 4 consecutive keys of one half operand.
+// Same mathematics and operand conventions as attn_fwd_bf16_kernel above.
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+
+__device__ __forceinline__ uint2 lds_read_tr16(const lds_char* p) {
+  v4i16_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) v4i16_t*)p);
+  return __builtin_bit_cast(uint2, r);
+}
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_read16(const lds_char* p) {
+  const u32x4_t r = *reinterpret_cast<const __attribute__((address_space(3))) u32x4_t*>(p);
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+
+constexpr int kTileBytes = kTile * 256;  // one 64-row tile of 128 bf16
+
+// Chunk swizzles (16-byte chunks of a 256-byte row).  K is read 16 rows x one chunk column
+// at a time; V is read 4 rows x two chunk columns x two halves at a time.
+__device__ __forceinline__ int k_swizzle(int row) { return row & 15; }
+__device__ __forceinline__ int v_swizzle(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+template <bool V_LAYOUT>
+__device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ Mg, int row0, int n,
+                                         lds_char* tile) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int rr = lane >> 4, pc = lane & 15;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int lrow = (u * 4 + wave) * 4 + rr;
+    const int c = pc ^ (V_LAYOUT ? v_swizzle(lrow) : k_swizzle(lrow));
+    int r = row0 + lrow;
+    r = r < n ? r : n - 1;
+    __builtin_amdgcn_global_load_lds((const void*)(Mg + (size_t)r * 128 + c * 8),
+                                     (__attribute__((address_space(3))) void*)(tile + (u * 4 + wave) * 1024),
+                                     16, 0, 0);
+  }
+}
+
+template <bool WITH_O>
+__global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+  constexpr int D = 128, BM = kWaves * 32, KK = D / 16, DB = D / 32;
+  // [buffer][K tile | V tile]
+  __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+  lds_char* const lds = (lds_char*)smem;
+
+  const long long total = (long long)G * nqb;
+  const long long vid = xcd_contiguous_id(total);
+  if (vid >= total) return;
+  const int g = (int)(vid / nqb);
+  const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * n * D;
+  const bf16_t* Vg = V + (size_t)g * n * D;
+  const int row0 = qb * BM;
+  const int wrow0 = row0 + wave * 32;
+
+  uint4 qf[KK];
+  {
+    int r = wrow0 + l32;
+    r = r < n ? r : n - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = load16(Qg + (size_t)r * D + kk * 16 + h * 8);
+  }
+  // per-lane LDS byte offsets inside a K / V tile
+  int koff[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) koff[kk] = l32 * 256 + (((2 * kk + h) ^ k_swizzle(l32)) << 4);
+  int voff[DB];
+  {
+    const int i = lane & 15, r = i >> 2, qd = i & 3, gq = (lane >> 4) & 1;
+    const int cl = 2 * gq + (qd >> 1), vs = (r << 1) | h;  // vs = v_swizzle(key): key%4 = r, (key/4)%2 = h
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      voff[db] = (4 * h + r) * 256 + ((((4 * db + cl) ^ vs)) << 4) + (qd & 1) * 8;
+  }
+
+  f32x16 oacc[DB];
+  float m = -INFINITY, lsum = 0.f;
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+
+  const int last_row = min(n, row0 + BM) - 1;
+  const int ntiles = last_row / kTile + 1;
+  dma_tile<false>(Kg, 0, n, lds);
+  if (WITH_O) dma_tile<true>(Vg, 0, n, lds + kTileBytes);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  auto tile_step = [&](int t, const lds_char* kt, const lds_char* vt_) {
+    const int key0 = t * kTile;
+    if (key0 > wrow0 + 31) return;  // no key of the tile is visible to this wave
+    f32x16 sacc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+    {
+      constexpr int NF = 2 * KK;  // fragment i = (kk, kb)
+      uint4 fr[NF];
+#pragma unroll
+      for (int i = 0; i < kPrefetch; ++i) fr[i] = lds_read16(kt + (i & 1) * 32 * 256 + koff[i >> 1]);
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        if (i + kPrefetch < NF)
+          fr[i + kPrefetch] = lds_read16(kt + ((i + kPrefetch) & 1) * 32 * 256 + koff[(i + kPrefetch) >> 1]);
+        sacc[i & 1] = mfma_bf16(fr[i], qf[i >> 1], sacc[i & 1]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+    }
+    if (key0 + kTile - 1 > wrow0) {  // tile reaches past the wave's first row: causal mask
+      const int qrow = wrow0 + l32;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+          if (key > qrow) sacc[kb][i] = -INFINITY;
+        }
+    }
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mxs = fmaxf(mx * scale_log2e, -1e30f);
+    if (__any(mxs > m + kLazyRescale)) {  // see attn_fwd_bf16_kernel
+      const float m_new = fmaxf(m, mxs);
+      const float corr = fast_exp2(m - m_new);
+      lsum *= corr;
+      if (WITH_O) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[db][i] *= corr;
+      }
+      m = m_new;
+    }
+    uint4 pf[2][2];
+    float rs = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float p[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = fast_exp2(fmaf(sacc[kb][i], scale_log2e, -m));
+        rs += p[i];
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt)
+        pf[kb][tt] = make_uint4(pack_bf16(p[8 * tt + 0], p[8 * tt + 1]), pack_bf16(p[8 * tt + 2], p[8 * tt + 3]),
+                                pack_bf16(p[8 * tt + 4], p[8 * tt + 5]), pack_bf16(p[8 * tt + 6], p[8 * tt + 7]));
+    }
+    lsum += rs;
+    if (WITH_O) {
+      constexpr int NF = DB * 4;  // fragment i = (kb, tt, db), db fastest
+      uint2 lo[NF], hi[NF];
+      auto vread = [&](int i, uint2& a, uint2& b) {
+        const lds_char* p = vt_ + ((i / DB) * 16) * 256 + voff[i % DB];
+        a = lds_read_tr16(p);
+        b = lds_read_tr16(p + 8 * 256);
+      };
+#pragma unroll
+      for (int i = 0; i < kPrefetch; ++i) vread(i, lo[i], hi[i]);
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        if (i + kPrefetch < NF) vread(i + kPrefetch, lo[i + kPrefetch], hi[i + kPrefetch]);
+        const uint4 a = make_uint4(lo[i].x, lo[i].y, hi[i].x, hi[i].y);
+        oacc[i % DB] = mfma_bf16(a, pf[(i / DB) >> 1][(i / DB) & 1], oacc[i % DB]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+    }
+  };
+
+  for (int t = 0; t < ntiles; t += 2) {
+    // even tile in buffer 0, odd tile in buffer 1: all LDS offsets are immediates
+    if (t + 1 < ntiles) {
+      dma_tile<false>(Kg, (t + 1) * kTile, n, lds + 2 * kTileBytes);
+      if (WITH_O) dma_tile<true>(Vg, (t + 1) * kTile, n, lds + 3 * kTileBytes);
+    }
+    tile_step(t, lds, lds + kTileBytes);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (t + 1 >= ntiles) break;
+    if (t + 2 < ntiles) {
+      dma_tile<false>(Kg, (t + 2) * kTile, n, lds);
+      if (WITH_O) dma_tile<true>(Vg, (t + 2) * kTile, n, lds + kTileBytes);
+    }
+    tile_step(t + 1, lds + 2 * kTileBytes, lds + 3 * kTileBytes);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+
+  const int qrow = wrow0 + l32;
+  const float l = lsum + __shfl_xor(lsum, 32, 64);
+  if (qrow < n) {
+    if (h == 0) LSE2[(size_t)g * n + qrow] = m + log2f(l);
+    if (WITH_O) {
+      const float inv = 1.0f / l;
+      bf16_t* orow = O + ((size_t)g * n + qrow) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          uint2 w;
+          w.x = pack_bf16(oacc[db][4 * i4 + 0] * inv, oacc[db][4 * i4 + 1] * inv);
+          w.y = pack_bf16(oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
+          *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i4 + 4 * h) = w;
+        }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
@@ -433,6 +668,19 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
   const int nqb = (n + BM - 1) / BM;
   const long long total = (long long)G * nqb;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+#ifndef A2SF_FWD_LEGACY
+  if (D == 128 && NB == 1) {
+    if (o)
+      hipLaunchKernelGGL((attn_fwd128_kernel<true>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
+                         G, nqb, scale_log2e);
+    else
+      hipLaunchKernelGGL((attn_fwd128_kernel<false>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
+                         lse2, n, G, nqb, scale_log2e);
+    return;
+  }
+#endif
   if (o)
     hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
                        (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
