@@ -360,10 +360,13 @@ __device__ __forceinline__ uint4 lds_read16(const lds_char* p) {
 
 constexpr int kTileBytes = kTile * 256;  // one 64-row tile of 128 bf16
 
-// Chunk swizzles (16-byte chunks of a 256-byte row).  K is read 16 rows x one chunk column
-// at a time; V is read 4 rows x two chunk columns x two halves at a time.
+// Chunk swizzles (16-byte chunks of a 256-byte row; the LDS has 64 four-byte banks).  K is
+// read 16 rows x one chunk column per 16 lanes: XOR with the row spreads them over all 16
+// chunk positions.  V is read by 32 lanes as 4 rows x 4 chunk columns x 2 halves: XOR with
+// 4*(row%4) sends the four rows to disjoint groups of four chunk positions.  Both measure
+// zero LDS bank conflicts (SQ_LDS_BANK_CONFLICT).
 __device__ __forceinline__ int k_swizzle(int row) { return row & 15; }
-__device__ __forceinline__ int v_swizzle(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+__device__ __forceinline__ int v_swizzle(int row) { return (row & 3) << 2; }
 
 template <bool V_LAYOUT>
 __device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ Mg, int row0, int n,
@@ -381,6 +384,30 @@ __device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ Mg, int row0
                                      (__attribute__((address_space(3))) void*)(tile + (u * 4 + wave) * 1024),
                                      16, 0, 0);
   }
+}
+
+// Same as dma_tile for a tile that lies completely inside the matrix: the per-lane byte
+// offsets `loff` (row-in-tile and swizzled chunk) are loop invariants, the tile base is
+// wave-uniform, so a tile costs four load instructions and no address arithmetic per lane.
+template <bool V_LAYOUT>
+__device__ __forceinline__ void dma_offsets(int (&loff)[4]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rr = lane >> 4, pc = lane & 15;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int lrow = (u * 4 + wave) * 4 + rr;
+    loff[u] = lrow * 256 + ((pc ^ (V_LAYOUT ? v_swizzle(lrow) : k_swizzle(lrow))) << 4);
+  }
+}
+__device__ __forceinline__ void dma_full_tile(const bf16_t* __restrict__ Mg, int row0,
+                                              const int (&loff)[4], lds_char* tile) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const char* base = reinterpret_cast<const char*>(Mg) + (size_t)row0 * 256;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    __builtin_amdgcn_global_load_lds((const void*)(base + loff[u]),
+                                     (__attribute__((address_space(3))) void*)(tile + (u * 4 + wave) * 1024),
+                                     16, 0, 0);
 }
 
 template <bool WITH_O>
@@ -420,7 +447,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
   int voff[DB];
   {
     const int i = lane & 15, r = i >> 2, qd = i & 3, gq = (lane >> 4) & 1;
-    const int cl = 2 * gq + (qd >> 1), vs = (r << 1) | h;  // vs = v_swizzle(key): key%4 = r, (key/4)%2 = h
+    const int cl = 2 * gq + (qd >> 1), vs = v_swizzle(4 * h + r);  // key = 8*x + 4h + r
 #pragma unroll
     for (int db = 0; db < DB; ++db)
       voff[db] = (4 * h + r) * 256 + ((((4 * db + cl) ^ vs)) << 4) + (qd & 1) * 8;
@@ -435,8 +462,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
 
   const int last_row = min(n, row0 + BM) - 1;
   const int ntiles = last_row / kTile + 1;
-  dma_tile<false>(Kg, 0, n, lds);
-  if (WITH_O) dma_tile<true>(Vg, 0, n, lds + kTileBytes);
+  int k_loff[4], v_loff[4];
+  dma_offsets<false>(k_loff);
+  dma_offsets<true>(v_loff);
+  auto fetch = [&](int t, lds_char* buf) {  // K tile t and V tile t into buf | buf + 16 KB
+    if ((t + 1) * kTile <= n) {
+      dma_full_tile(Kg, t * kTile, k_loff, buf);
+      if (WITH_O) dma_full_tile(Vg, t * kTile, v_loff, buf + kTileBytes);
+    } else {
+      dma_tile<false>(Kg, t * kTile, n, buf);
+      if (WITH_O) dma_tile<true>(Vg, t * kTile, n, buf + kTileBytes);
+    }
+  };
+  fetch(0, lds);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
@@ -530,18 +568,12 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
 
   for (int t = 0; t < ntiles; t += 2) {
     // even tile in buffer 0, odd tile in buffer 1: all LDS offsets are immediates
-    if (t + 1 < ntiles) {
-      dma_tile<false>(Kg, (t + 1) * kTile, n, lds + 2 * kTileBytes);
-      if (WITH_O) dma_tile<true>(Vg, (t + 1) * kTile, n, lds + 3 * kTileBytes);
-    }
+    if (t + 1 < ntiles) fetch(t + 1, lds + 2 * kTileBytes);
     tile_step(t, lds, lds + kTileBytes);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     if (t + 1 >= ntiles) break;
-    if (t + 2 < ntiles) {
-      dma_tile<false>(Kg, (t + 2) * kTile, n, lds);
-      if (WITH_O) dma_tile<true>(Vg, (t + 2) * kTile, n, lds + kTileBytes);
-    }
+    if (t + 2 < ntiles) fetch(t + 2, lds);
     tile_step(t + 1, lds + 2 * kTileBytes, lds + 3 * kTileBytes);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
