@@ -410,11 +410,11 @@ __device__ __forceinline__ void dma_full_tile(const bf16_t* __restrict__ Mg, int
                                      16, 0, 0);
 }
 
-template <bool WITH_O>
-__global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
+template <bool WITH_O, int NB>
+__global__ __launch_bounds__(kThreads, NB == 1 ? 2 : 1) void attn_fwd128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
-  constexpr int D = 128, BM = kWaves * 32, KK = D / 16, DB = D / 32;
+  constexpr int D = 128, BM = kWaves * 32 * NB, KK = D / 16, DB = D / 32;
   // [buffer][K tile | V tile]
   __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
   lds_char* const lds = (lds_char*)smem;
@@ -431,14 +431,16 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
   const bf16_t* Kg = K + (size_t)g * n * D;
   const bf16_t* Vg = V + (size_t)g * n * D;
   const int row0 = qb * BM;
-  const int wrow0 = row0 + wave * 32;
+  const int wrow0 = row0 + wave * 32 * NB;  // first query row of this wave
 
-  uint4 qf[KK];
-  {
-    int r = wrow0 + l32;
+  // Q fragments (B operand): lane (query l32, half h) holds Q[query][16kk + 8h .. +7]
+  uint4 qf[NB][KK];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    int r = wrow0 + nb * 32 + l32;
     r = r < n ? r : n - 1;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) qf[kk] = load16(Qg + (size_t)r * D + kk * 16 + h * 8);
+    for (int kk = 0; kk < KK; ++kk) qf[nb][kk] = load16(Qg + (size_t)r * D + kk * 16 + h * 8);
   }
   // per-lane LDS byte offsets inside a K / V tile
   int koff[KK];
@@ -453,12 +455,17 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
       voff[db] = (4 * h + r) * 256 + ((((4 * db + cl) ^ vs)) << 4) + (qd & 1) * 8;
   }
 
-  f32x16 oacc[DB];
-  float m = -INFINITY, lsum = 0.f;
+  f32x16 oacc[NB][DB];
+  float m[NB], lsum[NB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int nb = 0; nb < NB; ++nb) {
+    m[nb] = -INFINITY;
+    lsum[nb] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[nb][db][i] = 0.f;
+  }
 
   const int last_row = min(n, row0 + BM) - 1;
   const int ntiles = last_row / kTile + 1;
@@ -480,12 +487,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
 
   auto tile_step = [&](int t, const lds_char* kt, const lds_char* vt_) {
     const int key0 = t * kTile;
-    if (key0 > wrow0 + 31) return;  // no key of the tile is visible to this wave
-    f32x16 sacc[2];
+    if (key0 > wrow0 + 32 * NB - 1) return;  // no key of the tile is visible to this wave
+    f32x16 sacc[NB][2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[nb][kb][i] = 0.f;
     {
       constexpr int NF = 2 * KK;  // fragment i = (kk, kb)
       uint4 fr[NF];
@@ -495,56 +504,66 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
       for (int i = 0; i < NF; ++i) {
         if (i + kPrefetch < NF)
           fr[i + kPrefetch] = lds_read16(kt + ((i + kPrefetch) & 1) * 32 * 256 + koff[(i + kPrefetch) >> 1]);
-        sacc[i & 1] = mfma_bf16(fr[i], qf[i >> 1], sacc[i & 1]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) sacc[nb][i & 1] = mfma_bf16(fr[i], qf[nb][i >> 1], sacc[nb][i & 1]);
+      }
+      // keep that order: kPrefetch reads up front, then one new read per fragment's matrix ops
+      __builtin_amdgcn_sched_group_barrier(0x100, kPrefetch, 0);
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+        if (i + kPrefetch < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
     }
-    if (key0 + kTile - 1 > wrow0) {  // tile reaches past the wave's first row: causal mask
-      const int qrow = wrow0 + l32;
+    const bool diag = key0 + kTile - 1 > wrow0;  // tile reaches past the wave's first row
+    uint4 pf[NB][2][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      if (diag) {  // causal mask
+        const int qrow = wrow0 + nb * 32 + l32;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+            if (key > qrow) sacc[nb][kb][i] = -INFINITY;
+          }
+      }
+      float mx = sacc[nb][0][0];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-          if (key > qrow) sacc[kb][i] = -INFINITY;
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mxs = fmaxf(mx * scale_log2e, -1e30f);
+      if (__any(mxs > m[nb] + kLazyRescale)) {  // see attn_fwd_bf16_kernel
+        const float m_new = fmaxf(m[nb], mxs);
+        const float corr = fast_exp2(m[nb] - m_new);
+        lsum[nb] *= corr;
+        if (WITH_O) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[nb][db][i] *= corr;
         }
-    }
-    float mx = sacc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mxs = fmaxf(mx * scale_log2e, -1e30f);
-    if (__any(mxs > m + kLazyRescale)) {  // see attn_fwd_bf16_kernel
-      const float m_new = fmaxf(m, mxs);
-      const float corr = fast_exp2(m - m_new);
-      lsum *= corr;
-      if (WITH_O) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[db][i] *= corr;
+        m[nb] = m_new;
       }
-      m = m_new;
-    }
-    uint4 pf[2][2];
-    float rs = 0.f;
+      float rs = 0.f;
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float p[16];
+      for (int kb = 0; kb < 2; ++kb) {
+        float p[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = fast_exp2(fmaf(sacc[kb][i], scale_log2e, -m));
-        rs += p[i];
+        for (int i = 0; i < 16; ++i) {
+          p[i] = fast_exp2(fmaf(sacc[nb][kb][i], scale_log2e, -m[nb]));
+          rs += p[i];
+        }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+          pf[nb][kb][tt] = make_uint4(pack_bf16(p[8 * tt + 0], p[8 * tt + 1]), pack_bf16(p[8 * tt + 2], p[8 * tt + 3]),
+                                      pack_bf16(p[8 * tt + 4], p[8 * tt + 5]), pack_bf16(p[8 * tt + 6], p[8 * tt + 7]));
       }
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
-        pf[kb][tt] = make_uint4(pack_bf16(p[8 * tt + 0], p[8 * tt + 1]), pack_bf16(p[8 * tt + 2], p[8 * tt + 3]),
-                                pack_bf16(p[8 * tt + 4], p[8 * tt + 5]), pack_bf16(p[8 * tt + 6], p[8 * tt + 7]));
+      lsum[nb] += rs;
     }
-    lsum += rs;
     if (WITH_O) {
       constexpr int NF = DB * 4;  // fragment i = (kb, tt, db), db fastest
       uint2 lo[NF], hi[NF];
@@ -559,9 +578,15 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
       for (int i = 0; i < NF; ++i) {
         if (i + kPrefetch < NF) vread(i + kPrefetch, lo[i + kPrefetch], hi[i + kPrefetch]);
         const uint4 a = make_uint4(lo[i].x, lo[i].y, hi[i].x, hi[i].y);
-        oacc[i % DB] = mfma_bf16(a, pf[(i / DB) >> 1][(i / DB) & 1], oacc[i % DB]);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          oacc[nb][i % DB] = mfma_bf16(a, pf[nb][(i / DB) >> 1][(i / DB) & 1], oacc[nb][i % DB]);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kPrefetch, 0);
+#pragma unroll
+      for (int i = 0; i < NF; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, NB, 0);
+        if (i + kPrefetch < NF) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
     }
   };
@@ -579,22 +604,25 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd128_kernel(
     __syncthreads();
   }
 
-  const int qrow = wrow0 + l32;
-  const float l = lsum + __shfl_xor(lsum, 32, 64);
-  if (qrow < n) {
-    if (h == 0) LSE2[(size_t)g * n + qrow] = m + log2f(l);
-    if (WITH_O) {
-      const float inv = 1.0f / l;
-      bf16_t* orow = O + ((size_t)g * n + qrow) * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+  for (int nb = 0; nb < NB; ++nb) {
+    const int qrow = wrow0 + nb * 32 + l32;
+    const float l = lsum[nb] + __shfl_xor(lsum[nb], 32, 64);
+    if (qrow < n) {
+      if (h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
+      if (WITH_O) {
+        const float inv = 1.0f / l;
+        bf16_t* orow = O + ((size_t)g * n + qrow) * D;
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          uint2 w;
-          w.x = pack_bf16(oacc[db][4 * i4 + 0] * inv, oacc[db][4 * i4 + 1] * inv);
-          w.y = pack_bf16(oacc[db][4 * i4 + 2] * inv, oacc[db][4 * i4 + 3] * inv);
-          *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i4 + 4 * h) = w;
-        }
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            uint2 w;
+            w.x = pack_bf16(oacc[nb][db][4 * i4 + 0] * inv, oacc[nb][db][4 * i4 + 1] * inv);
+            w.y = pack_bf16(oacc[nb][db][4 * i4 + 2] * inv, oacc[nb][db][4 * i4 + 3] * inv);
+            *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i4 + 4 * h) = w;
+          }
+      }
     }
   }
 }
@@ -691,28 +719,34 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   }
 }
 
+#ifndef A2SF_FWD128_NB
+#define A2SF_FWD128_NB 1   // 32-row query blocks per wave of attn_fwd128_kernel
+#endif
+
 template <int D>
 void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
                 hipStream_t st) {
-  constexpr int NB = A2SF_FWD_NB;
-  constexpr int BM = kWaves * 32 * NB;
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  const int nqb = (n + BM - 1) / BM;
-  const long long total = (long long)G * nqb;
-  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-#ifndef A2SF_FWD_LEGACY
-  if (D == 128 && NB == 1) {
+  if (D == 128) {
+    constexpr int NB = A2SF_FWD128_NB;
+    const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
+    const long long total = (long long)G * nqb;
+    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
     if (o)
-      hipLaunchKernelGGL((attn_fwd128_kernel<true>), dim3(grid), dim3(kThreads), 0, st,
+      hipLaunchKernelGGL((attn_fwd128_kernel<true, NB>), dim3(grid), dim3(kThreads), 0, st,
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
                          G, nqb, scale_log2e);
     else
-      hipLaunchKernelGGL((attn_fwd128_kernel<false>), dim3(grid), dim3(kThreads), 0, st,
+      hipLaunchKernelGGL((attn_fwd128_kernel<false, NB>), dim3(grid), dim3(kThreads), 0, st,
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
                          lse2, n, G, nqb, scale_log2e);
     return;
   }
-#endif
+  constexpr int NB = A2SF_FWD_NB;
+  constexpr int BM = kWaves * 32 * NB;
+  const int nqb = (n + BM - 1) / BM;
+  const long long total = (long long)G * nqb;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
   if (o)
     hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
                        (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
