@@ -757,12 +757,120 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
                        lse2, n, G, nqb, scale_log2e);
 }
 
+// ---------------------------------------------------------------------------------------
+// col_scores for a short row window (alpha well below 1), d = 128.  Only rows >= first_row
+// contribute (see first_contributing_row), at most kTailTiles tiles of 64 rows.  One
+// workgroup per head stages those Q rows in LDS once (direct global-to-LDS loads) and then
+// walks over all key blocks of the head: a wave keeps 32 keys as A fragments in registers
+// (the next block's fragments are fetched while the current block is computed), recomputes
+// the logit tiles against the staged Q rows, applies exp2(s - lse_i + (n-1-i) log2 alpha) and
+// sums down the rows.  K is read exactly once, Q's window once per head.
+constexpr int kTailTiles = 4;
+
+__global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
+    float* __restrict__ S, int n, int first_row, float log2_alpha, float scale_log2e) {
+  constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
+  __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
+  lds_char* const qs = (lds_char*)smem;
+
+  const int g = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * n * D;
+  const float* lse = LSE2 + (size_t)g * n;
+  float* Sg = S + (size_t)g * n;
+
+  const int r_lo = (first_row / kTile) * kTile;          // first staged row
+  const int ntile = (n - r_lo + kTile - 1) / kTile;      // <= kTailTiles (checked by the host)
+#pragma unroll
+  for (int tt = 0; tt < kTailTiles; ++tt)
+    if (tt < ntile) dma_tile<false>(Qg, r_lo + tt * kTile, n, qs + tt * kTileBytes);
+
+  int qoff[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qoff[kk] = l32 * 256 + (((2 * kk + h) ^ k_swizzle(l32)) << 4);
+  // exponent offset of this lane's row in each 32-row block: lse_i - (n-1-i) log2 alpha;
+  // +inf (probability 0) for rows past the end or before the window
+  float bias[2 * kTailTiles];
+#pragma unroll
+  for (int rb = 0; rb < 2 * kTailTiles; ++rb) {
+    const int r = r_lo + rb * 32 + l32;
+    bias[rb] = (r < n && r >= first_row) ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+  }
+  auto load_keys = [&](int c0, uint4 (&kf)[KK]) {
+    int r = c0 + wave * 32 + l32;
+    r = r < n ? r : n - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+  };
+  uint4 kf0[KK], kf1[KK];
+  load_keys(0, kf0);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  auto block = [&](int c0, const uint4 (&kf)[KK]) {
+    const int wc0 = c0 + wave * 32;
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int rb = 0; rb < 2 * kTailTiles; ++rb) {
+      const int rr0 = r_lo + rb * 32;
+      if (rb < 2 * ntile && rr0 + 31 >= wc0 && rr0 + 31 >= first_row) {  // wave-uniform
+        f32x16 sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+        const lds_char* qt = qs + rb * 32 * 256;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) sacc = mfma_bf16(kf[kk], lds_read16(qt + qoff[kk]), sacc);
+        const int r = rr0 + l32;
+        if (wc0 + 31 > rr0) {  // block touches the diagonal: keys above the row contribute 0
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            const float p = fast_exp2(fmaf(sacc[i], scale_log2e, -bias[rb]));
+            acc[i] += key > r ? 0.f : p;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[i] += fast_exp2(fmaf(sacc[i], scale_log2e, -bias[rb]));
+        }
+      }
+    }
+    // sum over the 32 rows held by the lanes of one half
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = group_sum<32>(acc[i]);
+    if (l32 == 0) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
+        if (key < n) Sg[key] = acc[i];
+      }
+    }
+  };
+
+  for (int c0 = 0; c0 < n; c0 += 2 * BC) {
+    if (c0 + BC < n) load_keys(c0 + BC, kf1);
+    block(c0, kf0);
+    if (c0 + BC >= n) break;
+    if (c0 + 2 * BC < n) load_keys(c0 + 2 * BC, kf0);
+    block(c0 + BC, kf1);
+  }
+}
+
 template <int D>
 void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, float alpha,
                  float* scores, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   float l2a;
   const int first = first_contributing_row(n, alpha, &l2a);
+  if (D == 128 && n - (first / kTile) * kTile <= kTailTiles * kTile) {
+    hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
+                       (const bf16_t*)k, lse2, scores, n, first, l2a, scale_log2e);
+    return;
+  }
   const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
   const long long total = (long long)G * ncb;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
