@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-o", action="store_true", help="prompt phase without attention outputs")
     ap.add_argument("--mode", choices=["fast", "stable"], default="fast")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (every head is an independent problem; "
@@ -180,6 +182,13 @@ def main():
         if ev:
             ev[2].record()
 
+    if args.copy_calibration:   # a copy kernel of known size for the counter runs
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
