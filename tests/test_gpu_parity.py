@@ -129,6 +129,24 @@ def test_small_bf16_ragged(alpha, d, n, say):
     run_lockstep(w, alpha, say=say)
 
 
+@pytest.mark.parametrize("base,d,n", [(1, 128, 300), (1, 64, 200), (0, 64, 130)])
+def test_prefill_optional_outputs(base, d, n):
+    """o = NULL (no P*V work) and scores_full = NULL (scores kept in the workspace) must leave
+    exactly the same cache as the call that returns both."""
+    w = variant(base, heads=6, d=d, n=n, T=1, select=11, recent=9, name="optional outputs")
+    p = parity.Problem(w)
+    p.gpu_prefill(0.4)
+    torch.cuda.synchronize()
+    full = p.cache.snapshot()
+    for want_o, want_s in ((False, True), (True, False), (False, False)):
+        for t in p.cache.tensors():
+            t.zero_()
+        p.gpu_prefill(0.4, want_o=want_o, want_scores=want_s)
+        torch.cuda.synchronize()
+        for a, b in zip(full, p.cache.tensors()):
+            assert torch.equal(a, b), (want_o, want_s)
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_small_fp32(d, say):
     w = variant(0, heads=3, d=d, n=150, T=5, select=9, recent=4, name=f"f32 d{d}")
