@@ -128,6 +128,24 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
                              int32_t mode, void* o, void* workspace, size_t workspace_bytes,
                              void* hip_stream);
 
+/* The same two calls with one forgetting factor per head (Section 6 of the paper names a
+ * distinct factor per layer and head as the way to lift its limitation of a single one).
+ *   alpha_heads  [G] fp32, device: head g uses alpha_heads[g], each in [0, 1].
+ *   alpha_max    (prefill only) an upper bound of alpha_heads, checked like alpha; it sizes
+ *                the row window of the score pass.  A head whose factor exceeds it gets
+ *                scores that miss the rows outside that window.
+ * Everything else as in a2sf_prefill / a2sf_decode_step. */
+a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void* v, int32_t n,
+                                        const float* alpha_heads, float alpha_max,
+                                        a2sf_budget budget, const a2sf_cache* cache, void* o,
+                                        float* scores_full, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream);
+a2sf_status a2sf_decode_step_alpha_per_head(const void* q, const void* k_new, const void* v_new,
+                                            int32_t t_pos, const a2sf_cache* cache,
+                                            const float* alpha_heads, a2sf_budget budget,
+                                            int32_t mode, void* o, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream);
+
 /* Selection alone (Section 2.2, Section 4.1): which of the L tokens of each head survive.
  *   scores    [G, stride] fp32 (no NaN);  pos [G, stride] int32 or NULL (position = slot).
  *   len       [G] device, valid slots per head (<= L), or NULL: every head has L.

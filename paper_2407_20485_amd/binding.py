@@ -21,7 +21,8 @@ A2SF_EVICT_FAST, A2SF_EVICT_STABLE = 0, 1
 A2SF_MAX_CAPACITY = 12288
 
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",
-           "a2sf_compact", "a2sf_status_string")
+           "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
+           "a2sf_decode_step_alpha_per_head")
 
 
 class Budget(ctypes.Structure):
@@ -55,6 +56,12 @@ def lib() -> ctypes.CDLL:
         L.a2sf_decode_step.restype = i32
         L.a2sf_decode_step.argtypes = [vp, vp, vp, i32, ctypes.POINTER(CacheStruct), f32, Budget, i32,
                                        vp, vp, sz, vp]
+        L.a2sf_prefill_alpha_per_head.restype = i32
+        L.a2sf_prefill_alpha_per_head.argtypes = [vp, vp, vp, i32, vp, f32, Budget,
+                                                  ctypes.POINTER(CacheStruct), vp, vp, vp, sz, vp]
+        L.a2sf_decode_step_alpha_per_head.restype = i32
+        L.a2sf_decode_step_alpha_per_head.argtypes = [vp, vp, vp, i32, ctypes.POINTER(CacheStruct), vp,
+                                                      Budget, i32, vp, vp, sz, vp]
         L.a2sf_select.restype = i32
         L.a2sf_select.argtypes = [vp, vp, vp, i32, i32, i32, Budget, vp, vp, vp]
         L.a2sf_compact.restype = i32
@@ -155,6 +162,29 @@ def a2sf_decode_step(q, k_new, v_new, t_pos, cache, alpha, select, recent, o,
     _check(lib().a2sf_decode_step(_ptr(q), _ptr(k_new), _ptr(v_new), t_pos, ctypes.byref(cs), alpha,
                                   Budget(select, recent), mode, _ptr(o), _ptr(workspace),
                                   workspace_bytes, _stream(stream)))
+
+
+def a2sf_prefill_alpha_per_head(q, k, v, n, alpha_heads, alpha_max, select, recent, cache, o=None,
+                                scores_full=None, workspace=None, workspace_bytes=None, stream=None):
+    cs = _cache_struct(cache)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().a2sf_prefill_alpha_per_head(_ptr(q), _ptr(k), _ptr(v), n, _ptr(alpha_heads), alpha_max,
+                                             Budget(select, recent), ctypes.byref(cs), _ptr(o),
+                                             _ptr(scores_full), _ptr(workspace), workspace_bytes,
+                                             _stream(stream)))
+
+
+def a2sf_decode_step_alpha_per_head(q, k_new, v_new, t_pos, cache, alpha_heads, select, recent, o,
+                                    mode=A2SF_EVICT_FAST, workspace=None, workspace_bytes=None,
+                                    stream=None):
+    cs = _cache_struct(cache)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().a2sf_decode_step_alpha_per_head(_ptr(q), _ptr(k_new), _ptr(v_new), t_pos,
+                                                 ctypes.byref(cs), _ptr(alpha_heads),
+                                                 Budget(select, recent), mode, _ptr(o), _ptr(workspace),
+                                                 workspace_bytes, _stream(stream)))
 
 
 def a2sf_select(scores, pos, length, G, L, stride, select, recent, keep_idx, n_keep, stream=None):

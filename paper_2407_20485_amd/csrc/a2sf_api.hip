@@ -59,22 +59,9 @@ inline a2sf_status launch_status() {
   return hipGetLastError() == hipSuccess ? A2SF_OK : A2SF_EHIP;
 }
 
-}  // namespace
-
-extern "C" {
-
-size_t a2sf_workspace_bytes(int32_t G, int32_t n_max, int32_t capacity, int32_t d, int32_t dtype,
-                            a2sf_budget budget) {
-  if (G < 1 || n_max < 0 || capacity < 0 || (d != 64 && d != 128)) return 0;
-  if (dtype != A2SF_F32 && dtype != A2SF_BF16) return 0;
-  if (check_budget(budget) != A2SF_OK) return 0;
-  if (capacity > A2SF_MAX_CAPACITY) return 0;
-  return ws_layout(G, n_max, capacity, d, budget).total;
-}
-
-a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n, float alpha,
-                         a2sf_budget budget, const a2sf_cache* cache, void* o,
-                         float* scores_full, void* workspace, size_t workspace_bytes,
+a2sf_status prefill_impl(const void* q, const void* k, const void* v, int32_t n, float alpha,
+                         const float* alpha_heads, a2sf_budget budget, const a2sf_cache* cache,
+                         void* o, float* scores_full, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
   a2sf_status s;
   if ((s = check_budget(budget)) != A2SF_OK) return s;
@@ -99,20 +86,20 @@ a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n,
 
   if (cache->dtype == A2SF_F32) {
     launch_prefill_f32((const float*)q, (const float*)k, (const float*)v, G, n, d, (float*)o, lse2, st);
-    launch_scores_f32((const float*)q, (const float*)k, lse2, G, n, d, alpha, s_full, st);
+    launch_scores_f32((const float*)q, (const float*)k, lse2, G, n, d, alpha, alpha_heads, s_full, st);
   } else {
     launch_prefill_bf16(q, k, v, G, n, d, o, lse2, st);
-    launch_scores_bf16(q, k, lse2, G, n, d, alpha, s_full, st);
+    launch_scores_bf16(q, k, lse2, G, n, d, alpha, alpha_heads, s_full, st);
   }
   launch_select(s_full, nullptr, nullptr, G, n, n, budget.select, budget.recent, keep_idx, n_keep, st);
   launch_gather_prompt(k, v, s_full, n, keep_idx, B, n_keep, *cache, st);
   return launch_status();
 }
 
-a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
-                             const a2sf_cache* cache, float alpha, a2sf_budget budget,
-                             int32_t mode, void* o, void* workspace, size_t workspace_bytes,
-                             void* hip_stream) {
+a2sf_status decode_impl(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                        const a2sf_cache* cache, float alpha, const float* alpha_heads,
+                        a2sf_budget budget, int32_t mode, void* o, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
   a2sf_status s;
   if ((s = check_budget(budget)) != A2SF_OK) return s;
   if ((s = check_alpha(alpha)) != A2SF_OK) return s;
@@ -129,7 +116,7 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
 
   hipStream_t st = (hipStream_t)hip_stream;
   char* ws = (char*)workspace;
-  launch_decode(q, k_new, v_new, t_pos, *cache, alpha, budget.select, budget.recent,
+  launch_decode(q, k_new, v_new, t_pos, *cache, alpha, alpha_heads, budget.select, budget.recent,
                 mode == A2SF_EVICT_FAST, o, ws ? ws + w.split : nullptr, plan, st);
   if (mode == A2SF_EVICT_STABLE) {
     int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
@@ -139,6 +126,55 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
     launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
   }
   return launch_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t a2sf_workspace_bytes(int32_t G, int32_t n_max, int32_t capacity, int32_t d, int32_t dtype,
+                            a2sf_budget budget) {
+  if (G < 1 || n_max < 0 || capacity < 0 || (d != 64 && d != 128)) return 0;
+  if (dtype != A2SF_F32 && dtype != A2SF_BF16) return 0;
+  if (check_budget(budget) != A2SF_OK) return 0;
+  if (capacity > A2SF_MAX_CAPACITY) return 0;
+  return ws_layout(G, n_max, capacity, d, budget).total;
+}
+
+a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n, float alpha,
+                         a2sf_budget budget, const a2sf_cache* cache, void* o,
+                         float* scores_full, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  return prefill_impl(q, k, v, n, alpha, nullptr, budget, cache, o, scores_full, workspace,
+                      workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void* v, int32_t n,
+                                        const float* alpha_heads, float alpha_max,
+                                        a2sf_budget budget, const a2sf_cache* cache, void* o,
+                                        float* scores_full, void* workspace,
+                                        size_t workspace_bytes, void* hip_stream) {
+  if (!alpha_heads || ((uintptr_t)alpha_heads & 3u)) return A2SF_EINVAL;
+  return prefill_impl(q, k, v, n, alpha_max, alpha_heads, budget, cache, o, scores_full, workspace,
+                      workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                             const a2sf_cache* cache, float alpha, a2sf_budget budget,
+                             int32_t mode, void* o, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  return decode_impl(q, k_new, v_new, t_pos, cache, alpha, nullptr, budget, mode, o, workspace,
+                     workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_decode_step_alpha_per_head(const void* q, const void* k_new, const void* v_new,
+                                            int32_t t_pos, const a2sf_cache* cache,
+                                            const float* alpha_heads, a2sf_budget budget,
+                                            int32_t mode, void* o, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  if (!alpha_heads || ((uintptr_t)alpha_heads & 3u)) return A2SF_EINVAL;
+  return decode_impl(q, k_new, v_new, t_pos, cache, 1.0f, alpha_heads, budget, mode, o, workspace,
+                     workspace_bytes, hip_stream);
 }
 
 a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* len, int32_t G,

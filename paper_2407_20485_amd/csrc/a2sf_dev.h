@@ -143,6 +143,22 @@ __device__ __forceinline__ unsigned long long block_min_u64(unsigned long long v
   return a < b ? a : b;
 }
 
+// Row window and exponent slope of one head's forgotten score (Section 3.3 Eq.5): rows before
+// `first_row` have a weight alpha^(n-1-i) below the smallest fp32 subnormal and add exactly 0.
+// With alpha_heads the head's own factor narrows the window the host sized for the bound.
+__device__ __forceinline__ void head_window(const float* alpha_heads, int g, int n, int& first_row,
+                                            float& log2_alpha) {
+  if (!alpha_heads) return;  // host values apply to every head
+  const float a = alpha_heads[g];
+  if (!(a > 0.f)) { first_row = n - 1; log2_alpha = 0.f; return; }
+  if (!(a < 1.f)) { log2_alpha = 0.f; return; }
+  const float l2 = log2f(a);
+  log2_alpha = l2;
+  const float rows = 160.0f / (-l2);
+  const int own = rows >= (float)n ? 0 : n - ((int)rows + 1);
+  first_row = own > first_row ? own : first_row;
+}
+
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ void store16(void* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
 

@@ -29,19 +29,22 @@ struct DecodePlan {
 };
 DecodePlan plan_decode(int G, int capacity, int d);
 void launch_decode(const void* q, const void* k_new, const void* v_new, int t_pos,
-                   const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
-                   void* o, void* ws, const DecodePlan& plan, hipStream_t st);
+                   const a2sf_cache& c, float alpha, const float* alpha_heads, int select,
+                   int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
+                   hipStream_t st);
 
 // prefill_f32.hip / prefill_bf16.hip
 // lse2[g][i] = log2(sum_j exp(s_ij)) of the masked row i (s already scaled by 1/sqrt(d)).
 void launch_prefill_f32(const float* q, const float* k, const float* v, int G, int n, int d,
                         float* o, float* lse2, hipStream_t st);
+// alpha_heads (device [G]) may be null: then every head uses `alpha`; otherwise `alpha` is an
+// upper bound of the per-head factors.
 void launch_scores_f32(const float* q, const float* k, const float* lse2, int G, int n, int d,
-                       float alpha, float* scores, hipStream_t st);
+                       float alpha, const float* alpha_heads, float* scores, hipStream_t st);
 void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
                          void* o, float* lse2, hipStream_t st);
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
-                        float alpha, float* scores, hipStream_t st);
+                        float alpha, const float* alpha_heads, float* scores, hipStream_t st);
 
 // Rows i < first_row contribute exactly 0 to every fp32 score (their weight alpha^(n-1-i)
 // is below the smallest fp32 subnormal while P <= 1), so the score kernels skip them.

@@ -297,12 +297,14 @@ constexpr int kWaveUnroll = 8;   // loads in flight per lane, wave-per-head kern
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
     const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
-    T* K, T* V, float* S, int32_t* P, int32_t* len, int capacity, float alpha, int select,
-    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int capacity, float alpha,
+    const float* __restrict__ alpha_heads, int select, int recent, int evict_here,
+    T* __restrict__ o, float scale_log2e) {
   extern __shared__ float a[];  // [capacity]
   __shared__ StepSmem sm;
   __shared__ float part[kWaves][128];
   const int g = blockIdx.x, tid = threadIdx.x;
+  if (alpha_heads) alpha = alpha_heads[g];
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;  // precondition len+1 <= capacity violated
   const int L = n_old + 1;
@@ -348,8 +350,9 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
 template <typename T, int D, int NJ>
 __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
     const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
-    T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha, int select,
-    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha,
+    const float* __restrict__ alpha_heads, int select, int recent, int evict_here,
+    T* __restrict__ o, float scale_log2e) {
   using Gm = RowGeom<T, D>;
   using Grp = WaveGroup;
   __shared__ float zs[kWaves][NJ * 64];
@@ -360,6 +363,7 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;
   const int L = n_old + 1;
+  if (alpha_heads) alpha = alpha_heads[g];
   float* z = zs[wave];
   StepSmem& sm = sms[wave];
   T* Kg = K + (size_t)g * capacity * D;
@@ -539,11 +543,13 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
     const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos, T* K, T* V, float* S,
     int32_t* P, int32_t* len, int capacity, int nsplit, const float* __restrict__ zbuf,
-    const float* __restrict__ ml, const float* __restrict__ po, float alpha, int select,
-    int recent, int evict_here, T* __restrict__ o) {
+    const float* __restrict__ ml, const float* __restrict__ po, float alpha,
+    const float* __restrict__ alpha_heads, int select, int recent, int evict_here,
+    T* __restrict__ o) {
   extern __shared__ float a[];  // [capacity]
   __shared__ StepSmem sm;
   const int g = blockIdx.x, tid = threadIdx.x;
+  if (alpha_heads) alpha = alpha_heads[g];
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;
   const int L = n_old + 1;
@@ -569,16 +575,17 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
 
 template <typename T, int D>
 void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos,
-                  const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
-                  void* o, void* ws, const DecodePlan& plan, hipStream_t st) {
+                  const a2sf_cache& c, float alpha, const float* alpha_heads, int select,
+                  int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
+                  hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   if (plan.nsplit <= 1 && plan.wave_slots > 0) {
     const dim3 grid((c.G + kWaves - 1) / kWaves);
 #define A2SF_WAVE(NJ)                                                                            \
   hipLaunchKernelGGL((decode_wave_kernel<T, D, NJ>), grid, dim3(kThreads), 0, st, (const T*)q,   \
                      (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, \
-                     c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o,      \
-                     scale_log2e)
+                     c.len, c.G, c.capacity, alpha, alpha_heads, select, recent, (int)evict_here, \
+                     (T*)o, scale_log2e)
     if (plan.wave_slots == 2) A2SF_WAVE(2);
     else if (plan.wave_slots == 4) A2SF_WAVE(4);
     else A2SF_WAVE(8);
@@ -589,7 +596,8 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
     hipLaunchKernelGGL((decode_fused_kernel<T, D>), dim3(c.G), dim3(kThreads),
                        (size_t)c.capacity * sizeof(float), st, (const T*)q, (const T*)k_new,
                        (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
-                       c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+                       c.capacity, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o,
+                       scale_log2e);
     return;
   }
   float* zbuf = (float*)ws;
@@ -603,7 +611,7 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(c.G), dim3(kThreads),
                      (size_t)c.capacity * sizeof(float), st, (const T*)k_new, (const T*)v_new,
                      t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len, c.capacity, plan.nsplit,
-                     zbuf, ml, po, alpha, select, recent, (int)evict_here, (T*)o);
+                     zbuf, ml, po, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o);
 }
 
 }  // namespace
@@ -631,14 +639,15 @@ DecodePlan plan_decode(int G, int capacity, int d) {
 }
 
 void launch_decode(const void* q, const void* k_new, const void* v_new, int t_pos,
-                   const a2sf_cache& c, float alpha, int select, int recent, bool evict_here,
-                   void* o, void* ws, const DecodePlan& plan, hipStream_t st) {
+                   const a2sf_cache& c, float alpha, const float* alpha_heads, int select,
+                   int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
+                   hipStream_t st) {
   if (c.dtype == A2SF_F32) {
-    if (c.d == 64) launch_typed<float, 64>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
-    else launch_typed<float, 128>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+    if (c.d == 64) launch_typed<float, 64>(q, k_new, v_new, t_pos, c, alpha, alpha_heads, select, recent, evict_here, o, ws, plan, st);
+    else launch_typed<float, 128>(q, k_new, v_new, t_pos, c, alpha, alpha_heads, select, recent, evict_here, o, ws, plan, st);
   } else {
-    if (c.d == 64) launch_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
-    else launch_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, alpha, select, recent, evict_here, o, ws, plan, st);
+    if (c.d == 64) launch_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, alpha, alpha_heads, select, recent, evict_here, o, ws, plan, st);
+    else launch_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, alpha, alpha_heads, select, recent, evict_here, o, ws, plan, st);
   }
 }
 

@@ -632,7 +632,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
     float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
-    float scale_log2e) {
+    const float* __restrict__ alpha_heads, float scale_log2e) {
   constexpr int BC = kWaves * 32;  // key columns per workgroup
   constexpr int CPR = D / 8;
   constexpr int KK = D / 16;
@@ -643,6 +643,7 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   if (vid >= total) return;
   const int g = (int)(vid / ncb);
   const int cb = (int)(vid % ncb);  // column block 0 has the most rows: first
+  head_window(alpha_heads, g, n, first_row, log2_alpha);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
@@ -769,7 +770,8 @@ constexpr int kTailTiles = 4;
 
 __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
-    float* __restrict__ S, int n, int first_row, float log2_alpha, float scale_log2e) {
+    float* __restrict__ S, int n, int first_row, float log2_alpha,
+    const float* __restrict__ alpha_heads, float scale_log2e) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
   __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
   lds_char* const qs = (lds_char*)smem;
@@ -782,7 +784,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   const float* lse = LSE2 + (size_t)g * n;
   float* Sg = S + (size_t)g * n;
 
-  const int r_lo = (first_row / kTile) * kTile;          // first staged row
+  const int r_lo = (first_row / kTile) * kTile;          // first staged row (sized by the host)
+  head_window(alpha_heads, g, n, first_row, log2_alpha);  // this head's own window inside it
   const int ntile = (n - r_lo + kTile - 1) / kTile;      // <= kTailTiles (checked by the host)
 #pragma unroll
   for (int tt = 0; tt < kTailTiles; ++tt)
@@ -862,13 +865,13 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
 
 template <int D>
 void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, float alpha,
-                 float* scores, hipStream_t st) {
+                 const float* alpha_heads, float* scores, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   float l2a;
   const int first = first_contributing_row(n, alpha, &l2a);
   if (D == 128 && n - (first / kTile) * kTile <= kTailTiles * kTile) {
     hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
-                       (const bf16_t*)k, lse2, scores, n, first, l2a, scale_log2e);
+                       (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e);
     return;
   }
   const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
@@ -876,7 +879,7 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
   hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st,
                      (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
-                     scale_log2e);
+                     alpha_heads, scale_log2e);
 }
 
 }  // namespace
@@ -888,9 +891,9 @@ void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int
 }
 
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
-                        float alpha, float* scores, hipStream_t st) {
-  if (d == 64) launch_cols<64>(q, k, lse2, G, n, alpha, scores, st);
-  else launch_cols<128>(q, k, lse2, G, n, alpha, scores, st);
+                        float alpha, const float* alpha_heads, float* scores, hipStream_t st) {
+  if (d == 64) launch_cols<64>(q, k, lse2, G, n, alpha, alpha_heads, scores, st);
+  else launch_cols<128>(q, k, lse2, G, n, alpha, alpha_heads, scores, st);
 }
 
 }  // namespace a2sf

@@ -84,9 +84,11 @@ __global__ __launch_bounds__(kThreads) void attn_rows_f32_kernel(
 template <int D>
 __global__ __launch_bounds__(kThreads) void scores_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ lse2, int n,
-    int first_row, float log2_alpha, float* __restrict__ scores, float scale_log2e) {
+    int first_row, float log2_alpha, const float* __restrict__ alpha_heads,
+    float* __restrict__ scores, float scale_log2e) {
   __shared__ float red[8];
   const int g = blockIdx.x / n, j = blockIdx.x % n, tid = threadIdx.x;
+  head_window(alpha_heads, g, n, first_row, log2_alpha);
   const float* kj = k + ((size_t)g * n + j) * D;
   const float* qg = q + (size_t)g * n * D;
   const float* lg = lse2 + (size_t)g * n;
@@ -124,15 +126,15 @@ void launch_prefill_f32(const float* q, const float* k, const float* v, int G, i
 }
 
 void launch_scores_f32(const float* q, const float* k, const float* lse2, int G, int n, int d,
-                       float alpha, float* scores, hipStream_t st) {
+                       float alpha, const float* alpha_heads, float* scores, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
   float l2a;
   const int first = first_contributing_row(n, alpha, &l2a);
   dim3 grid((unsigned)G * (unsigned)n);
   if (d == 64)
-    hipLaunchKernelGGL(scores_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, scores, scale_log2e);
+    hipLaunchKernelGGL(scores_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, alpha_heads, scores, scale_log2e);
   else
-    hipLaunchKernelGGL(scores_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, scores, scale_log2e);
+    hipLaunchKernelGGL(scores_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, alpha_heads, scores, scale_log2e);
 }
 
 }  // namespace a2sf

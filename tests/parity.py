@@ -64,22 +64,35 @@ class Problem:
 
     # ---- GPU calls
     def gpu_prefill(self, alpha, want_o=True, want_scores=True, select=None, recent=None):
+        """alpha: one factor, or a sequence of G per-head factors."""
         w = self.w
         select = w.select if select is None else select
         recent = w.recent if recent is None else recent
         o = torch.empty_like(self.dev["q"]) if want_o else None
         s = torch.empty((self.G, w.n), dtype=torch.float32, device="cuda") if want_scores else None
-        a2sf.a2sf_prefill(self.dev["q"], self.dev["k"], self.dev["v"], w.n, alpha, select, recent,
-                          self.cache, o=o, scores_full=s, workspace=self.ws)
+        if np.ndim(alpha) == 0:
+            a2sf.a2sf_prefill(self.dev["q"], self.dev["k"], self.dev["v"], w.n, float(alpha), select,
+                              recent, self.cache, o=o, scores_full=s, workspace=self.ws)
+        else:
+            ah = torch.tensor(np.asarray(alpha, dtype=np.float32), device="cuda")
+            a2sf.a2sf_prefill_alpha_per_head(self.dev["q"], self.dev["k"], self.dev["v"], w.n, ah,
+                                             float(np.max(alpha)), select, recent, self.cache, o=o,
+                                             scores_full=s, workspace=self.ws)
         return o, s
 
     def gpu_decode(self, t, alpha, mode=a2sf.A2SF_EVICT_FAST, select=None, recent=None):
         w = self.w
         select = w.select if select is None else select
         recent = w.recent if recent is None else recent
-        a2sf.a2sf_decode_step(self.dev["qd"][t], self.dev["kd"][t], self.dev["vd"][t], w.n + t,
-                              self.cache, alpha, select, recent, self.o_dec, mode=mode,
-                              workspace=self.ws)
+        if np.ndim(alpha) == 0:
+            a2sf.a2sf_decode_step(self.dev["qd"][t], self.dev["kd"][t], self.dev["vd"][t], w.n + t,
+                                  self.cache, float(alpha), select, recent, self.o_dec, mode=mode,
+                                  workspace=self.ws)
+        else:
+            ah = torch.tensor(np.asarray(alpha, dtype=np.float32), device="cuda")
+            a2sf.a2sf_decode_step_alpha_per_head(self.dev["qd"][t], self.dev["kd"][t], self.dev["vd"][t],
+                                                 w.n + t, self.cache, ah, select, recent, self.o_dec,
+                                                 mode=mode, workspace=self.ws)
         return self.o_dec
 
     def fetch(self, rows=True):
@@ -143,6 +156,11 @@ class LockStep:
         self.check_rows = True
         self.ascending = True    # slots in ascending position so far (lost by a fast-mode eviction)
 
+    def alpha_of(self, i):
+        """Factor of GPU head i as the kernels see it (fp32)."""
+        a = self.alpha if np.ndim(self.alpha) == 0 else self.alpha[i]
+        return float(np.float32(a))
+
     def prefill(self, check_o_rows=None):
         p, w = self.p, self.p.w
         o, s = p.gpu_prefill(self.alpha, select=self.select, recent=self.recent)
@@ -151,10 +169,10 @@ class LockStep:
         for i in p.sample:
             Q, K, V = (x[:w.n] for x in p.host[i])
             _, gpos, _, _, _ = p.gpu_cache_of(i)
-            O, S_full, oc = orc.prefill(Q, K, V, self.alpha, self.select, self.recent)
+            O, S_full, oc = orc.prefill(Q, K, V, self.alpha_of(i), self.select, self.recent)
             if set(gpos.tolist()) != set(oc.pos.tolist()):
                 before = set(oc.pos.tolist())
-                O, S_full, oc = orc.prefill(Q, K, V, self.alpha, self.select, self.recent,
+                O, S_full, oc = orc.prefill(Q, K, V, self.alpha_of(i), self.select, self.recent,
                                             forced_retained=gpos.tolist(), margin=MARGIN)
                 self.swaps += len(before - set(gpos.tolist()))
             self.oc[i] = oc
@@ -183,7 +201,7 @@ class LockStep:
             oc = self.oc[i]
             r = w.n + t
             _, gpos, _, _, _ = p.gpu_cache_of(i)
-            o_ref, a = orc.attend_and_update(oc, Q[r], K[r], V[r], r, self.alpha)
+            o_ref, a = orc.attend_and_update(oc, Q[r], K[r], V[r], r, self.alpha_of(i))
             _, sw = orc.evict(oc, self.select, self.recent, forced_retained=gpos.tolist(), margin=MARGIN)
             self.swaps += sw
             err = np.abs(og[i] - o_ref).max()

@@ -93,6 +93,20 @@ def test_decode_argument_errors():
     assert decode_status(fake_cache(G=4096), mode=1, ws=None) == B.A2SF_EWORKSPACE
 
 
+def test_per_head_alpha_argument_errors():
+    lib = B.lib()
+    c = fake_cache()
+    b = B.Budget(4, 4)
+    assert lib.a2sf_prefill_alpha_per_head(FAKE, FAKE, FAKE, 16, None, 0.5, b, ctypes.byref(c), None,
+                                           None, FAKE, 1 << 30, None) == B.A2SF_EINVAL
+    assert lib.a2sf_prefill_alpha_per_head(FAKE, FAKE, FAKE, 16, FAKE, 1.5, b, ctypes.byref(c), None,
+                                           None, FAKE, 1 << 30, None) == B.A2SF_EINVAL
+    assert lib.a2sf_decode_step_alpha_per_head(FAKE, FAKE, FAKE, 5, ctypes.byref(c), None, b, 0, FAKE,
+                                               FAKE, 1 << 30, None) == B.A2SF_EINVAL
+    assert lib.a2sf_decode_step_alpha_per_head(FAKE, FAKE, FAKE, 5, ctypes.byref(c), FAKE + 2, b, 0, FAKE,
+                                               FAKE, 1 << 30, None) == B.A2SF_EINVAL
+
+
 def test_select_and_compact_argument_errors():
     lib = B.lib()
     assert lib.a2sf_select(None, None, None, 1, 8, 8, B.Budget(2, 2), FAKE, FAKE, None) == B.A2SF_EINVAL

@@ -112,7 +112,7 @@ def run_lockstep(w, alpha, steps=None, mode=a2sf.A2SF_EVICT_FAST, heads=None, sa
     for t in range(w.T if steps is None else steps):
         ls.step(t, mode=mode)
     if say:
-        say(f"  [{w.name} alpha={alpha} mode={mode}] max|o err|={ls.max_o_err:.2e} "
+        say(f"  [{w.name} alpha={alpha if np.ndim(alpha) == 0 else 'per head'} mode={mode}] max|o err|={ls.max_o_err:.2e} "
             f"max score rel={ls.max_s_rel:.2e} in-margin swaps={ls.swaps}")
     return ls
 
@@ -205,6 +205,22 @@ def test_budget_lowered_between_steps(G, say):
     ls.select, ls.recent = 4, 4
     ls.step(5, mode=a2sf.A2SF_EVICT_STABLE)
     say(f"  [multi-evict G={G}] max|o err|={ls.max_o_err:.2e} max score rel={ls.max_s_rel:.2e}")
+
+
+@pytest.mark.parametrize("base,G,d,n", [(1, 7, 128, 300), (1, 4200, 128, 150), (0, 5, 64, 140),
+                                         (1, 6, 64, 260), (1, 3, 128, 2100)])
+def test_alpha_per_head(base, G, d, n, say):
+    """A distinct forgetting factor per head (Section 6 of the paper), both ends included."""
+    w = variant(base, heads=G, d=d, n=n, T=6, select=10, recent=10, name=f"per-head alpha G={G} d={d}")
+    rng = np.random.default_rng(G)
+    alphas = rng.choice([0.0, 0.05, 0.1, 0.3, 0.5, 0.7, 0.9, 0.97, 1.0], size=G).astype(np.float32)
+    alphas[:3] = [0.0, 1.0, 0.9][: min(3, G)]
+    sample = list(range(G)) if G <= 8 else [0, 1, 2, 77, 2049, G - 1]
+    run_lockstep(w, alphas, sample=sample, say=say)
+    run_lockstep(w, alphas, sample=sample[:3], mode=a2sf.A2SF_EVICT_STABLE, say=say)
+    # a narrow bound: every head below 0.5 (short-window score kernel on d = 128)
+    low = np.minimum(alphas, 0.45).astype(np.float32)
+    run_lockstep(w, low, sample=sample[:4], say=say)
 
 
 def test_cfg1_llama_layer(say):
