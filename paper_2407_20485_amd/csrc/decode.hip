@@ -219,43 +219,47 @@ __device__ void evict_general(float* a, int n_old, int excess, T* Kg, T* Vg, flo
   if (tid == 0) *len_g = live;
 }
 
-// Score update and eviction of one head by a whole workgroup.  On entry a[0..L) in LDS holds
-// the probabilities of the L = n_old+1 tokens (slot n_old = the new token, not yet stored in
-// the cache).  All 256 threads call this.  a[] is overwritten with the updated scores.
-template <typename T, int D>
-__device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, int32_t* Pg,
-                                 int32_t* len_g, const T* knew, const T* vnew, int t_pos,
-                                 float alpha, int select, int recent, bool evict_here,
+// Score update and eviction of one head by a whole workgroup.  prob(j) returns the
+// probability of slot j (slot n_old = the new token, not yet stored in the cache); the
+// updated scores are left in LDS a[0..L).  All 256 threads call this.  One pass reads the
+// scores and positions (independent loads, batched four deep), one pass writes the scores.
+template <typename T, int D, typename ProbFn>
+__device__ void update_and_evict(ProbFn prob, float* a, int n_old, T* Kg, T* Vg, float* Sg,
+                                 int32_t* Pg, int32_t* len_g, const T* knew, const T* vnew,
+                                 int t_pos, float alpha, int select, int recent, bool evict_here,
                                  StepSmem& sm) {
   using Grp = BlockGroup;
   const int tid = threadIdx.x;
   const int L = n_old + 1;
   const int excess = evict_here ? L - (select + recent) : 0;
 
-  // forgetting update into LDS
-  for (int j = tid; j < n_old; j += kThreads) a[j] = fmaf(alpha, Sg[j], a[j]);
+  // Recent window by position: in a cache that always kept its newest `recent` tokens the
+  // window is exactly pos > t_pos - recent.  Verified by counting; otherwise rank by position.
+  const int thr = t_pos - recent;
+  int cnt = 0, best_slot = n_old;
+  unsigned long long best = ~0ull;
+#pragma unroll 4
+  for (int j = tid; j < L; j += kThreads) {
+    const float pj = prob(j);
+    const float s_old = j < n_old ? Sg[j] : 0.f;
+    const int p = j < n_old ? Pg[j] : t_pos;
+    const float s = fmaf(alpha, s_old, pj);  // the forgetting update
+    a[j] = s;
+    if (p > thr) {
+      ++cnt;
+    } else {
+      const unsigned long long key = evict_key(s, p);
+      if (key < best) { best = key; best_slot = j; }
+    }
+  }
   __syncthreads();
 
   if (excess <= 0) {  // room left: plain append
+#pragma unroll 4
     for (int j = tid; j < L; j += kThreads) Sg[j] = a[j];
     if (tid == 0) { Pg[n_old] = t_pos; *len_g = L; }
     copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
     return;
-  }
-
-  // Recent window by position: in a cache that always kept its newest `recent` tokens the
-  // window is exactly pos > t_pos - recent.  Verify by counting; otherwise rank by position.
-  const int thr = t_pos - recent;
-  int cnt = 0;
-  unsigned long long best = ~0ull;
-  for (int j = tid; j < L; j += kThreads) {
-    const int p = j < n_old ? Pg[j] : t_pos;
-    if (p > thr) {
-      ++cnt;
-    } else {
-      const unsigned long long key = evict_key(a[j], p);
-      best = key < best ? key : best;
-    }
   }
   cnt = block_sum_i(cnt, sm.redi);
 
@@ -263,20 +267,17 @@ __device__ void update_and_evict(float* a, int n_old, T* Kg, T* Vg, float* Sg, i
     // ---- steady state: one eviction, no row moves
     if (tid == 0) sm.victim = n_old;  // overwritten below by the owner of the minimum
     const unsigned long long win = block_min_u64(best, sm.red64);
-    for (int j = tid; j < L; j += kThreads) {
-      const int p = j < n_old ? Pg[j] : t_pos;
-      if (p <= thr && evict_key(a[j], p) == win) sm.victim = j;
-    }
+    if (best == win && best != ~0ull) sm.victim = best_slot;  // keys are unique (positions are)
     __syncthreads();
     const int v = sm.victim;
-    for (int j = tid; j < n_old; j += kThreads)
-      if (j != v) Sg[j] = a[j];
+    const float s_tok = a[n_old];
+#pragma unroll 4
+    for (int j = tid; j < n_old; j += kThreads) Sg[j] = (j == v) ? s_tok : a[j];
     if (v != n_old) {
-      if (tid == kThreads - 1) { Sg[v] = a[n_old]; Pg[v] = t_pos; }
+      if (tid == kThreads - 1) Pg[v] = t_pos;
       copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, knew, Vg + (size_t)v * D, vnew);
     }
-    if (tid == 0) *len_g = n_old;  // = select + recent
-    return;
+    return;  // len stays n_old (= select + recent)
   }
   evict_general<Grp, T, D>(a, n_old, excess, Kg, Vg, Sg, Pg, len_g, knew, vnew, t_pos, recent, sm);
 }
@@ -337,8 +338,9 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
   reduce_output<T, D>(acc, part);
   if (tid < D) Elem<T>::store(o + (size_t)g * D + tid, part[0][tid]);
 
-  update_and_evict<T, D>(a, n_old, Kg, Vg, S + (size_t)g * capacity, P + (size_t)g * capacity,
-                         len + g, knew, vnew, t_pos, alpha, select, recent, evict_here != 0, sm);
+  update_and_evict<T, D>([&](int j) { return a[j]; }, a, n_old, Kg, Vg, S + (size_t)g * capacity,
+                         P + (size_t)g * capacity, len + g, knew, vnew, t_pos, alpha, select,
+                         recent, evict_here != 0, sm);
 }
 
 // ---- one wave per head ----------------------------------------------------------------
@@ -553,21 +555,30 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) return;
   const int L = n_old + 1;
+  // merge the per-split (max, sum): one lane per split (nsplit <= 64), wave reductions
+  __shared__ float wsplit[kWave];
   const float* mlg = ml + (size_t)g * nsplit * 2;
-  float mx = -INFINITY;
-  for (int c = 0; c < nsplit; ++c) mx = fmaxf(mx, mlg[2 * c]);
-  float sum = 0.f;
-  for (int c = 0; c < nsplit; ++c) sum += mlg[2 * c + 1] * exp2f(mlg[2 * c] - mx);
-  const float inv = 1.0f / sum;
+  if (tid < kWave) {
+    const float mc = tid < nsplit ? mlg[2 * tid] : -INFINITY;
+    const float lc = tid < nsplit ? mlg[2 * tid + 1] : 0.f;
+    const float mw = wave_max(mc);
+    const float w = exp2f(mc - mw);  // 0 for empty splits
+    const float sw = wave_sum(lc * w);
+    wsplit[tid] = w;
+    if (tid == 0) { sm.redf[6] = mw; sm.redf[7] = sw; }
+  }
+  __syncthreads();
+  const float mx = sm.redf[6];
+  const float inv = 1.0f / sm.redf[7];
   if (tid < D) {
     float acc = 0.f;
-    for (int c = 0; c < nsplit; ++c)
-      acc += po[((size_t)g * nsplit + c) * D + tid] * exp2f(mlg[2 * c] - mx);
+#pragma unroll 4
+    for (int c = 0; c < nsplit; ++c) acc = fmaf(po[((size_t)g * nsplit + c) * D + tid], wsplit[c], acc);
     Elem<T>::store(o + (size_t)g * D + tid, acc * inv);
   }
-  for (int j = tid; j < L; j += kThreads) a[j] = exp2f(zbuf[(size_t)g * capacity + j] - mx) * inv;
-  __syncthreads();
-  update_and_evict<T, D>(a, n_old, K + (size_t)g * capacity * D, V + (size_t)g * capacity * D,
+  const float* zg = zbuf + (size_t)g * capacity;
+  update_and_evict<T, D>([&](int j) { return exp2f(zg[j] - mx) * inv; }, a, n_old,
+                         K + (size_t)g * capacity * D, V + (size_t)g * capacity * D,
                          S + (size_t)g * capacity, P + (size_t)g * capacity, len + g,
                          k_new + (size_t)g * D, v_new + (size_t)g * D, t_pos, alpha, select,
                          recent, evict_here != 0, sm);
