@@ -358,6 +358,12 @@ __device__ __forceinline__ uint4 lds_read16(const lds_char* p) {
   return make_uint4(r.x, r.y, r.z, r.w);
 }
 
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void lds_write8(lds_char* p, const uint2& v) {
+  const u32x2_t x = {v.x, v.y};
+  *reinterpret_cast<__attribute__((address_space(3))) u32x2_t*>(p) = x;
+}
+
 constexpr int kTileBytes = kTile * 256;  // one 64-row tile of 128 bf16
 
 // Chunk swizzles (16-byte chunks of a 256-byte row; the LDS has 64 four-byte banks).  K is
@@ -604,25 +610,41 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 2 : 1) void attn_fwd128_kernel(
     __syncthreads();
   }
 
+  // ---- epilogue.  The accumulator layout gives a lane 4 consecutive d of one row at a time:
+  // written straight to memory that is 32 rows x 16 bytes per instruction.  Instead each wave
+  // transposes its 32 x 128 output block through its own 8 KB strip of LDS (free after the
+  // loop's last barrier; 16-byte chunks XOR-swizzled by the row) and stores whole 256-byte
+  // rows, 4 rows per instruction.
+  lds_char* const ostrip = lds + wave * 8192;
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int qrow = wrow0 + nb * 32 + l32;
     const float l = lsum[nb] + __shfl_xor(lsum[nb], 32, 64);
-    if (qrow < n) {
-      if (h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
-      if (WITH_O) {
-        const float inv = 1.0f / l;
-        bf16_t* orow = O + ((size_t)g * n + qrow) * D;
+    if (qrow < n && h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
+    if (WITH_O) {
+      const float inv = 1.0f / l;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
-            uint2 w;
-            w.x = pack_bf16(oacc[nb][db][4 * i4 + 0] * inv, oacc[nb][db][4 * i4 + 1] * inv);
-            w.y = pack_bf16(oacc[nb][db][4 * i4 + 2] * inv, oacc[nb][db][4 * i4 + 3] * inv);
-            *reinterpret_cast<uint2*>(orow + db * 32 + 8 * i4 + 4 * h) = w;
-          }
+        for (int i4 = 0; i4 < 4; ++i4) {
+          uint2 w;
+          w.x = pack_bf16(oacc[nb][db][4 * i4 + 0] * inv, oacc[nb][db][4 * i4 + 1] * inv);
+          w.y = pack_bf16(oacc[nb][db][4 * i4 + 2] * inv, oacc[nb][db][4 * i4 + 3] * inv);
+          // row l32, elements 32db + 8*i4 + 4h .. +3  ->  chunk 4db + i4, half h
+          lds_write8(ostrip + l32 * 256 + (((4 * db + i4) ^ (l32 & 15)) << 4) + 8 * h, w);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+      __builtin_amdgcn_wave_barrier();
+      const int rr = lane >> 4, c = lane & 15;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = 4 * u + rr;
+        const uint4 v = lds_read16(ostrip + r * 256 + ((c ^ (r & 15)) << 4));
+        const int orow = wrow0 + nb * 32 + r;
+        if (orow < n) store16(O + ((size_t)g * n + orow) * D + c * 8, v);
       }
+      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
