@@ -50,7 +50,7 @@ def prefill_model_flops(G, n, d, with_o=True):
 
 
 def read_traffic(name):
-    """HBM bytes per launch measured with rocprofv3 --pmc (see profiles/), if recorded."""
+    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/traffic.txt), if recorded."""
     path = os.path.join(ROOT, "profiles", "traffic.txt")
     if not os.path.exists(path):
         return None
@@ -61,7 +61,7 @@ def read_traffic(name):
     return None
 
 
-def cpu_baseline(w, budget_s=12.0):
+def cpu_baseline(w, alpha, budget_s=12.0):
     """The oracle, as it stands, on this machine's host cores: prompt phase of two heads, then
     generation steps head by head until about `budget_s` seconds have been spent."""
     import numpy as np
@@ -74,7 +74,6 @@ def cpu_baseline(w, budget_s=12.0):
         blas_threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
     except Exception:  # pragma: no cover
         blas_threads = 1
-    alpha = w.alpha
     heads = [0, w.G // 2]
     caches, data = [], []
     t0 = time.perf_counter()
@@ -124,12 +123,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-o", action="store_true", help="prompt phase without attention outputs")
     ap.add_argument("--mode", choices=["fast", "stable"], default="fast")
+    ap.add_argument("--alpha", type=float, default=None,
+                    help="forgetting factor (default: the workload's; config 4 sweeps 0.1, 0.5, 0.9, 1.0)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU only (every head is an independent problem; "
-            "see DESIGN.md for how the path would shard). Run with --gpus 1.")
+        log("bench.py: this build runs on ONE GPU only (every head is an independent problem, so "
+            "more GPUs would each take a share of the heads with no exchange). Run with --gpus 1.")
         sys.exit(2)
 
     import numpy as np
@@ -142,7 +143,7 @@ def main():
         log("bench.py: no GPU visible; the HIP path has no CPU fallback.")
         sys.exit(3)
     w = synth.CONFIGS[args.config]
-    alpha = w.alpha
+    alpha = w.alpha if args.alpha is None else args.alpha
     G, n, d, T = w.G, w.n, w.d, w.T
     e = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
@@ -244,7 +245,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the float64 oracle on the host cores ...")
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, alpha)
     print(json.dumps(out), flush=True)
 
 
