@@ -19,8 +19,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Wno-unused-command-line-argument"]
 
 
+def generate() -> None:
+    """Writes the generated instruction stream(s) the kernels include."""
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_fwd128x2.py")], check=True,
+                   capture_output=True)
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    generate()
     cmd = [hipcc, *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -1,0 +1,655 @@
+#!/usr/bin/env python3
+"""Writes attn_fwd128x2_body.inc: the gfx950 instruction stream of attn_fwd128x2_kernel.
+
+The kernel computes the masked attention rows of the prompt (Section 1 and Section 3.1 Eq.3
+of the paper) for d = 128 in bf16, 64 query rows per wave (two 32-row blocks, "block 0" and
+"block 1") and 256 per workgroup, one wave per SIMD with the whole 512-register file.
+Holding two query blocks per wave halves the LDS operand traffic per matrix op, which is
+what bounds the one-block kernel; with a single wave per SIMD the overlap of matrix ops and
+softmax arithmetic has to come from the instruction order inside the wave, and the register
+file has to be laid out by hand (accumulators and Q in AccVGPRs), which is why the stream is
+written out here instead of being left to the compiler.
+
+Schedule for K/V tile t of 64 keys (S = logits, P = probabilities, O = output accumulator):
+
+    phase X(t):  matrix ops  S0(t+1), S1(t+1) = K(t+1) Q^T       (one K fragment feeds both blocks)
+                 vector ops  softmax of S1(t) -> P1(t)
+    phase Y(t):  matrix ops  O0 += V(t)^T P0(t), O1 += V(t)^T P1(t)  (one V fragment feeds both)
+                 vector ops  softmax of S0(t+1) -> P0(t+1)
+
+so every phase pairs 32 matrix ops with one block's softmax, and nothing a phase's vector
+ops touch is written by the matrix ops of the same phase (S1 and P0 are double-buffered; the
+rare rescale of O by the running-maximum correction is deferred to the end of the phase).
+
+K/V tiles arrive by global_load_lds DMA into a ring of four LDS stages; the barrier at the
+top of iteration t publishes the tiles of iteration t+1, so fragment reads may run ahead
+across phase and iteration boundaries.
+
+Hazards the hardware does not interlock are kept apart by construction: a vector op reads a
+matrix-op result only after two later matrix ops have been issued plus explicit s_nop, a
+transcendental result is never consumed by the next instruction, and M0 writes are followed
+by s_nop before the DMA instruction.
+
+Usage: python gen_attn_fwd128x2.py [output path]
+"""
+import os
+import sys
+
+PF = 4  # operand fragments in flight ahead of their matrix ops
+DROP = set()  # timing experiments only (--drop): instruction classes left out, results are wrong
+
+# ---- vector registers ----------------------------------------------------------------
+S0 = 0                  # logits of block 0 (32 registers: key sub-block 0, then 1)
+S1 = (32, 64)           # logits of block 1, double-buffered by tile parity
+P0 = (96, 112)          # bf16 probabilities of block 0, double-buffered
+P1 = 128                # bf16 probabilities of block 1
+RING = 144              # 8 operand fragments x 4 registers
+KADDR = 176             # 8 LDS addresses of the K fragments (one per 16 d)
+VADDR = 184             # 4 LDS addresses of the V fragments (one per 32 d)
+KL = 188                # 4 per-lane global offsets of the K DMA
+VL = 192                # 4 per-lane global offsets of the V DMA
+M = (196, 197)          # running maximum (log2 units), per block
+L = (198, 199)          # running sum, per block
+CORR = (200, 201)       # correction factor of the last softmax, per block
+MX, T1, T2, NEGINF = 202, 203, 204, 205
+TMP = 206               # 16 temporaries
+RS = 222                # sum of the current tile's probabilities (per lane)
+NV = 230                # v0 .. v229 are used (and clobbered)
+# ---- accumulation registers -----------------------------------------------------------
+O = (0, 64)             # O^T accumulators: 4 blocks of 32 d x 16 registers each
+Q = (128, 160)          # Q fragments: 8 x 4 registers each
+NA = 192
+# ---- scalar registers -----------------------------------------------------------------
+KP, VP = 40, 42         # global pointer of the next K / V tile to fetch
+T, TFIN, NTMAX = 44, 45, 46
+KJ, VJ = 47, 48         # index of the next K / V tile to fetch
+KST, VST = 49, 50       # LDS stage the K / V fragment addresses point at
+KD, VD = 51, 52
+FLAG = (56, 58)         # per block: all ones when the running maximum moved
+ST0, ST1 = 60, 61
+PAIR = 62               # scratch pair
+OB = 64                 # output base pair
+SLO, SHI = 40, 67
+
+STAGE = 32768           # one LDS stage: K tile (16 KB) then V tile (16 KB)
+NSTAGE = 4
+
+
+def v(n):
+    return f"v{n}"
+
+
+def vr(n, c):
+    return f"v[{n}:{n + c - 1}]"
+
+
+def ar(n, c):
+    return f"a[{n}:{n + c - 1}]"
+
+
+def sp(n):
+    return f"s[{n}:{n + 1}]"
+
+
+class Out:
+    def __init__(self):
+        self.lines = []
+        self.far = []       # out-of-line code, appended after the main stream
+        self.nlabel = 0
+
+    def e(self, line):
+        self.lines.append(line)
+
+    def ext(self, lines):
+        self.lines.extend(lines)
+
+    def label(self, stem):
+        self.nlabel += 1
+        return f"L{stem}{self.nlabel}_%="
+
+
+class Fifo:
+    """Outstanding LDS reads, in issue order; they return in order."""
+
+    def __init__(self, tags=()):
+        self.q = list(tags)
+
+    def push(self, tag):
+        self.q.append(tag)
+
+    def wait(self, tag):
+        """Instruction that waits until every read tagged `tag` has returned."""
+        idx = max(i for i, t in enumerate(self.q) if t == tag)
+        left = len(self.q) - 1 - idx
+        self.q = self.q[idx + 1:]
+        assert left <= 15
+        return f"s_waitcnt lgkmcnt({left})"
+
+
+def slot(f):
+    return RING + 4 * (f % 8)
+
+
+def k_read(f):
+    kk, kb = f >> 1, f & 1
+    return [f"ds_read_b128 {vr(slot(f), 4)}, {v(KADDR + kk)} offset:{kb * 8192}"]
+
+
+def v_read(j):
+    g, db = j >> 2, j & 3
+    return [f"ds_read_b64_tr_b16 {vr(slot(j), 2)}, {v(VADDR + db)} offset:{g * 4096}",
+            f"ds_read_b64_tr_b16 {vr(slot(j) + 2, 2)}, {v(VADDR + db)} offset:{g * 4096 + 2048}"]
+
+
+def advance(addr, count, st, dl):
+    """Point `count` fragment addresses at the next LDS stage (ring of NSTAGE)."""
+    out = [f"s_add_u32 s{ST0}, s{st}, 1",
+           f"s_and_b32 s{ST0}, s{ST0}, {NSTAGE - 1}",
+           f"s_sub_i32 s{dl}, s{ST0}, s{st}",
+           f"s_lshl_b32 s{dl}, s{dl}, 15",
+           f"s_mov_b32 s{st}, s{ST0}"]
+    out += [f"v_add_u32 {v(addr + i)}, s{dl}, {v(addr + i)}" for i in range(count)]
+    return out
+
+
+def mask_partial(base):
+    """Causal mask of the 32 x 32 sub-block that holds the diagonal: local key
+    8 (i/4) + 4 h + i%4 against local query l32, with %[lv] = l32 - 4 h."""
+    out = []
+    for i in range(16):
+        c = 8 * (i >> 2) + (i & 3)
+        out.append(f"v_cmp_gt_i32 vcc, {c}, %[lv]")
+        out.append(f"v_cndmask_b32 {v(base + i)}, {v(base + i)}, {v(NEGINF)}, vcc")
+    return out
+
+
+def mask_full(base):
+    return [f"v_mov_b32 {v(base + i)}, {v(NEGINF)}" for i in range(16)]
+
+
+RESCALE_AT = 0x4e800000  # 2^30
+
+
+def softmax(out, b, s, p):
+    """Vector ops of one block's softmax over a 64-key tile, common case: the running maximum
+    m is left alone and p = exp2(s * scale - m) is formed directly (logits in v[s..s+31] stay
+    intact, bf16 probabilities go to v[p..p+15]).  Floating point keeps full relative
+    precision while p stays far from overflow, so m only has to move when the tile's sum
+    passes 2^30 (or is not a number, which is how the first tile, with m = -inf, announces
+    itself); then the out-of-line slow path redoes the tile with a fresh maximum.  Returns
+    (vector-op list, slow-path lines to be placed out of line)."""
+    m, l, flag = M[b], L[b], FLAG[b]
+    if "softmax" in DROP:
+        return [f"s_mov_b64 {sp(flag)}, 0"], []
+    slow, back = out.label("slow"), out.label("back")
+    t = [TMP + i for i in range(8)]
+    o = [f"s_mov_b64 {sp(flag)}, 0"]
+
+    def fma(i):
+        return f"v_fma_f32 {v(t[i % 8])}, {v(s + i)}, %[scale], -{v(m)}"
+
+    def ex(i):
+        return f"v_exp_f32 {v(t[i % 8])}, {v(t[i % 8])}"
+
+    def add(i):
+        if i == 0:
+            return f"v_mov_b32 {v(RS)}, {v(t[0])}"
+        return f"v_add_f32 {v(RS)}, {v(RS)}, {v(t[i % 8])}"
+
+    def cvt(j):
+        return f"v_cvt_pk_bf16_f32 {v(p + j)}, {v(t[(2 * j) % 8])}, {v(t[(2 * j + 1) % 8])}"
+
+    o += [fma(0), ex(0)]
+    for i in range(1, 32):
+        o += [fma(i), ex(i), add(i - 1)]
+        if (i - 1) & 1:
+            o.append(cvt((i - 1) // 2))
+    o += ["s_nop 0", add(31), cvt(15),
+          f"v_cmp_nge_f32 vcc, {RESCALE_AT:#x}, {v(RS)}",
+          "s_cmp_lg_u64 vcc, 0",
+          f"s_cbranch_scc1 {slow}",
+          f"{back}:",
+          f"v_add_f32 {v(l)}, {v(l)}, {v(RS)}"]
+    far = [f"{slow}:"] + softmax_slow(b, s, p) + [f"v_mov_b32 {v(RS)}, 0", f"s_branch {back}"]
+    return o, far
+
+
+def softmax_slow(b, s, p):
+    """One block's online softmax over a 64-key tile with a new running maximum: logits in
+    v[s..s+31] become probabilities in place and, rounded to bf16, in v[p..p+15]; m, l and
+    the correction factor are updated and the block's flag is raised."""
+    m, l, corr, flag = M[b], L[b], CORR[b], FLAG[b]
+    o = [f"v_max3_f32 {v(MX)}, {v(s)}, {v(s + 1)}, {v(s + 2)}"]
+    for k in range(3, 31, 2):
+        o.append(f"v_max3_f32 {v(MX)}, {v(MX)}, {v(s + k)}, {v(s + k + 1)}")
+    o += [f"v_max_f32 {v(MX)}, {v(MX)}, {v(s + 31)}",
+          f"v_mov_b32 {v(T1)}, {v(MX)}",
+          "s_nop 1",
+          f"v_permlane32_swap_b32 {v(MX)}, {v(T1)}",  # the two lanes of a query exchange halves
+          "s_nop 1",
+          f"v_max_f32 {v(MX)}, {v(MX)}, {v(T1)}",
+          f"v_mul_f32 {v(MX)}, %[scale], {v(MX)}",
+          f"v_max_f32 {v(MX)}, 0xf149f2ca, {v(MX)}",          # -1e30 floor
+          f"v_add_f32 {v(T1)}, 0x41000000, {v(m)}",            # lazy rescale: only past m + 8
+          f"v_cmp_gt_f32 vcc, {v(MX)}, {v(T1)}",
+          "s_cmp_lg_u64 vcc, 0",
+          f"s_cselect_b64 {sp(flag)}, -1, 0",
+          f"v_max_f32 {v(T1)}, {v(m)}, {v(MX)}",
+          f"v_cndmask_b32 {v(T1)}, {v(m)}, {v(T1)}, {sp(flag)}",
+          f"v_sub_f32 {v(T2)}, {v(m)}, {v(T1)}",
+          f"v_exp_f32 {v(corr)}, {v(T2)}",
+          f"v_mov_b32 {v(m)}, {v(T1)}",
+          f"v_mul_f32 {v(l)}, {v(l)}, {v(corr)}"]
+
+    def fma(i):
+        return f"v_fma_f32 {v(s + i)}, {v(s + i)}, %[scale], -{v(m)}"
+
+    def ex(i):
+        return f"v_exp_f32 {v(s + i)}, {v(s + i)}"
+
+    def add(i):
+        return f"v_add_f32 {v(l)}, {v(l)}, {v(s + i)}"
+
+    def cvt(j):
+        return f"v_cvt_pk_bf16_f32 {v(p + j)}, {v(s + 2 * j)}, {v(s + 2 * j + 1)}"
+
+    o += [fma(0), ex(0)]
+    for i in range(1, 32):
+        o += [fma(i), ex(i), add(i - 1)]
+        if (i - 1) & 1:
+            o.append(cvt((i - 1) // 2))
+    o += ["s_nop 0", add(31), cvt(15)]
+    return o
+
+
+def rescale(out, b, settle):
+    """O_b *= corr_b when block b's running maximum moved (rare after the first tiles)."""
+    skip = out.label("nr")
+    out.e(f"s_cmp_lg_u64 {sp(FLAG[b])}, 0")
+    out.e(f"s_cbranch_scc0 {skip}")
+    if settle:
+        out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
+    for j in range(0, 64, 16):
+        for k in range(16):
+            out.e(f"v_accvgpr_read_b32 {v(TMP + k)}, a{O[b] + j + k}")
+        for k in range(16):
+            out.e(f"v_mul_f32 {v(TMP + k)}, {v(TMP + k)}, {v(CORR[b])}")
+        for k in range(16):
+            out.e(f"v_accvgpr_write_b32 a{O[b] + j + k}, {v(TMP + k)}")
+    out.e("s_nop 7")
+    out.e(f"{skip}:")
+
+
+def merge(out, steps, valu, lead=0, lead_lines=()):
+    """Interleave: every matrix op is followed by its share of the vector-op list.  `lead`
+    matrix ops are issued before any vector op (then `lead_lines`)."""
+    mf = sum(len(s[2]) for s in steps)
+    slots = max(mf - lead, 1)
+    done_v, seen = 0, 0
+    for pre, wait, mfmas in steps:
+        out.ext(pre)
+        if wait:
+            out.e(wait)
+        for m in mfmas:
+            out.e(m)
+            seen += 1
+            if seen == lead:
+                out.ext(lead_lines)
+            if seen > lead or lead == 0:
+                k = seen - lead
+                upto = (len(valu) * k + slots - 1) // slots
+                out.ext(valu[done_v:upto])
+                done_v = upto
+    out.ext(valu[done_v:])
+
+
+def qk_steps(fifo, s0, s1, next_reads, extra=None):
+    """Matrix side of S0, S1 = K Q^T over the 16 K fragments of a tile (fragments 0..PF-1
+    already requested), two fragments = four matrix ops per step.  next_reads(i) = reads to
+    request once the K reads ran out; extra[i] = further lines ahead of step i."""
+    steps = []
+    for f in range(0, 16, 2):
+        pre = list((extra or {}).get(f // 2, []))
+        for g in (f, f + 1):
+            if g + PF < 16:
+                pre += k_read(g + PF)
+                fifo.push(("K", g + PF))
+            else:
+                if g + PF == 16:
+                    pre += advance(KADDR, 8, KST, KD)
+                pre += next_reads(g + PF - 16)
+        wait = fifo.wait(("K", f + 1))
+        mf = []
+        for g in (f, f + 1):
+            kk, kb = g >> 1, g & 1
+            for b, sb in ((0, s0), (1, s1)):
+                d = vr(sb + 16 * kb, 16)
+                c = "0" if kk == 0 else d
+                mf.append(f"v_mfma_f32_32x32x16_bf16 {d}, {vr(slot(g), 4)}, {ar(Q[b] + 4 * kk, 4)}, {c}")
+        steps.append((pre, wait, mf))
+    return steps
+
+
+def pv_steps(fifo, p0, p1, next_reads):
+    """Matrix side of O0, O1 += V^T P^T over the 16 V fragments of a tile."""
+    steps = []
+    for j in range(0, 16, 2):
+        pre = []
+        for i in (j, j + 1):
+            if i + PF < 16:
+                pre += v_read(i + PF)
+                fifo.push(("V", i + PF))
+                fifo.push(("V", i + PF))
+            else:
+                if i + PF == 16:
+                    pre += advance(VADDR, 4, VST, VD)
+                pre += next_reads(i + PF - 16)
+        wait = fifo.wait(("V", j + 1))
+        mf = []
+        for i in (j, j + 1):
+            g, db = i >> 2, i & 3
+            for b, pb in ((0, p0), (1, p1)):
+                d = ar(O[b] + 16 * db, 16)
+                mf.append(f"v_mfma_f32_32x32x16_bf16 {d}, {vr(slot(i), 4)}, {vr(pb + 4 * g, 4)}, {d}")
+        steps.append((pre, wait, mf))
+    return steps
+
+
+def dma_pieces(out):
+    """The fetch of {K(t+4), V(t+3)} cut into four pieces that ride in front of the first
+    matrix-op steps of phase X (same instruction order as dma(K); dma(V))."""
+    pieces = {}
+    for n, (j, p, lo, off) in enumerate(((KJ, KP, KL, 0), (VJ, VP, VL, 16384))):
+        for half in (0, 1):
+            skip = out.label("np")
+            ln = [f"s_cmp_lt_u32 s{j}, s{NTMAX}", f"s_cbranch_scc0 {skip}"]
+            if half == 0:
+                ln += [f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
+                       f"s_lshl_b32 s{ST1}, s{ST1}, 15",
+                       f"s_add_u32 s{ST1}, s{ST1}, %[wave_lds]"]
+            for u in (2 * half, 2 * half + 1):
+                ln += [f"s_add_u32 m0, s{ST1}, {off + u * 4096}", "s_nop 0",
+                       f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)}"]
+            if half == 1:
+                ln += [f"s_add_u32 s{p}, s{p}, 16384", f"s_addc_u32 s{p + 1}, s{p + 1}, 0",
+                       f"s_add_u32 s{j}, s{j}, 1"]
+            ln.append(f"{skip}:")
+            pieces[2 * n + half] = ln
+    return pieces
+
+
+def dma(out, which):
+    j, p, lo, off = (KJ, KP, KL, 0) if which == "K" else (VJ, VP, VL, 16384)
+    skip = out.label("nd")
+    out.e(f"s_cmp_lt_u32 s{j}, s{NTMAX}")
+    out.e(f"s_cbranch_scc0 {skip}")
+    out.e(f"s_and_b32 s{ST0}, s{j}, {NSTAGE - 1}")
+    out.e(f"s_lshl_b32 s{ST0}, s{ST0}, 15")
+    out.e(f"s_add_u32 s{ST0}, s{ST0}, %[wave_lds]")
+    for u in range(4):
+        out.e(f"s_add_u32 m0, s{ST0}, {off + u * 4096}")
+        out.e("s_nop 0")
+        out.e(f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)}")
+    out.e(f"s_add_u32 s{p}, s{p}, 16384")
+    out.e(f"s_addc_u32 s{p + 1}, s{p + 1}, 0")
+    out.e(f"s_add_u32 s{j}, s{j}, 1")
+    out.e(f"{skip}:")
+
+
+def top(out, fetch=True):
+    """Top of iteration t: the group {K(t+2), V(t+1)} has landed for every wave; then fetch
+    {K(t+4), V(t+3)} into the stages that held K(t) and V(t-1) (fetch=False: the caller
+    issues that fetch itself, right after)."""
+    tail, done = out.label("tl"), out.label("td")
+    out.e(f"s_add_u32 s{ST0}, s{T}, 3")
+    out.e(f"s_cmp_ge_u32 s{ST0}, s{NTMAX}")
+    out.e(f"s_cbranch_scc1 {tail}")
+    out.e("s_waitcnt vmcnt(8)")
+    out.e(f"s_branch {done}")
+    out.e(f"{tail}:")
+    out.e("s_waitcnt vmcnt(0)")
+    out.e(f"{done}:")
+    out.e("s_barrier")
+    if fetch:
+        dma(out, "K")
+        dma(out, "V")
+
+
+def k_prefetch_tags():
+    return [("K", i) for i in range(PF)]
+
+
+def body(out, par):
+    """Iteration t of parity par = t % 2 with t < (last tile of this wave)."""
+    fifo = Fifo(k_prefetch_tags())
+
+    def next_v(i):
+        fifo.push(("V", i))
+        fifo.push(("V", i))
+        return v_read(i)
+
+    def next_k(i):
+        fifo.push(("K", i))
+        return k_read(i)
+
+    # ---- X: S0(t+1), S1(t+1) on the matrix cores | softmax of S1(t)
+    out.e(f"; ---- X phase, parity {par}")
+    steps = qk_steps(fifo, S0, S1[1 - par], next_v, extra=dma_pieces(out))
+    valu, far = softmax(out, 1, S1[par], P1)
+    out.far += far
+    merge(out, steps, valu)
+    rescale(out, 1, settle=False)
+    # ---- Y: O += V(t)^T P(t) | softmax of S0(t+1)
+    out.e(f"; ---- Y phase, parity {par}")
+    steps = pv_steps(fifo, P0[par], P1, next_k)
+    nomask = out.label("nm")
+    lead = ["s_nop 7",
+            f"s_add_u32 s{ST0}, s{T}, 1",
+            f"s_cmp_eq_u32 s{ST0}, s{TFIN}",
+            f"s_cbranch_scc0 {nomask}"] + mask_partial(S0) + mask_full(S0 + 16) + [f"{nomask}:"]
+    valu, far = softmax(out, 0, S0, P0[1 - par])
+    out.far += far
+    merge(out, steps, valu, lead=2, lead_lines=lead)
+    rescale(out, 0, settle=True)
+    assert fifo.q == k_prefetch_tags()
+
+
+def final(out, par):
+    """Last tile of this wave (the one holding the diagonal): softmax of S1, then O += V^T P."""
+    out.e(f"; ---- final, parity {par}")
+    dma(out, "K")
+    dma(out, "V")
+    out.e("s_waitcnt lgkmcnt(0)")
+    out.ext(mask_partial(S1[par] + 16))
+    fifo = Fifo()
+    pre = []
+    for j in range(PF):
+        pre += v_read(j)
+        fifo.push(("V", j))
+        fifo.push(("V", j))
+    out.ext(pre)
+    valu, far = softmax(out, 1, S1[par], P1)
+    out.far += far
+    out.ext(valu)
+    rescale(out, 1, settle=False)
+    steps = pv_steps(fifo, P0[par], P1, lambda i: [])
+    merge(out, steps, [])
+    assert not fifo.q
+
+
+def prologue(out):
+    out.e("; ---- prologue")
+    out.e(f"v_mov_b32 {v(NEGINF)}, 0xff800000")
+    for b in (0, 1):
+        out.e(f"v_mov_b32 {v(M[b])}, {v(NEGINF)}")
+        out.e(f"v_mov_b32 {v(L[b])}, 0")
+    for kk in range(8):
+        out.e(f"v_xor_b32 {v(KADDR + kk)}, {kk * 32}, %[hx16]")
+        out.e(f"v_add_u32 {v(KADDR + kk)}, {v(KADDR + kk)}, %[krow]")
+    for db in range(4):
+        out.e(f"v_xor_b32 {v(VADDR + db)}, {db * 64}, %[clvs16]")
+        out.e(f"v_add_u32 {v(VADDR + db)}, {v(VADDR + db)}, %[vrow]")
+    for u in range(4):
+        out.e(f"v_add_u32 {v(KL + u)}, {u * 4096}, %[kl0]")
+        out.e(f"v_add_u32 {v(VL + u)}, {u * 4096}, %[vl0]")
+    out.e(f"s_mov_b64 {sp(KP)}, %[kg]")
+    out.e(f"s_mov_b64 {sp(VP)}, %[vg]")
+    out.e(f"s_mov_b32 s{T}, 0")
+    out.e(f"s_mov_b32 s{TFIN}, %[tfin]")
+    out.e(f"s_mov_b32 s{NTMAX}, %[ntmax]")
+    out.e(f"s_mov_b32 s{KJ}, 0")
+    out.e(f"s_mov_b32 s{VJ}, 0")
+    out.e(f"s_mov_b32 s{KST}, 0")
+    out.e(f"s_mov_b32 s{VST}, 0")
+    for kk in range(8):
+        out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw] offset:{kk * 32}")
+    for kk in range(8):
+        out.e(f"global_load_dwordx4 {ar(Q[1] + 4 * kk, 4)}, %[qoff], %[qw1] offset:{kk * 32}")
+    for which in "KKVKVKV":
+        dma(out, which)
+    for i in range(128):
+        out.e(f"v_accvgpr_write_b32 a{i}, 0")
+    out.e("s_waitcnt vmcnt(16)")   # Q, K(0), K(1), V(0)
+    out.e("s_barrier")
+    # S0(0), S1(0)
+    fifo = Fifo()
+    for f in range(PF):
+        out.ext(k_read(f))
+        fifo.push(("K", f))
+
+    def next_k(i):
+        fifo.push(("K", i))
+        return k_read(i)
+
+    merge(out, qk_steps(fifo, S0, S1[0], next_k), [])
+    assert fifo.q == k_prefetch_tags()
+    out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
+    nomask = out.label("nm")
+    out.e(f"s_cmp_eq_u32 s{TFIN}, 0")
+    out.e(f"s_cbranch_scc0 {nomask}")
+    out.ext(mask_partial(S0) + mask_full(S0 + 16))
+    out.e(f"{nomask}:")
+    valu, far = softmax(out, 0, S0, P0[0])
+    out.far += far
+    out.ext(valu)
+
+
+def epilogue(out):
+    out.e("; ---- epilogue")
+    out.e("s_barrier")          # every wave is done with the K/V stages; they become the strips
+    out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
+    inv, lg, adr = TMP + 12, TMP + 13, TMP + 14
+    out.e(f"s_mov_b64 {sp(OB)}, %[ow]")
+    for b in (0, 1):
+        l, m = L[b], M[b]
+        out.ext([f"v_mov_b32 {v(T1)}, {v(l)}", "s_nop 1",
+                 f"v_permlane32_swap_b32 {v(l)}, {v(T1)}", "s_nop 1",
+                 f"v_add_f32 {v(l)}, {v(l)}, {v(T1)}",
+                 f"v_log_f32 {v(lg)}, {v(l)}",
+                 f"v_rcp_f32 {v(inv)}, {v(l)}",
+                 "s_nop 0",
+                 f"v_add_f32 {v(lg)}, {v(lg)}, {v(m)}",
+                 f"global_store_dword %[l32x4], {v(lg)}, %[lsew] offset:{b * 128}"])
+        n = 0
+        for db in range(4):
+            for i4 in range(4):
+                t = TMP + 4 * (n % 2)          # two sets of four temporaries
+                w = S0 + 2 * (n % 8)           # eight result pairs (the logit registers are free now)
+                src = O[b] + 16 * db + 4 * i4
+                for k in range(4):
+                    out.e(f"v_accvgpr_read_b32 {v(t + k)}, a{src + k}")
+                for k in range(4):
+                    out.e(f"v_mul_f32 {v(t + k)}, {v(t + k)}, {v(inv)}")
+                out.e(f"v_cvt_pk_bf16_f32 {v(w)}, {v(t)}, {v(t + 1)}")
+                out.e(f"v_cvt_pk_bf16_f32 {v(w + 1)}, {v(t + 2)}, {v(t + 3)}")
+                out.e(f"v_xor_b32 {v(adr)}, {(4 * db + i4) * 16}, %[x16]")
+                out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_w]")
+                out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)}")
+                n += 1
+        out.e("s_waitcnt lgkmcnt(0)")
+        for u in range(8):
+            out.e(f"v_xor_b32 {v(adr)}, {64 * (u & 3)}, %[crr16]")
+            out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_r]")
+            out.e(f"ds_read_b128 {vr(S1[0] + 4 * u, 4)}, {v(adr)} offset:{u * 1024}")
+        out.e("s_waitcnt lgkmcnt(0)")
+        for u in range(8):
+            if u == 4 or (u == 0 and b == 1):
+                out.e(f"s_add_u32 s{OB}, s{OB}, 4096")
+                out.e(f"s_addc_u32 s{OB + 1}, s{OB + 1}, 0")
+            out.e(f"global_store_dwordx4 %[lanex16], {vr(S1[0] + 4 * u, 4)}, {sp(OB)} offset:{(u & 3) * 1024}")
+
+
+def generate():
+    out = Out()
+    prologue(out)
+    loop, fin_e, fin_o, drain, epi = (out.label(x) for x in ("loop", "fe", "fo", "dr", "ep"))
+    out.e(f"{loop}:")
+    top(out, fetch=False)
+    out.e(f"s_cmp_eq_u32 s{T}, s{TFIN}")
+    out.e(f"s_cbranch_scc1 {fin_e}")
+    body(out, 0)
+    out.e(f"s_add_u32 s{T}, s{T}, 1")
+    top(out, fetch=False)
+    out.e(f"s_cmp_eq_u32 s{T}, s{TFIN}")
+    out.e(f"s_cbranch_scc1 {fin_o}")
+    body(out, 1)
+    out.e(f"s_add_u32 s{T}, s{T}, 1")
+    out.e(f"s_branch {loop}")
+    out.e(f"{fin_e}:")
+    final(out, 0)
+    out.e(f"s_branch {drain}")
+    out.e(f"{fin_o}:")
+    final(out, 1)
+    out.e(f"{drain}:")
+    out.e(f"s_add_u32 s{T}, s{T}, 1")
+    out.e(f"s_cmp_lt_u32 s{T}, s{NTMAX}")
+    out.e(f"s_cbranch_scc0 {epi}")
+    top(out)
+    out.e(f"s_branch {drain}")
+    out.e(f"{epi}:")
+    epilogue(out)
+    done = out.label("done")
+    out.e(f"s_branch {done}")
+    out.ext(out.far)
+    out.e(f"{done}:")
+    return out.lines
+
+
+def clobbers():
+    c = [f"v{i}" for i in range(NV)] + [f"a{i}" for i in range(NA)]
+    c += [f"s{i}" for i in range(SLO, SHI + 1)] + ["vcc", "scc", "memory"]
+    return ", ".join(f'"{x}"' for x in c)
+
+
+def dropped(ln):
+    op = ln.split()[0] if ln.split() else ""
+    return (("mfma" in DROP and op.startswith("v_mfma")) or ("exp" in DROP and op == "v_exp_f32")
+            or ("ds" in DROP and op.startswith("ds_read")) or ("barrier" in DROP and op == "s_barrier")
+            or ("dma" in DROP and op.startswith("global_load_lds"))
+            or ("vmwait" in DROP and op == "s_waitcnt" and "vmcnt" in ln)
+            or ("lgkmwait" in DROP and op == "s_waitcnt" and "lgkmcnt" in ln)
+            or ("slowbranch" in DROP and op == "s_cbranch_scc1" and "Lslow" in ln))
+
+
+def main():
+    here = os.path.dirname(os.path.abspath(__file__))
+    args = sys.argv[1:]
+    while "--drop" in args:  # e.g. --drop mfma --drop softmax: measures what the rest costs
+        i = args.index("--drop")
+        DROP.add(args[i + 1])
+        del args[i:i + 2]
+    path = args[0] if args else os.path.join(here, "attn_fwd128x2_body.inc")
+    lines = [ln for ln in generate() if not dropped(ln)]
+    with open(path, "w") as f:
+        f.write("// Written by gen_attn_fwd128x2.py; edit the generator, not this file.\n")
+        f.write("#define A2SF_FWD128X2_ASM \\\n")
+        for ln in lines:
+            assert '"' not in ln and "\\" not in ln
+            f.write(f'  "{ln}\\n" \\\n')
+        f.write('  ""\n')
+        f.write(f"#define A2SF_FWD128X2_CLOBBERS {clobbers()}\n")
+    print(f"{path}: {len(lines)} lines")
+
+
+if __name__ == "__main__":
+    main()

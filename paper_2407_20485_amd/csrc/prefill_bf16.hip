@@ -37,6 +37,9 @@ constexpr int kPrefetch = A2SF_FWD_PREFETCH;  // LDS fragment reads in flight ah
 #ifndef A2SF_FWD_NB
 #define A2SF_FWD_NB 1      // 32-row query blocks per wave in attn_fwd
 #endif
+#ifndef A2SF_FWD128_X2
+#define A2SF_FWD128_X2 1   // d = 128: two query blocks per wave where the shape allows it
+#endif
 #ifndef A2SF_FWD_OCC
 #define A2SF_FWD_OCC 2     // workgroups per compute unit the register budget is sized for
 #endif
@@ -650,6 +653,75 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 2 : 1) void attn_fwd128_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// d = 128 with two 32-row query blocks per wave (64 rows per wave, 256 per workgroup) and one
+// wave per SIMD.  Same operand conventions, LDS tile layouts and mathematics as
+// attn_fwd128_kernel; the instruction stream (register map, phase schedule, hazards) is
+// written by gen_attn_fwd128x2.py, whose header describes it.  This wrapper derives the
+// per-lane offsets and per-wave pointers and hands them to that stream.  Requires
+// n % 256 == 0 and an output pointer.
+#include "attn_fwd128x2_body.inc"
+
+constexpr int kX2Rows = 256;            // query rows per workgroup
+constexpr int kX2LdsBytes = 4 * 32768;  // four stages of one K tile + one V tile
+
+__global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+  __shared__ __attribute__((aligned(1024))) char smem[kX2LdsBytes];
+  const long long total = (long long)G * nqb;
+  const long long vid = xcd_contiguous_id(total);
+  if (vid >= total) return;
+  const int g = (int)(vid / nqb);
+  const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, h = lane >> 5;
+  const int row0 = qb * kX2Rows, wrow0 = row0 + wave * 64;
+  const unsigned lds0 = (unsigned)(size_t)smem;  // LDS byte address of the stage ring
+
+  // K fragment (16 d-chunk 2kk+h of key row l32): row base and the kk-independent swizzle term
+  const unsigned krow = lds0 + l32 * 256, hx16 = (unsigned)((h ^ k_swizzle(l32)) << 4);
+  // V fragment (see attn_fwd128_kernel): source lane (r, qd) of group gq, key rows 4h + r
+  const int i16 = lane & 15, r4 = i16 >> 2, qd = i16 & 3, gq = (lane >> 4) & 1;
+  const unsigned clvs16 = (unsigned)(((2 * gq + (qd >> 1)) ^ v_swizzle(r4)) << 4);
+  const unsigned vrow = lds0 + kTileBytes + (4 * h + r4) * 256 + (qd & 1) * 8;
+  // DMA: this wave fills rows 16u + 4 wave + rr of a tile, lane (rr, pc) the chunk slot pc
+  const int rr = lane >> 4, pc = lane & 15, lrow = 4 * wave + rr;
+  const unsigned kl0 = (unsigned)(lrow * 256 + ((pc ^ k_swizzle(lrow)) << 4));
+  const unsigned vl0 = (unsigned)(lrow * 256 + ((pc ^ v_swizzle(lrow)) << 4));
+  const unsigned qoff = (unsigned)(l32 * 256 + h * 16);
+  const int lv = l32 - 4 * h;
+  const unsigned l32x4 = l32 * 4, lanex16 = lane * 16;
+  // epilogue: a wave's 32 x 128 output block goes through its own 8 KB strip of LDS
+  const unsigned strip = lds0 + wave * 8192;
+  const unsigned strip_w = strip + l32 * 256 + 8 * h, x16 = (unsigned)((l32 & 15) << 4);
+  const unsigned strip_r = strip + rr * 256, crr16 = (unsigned)((pc ^ rr) << 4);
+
+  const size_t head = (size_t)g * n;
+  const bf16_t* kg = K + head * 128;
+  const bf16_t* vg = V + head * 128;
+  const bf16_t* qw = Q + (head + wrow0) * 128;
+  const bf16_t* qw1 = qw + 32 * 128;
+  bf16_t* ow = O + (head + wrow0) * 128;
+  float* lsew = LSE2 + head + wrow0;
+  const int tfin = wrow0 >> 6;        // this wave's last key tile (the one with the diagonal)
+  const int ntmax = (row0 >> 6) + 4;  // key tiles the workgroup streams
+  const unsigned wave_lds = lds0 + wave * 1024;
+
+  asm volatile(A2SF_FWD128X2_ASM
+               :
+               : [hx16] "v"(hx16), [krow] "v"(krow), [clvs16] "v"(clvs16), [vrow] "v"(vrow),
+                 [kl0] "v"(kl0), [vl0] "v"(vl0), [qoff] "v"(qoff), [lv] "v"(lv),
+                 [l32x4] "v"(l32x4), [lanex16] "v"(lanex16), [strip_w] "v"(strip_w),
+                 [x16] "v"(x16), [crr16] "v"(crr16), [strip_r] "v"(strip_r), [kg] "s"(kg),
+                 [vg] "s"(vg), [qw] "s"(qw), [qw1] "s"(qw1), [ow] "s"(ow), [lsew] "s"(lsew),
+                 [tfin] "s"(tfin), [ntmax] "s"(ntmax), [wave_lds] "s"(wave_lds),
+                 [scale] "s"(scale_log2e)
+               : A2SF_FWD128X2_CLOBBERS);
+}
+
+// ---------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
@@ -753,6 +825,14 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
   if (D == 128) {
     constexpr int NB = A2SF_FWD128_NB;
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
+    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0) {
+      const int nqb2 = n / kX2Rows;
+      const unsigned grid2 = (unsigned)((((long long)G * nqb2 + 7) / 8) * 8);
+      hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st, (const bf16_t*)q,
+                         (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G, nqb2,
+                         scale_log2e);
+      return;
+    }
     const long long total = (long long)G * nqb;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
     if (o)
