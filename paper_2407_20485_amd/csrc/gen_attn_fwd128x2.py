@@ -61,11 +61,13 @@ Q = (128, 160)          # Q fragments: 8 x 4 registers each
 NA = 192
 # ---- scalar registers -----------------------------------------------------------------
 KP, VP = 40, 42         # global pointer of the next K / V tile to fetch
-T, TFIN, NTMAX = 44, 45, 46
+T, TF0, NTMAX = 44, 45, 46   # iteration, block 0's last tile, tiles the workgroup streams
+TF1 = 53                      # block 1's last tile
 KJ, VJ = 47, 48         # index of the next K / V tile to fetch
 KST, VST = 49, 50       # LDS stage the K / V fragment addresses point at
 KD, VD = 51, 52
 FLAG = (56, 58)         # per block: all ones when the running maximum moved
+FLAGO = (54, 66)        # per block: nonzero when O has to be rescaled (moved, and not from -inf)
 ST0, ST1 = 60, 61
 PAIR = 62               # scratch pair
 OB = 64                 # output base pair
@@ -180,10 +182,10 @@ def softmax(out, b, s, p):
     (vector-op list, slow-path lines to be placed out of line)."""
     m, l, flag = M[b], L[b], FLAG[b]
     if "softmax" in DROP:
-        return [f"s_mov_b64 {sp(flag)}, 0"], []
+        return [f"s_mov_b64 {sp(FLAGO[b])}, 0"], []
     slow, back = out.label("slow"), out.label("back")
     t = [TMP + i for i in range(8)]
-    o = [f"s_mov_b64 {sp(flag)}, 0"]
+    o = [f"s_mov_b64 {sp(FLAGO[b])}, 0"]
 
     def fma(i):
         return f"v_fma_f32 {v(t[i % 8])}, {v(s + i)}, %[scale], -{v(m)}"
@@ -199,13 +201,17 @@ def softmax(out, b, s, p):
     def cvt(j):
         return f"v_cvt_pk_bf16_f32 {v(p + j)}, {v(t[(2 * j) % 8])}, {v(t[(2 * j + 1) % 8])}"
 
-    o += [fma(0), ex(0)]
-    for i in range(1, 32):
-        o += [fma(i), ex(i), add(i - 1)]
-        if (i - 1) & 1:
-            o.append(cvt((i - 1) // 2))
-    o += ["s_nop 0", add(31), cvt(15),
-          f"v_cmp_nge_f32 vcc, {RESCALE_AT:#x}, {v(RS)}",
+    # software-pipelined so that no instruction reads what the one before it wrote
+    for i in range(34):
+        if i < 32:
+            o.append(fma(i))
+        if 0 <= i - 1 < 32:
+            o.append(ex(i - 1))
+        if 0 <= i - 2 < 32:
+            o.append(add(i - 2))
+            if (i - 2) & 1:
+                o.append(cvt((i - 2) // 2))
+    o += [f"v_cmp_nge_f32 vcc, {RESCALE_AT:#x}, {v(RS)}",
           "s_cmp_lg_u64 vcc, 0",
           f"s_cbranch_scc1 {slow}",
           f"{back}:",
@@ -234,6 +240,8 @@ def softmax_slow(b, s, p):
           f"v_cmp_gt_f32 vcc, {v(MX)}, {v(T1)}",
           "s_cmp_lg_u64 vcc, 0",
           f"s_cselect_b64 {sp(flag)}, -1, 0",
+          f"v_cmp_lg_f32 vcc, {v(m)}, {v(NEGINF)}",            # O is still all zero on the first tile
+          f"s_and_b64 {sp(FLAGO[b])}, vcc, {sp(flag)}",
           f"v_max_f32 {v(T1)}, {v(m)}, {v(MX)}",
           f"v_cndmask_b32 {v(T1)}, {v(m)}, {v(T1)}, {sp(flag)}",
           f"v_sub_f32 {v(T2)}, {v(m)}, {v(T1)}",
@@ -265,7 +273,7 @@ def softmax_slow(b, s, p):
 def rescale(out, b, settle):
     """O_b *= corr_b when block b's running maximum moved (rare after the first tiles)."""
     skip = out.label("nr")
-    out.e(f"s_cmp_lg_u64 {sp(FLAG[b])}, 0")
+    out.e(f"s_cmp_lg_u64 {sp(FLAGO[b])}, 0")
     out.e(f"s_cbranch_scc0 {skip}")
     if settle:
         out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
@@ -303,7 +311,7 @@ def merge(out, steps, valu, lead=0, lead_lines=()):
     out.ext(valu[done_v:])
 
 
-def qk_steps(fifo, s0, s1, next_reads, extra=None):
+def qk_steps(fifo, s0, s1, next_reads, extra=None, blocks=(0, 1)):
     """Matrix side of S0, S1 = K Q^T over the 16 K fragments of a tile (fragments 0..PF-1
     already requested), two fragments = four matrix ops per step.  next_reads(i) = reads to
     request once the K reads ran out; extra[i] = further lines ahead of step i."""
@@ -323,6 +331,8 @@ def qk_steps(fifo, s0, s1, next_reads, extra=None):
         for g in (f, f + 1):
             kk, kb = g >> 1, g & 1
             for b, sb in ((0, s0), (1, s1)):
+                if b not in blocks:
+                    continue
                 d = vr(sb + 16 * kb, 16)
                 c = "0" if kk == 0 else d
                 mf.append(f"v_mfma_f32_32x32x16_bf16 {d}, {vr(slot(g), 4)}, {ar(Q[b] + 4 * kk, 4)}, {c}")
@@ -330,7 +340,7 @@ def qk_steps(fifo, s0, s1, next_reads, extra=None):
     return steps
 
 
-def pv_steps(fifo, p0, p1, next_reads):
+def pv_steps(fifo, p0, p1, next_reads, blocks=(0, 1)):
     """Matrix side of O0, O1 += V^T P^T over the 16 V fragments of a tile."""
     steps = []
     for j in range(0, 16, 2):
@@ -349,6 +359,8 @@ def pv_steps(fifo, p0, p1, next_reads):
         for i in (j, j + 1):
             g, db = i >> 2, i & 3
             for b, pb in ((0, p0), (1, p1)):
+                if b not in blocks:
+                    continue
                 d = ar(O[b] + 16 * db, 16)
                 mf.append(f"v_mfma_f32_32x32x16_bf16 {d}, {vr(slot(i), 4)}, {vr(pb + 4 * g, 4)}, {d}")
         steps.append((pre, wait, mf))
@@ -419,48 +431,71 @@ def k_prefetch_tags():
     return [("K", i) for i in range(PF)]
 
 
-def body(out, par):
-    """Iteration t of parity par = t % 2 with t < (last tile of this wave)."""
-    fifo = Fifo(k_prefetch_tags())
+def mask_block(out, b, s):
+    """Causal mask of block b's diagonal tile.  A block whose index inside the 256-row
+    workgroup block is even starts a 64-key tile (first key sub-block partial, second fully
+    masked); an odd one sits in the tile's second half (second sub-block partial).  Block 0
+    of wave w has index w, block 1 index 7 - w."""
+    up, done = out.label("mu"), out.label("md")
+    return ([f"s_cmp_eq_u32 %[wodd], {b}", f"s_cbranch_scc0 {up}"]
+            + mask_partial(s) + mask_full(s + 16) + [f"s_branch {done}", f"{up}:"]
+            + mask_partial(s + 16) + [f"{done}:"])
 
-    def next_v(i):
+
+def reader(fifo, kind):
+    def nxt(i):
+        if kind == "K":
+            fifo.push(("K", i))
+            return k_read(i)
         fifo.push(("V", i))
         fifo.push(("V", i))
         return v_read(i)
+    return nxt
 
-    def next_k(i):
-        fifo.push(("K", i))
-        return k_read(i)
 
-    # ---- X: S0(t+1), S1(t+1) on the matrix cores | softmax of S1(t)
-    out.e(f"; ---- X phase, parity {par}")
-    steps = qk_steps(fifo, S0, S1[1 - par], next_v, extra=dma_pieces(out))
+def phase_x(out, fifo, par, blocks):
+    """Matrix ops: logits of tile t+1 for `blocks` | vector ops: softmax of S1(t)."""
+    out.e(f"; ---- X phase, parity {par}, blocks {blocks}")
+    steps = qk_steps(fifo, S0, S1[1 - par], reader(fifo, "V"), extra=dma_pieces(out), blocks=blocks)
     valu, far = softmax(out, 1, S1[par], P1)
     out.far += far
     merge(out, steps, valu)
     rescale(out, 1, settle=False)
-    # ---- Y: O += V(t)^T P(t) | softmax of S0(t+1)
-    out.e(f"; ---- Y phase, parity {par}")
-    steps = pv_steps(fifo, P0[par], P1, next_k)
+
+
+def phase_y(out, fifo, par, blocks, sm0):
+    """Matrix ops: O += V(t)^T P(t) for `blocks` | vector ops: softmax of S0(t+1) (if sm0)."""
+    out.e(f"; ---- Y phase, parity {par}, blocks {blocks}")
+    steps = pv_steps(fifo, P0[par], P1, reader(fifo, "K"), blocks=blocks)
+    if not sm0:
+        merge(out, steps, [])
+        return
     nomask = out.label("nm")
-    lead = ["s_nop 7",
-            f"s_add_u32 s{ST0}, s{T}, 1",
-            f"s_cmp_eq_u32 s{ST0}, s{TFIN}",
-            f"s_cbranch_scc0 {nomask}"] + mask_partial(S0) + mask_full(S0 + 16) + [f"{nomask}:"]
+    lead = (["s_nop 7", f"s_add_u32 s{ST0}, s{T}, 1", f"s_cmp_eq_u32 s{ST0}, s{TF0}",
+             f"s_cbranch_scc0 {nomask}"] + mask_block(out, 0, S0) + [f"{nomask}:"])
     valu, far = softmax(out, 0, S0, P0[1 - par])
     out.far += far
     merge(out, steps, valu, lead=2, lead_lines=lead)
     rescale(out, 0, settle=True)
+
+
+def iteration(out, par, kind):
+    """Iteration t of parity par.  kind: "both" (t before block 0's last tile), "split" (t is
+    block 0's last tile: its logits are complete, only its last O update remains), "one"
+    (only block 1 is still running)."""
+    fifo = Fifo(k_prefetch_tags())
+    phase_x(out, fifo, par, (0, 1) if kind == "both" else (1,))
+    phase_y(out, fifo, par, (1,) if kind == "one" else (0, 1), sm0=(kind == "both"))
     assert fifo.q == k_prefetch_tags()
 
 
 def final(out, par):
-    """Last tile of this wave (the one holding the diagonal): softmax of S1, then O += V^T P."""
+    """Block 1's last tile (the one holding its diagonal): softmax of S1, then O1 += V^T P1."""
     out.e(f"; ---- final, parity {par}")
     dma(out, "K")
     dma(out, "V")
     out.e("s_waitcnt lgkmcnt(0)")
-    out.ext(mask_partial(S1[par] + 16))
+    out.ext(mask_block(out, 1, S1[par]))
     fifo = Fifo()
     pre = []
     for j in range(PF):
@@ -472,7 +507,7 @@ def final(out, par):
     out.far += far
     out.ext(valu)
     rescale(out, 1, settle=False)
-    steps = pv_steps(fifo, P0[par], P1, lambda i: [])
+    steps = pv_steps(fifo, P0[par], P1, lambda i: [], blocks=(1,))
     merge(out, steps, [])
     assert not fifo.q
 
@@ -495,14 +530,15 @@ def prologue(out):
     out.e(f"s_mov_b64 {sp(KP)}, %[kg]")
     out.e(f"s_mov_b64 {sp(VP)}, %[vg]")
     out.e(f"s_mov_b32 s{T}, 0")
-    out.e(f"s_mov_b32 s{TFIN}, %[tfin]")
+    out.e(f"s_mov_b32 s{TF0}, %[tf0]")
+    out.e(f"s_mov_b32 s{TF1}, %[tf1]")
     out.e(f"s_mov_b32 s{NTMAX}, %[ntmax]")
     out.e(f"s_mov_b32 s{KJ}, 0")
     out.e(f"s_mov_b32 s{VJ}, 0")
     out.e(f"s_mov_b32 s{KST}, 0")
     out.e(f"s_mov_b32 s{VST}, 0")
     for kk in range(8):
-        out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw] offset:{kk * 32}")
+        out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw0] offset:{kk * 32}")
     for kk in range(8):
         out.e(f"global_load_dwordx4 {ar(Q[1] + 4 * kk, 4)}, %[qoff], %[qw1] offset:{kk * 32}")
     for which in "KKVKVKV":
@@ -525,9 +561,9 @@ def prologue(out):
     assert fifo.q == k_prefetch_tags()
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     nomask = out.label("nm")
-    out.e(f"s_cmp_eq_u32 s{TFIN}, 0")
+    out.e(f"s_cmp_eq_u32 s{TF0}, 0")
     out.e(f"s_cbranch_scc0 {nomask}")
-    out.ext(mask_partial(S0) + mask_full(S0 + 16))
+    out.ext(mask_block(out, 0, S0))
     out.e(f"{nomask}:")
     valu, far = softmax(out, 0, S0, P0[0])
     out.far += far
@@ -539,7 +575,6 @@ def epilogue(out):
     out.e("s_barrier")          # every wave is done with the K/V stages; they become the strips
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     inv, lg, adr = TMP + 12, TMP + 13, TMP + 14
-    out.e(f"s_mov_b64 {sp(OB)}, %[ow]")
     for b in (0, 1):
         l, m = L[b], M[b]
         out.ext([f"v_mov_b32 {v(T1)}, {v(l)}", "s_nop 1",
@@ -549,7 +584,7 @@ def epilogue(out):
                  f"v_rcp_f32 {v(inv)}, {v(l)}",
                  "s_nop 0",
                  f"v_add_f32 {v(lg)}, {v(lg)}, {v(m)}",
-                 f"global_store_dword %[l32x4], {v(lg)}, %[lsew] offset:{b * 128}"])
+                 f"global_store_dword %[l32x4], {v(lg)}, %[lsew{b}]"])
         n = 0
         for db in range(4):
             for i4 in range(4):
@@ -572,8 +607,9 @@ def epilogue(out):
             out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_r]")
             out.e(f"ds_read_b128 {vr(S1[0] + 4 * u, 4)}, {v(adr)} offset:{u * 1024}")
         out.e("s_waitcnt lgkmcnt(0)")
+        out.e(f"s_mov_b64 {sp(OB)}, %[ow{b}]")
         for u in range(8):
-            if u == 4 or (u == 0 and b == 1):
+            if u == 4:
                 out.e(f"s_add_u32 s{OB}, s{OB}, 4096")
                 out.e(f"s_addc_u32 s{OB + 1}, s{OB + 1}, 0")
             out.e(f"global_store_dwordx4 %[lanex16], {vr(S1[0] + 4 * u, 4)}, {sp(OB)} offset:{(u & 3) * 1024}")
@@ -582,19 +618,35 @@ def epilogue(out):
 def generate():
     out = Out()
     prologue(out)
-    loop, fin_e, fin_o, drain, epi = (out.label(x) for x in ("loop", "fe", "fo", "dr", "ep"))
-    out.e(f"{loop}:")
-    top(out, fetch=False)
-    out.e(f"s_cmp_eq_u32 s{T}, s{TFIN}")
-    out.e(f"s_cbranch_scc1 {fin_e}")
-    body(out, 0)
+    la, lb_e, lb_o, sp_e, sp_o, fin_e, fin_o, drain, epi = (
+        out.label(x) for x in ("la", "lbe", "lbo", "spe", "spo", "fe", "fo", "dr", "ep"))
+
+    def step(kind, par, last, target):
+        top(out, fetch=False)
+        out.e(f"s_cmp_eq_u32 s{T}, s{last}")
+        out.e(f"s_cbranch_scc1 {target}")
+        iteration(out, par, kind)
+        out.e(f"s_add_u32 s{T}, s{T}, 1")
+
+    # both blocks running: until block 0 reaches its last tile
+    out.e(f"{la}:")
+    step("both", 0, TF0, sp_e)
+    step("both", 1, TF0, sp_o)
+    out.e(f"s_branch {la}")
+    # block 0's last tile (no barrier here: the branch came from a top)
+    out.e(f"{sp_e}:")
+    iteration(out, 0, "split")
     out.e(f"s_add_u32 s{T}, s{T}, 1")
-    top(out, fetch=False)
-    out.e(f"s_cmp_eq_u32 s{T}, s{TFIN}")
-    out.e(f"s_cbranch_scc1 {fin_o}")
-    body(out, 1)
+    out.e(f"s_branch {lb_o}")
+    out.e(f"{sp_o}:")
+    iteration(out, 1, "split")
     out.e(f"s_add_u32 s{T}, s{T}, 1")
-    out.e(f"s_branch {loop}")
+    # only block 1 running: until its last tile
+    out.e(f"{lb_e}:")
+    step("one", 0, TF1, fin_e)
+    out.e(f"{lb_o}:")
+    step("one", 1, TF1, fin_o)
+    out.e(f"s_branch {lb_e}")
     out.e(f"{fin_e}:")
     final(out, 0)
     out.e(f"s_branch {drain}")

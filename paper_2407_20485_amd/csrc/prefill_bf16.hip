@@ -677,7 +677,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, h = lane >> 5;
-  const int row0 = qb * kX2Rows, wrow0 = row0 + wave * 64;
+  const int row0 = qb * kX2Rows;
   const unsigned lds0 = (unsigned)(size_t)smem;  // LDS byte address of the stage ring
 
   // K fragment (16 d-chunk 2kk+h of key row l32): row base and the kk-independent swizzle term
@@ -698,15 +698,22 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
   const unsigned strip_w = strip + l32 * 256 + 8 * h, x16 = (unsigned)((l32 & 15) << 4);
   const unsigned strip_r = strip + rr * 256, crr16 = (unsigned)((pc ^ rr) << 4);
 
+  // Rows: the 256-row block is cut into eight 32-row blocks; wave w owns blocks w ("block 0")
+  // and 7 - w ("block 1"), so that every wave has the same number of key tiles to go through
+  // although the rows further down see more keys.
   const size_t head = (size_t)g * n;
+  const int r0 = row0 + 32 * wave, r1 = row0 + 32 * (7 - wave);
   const bf16_t* kg = K + head * 128;
   const bf16_t* vg = V + head * 128;
-  const bf16_t* qw = Q + (head + wrow0) * 128;
-  const bf16_t* qw1 = qw + 32 * 128;
-  bf16_t* ow = O + (head + wrow0) * 128;
-  float* lsew = LSE2 + head + wrow0;
-  const int tfin = wrow0 >> 6;        // this wave's last key tile (the one with the diagonal)
-  const int ntmax = (row0 >> 6) + 4;  // key tiles the workgroup streams
+  const bf16_t* qw0 = Q + (head + r0) * 128;
+  const bf16_t* qw1 = Q + (head + r1) * 128;
+  bf16_t* ow0 = O + (head + r0) * 128;
+  bf16_t* ow1 = O + (head + r1) * 128;
+  float* lsew0 = LSE2 + head + r0;
+  float* lsew1 = LSE2 + head + r1;
+  const int tf0 = r0 >> 6, tf1 = r1 >> 6;  // last key tile of each block (the one with its diagonal)
+  const int ntmax = (row0 >> 6) + 4;       // key tiles the workgroup streams
+  const int wodd = wave & 1;
   const unsigned wave_lds = lds0 + wave * 1024;
 
   asm volatile(A2SF_FWD128X2_ASM
@@ -715,8 +722,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
                  [kl0] "v"(kl0), [vl0] "v"(vl0), [qoff] "v"(qoff), [lv] "v"(lv),
                  [l32x4] "v"(l32x4), [lanex16] "v"(lanex16), [strip_w] "v"(strip_w),
                  [x16] "v"(x16), [crr16] "v"(crr16), [strip_r] "v"(strip_r), [kg] "s"(kg),
-                 [vg] "s"(vg), [qw] "s"(qw), [qw1] "s"(qw1), [ow] "s"(ow), [lsew] "s"(lsew),
-                 [tfin] "s"(tfin), [ntmax] "s"(ntmax), [wave_lds] "s"(wave_lds),
+                 [vg] "s"(vg), [qw0] "s"(qw0), [qw1] "s"(qw1), [ow0] "s"(ow0), [ow1] "s"(ow1),
+                 [lsew0] "s"(lsew0), [lsew1] "s"(lsew1), [tf0] "s"(tf0), [tf1] "s"(tf1),
+                 [ntmax] "s"(ntmax), [wodd] "s"(wodd), [wave_lds] "s"(wave_lds),
                  [scale] "s"(scale_log2e)
                : A2SF_FWD128X2_CLOBBERS);
 }
