@@ -60,7 +60,8 @@ O = (0, 64)             # O^T accumulators: 4 blocks of 32 d x 16 registers each
 Q = (128, 160)          # Q fragments: 8 x 4 registers each
 NA = 192
 # ---- scalar registers -----------------------------------------------------------------
-KP, VP = 40, 42         # global pointer of the next K / V tile to fetch
+KP, VP = 40, 42         # global pointers of the head's K and V
+NTM1 = 68               # NTMAX - 1
 T, TF0, NTMAX = 44, 45, 46   # iteration, block 0's last tile, tiles the workgroup streams
 TF1 = 53                      # block 1's last tile
 KJ, VJ = 47, 48         # index of the next K / V tile to fetch
@@ -71,7 +72,9 @@ FLAGO = (54, 66)        # per block: nonzero when O has to be rescaled (moved, a
 ST0, ST1 = 60, 61
 PAIR = 62               # scratch pair
 OB = 64                 # output base pair
-SLO, SHI = 40, 67
+SLO, SHI = 40, 87
+STAMP = 70              # --stamps: eight timestamps (s_memtime) in s[70:85]
+STAMPS = False          # development aid: the stamps overwrite the first output row of the wave
 
 STAGE = 32768           # one LDS stage: K tile (16 KB) then V tile (16 KB)
 NSTAGE = 4
@@ -126,6 +129,24 @@ class Fifo:
         self.q = self.q[idx + 1:]
         assert left <= 15
         return f"s_waitcnt lgkmcnt({left})"
+
+
+def stamp(out, k, mode=1):
+    if STAMPS == mode:
+        out.e(f"s_memtime {sp(STAMP + 2 * k)}")
+
+
+def stamps_store(out):
+    if not STAMPS:
+        return
+    out.e("s_waitcnt vmcnt(0) lgkmcnt(0)")
+    out.e("s_mov_b64 exec, 1")
+    out.e(f"v_mov_b32 {v(TMP + 15)}, 0")
+    for q in range(4):
+        for k in range(4):
+            out.e(f"v_mov_b32 {v(TMP + k)}, s{STAMP + 4 * q + k}")
+        out.e(f"global_store_dwordx4 {v(TMP + 15)}, {vr(TMP, 4)}, %[ow0] offset:{16 * q}")
+    out.e("s_mov_b64 exec, -1")
 
 
 def slot(f):
@@ -289,25 +310,32 @@ def rescale(out, b, settle):
 
 
 def merge(out, steps, valu, lead=0, lead_lines=()):
-    """Interleave: every matrix op is followed by its share of the vector-op list.  `lead`
-    matrix ops are issued before any vector op (then `lead_lines`)."""
+    """Interleave one phase: every matrix op is followed by its share of the vector-op list
+    and by its share of the NEXT step's operand requests, so that the issue stream between
+    two matrix ops is short and even (a lone wave issues about one instruction per 4.5
+    cycles; a matrix op occupies its pipe for 32).  `lead` matrix ops are issued before any
+    vector op (then `lead_lines`)."""
     mf = sum(len(s[2]) for s in steps)
     slots = max(mf - lead, 1)
     done_v, seen = 0, 0
-    for pre, wait, mfmas in steps:
-        out.ext(pre)
+    out.ext(steps[0][0])
+    for k, (pre, wait, mfmas) in enumerate(steps):
+        nxt = steps[k + 1][0] if k + 1 < len(steps) else []
+        done_n = 0
         if wait:
             out.e(wait)
-        for m in mfmas:
+        for j, m in enumerate(mfmas):
             out.e(m)
             seen += 1
             if seen == lead:
                 out.ext(lead_lines)
             if seen > lead or lead == 0:
-                k = seen - lead
-                upto = (len(valu) * k + slots - 1) // slots
+                upto = (len(valu) * (seen - lead) + slots - 1) // slots
                 out.ext(valu[done_v:upto])
                 done_v = upto
+            upto_n = (len(nxt) * (j + 1)) // len(mfmas)
+            out.ext(nxt[done_n:upto_n])
+            done_n = upto_n
     out.ext(valu[done_v:])
 
 
@@ -367,44 +395,37 @@ def pv_steps(fifo, p0, p1, next_reads, blocks=(0, 1)):
     return steps
 
 
+def dma_lines(j, base, lo, off):
+    """Fetch of tile number s[j] (clamped to the last tile: past the end the last tile is
+    simply fetched again, which keeps the stream free of branches and the vmcnt bookkeeping
+    uniform) into LDS stage s[j] % NSTAGE; then s[j] += 1."""
+    ln = [f"s_min_u32 s{ST1}, s{j}, s{NTM1}",
+          f"s_lshl_b32 s{ST1}, s{ST1}, 14",
+          f"s_add_u32 s{PAIR}, s{base}, s{ST1}",
+          f"s_addc_u32 s{PAIR + 1}, s{base + 1}, 0",
+          f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
+          f"s_lshl_b32 s{ST1}, s{ST1}, 15",
+          f"s_add_u32 s{ST1}, s{ST1}, %[wave_lds]"]
+    for u in range(4):
+        ln += [f"s_add_u32 m0, s{ST1}, {off + u * 4096}", "s_nop 0",
+               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(PAIR)}"]
+    ln.append(f"s_add_u32 s{j}, s{j}, 1")
+    return ln
+
+
 def dma_pieces(out):
-    """The fetch of {K(t+4), V(t+3)} cut into four pieces that ride in front of the first
-    matrix-op steps of phase X (same instruction order as dma(K); dma(V))."""
-    pieces = {}
-    for n, (j, p, lo, off) in enumerate(((KJ, KP, KL, 0), (VJ, VP, VL, 16384))):
-        for half in (0, 1):
-            skip = out.label("np")
-            ln = [f"s_cmp_lt_u32 s{j}, s{NTMAX}", f"s_cbranch_scc0 {skip}"]
-            if half == 0:
-                ln += [f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
-                       f"s_lshl_b32 s{ST1}, s{ST1}, 15",
-                       f"s_add_u32 s{ST1}, s{ST1}, %[wave_lds]"]
-            for u in (2 * half, 2 * half + 1):
-                ln += [f"s_add_u32 m0, s{ST1}, {off + u * 4096}", "s_nop 0",
-                       f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)}"]
-            if half == 1:
-                ln += [f"s_add_u32 s{p}, s{p}, 16384", f"s_addc_u32 s{p + 1}, s{p + 1}, 0",
-                       f"s_add_u32 s{j}, s{j}, 1"]
-            ln.append(f"{skip}:")
-            pieces[2 * n + half] = ln
-    return pieces
+    """The fetch of {K(t+4), V(t+3)}, to ride between the first matrix ops of phase X."""
+    return {1: dma_lines(KJ, KP, KL, 0), 3: dma_lines(VJ, VP, VL, 16384)}
 
 
 def dma(out, which):
-    j, p, lo, off = (KJ, KP, KL, 0) if which == "K" else (VJ, VP, VL, 16384)
+    """Same fetch as one block, skipped when the tile does not exist (prologue, last tile,
+    drain: places where nothing is interleaved)."""
+    j, base, lo, off = (KJ, KP, KL, 0) if which == "K" else (VJ, VP, VL, 16384)
     skip = out.label("nd")
     out.e(f"s_cmp_lt_u32 s{j}, s{NTMAX}")
     out.e(f"s_cbranch_scc0 {skip}")
-    out.e(f"s_and_b32 s{ST0}, s{j}, {NSTAGE - 1}")
-    out.e(f"s_lshl_b32 s{ST0}, s{ST0}, 15")
-    out.e(f"s_add_u32 s{ST0}, s{ST0}, %[wave_lds]")
-    for u in range(4):
-        out.e(f"s_add_u32 m0, s{ST0}, {off + u * 4096}")
-        out.e("s_nop 0")
-        out.e(f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)}")
-    out.e(f"s_add_u32 s{p}, s{p}, 16384")
-    out.e(f"s_addc_u32 s{p + 1}, s{p + 1}, 0")
-    out.e(f"s_add_u32 s{j}, s{j}, 1")
+    out.ext(dma_lines(j, base, lo, off))
     out.e(f"{skip}:")
 
 
@@ -514,6 +535,8 @@ def final(out, par):
 
 def prologue(out):
     out.e("; ---- prologue")
+    stamp(out, 0)
+    stamp(out, 0, 2)
     out.e(f"v_mov_b32 {v(NEGINF)}, 0xff800000")
     for b in (0, 1):
         out.e(f"v_mov_b32 {v(M[b])}, {v(NEGINF)}")
@@ -533,6 +556,7 @@ def prologue(out):
     out.e(f"s_mov_b32 s{TF0}, %[tf0]")
     out.e(f"s_mov_b32 s{TF1}, %[tf1]")
     out.e(f"s_mov_b32 s{NTMAX}, %[ntmax]")
+    out.e(f"s_sub_u32 s{NTM1}, s{NTMAX}, 1")
     out.e(f"s_mov_b32 s{KJ}, 0")
     out.e(f"s_mov_b32 s{VJ}, 0")
     out.e(f"s_mov_b32 s{KST}, 0")
@@ -541,24 +565,26 @@ def prologue(out):
         out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw0] offset:{kk * 32}")
     for kk in range(8):
         out.e(f"global_load_dwordx4 {ar(Q[1] + 4 * kk, 4)}, %[qoff], %[qw1] offset:{kk * 32}")
-    for which in "KKVKVKV":
-        dma(out, which)
+    stamp(out, 1, 2)
+    out.ext(dma_lines(KJ, KP, KL, 0))                       # K(0)
+    stamp(out, 2, 2)
     for i in range(128):
         out.e(f"v_accvgpr_write_b32 a{i}, 0")
-    out.e("s_waitcnt vmcnt(16)")   # Q, K(0), K(1), V(0)
+    stamp(out, 3, 2)
+    stamp(out, 1)
+    out.e("s_waitcnt vmcnt(0)")    # Q and K(0): all the first logits need
     out.e("s_barrier")
-    # S0(0), S1(0)
+    stamp(out, 2)
+    stamp(out, 4, 2)
+    # S0(0), S1(0); the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are issued on the way
     fifo = Fifo()
     for f in range(PF):
         out.ext(k_read(f))
         fifo.push(("K", f))
-
-    def next_k(i):
-        fifo.push(("K", i))
-        return k_read(i)
-
-    merge(out, qk_steps(fifo, S0, S1[0], next_k), [])
-    assert fifo.q == k_prefetch_tags()
+    extra = {i + 1: dma_lines(*((KJ, KP, KL, 0) if w == "K" else (VJ, VP, VL, 16384)))
+             for i, w in enumerate("KVKVKV")}
+    merge(out, qk_steps(fifo, S0, S1[0], lambda i: [], extra=extra), [])
+    assert not fifo.q
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     nomask = out.label("nm")
     out.e(f"s_cmp_eq_u32 s{TF0}, 0")
@@ -568,13 +594,24 @@ def prologue(out):
     valu, far = softmax(out, 0, S0, P0[0])
     out.far += far
     out.ext(valu)
+    # K(1) and V(0) have landed for every wave (K(2) V(1) K(3) V(2) may still be under way)
+    out.e("s_waitcnt vmcnt(16)")
+    out.e("s_barrier")
+    for f in range(PF):
+        out.ext(k_read(f))
 
 
 def epilogue(out):
+    """Normalise, round to bf16 and store O; store the base-2 log-sum-exp.  A lane holds four
+    consecutive d of one row at a time, so the 2 x (32 x 128) block of the wave is transposed
+    through a 16 KB strip of LDS (16-byte chunks XOR-swizzled by the row) and leaves as whole
+    256-byte rows, four rows per store instruction."""
     out.e("; ---- epilogue")
+    out.e("s_waitcnt vmcnt(0)")
     out.e("s_barrier")          # every wave is done with the K/V stages; they become the strips
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     inv, lg, adr = TMP + 12, TMP + 13, TMP + 14
+    n = 0
     for b in (0, 1):
         l, m = L[b], M[b]
         out.ext([f"v_mov_b32 {v(T1)}, {v(l)}", "s_nop 1",
@@ -585,7 +622,6 @@ def epilogue(out):
                  "s_nop 0",
                  f"v_add_f32 {v(lg)}, {v(lg)}, {v(m)}",
                  f"global_store_dword %[l32x4], {v(lg)}, %[lsew{b}]"])
-        n = 0
         for db in range(4):
             for i4 in range(4):
                 t = TMP + 4 * (n % 2)          # two sets of four temporaries
@@ -599,20 +635,23 @@ def epilogue(out):
                 out.e(f"v_cvt_pk_bf16_f32 {v(w + 1)}, {v(t + 2)}, {v(t + 3)}")
                 out.e(f"v_xor_b32 {v(adr)}, {(4 * db + i4) * 16}, %[x16]")
                 out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_w]")
-                out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)}")
+                out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)} offset:{b * 8192}")
                 n += 1
-        out.e("s_waitcnt lgkmcnt(0)")
+    out.e("s_waitcnt lgkmcnt(0)")
+    stamp(out, 6, 2)
+    for b in (0, 1):
         for u in range(8):
             out.e(f"v_xor_b32 {v(adr)}, {64 * (u & 3)}, %[crr16]")
             out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_r]")
-            out.e(f"ds_read_b128 {vr(S1[0] + 4 * u, 4)}, {v(adr)} offset:{u * 1024}")
-        out.e("s_waitcnt lgkmcnt(0)")
+            out.e(f"ds_read_b128 {vr(S1[b] + 4 * u, 4)}, {v(adr)} offset:{b * 8192 + u * 1024}")
+    for b in (0, 1):
+        out.e(f"s_waitcnt lgkmcnt({8 * (1 - b)})")
         out.e(f"s_mov_b64 {sp(OB)}, %[ow{b}]")
         for u in range(8):
             if u == 4:
                 out.e(f"s_add_u32 s{OB}, s{OB}, 4096")
                 out.e(f"s_addc_u32 s{OB + 1}, s{OB + 1}, 0")
-            out.e(f"global_store_dwordx4 %[lanex16], {vr(S1[0] + 4 * u, 4)}, {sp(OB)} offset:{(u & 3) * 1024}")
+            out.e(f"global_store_dwordx4 %[lanex16], {vr(S1[b] + 4 * u, 4)}, {sp(OB)} offset:{(u & 3) * 1024}")
 
 
 def generate():
@@ -629,6 +668,7 @@ def generate():
         out.e(f"s_add_u32 s{T}, s{T}, 1")
 
     # both blocks running: until block 0 reaches its last tile
+    stamp(out, 3)
     out.e(f"{la}:")
     step("both", 0, TF0, sp_e)
     step("both", 1, TF0, sp_o)
@@ -648,18 +688,26 @@ def generate():
     step("one", 1, TF1, fin_o)
     out.e(f"s_branch {lb_e}")
     out.e(f"{fin_e}:")
+    stamp(out, 4)
     final(out, 0)
     out.e(f"s_branch {drain}")
     out.e(f"{fin_o}:")
+    stamp(out, 4)
     final(out, 1)
     out.e(f"{drain}:")
+    stamp(out, 5)
     out.e(f"s_add_u32 s{T}, s{T}, 1")
     out.e(f"s_cmp_lt_u32 s{T}, s{NTMAX}")
     out.e(f"s_cbranch_scc0 {epi}")
     top(out)
     out.e(f"s_branch {drain}")
     out.e(f"{epi}:")
+    stamp(out, 6)
+    stamp(out, 5, 2)
     epilogue(out)
+    stamp(out, 7)
+    stamp(out, 7, 2)
+    stamps_store(out)
     done = out.label("done")
     out.e(f"s_branch {done}")
     out.ext(out.far)
@@ -686,6 +734,12 @@ def dropped(ln):
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     args = sys.argv[1:]
+    if "--stamps" in args:
+        args.remove("--stamps")
+        globals()["STAMPS"] = 1
+    if "--stamps2" in args:
+        args.remove("--stamps2")
+        globals()["STAMPS"] = 2
     while "--drop" in args:  # e.g. --drop mfma --drop softmax: measures what the rest costs
         i = args.index("--drop")
         DROP.add(args[i + 1])

@@ -693,8 +693,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
   const unsigned qoff = (unsigned)(l32 * 256 + h * 16);
   const int lv = l32 - 4 * h;
   const unsigned l32x4 = l32 * 4, lanex16 = lane * 16;
-  // epilogue: a wave's 32 x 128 output block goes through its own 8 KB strip of LDS
-  const unsigned strip = lds0 + wave * 8192;
+  // epilogue: a wave's two 32 x 128 output blocks go through its own 16 KB strip of LDS
+  const unsigned strip = lds0 + wave * 16384;
   const unsigned strip_w = strip + l32 * 256 + 8 * h, x16 = (unsigned)((l32 & 15) << 4);
   const unsigned strip_r = strip + rr * 256, crr16 = (unsigned)((pc ^ rr) << 4);
 

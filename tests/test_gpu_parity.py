@@ -147,6 +147,43 @@ def test_prefill_optional_outputs(base, d, n):
             assert torch.equal(a, b), (want_o, want_s)
 
 
+@pytest.mark.parametrize("d,n", [(128, 256), (128, 512), (128, 1024), (128, 1280), (128, 300), (64, 320)])
+@pytest.mark.parametrize("rise", [200.0, -60.0, 40.0])
+def test_prefill_moving_maximum(d, n, rise, say):
+    """Logits that climb (or fall) by `rise` base-2 units over the sequence: the running maximum
+    of the online softmax has to move again and again, in every phase of the tile loop, for
+    both row blocks of a wave and in the tiles that hold the diagonal.  Outputs, and the scores
+    (which depend on the log-sum-exp the attention pass leaves behind), against the oracle."""
+    G, alpha = 3, 0.97
+    rng = np.random.Generator(np.random.Philox(key=[n, d + int(abs(rise))]))
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    a = math.sqrt(abs(rise) * math.log(2.0) * math.sqrt(d))      # q.k / sqrt(d) spans |rise| ln 2
+    q = rng.standard_normal((G, n, d)) + a * u
+    k = rng.standard_normal((G, n, d)) + math.copysign(a, rise) * (np.arange(n) / n)[None, :, None] * u
+    v = rng.standard_normal((G, n, d))
+    bits = [synth.round_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v)]
+    host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+    dev = [parity.to_device(b, "bf16") for b in bits]
+    select = recent = 8
+    cache = a2sf.Cache(G, select + recent + 1, d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, n, select + recent + 1, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    o = torch.full((G, n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sf = torch.full((G, n), float("nan"), dtype=torch.float32, device="cuda")
+    a2sf.a2sf_prefill(dev[0], dev[1], dev[2], n, alpha, select, recent, cache, o=o, scores_full=sf, workspace=ws)
+    torch.cuda.synchronize()
+    o_err = s_rel = 0.0
+    for g in range(G):
+        P = orc.causal_probabilities(host[0][g], host[1][g])
+        o_err = max(o_err, float(np.abs(parity.to_f64(o[g]) - orc.attention_output(P, host[2][g])).max()))
+        S = orc.forgotten_scores(P, alpha)
+        s_rel = max(s_rel, float((np.abs(parity.to_f64(sf[g]) - S) / np.maximum(np.abs(S), 1e-30)).max()))
+    say(f"  [moving maximum d={d} n={n} rise={rise}] |o err|={o_err:.2e} score rel={s_rel:.2e}")
+    assert o_err <= parity.O_TOL["bf16"]
+    assert s_rel <= parity.SCORE_RTOL
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_small_fp32(d, say):
     w = variant(0, heads=3, d=d, n=150, T=5, select=9, recent=4, name=f"f32 d{d}")
