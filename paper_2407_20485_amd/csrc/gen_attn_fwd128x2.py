@@ -65,8 +65,6 @@ NTM1 = 68               # NTMAX - 1
 T, TF0, NTMAX = 44, 45, 46   # iteration, block 0's last tile, tiles the workgroup streams
 TF1 = 53                      # block 1's last tile
 KJ, VJ = 47, 48         # index of the next K / V tile to fetch
-KST, VST = 49, 50       # LDS stage the K / V fragment addresses point at
-KD, VD = 51, 52
 FLAG = (56, 58)         # per block: all ones when the running maximum moved
 FLAGO = (54, 66)        # per block: nonzero when O has to be rescaled (moved, and not from -inf)
 ST0, ST1 = 60, 61
@@ -153,26 +151,23 @@ def slot(f):
     return RING + 4 * (f % 8)
 
 
-def k_read(f):
+# Tile j lives in LDS stage j % 4.  Bit 0 of the stage is known where the code is generated (the
+# loop is unrolled by two) and goes into the instruction's immediate offset; bit 1 is bit 16 of
+# the fragment address registers, toggled once every second iteration.
+def k_read(f, odd):
     kk, kb = f >> 1, f & 1
-    return [f"ds_read_b128 {vr(slot(f), 4)}, {v(KADDR + kk)} offset:{kb * 8192}"]
+    return [f"ds_read_b128 {vr(slot(f), 4)}, {v(KADDR + kk)} offset:{odd * STAGE + kb * 8192}"]
 
 
-def v_read(j):
+def v_read(j, odd):
     g, db = j >> 2, j & 3
-    return [f"ds_read_b64_tr_b16 {vr(slot(j), 2)}, {v(VADDR + db)} offset:{g * 4096}",
-            f"ds_read_b64_tr_b16 {vr(slot(j) + 2, 2)}, {v(VADDR + db)} offset:{g * 4096 + 2048}"]
+    o = odd * STAGE + g * 4096
+    return [f"ds_read_b64_tr_b16 {vr(slot(j), 2)}, {v(VADDR + db)} offset:{o}",
+            f"ds_read_b64_tr_b16 {vr(slot(j) + 2, 2)}, {v(VADDR + db)} offset:{o + 2048}"]
 
 
-def advance(addr, count, st, dl):
-    """Point `count` fragment addresses at the next LDS stage (ring of NSTAGE)."""
-    out = [f"s_add_u32 s{ST0}, s{st}, 1",
-           f"s_and_b32 s{ST0}, s{ST0}, {NSTAGE - 1}",
-           f"s_sub_i32 s{dl}, s{ST0}, s{st}",
-           f"s_lshl_b32 s{dl}, s{dl}, 15",
-           f"s_mov_b32 s{st}, s{ST0}"]
-    out += [f"v_add_u32 {v(addr + i)}, s{dl}, {v(addr + i)}" for i in range(count)]
-    return out
+def toggle(addr, count):
+    return [f"v_xor_b32 {v(addr + i)}, 0x10000, {v(addr + i)}" for i in range(count)]
 
 
 def mask_partial(base):
@@ -339,7 +334,7 @@ def merge(out, steps, valu, lead=0, lead_lines=()):
     out.ext(valu[done_v:])
 
 
-def qk_steps(fifo, s0, s1, next_reads, extra=None, blocks=(0, 1)):
+def qk_steps(fifo, s0, s1, odd, flip, next_reads, extra=None, blocks=(0, 1)):
     """Matrix side of S0, S1 = K Q^T over the 16 K fragments of a tile (fragments 0..PF-1
     already requested), two fragments = four matrix ops per step.  next_reads(i) = reads to
     request once the K reads ran out; extra[i] = further lines ahead of step i."""
@@ -348,11 +343,11 @@ def qk_steps(fifo, s0, s1, next_reads, extra=None, blocks=(0, 1)):
         pre = list((extra or {}).get(f // 2, []))
         for g in (f, f + 1):
             if g + PF < 16:
-                pre += k_read(g + PF)
+                pre += k_read(g + PF, odd)
                 fifo.push(("K", g + PF))
             else:
-                if g + PF == 16:
-                    pre += advance(KADDR, 8, KST, KD)
+                if g + PF == 16 and flip:
+                    pre += toggle(KADDR, 8)
                 pre += next_reads(g + PF - 16)
         wait = fifo.wait(("K", f + 1))
         mf = []
@@ -368,19 +363,19 @@ def qk_steps(fifo, s0, s1, next_reads, extra=None, blocks=(0, 1)):
     return steps
 
 
-def pv_steps(fifo, p0, p1, next_reads, blocks=(0, 1)):
+def pv_steps(fifo, p0, p1, odd, flip, next_reads, blocks=(0, 1)):
     """Matrix side of O0, O1 += V^T P^T over the 16 V fragments of a tile."""
     steps = []
     for j in range(0, 16, 2):
         pre = []
         for i in (j, j + 1):
             if i + PF < 16:
-                pre += v_read(i + PF)
+                pre += v_read(i + PF, odd)
                 fifo.push(("V", i + PF))
                 fifo.push(("V", i + PF))
             else:
-                if i + PF == 16:
-                    pre += advance(VADDR, 4, VST, VD)
+                if i + PF == 16 and flip:
+                    pre += toggle(VADDR, 4)
                 pre += next_reads(i + PF - 16)
         wait = fifo.wait(("V", j + 1))
         mf = []
@@ -406,8 +401,11 @@ def dma_lines(j, base, lo, off):
           f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
           f"s_lshl_b32 s{ST1}, s{ST1}, 15",
           f"s_add_u32 s{ST1}, s{ST1}, %[wave_lds]"]
-    for u in range(4):
+    # the instruction's immediate offset moves the global and the LDS address alike, and the
+    # four loads of a wave sit 4 KB apart in both: one M0 value serves two loads
+    for u in (1, 3):
         ln += [f"s_add_u32 m0, s{ST1}, {off + u * 4096}", "s_nop 0",
+               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(PAIR)} offset:-4096",
                f"global_load_lds_dwordx4 {v(lo + u)}, {sp(PAIR)}"]
     ln.append(f"s_add_u32 s{j}, s{j}, 1")
     return ln
@@ -463,21 +461,24 @@ def mask_block(out, b, s):
             + mask_partial(s + 16) + [f"{done}:"])
 
 
-def reader(fifo, kind):
+def reader(fifo, kind, odd):
     def nxt(i):
         if kind == "K":
             fifo.push(("K", i))
-            return k_read(i)
+            return k_read(i, odd)
         fifo.push(("V", i))
         fifo.push(("V", i))
-        return v_read(i)
+        return v_read(i, odd)
     return nxt
 
 
 def phase_x(out, fifo, par, blocks):
     """Matrix ops: logits of tile t+1 for `blocks` | vector ops: softmax of S1(t)."""
     out.e(f"; ---- X phase, parity {par}, blocks {blocks}")
-    steps = qk_steps(fifo, S0, S1[1 - par], reader(fifo, "V"), extra=dma_pieces(out), blocks=blocks)
+    # K(t+1) now; K address bit 16 flips after the last read when t+2 has another bit 1 than t+1;
+    # then the first V(t) fragments
+    steps = qk_steps(fifo, S0, S1[1 - par], 1 - par, par == 0, reader(fifo, "V", par),
+                     extra=dma_pieces(out), blocks=blocks)
     valu, far = softmax(out, 1, S1[par], P1)
     out.far += far
     merge(out, steps, valu)
@@ -487,7 +488,8 @@ def phase_x(out, fifo, par, blocks):
 def phase_y(out, fifo, par, blocks, sm0):
     """Matrix ops: O += V(t)^T P(t) for `blocks` | vector ops: softmax of S0(t+1) (if sm0)."""
     out.e(f"; ---- Y phase, parity {par}, blocks {blocks}")
-    steps = pv_steps(fifo, P0[par], P1, reader(fifo, "K"), blocks=blocks)
+    # V(t) now, then the first K(t+2) fragments
+    steps = pv_steps(fifo, P0[par], P1, par, par == 1, reader(fifo, "K", par), blocks=blocks)
     if not sm0:
         merge(out, steps, [])
         return
@@ -505,8 +507,16 @@ def iteration(out, par, kind):
     block 0's last tile: its logits are complete, only its last O update remains), "one"
     (only block 1 is still running)."""
     fifo = Fifo(k_prefetch_tags())
+    if kind == "both" and par == 0:
+        stamp(out, 1, 3)
     phase_x(out, fifo, par, (0, 1) if kind == "both" else (1,))
+    if kind == "both" and par == 0:
+        stamp(out, 2, 3)
     phase_y(out, fifo, par, (1,) if kind == "one" else (0, 1), sm0=(kind == "both"))
+    if kind == "both" and par == 0:
+        stamp(out, 3, 3)
+    if kind == "both" and par == 1:
+        stamp(out, 5, 3)
     assert fifo.q == k_prefetch_tags()
 
 
@@ -520,7 +530,7 @@ def final(out, par):
     fifo = Fifo()
     pre = []
     for j in range(PF):
-        pre += v_read(j)
+        pre += v_read(j, par)
         fifo.push(("V", j))
         fifo.push(("V", j))
     out.ext(pre)
@@ -528,7 +538,7 @@ def final(out, par):
     out.far += far
     out.ext(valu)
     rescale(out, 1, settle=False)
-    steps = pv_steps(fifo, P0[par], P1, lambda i: [], blocks=(1,))
+    steps = pv_steps(fifo, P0[par], P1, par, False, lambda i: [], blocks=(1,))
     merge(out, steps, [])
     assert not fifo.q
 
@@ -559,8 +569,6 @@ def prologue(out):
     out.e(f"s_sub_u32 s{NTM1}, s{NTMAX}, 1")
     out.e(f"s_mov_b32 s{KJ}, 0")
     out.e(f"s_mov_b32 s{VJ}, 0")
-    out.e(f"s_mov_b32 s{KST}, 0")
-    out.e(f"s_mov_b32 s{VST}, 0")
     for kk in range(8):
         out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw0] offset:{kk * 32}")
     for kk in range(8):
@@ -579,11 +587,11 @@ def prologue(out):
     # S0(0), S1(0); the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are issued on the way
     fifo = Fifo()
     for f in range(PF):
-        out.ext(k_read(f))
+        out.ext(k_read(f, 0))
         fifo.push(("K", f))
     extra = {i + 1: dma_lines(*((KJ, KP, KL, 0) if w == "K" else (VJ, VP, VL, 16384)))
              for i, w in enumerate("KVKVKV")}
-    merge(out, qk_steps(fifo, S0, S1[0], lambda i: [], extra=extra), [])
+    merge(out, qk_steps(fifo, S0, S1[0], 0, False, lambda i: [], extra=extra), [])
     assert not fifo.q
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     nomask = out.label("nm")
@@ -598,7 +606,7 @@ def prologue(out):
     out.e("s_waitcnt vmcnt(16)")
     out.e("s_barrier")
     for f in range(PF):
-        out.ext(k_read(f))
+        out.ext(k_read(f, 1))
 
 
 def epilogue(out):
@@ -661,7 +669,11 @@ def generate():
         out.label(x) for x in ("la", "lbe", "lbo", "spe", "spo", "fe", "fo", "dr", "ep"))
 
     def step(kind, par, last, target):
+        if kind == "both" and par == 0:
+            stamp(out, 0, 3)
         top(out, fetch=False)
+        if kind == "both" and par == 1:
+            stamp(out, 4, 3)
         out.e(f"s_cmp_eq_u32 s{T}, s{last}")
         out.e(f"s_cbranch_scc1 {target}")
         iteration(out, par, kind)
@@ -740,6 +752,9 @@ def main():
     if "--stamps2" in args:
         args.remove("--stamps2")
         globals()["STAMPS"] = 2
+    if "--stamps3" in args:
+        args.remove("--stamps3")
+        globals()["STAMPS"] = 3
     while "--drop" in args:  # e.g. --drop mfma --drop softmax: measures what the rest costs
         i = args.index("--drop")
         DROP.add(args[i + 1])

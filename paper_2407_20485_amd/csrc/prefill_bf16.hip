@@ -663,6 +663,7 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 2 : 1) void attn_fwd128_kernel(
 
 constexpr int kX2Rows = 256;            // query rows per workgroup
 constexpr int kX2LdsBytes = 4 * 32768;  // four stages of one K tile + one V tile
+constexpr int kX2MinRows = 2048;
 
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
@@ -833,7 +834,9 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
   if (D == 128) {
     constexpr int NB = A2SF_FWD128_NB;
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
-    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0) {
+    // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
+    // its start and end (measured crossover between n = 1024 and n = 2048).
+    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && n >= kX2MinRows) {
       const int nqb2 = n / kX2Rows;
       const unsigned grid2 = (unsigned)((((long long)G * nqb2 + 7) / 8) * 8);
       hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st, (const bf16_t*)q,

@@ -147,7 +147,7 @@ def test_prefill_optional_outputs(base, d, n):
             assert torch.equal(a, b), (want_o, want_s)
 
 
-@pytest.mark.parametrize("d,n", [(128, 256), (128, 512), (128, 1024), (128, 1280), (128, 300), (64, 320)])
+@pytest.mark.parametrize("d,n", [(128, 2048), (128, 2304), (128, 1024), (128, 300), (64, 320)])
 @pytest.mark.parametrize("rise", [200.0, -60.0, 40.0])
 def test_prefill_moving_maximum(d, n, rise, say):
     """Logits that climb (or fall) by `rise` base-2 units over the sequence: the running maximum
