@@ -880,6 +880,7 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
 // the logit tiles against the staged Q rows, applies exp2(s - lse_i + (n-1-i) log2 alpha) and
 // sums down the rows.  K is read exactly once, Q's window once per head.
 constexpr int kTailTiles = 4;
+constexpr int kTailKB = 2;  // 32-key blocks per wave and step
 
 __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
@@ -915,64 +916,203 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const int r = r_lo + rb * 32 + l32;
     bias[rb] = (r < n && r >= first_row) ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
   }
-  auto load_keys = [&](int c0, uint4 (&kf)[KK]) {
-    int r = c0 + wave * 32 + l32;
-    r = r < n ? r : n - 1;
+  // A wave owns kTailKB blocks of 32 keys at a time: every Q fragment read from LDS feeds
+  // kTailKB matrix ops (one LDS kilobyte per matrix op is more than the LDS delivers).
+  auto load_keys = [&](int c0, uint4 (&kf)[kTailKB][KK]) {
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) kf[kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+    for (int b = 0; b < kTailKB; ++b) {
+      int r = c0 + (wave * kTailKB + b) * 32 + l32;
+      r = r < n ? r : n - 1;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) kf[b][kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+    }
   };
-  uint4 kf0[KK], kf1[KK];
-  load_keys(0, kf0);
+  uint4 kf[kTailKB][KK];
+  load_keys(0, kf);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
-  auto block = [&](int c0, const uint4 (&kf)[KK]) {
-    const int wc0 = c0 + wave * 32;
-    float acc[16];
+  constexpr int STEP = BC * kTailKB;  // keys per workgroup step
+  for (int c0 = 0; c0 < n; c0 += STEP) {
+    const int wc0 = c0 + wave * kTailKB * 32;  // first key of this wave in this step
+    float acc[kTailKB][16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int b = 0; b < kTailKB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 #pragma unroll
     for (int rb = 0; rb < 2 * kTailTiles; ++rb) {
       const int rr0 = r_lo + rb * 32;
       if (rb < 2 * ntile && rr0 + 31 >= wc0 && rr0 + 31 >= first_row) {  // wave-uniform
-        f32x16 sacc;
+        f32x16 sacc[kTailKB];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+        for (int b = 0; b < kTailKB; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[b][i] = 0.f;
         const lds_char* qt = qs + rb * 32 * 256;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) sacc = mfma_bf16(kf[kk], lds_read16(qt + qoff[kk]), sacc);
-        const int r = rr0 + l32;
-        if (wc0 + 31 > rr0) {  // block touches the diagonal: keys above the row contribute 0
+        for (int kk = 0; kk < KK; ++kk) {
+          const uint4 qf = lds_read16(qt + qoff[kk]);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
-            const float p = fast_exp2(fmaf(sacc[i], scale_log2e, -bias[rb]));
-            acc[i] += key > r ? 0.f : p;
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[i] += fast_exp2(fmaf(sacc[i], scale_log2e, -bias[rb]));
+          for (int b = 0; b < kTailKB; ++b) sacc[b] = mfma_bf16(kf[b][kk], qf, sacc[b]);
         }
+        if (rb == 2 * ntile - 1 && c0 + STEP < n) load_keys(c0 + STEP, kf);  // last use of kf is behind us
+        const int r = rr0 + l32;
+#pragma unroll
+        for (int b = 0; b < kTailKB; ++b) {
+          const int bk0 = wc0 + b * 32;
+          if (bk0 + 31 > rr0) {  // block touches the diagonal: keys above the row contribute 0
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = bk0 + 8 * (i >> 2) + 4 * h + (i & 3);
+              const float p = fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias[rb]));
+              acc[b][i] += key > r ? 0.f : p;
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[b][i] += fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias[rb]));
+          }
+        }
+      } else if (rb == 2 * ntile - 1 && c0 + STEP < n) {
+        load_keys(c0 + STEP, kf);
       }
     }
     // sum over the 32 rows held by the lanes of one half
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = group_sum<32>(acc[i]);
+    for (int b = 0; b < kTailKB; ++b) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[b][i] = group_sum<32>(acc[b][i]);
+      if (l32 == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int key = wc0 + b * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+          if (key < n) Sg[key] = acc[b][i];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// col_scores for a long row window (alpha close to 1), d = 128: the streaming form of
+// col_scores_tail128_kernel.  A workgroup owns 256 key columns (a wave two blocks of 32 keys,
+// their K fragments resident in registers for the whole kernel) and walks down the rows that
+// see them; Q tiles of 64 rows arrive by direct global-to-LDS loads in a ring of four stages,
+// three tiles ahead of the one being used.  One barrier per tile publishes the tile that has
+// landed and frees the stage of the previous one for the next fetch.
+constexpr int kStreamStages = 4;
+constexpr int kStreamKB = 2;  // 32-key blocks per wave
+
+__global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
+    const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
+    float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
+    const float* __restrict__ alpha_heads, float scale_log2e) {
+  constexpr int D = 128, KK = D / 16, BC = kWaves * 32 * kStreamKB;
+  __shared__ __attribute__((aligned(1024))) char smem[kStreamStages * kTileBytes];
+  lds_char* const qs = (lds_char*)smem;
+
+  const long long total = (long long)G * ncb;
+  const long long vid = xcd_contiguous_id(total);
+  if (vid >= total) return;
+  const int g = (int)(vid / ncb);
+  const int cb = (int)(vid % ncb);  // column block 0 has the most rows: first
+  head_window(alpha_heads, g, n, first_row, log2_alpha);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, h = lane >> 5;
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * n * D;
+  const float* lse = LSE2 + (size_t)g * n;
+  const int c0 = cb * BC;
+  const int wc0 = c0 + wave * 32 * kStreamKB;  // first key of this wave
+
+  const int t_begin = max(c0, first_row) / kTile;
+  const int t_end = (n + kTile - 1) / kTile;
+  auto fetch = [&](int t) {  // Q tile t into its ring stage (every wave a quarter of the rows)
+    if (t < t_end) dma_tile<false>(Qg, t * kTile, n, qs + ((t - t_begin) % kStreamStages) * kTileBytes);
+  };
+  fetch(t_begin);
+  fetch(t_begin + 1);
+  fetch(t_begin + 2);
+
+  // K fragments (A operand): lane (key l32, half h) holds K[key][16kk + 8h .. +7]
+  uint4 kf[kStreamKB][KK];
+#pragma unroll
+  for (int b = 0; b < kStreamKB; ++b) {
+    int r = wc0 + b * 32 + l32;
+    r = r < n ? r : n - 1;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[b][kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+  }
+  int qoff[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qoff[kk] = l32 * 256 + (((2 * kk + h) ^ k_swizzle(l32)) << 4);
+  float acc[kStreamKB][16];
+#pragma unroll
+  for (int b = 0; b < kStreamKB; ++b)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+
+  for (int t = t_begin; t < t_end; ++t) {
+    // tile t has landed: of this wave's fetches only those of tiles t+1 and t+2 (four loads
+    // each, fewer at the end) may still be under way
+    const int ahead = min(t_end - 1 - t, 2);
+    if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 8);        // vmcnt(8)
+    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 4);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0f70);                       // vmcnt(0)
+    __syncthreads();
+    fetch(t + 3);  // into the stage of tile t-1, which every wave has left
+    const int row0 = t * kTile;
+    if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
+      const lds_char* qt = qs + ((t - t_begin) % kStreamStages) * kTileBytes;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 sacc[kStreamKB];
+#pragma unroll
+        for (int b = 0; b < kStreamKB; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[b][i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const uint4 qf = lds_read16(qt + qb * 32 * 256 + qoff[kk]);
+#pragma unroll
+          for (int b = 0; b < kStreamKB; ++b) sacc[b] = mfma_bf16(kf[b][kk], qf, sacc[b]);
+        }
+        const int r = row0 + qb * 32 + l32;
+        // exponent offset of row r: lse_r - (n-1-r) log2(alpha); rows past the end, and rows
+        // whose weight is exactly 0 in fp32 (before first_row), add nothing
+        const float bias = (r < n && r >= first_row)
+                               ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+#pragma unroll
+        for (int b = 0; b < kStreamKB; ++b) {
+          const int bk0 = wc0 + b * 32;
+          if (bk0 + 31 > row0 + qb * 32) {  // block reaches above the diagonal
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = bk0 + 8 * (i >> 2) + 4 * h + (i & 3);
+              const float p = fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias));
+              acc[b][i] += key > r ? 0.f : p;
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[b][i] += fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias));
+          }
+        }
+      }
+    }
+  }
+  // sum over the 32 rows held by the lanes of one half
+#pragma unroll
+  for (int b = 0; b < kStreamKB; ++b) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[b][i] = group_sum<32>(acc[b][i]);
     if (l32 == 0) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
-        if (key < n) Sg[key] = acc[i];
+        const int key = wc0 + b * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+        if (key < n) S[(size_t)g * n + key] = acc[b][i];
       }
     }
-  };
-
-  for (int c0 = 0; c0 < n; c0 += 2 * BC) {
-    if (c0 + BC < n) load_keys(c0 + BC, kf1);
-    block(c0, kf0);
-    if (c0 + BC >= n) break;
-    if (c0 + 2 * BC < n) load_keys(c0 + 2 * BC, kf0);
-    block(c0 + BC, kf1);
   }
 }
 
@@ -985,6 +1125,15 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
   if (D == 128 && n - (first / kTile) * kTile <= kTailTiles * kTile) {
     hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
                        (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e);
+    return;
+  }
+  if (D == 128) {
+    constexpr int BC = kWaves * 32 * kStreamKB;
+    const int ncb = (n + BC - 1) / BC;
+    const unsigned grid = (unsigned)((((long long)G * ncb + 7) / 8) * 8);
+    hipLaunchKernelGGL(col_scores_stream128_kernel, dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
+                       alpha_heads, scale_log2e);
     return;
   }
   const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
