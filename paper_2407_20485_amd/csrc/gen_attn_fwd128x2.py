@@ -70,7 +70,11 @@ FLAGO = (54, 66)        # per block: nonzero when O has to be rescaled (moved, a
 ST0, ST1 = 60, 61
 PAIR = 62               # scratch pair
 OB = 64                 # output base pair
-SLO, SHI = 40, 87
+SHEAD, J, HASNEXT, SG, SQB = 49, 50, 51, 52, 69   # head * n (scratch), round, 1 if another block follows, head, row block
+QW = (86, 88)           # Q row pointers of the two 32-row blocks
+OW = (90, 92)           # O row pointers
+LSEW = (94, 96)         # log-sum-exp pointers
+SLO, SHI = 40, 97
 STAMP = 70              # --stamps: eight timestamps (s_memtime) in s[70:85]
 STAMPS = False          # development aid: the stamps overwrite the first output row of the wave
 
@@ -427,6 +431,22 @@ def dma(out, which):
     out.e(f"{skip}:")
 
 
+def top_drain(out):
+    """Top of an iteration for a wave that has finished its rows: its own outstanding fetches
+    are older than the next block's first loads, which may stay in flight."""
+    nonext, done = out.label("tn"), out.label("tm")
+    out.e(f"s_cmp_eq_u32 s{HASNEXT}, 1")
+    out.e(f"s_cbranch_scc0 {nonext}")
+    out.e(f"s_waitcnt vmcnt({FIRST_LOADS})")
+    out.e(f"s_branch {done}")
+    out.e(f"{nonext}:")
+    out.e("s_waitcnt vmcnt(0)")
+    out.e(f"{done}:")
+    out.e("s_barrier")
+    dma(out, "K")
+    dma(out, "V")
+
+
 def top(out, fetch=True):
     """Top of iteration t: the group {K(t+2), V(t+1)} has landed for every wave; then fetch
     {K(t+4), V(t+3)} into the stages that held K(t) and V(t-1) (fetch=False: the caller
@@ -525,6 +545,7 @@ def final(out, par):
     out.e(f"; ---- final, parity {par}")
     dma(out, "K")
     dma(out, "V")
+    next_block(out)     # Q registers and LDS stage 0 are free from here on
     out.e("s_waitcnt lgkmcnt(0)")
     out.ext(mask_block(out, 1, S1[par]))
     fifo = Fifo()
@@ -543,11 +564,90 @@ def final(out, par):
     assert not fifo.q
 
 
-def prologue(out):
-    out.e("; ---- prologue")
+def pointer(dst, base, t, shift):
+    """s[dst:dst+1] = %[base_lo]:%[base_hi] + (s[t] << shift), s[t] < 2^31."""
+    return [f"s_lshr_b32 s{OB}, s{t}, {32 - shift}", f"s_lshl_b32 s{OB + 1}, s{t}, {shift}",
+            f"s_add_u32 s{dst}, %[{base}lo], s{OB + 1}", f"s_addc_u32 s{dst + 1}, %[{base}hi], s{OB}"]
+
+
+def block_rows():
+    """From head s[SG] and 256-row block s[SQB]: s[SHEAD] = head * n, s[ST0] = first row of the
+    block, s[ST1] / s[PAIR] = head * n + first row of this wave's block 0 / block 1."""
+    return [f"s_mul_i32 s{SHEAD}, s{SG}, %[n]",
+            f"s_lshl_b32 s{ST0}, s{SQB}, 8",
+            f"s_add_u32 s{ST1}, s{ST0}, %[w32a]", f"s_add_u32 s{PAIR}, s{ST0}, %[w32b]",
+            f"s_add_u32 s{ST1}, s{ST1}, s{SHEAD}", f"s_add_u32 s{PAIR}, s{PAIR}, s{SHEAD}"]
+
+
+def first_loads(out):
+    """Pointers of K, V and of this wave's Q rows for the block (s[SG], s[SQB]); then the loads
+    the first logits wait for: Q straight into the accumulation registers, K(0) into stage 0."""
+    out.ext(block_rows())
+    out.ext(pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8))
+    out.ext(pointer(QW[0], "q", ST1, 8) + pointer(QW[1], "q", PAIR, 8))
+    for b in (0, 1):
+        for kk in range(8):
+            out.e(f"global_load_dwordx4 {ar(Q[b] + 4 * kk, 4)}, %[qoff], {sp(QW[b])} offset:{kk * 32}")
+    for u in (1, 3):
+        out.ext([f"s_add_u32 m0, %[wave_lds], {u * 4096}", "s_nop 0",
+                 f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)} offset:-4096",
+                 f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)}"])
+FIRST_LOADS = 16 + 4   # memory instructions first_loads issues
+
+
+def next_block(out):
+    """s[SG], s[SQB] of round s[J] + 1 (persistent launch: work id = vid0 + 32 round, the row
+    blocks of a head in turn from the long end and from the short end, so that two rounds
+    together cost every workgroup the same); s[HASNEXT] = 0 and nothing else if there is none."""
+    none = out.label("nn")
+    out.e(f"s_mov_b32 s{HASNEXT}, 0")
+    out.e(f"s_add_u32 s{ST0}, s{J}, 1")
+    out.e(f"s_cmp_lt_u32 s{ST0}, %[rounds]")
+    out.e(f"s_cbranch_scc0 {none}")
+    out.e(f"s_mov_b32 s{HASNEXT}, 1")
+    out.e(f"s_lshl_b32 s{ST1}, s{ST0}, 5")
+    out.e(f"s_add_u32 s{ST1}, s{ST1}, %[vid0]")
+    out.e(f"s_lshr_b32 s{SG}, s{ST1}, %[lgnqb]")
+    out.e(f"s_and_b32 s{SQB}, s{ST1}, %[nqbm1]")
+    out.e(f"s_sub_u32 s{ST1}, %[nqbm1], s{SQB}")
+    out.e(f"s_and_b32 s{ST0}, s{ST0}, 1")
+    out.e(f"s_cmp_eq_u32 s{ST0}, 1")                      # odd round: from the short end
+    out.e(f"s_cselect_b32 s{SQB}, s{SQB}, s{ST1}")
+    first_loads(out)
+    out.e(f"{none}:")
+
+
+def setup(out):
+    """Once per launch: constants and the first block's loads."""
+    out.e("; ---- setup")
     stamp(out, 0)
     stamp(out, 0, 2)
     out.e(f"v_mov_b32 {v(NEGINF)}, 0xff800000")
+    for u in range(4):
+        out.e(f"v_add_u32 {v(KL + u)}, {u * 4096}, %[kl0]")
+        out.e(f"v_add_u32 {v(VL + u)}, {u * 4096}, %[vl0]")
+    out.e(f"s_mov_b32 s{J}, 0")
+    out.e(f"s_mov_b32 s{SG}, %[g0]")
+    out.e(f"s_mov_b32 s{SQB}, %[qb0]")
+    first_loads(out)
+
+
+def prologue(out):
+    """Start of a 256-row block: its Q and K(0) are already on their way."""
+    out.e("; ---- block start")
+    out.ext(block_rows())
+    out.ext(pointer(OW[0], "o", ST1, 8) + pointer(OW[1], "o", PAIR, 8))
+    out.ext(pointer(LSEW[0], "l", ST1, 2) + pointer(LSEW[1], "l", PAIR, 2))
+    out.e(f"s_sub_u32 s{ST1}, s{ST1}, s{SHEAD}")
+    out.e(f"s_sub_u32 s{PAIR}, s{PAIR}, s{SHEAD}")
+    out.e(f"s_lshr_b32 s{TF0}, s{ST1}, 6")
+    out.e(f"s_lshr_b32 s{TF1}, s{PAIR}, 6")
+    out.e(f"s_lshr_b32 s{NTMAX}, s{ST0}, 6")
+    out.e(f"s_add_u32 s{NTMAX}, s{NTMAX}, 4")
+    out.e(f"s_sub_u32 s{NTM1}, s{NTMAX}, 1")
+    out.e(f"s_mov_b32 s{T}, 0")
+    out.e(f"s_mov_b32 s{KJ}, 1")
+    out.e(f"s_mov_b32 s{VJ}, 0")
     for b in (0, 1):
         out.e(f"v_mov_b32 {v(M[b])}, {v(NEGINF)}")
         out.e(f"v_mov_b32 {v(L[b])}, 0")
@@ -557,31 +657,13 @@ def prologue(out):
     for db in range(4):
         out.e(f"v_xor_b32 {v(VADDR + db)}, {db * 64}, %[clvs16]")
         out.e(f"v_add_u32 {v(VADDR + db)}, {v(VADDR + db)}, %[vrow]")
-    for u in range(4):
-        out.e(f"v_add_u32 {v(KL + u)}, {u * 4096}, %[kl0]")
-        out.e(f"v_add_u32 {v(VL + u)}, {u * 4096}, %[vl0]")
-    out.e(f"s_mov_b64 {sp(KP)}, %[kg]")
-    out.e(f"s_mov_b64 {sp(VP)}, %[vg]")
-    out.e(f"s_mov_b32 s{T}, 0")
-    out.e(f"s_mov_b32 s{TF0}, %[tf0]")
-    out.e(f"s_mov_b32 s{TF1}, %[tf1]")
-    out.e(f"s_mov_b32 s{NTMAX}, %[ntmax]")
-    out.e(f"s_sub_u32 s{NTM1}, s{NTMAX}, 1")
-    out.e(f"s_mov_b32 s{KJ}, 0")
-    out.e(f"s_mov_b32 s{VJ}, 0")
-    for kk in range(8):
-        out.e(f"global_load_dwordx4 {ar(Q[0] + 4 * kk, 4)}, %[qoff], %[qw0] offset:{kk * 32}")
-    for kk in range(8):
-        out.e(f"global_load_dwordx4 {ar(Q[1] + 4 * kk, 4)}, %[qoff], %[qw1] offset:{kk * 32}")
-    stamp(out, 1, 2)
-    out.ext(dma_lines(KJ, KP, KL, 0))                       # K(0)
     stamp(out, 2, 2)
     for i in range(128):
         out.e(f"v_accvgpr_write_b32 a{i}, 0")
     stamp(out, 3, 2)
     stamp(out, 1)
-    out.e("s_waitcnt vmcnt(0)")    # Q and K(0): all the first logits need
-    out.e("s_barrier")
+    out.e("s_waitcnt vmcnt(0)")    # Q and K(0): all the first logits need (and the last block's stores)
+    out.e("s_barrier")             # also: every wave has left the last block's tiles
     stamp(out, 2)
     stamp(out, 4, 2)
     # S0(0), S1(0); the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are issued on the way
@@ -611,12 +693,11 @@ def prologue(out):
 
 def epilogue(out):
     """Normalise, round to bf16 and store O; store the base-2 log-sum-exp.  A lane holds four
-    consecutive d of one row at a time, so the 2 x (32 x 128) block of the wave is transposed
-    through a 16 KB strip of LDS (16-byte chunks XOR-swizzled by the row) and leaves as whole
-    256-byte rows, four rows per store instruction."""
+    consecutive d of one row at a time, so each 32 x 128 block of the wave is transposed
+    through the wave's own 8 KB strip of LDS (above the stage ring; 16-byte chunks
+    XOR-swizzled by the row) and leaves as whole 256-byte rows, four rows per store
+    instruction.  No barrier: the strip is private, the next block's start has one."""
     out.e("; ---- epilogue")
-    out.e("s_waitcnt vmcnt(0)")
-    out.e("s_barrier")          # every wave is done with the K/V stages; they become the strips
     out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
     inv, lg, adr = TMP + 12, TMP + 13, TMP + 14
     n = 0
@@ -629,7 +710,7 @@ def epilogue(out):
                  f"v_rcp_f32 {v(inv)}, {v(l)}",
                  "s_nop 0",
                  f"v_add_f32 {v(lg)}, {v(lg)}, {v(m)}",
-                 f"global_store_dword %[l32x4], {v(lg)}, %[lsew{b}]"])
+                 f"global_store_dword %[l32x4], {v(lg)}, {sp(LSEW[b])}"])
         for db in range(4):
             for i4 in range(4):
                 t = TMP + 4 * (n % 2)          # two sets of four temporaries
@@ -643,18 +724,17 @@ def epilogue(out):
                 out.e(f"v_cvt_pk_bf16_f32 {v(w + 1)}, {v(t + 2)}, {v(t + 3)}")
                 out.e(f"v_xor_b32 {v(adr)}, {(4 * db + i4) * 16}, %[x16]")
                 out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_w]")
-                out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)} offset:{b * 8192}")
+                out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)}")
                 n += 1
-    out.e("s_waitcnt lgkmcnt(0)")
-    stamp(out, 6, 2)
-    for b in (0, 1):
+        out.e("s_waitcnt lgkmcnt(0)")
+        if b == 1:
+            stamp(out, 6, 2)
         for u in range(8):
             out.e(f"v_xor_b32 {v(adr)}, {64 * (u & 3)}, %[crr16]")
             out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_r]")
-            out.e(f"ds_read_b128 {vr(S1[b] + 4 * u, 4)}, {v(adr)} offset:{b * 8192 + u * 1024}")
-    for b in (0, 1):
-        out.e(f"s_waitcnt lgkmcnt({8 * (1 - b)})")
-        out.e(f"s_mov_b64 {sp(OB)}, %[ow{b}]")
+            out.e(f"ds_read_b128 {vr(S1[b] + 4 * u, 4)}, {v(adr)} offset:{u * 1024}")
+        out.e("s_waitcnt lgkmcnt(0)")
+        out.e(f"s_mov_b64 {sp(OB)}, {sp(OW[b])}")
         for u in range(8):
             if u == 4:
                 out.e(f"s_add_u32 s{OB}, s{OB}, 4096")
@@ -664,6 +744,9 @@ def epilogue(out):
 
 def generate():
     out = Out()
+    setup(out)
+    block = out.label("blk")
+    out.e(f"{block}:")
     prologue(out)
     la, lb_e, lb_o, sp_e, sp_o, fin_e, fin_o, drain, epi = (
         out.label(x) for x in ("la", "lbe", "lbo", "spe", "spo", "fe", "fo", "dr", "ep"))
@@ -711,7 +794,7 @@ def generate():
     out.e(f"s_add_u32 s{T}, s{T}, 1")
     out.e(f"s_cmp_lt_u32 s{T}, s{NTMAX}")
     out.e(f"s_cbranch_scc0 {epi}")
-    top(out)
+    top_drain(out)
     out.e(f"s_branch {drain}")
     out.e(f"{epi}:")
     stamp(out, 6)
@@ -720,6 +803,9 @@ def generate():
     stamp(out, 7)
     stamp(out, 7, 2)
     stamps_store(out)
+    out.e(f"s_add_u32 s{J}, s{J}, 1")
+    out.e(f"s_cmp_eq_u32 s{HASNEXT}, 1")
+    out.e(f"s_cbranch_scc1 {block}")
     done = out.label("done")
     out.e(f"s_branch {done}")
     out.ext(out.far)

@@ -661,24 +661,39 @@ __global__ __launch_bounds__(kThreads, NB == 1 ? 2 : 1) void attn_fwd128_kernel(
 // n % 256 == 0 and an output pointer.
 #include "attn_fwd128x2_body.inc"
 
-constexpr int kX2Rows = 256;            // query rows per workgroup
-constexpr int kX2LdsBytes = 4 * 32768;  // four stages of one K tile + one V tile
+constexpr int kX2Rows = 256;             // query rows per workgroup and block
+constexpr int kX2RingBytes = 4 * 32768;  // four stages of one K tile + one V tile
+constexpr int kX2LdsBytes = kX2RingBytes + 4 * 8192;  // + one 8 KB output strip per wave
 constexpr int kX2MinRows = 2048;
+constexpr int kX2Slots = 32;             // persistent launch: workgroups per XCD (one per CU)
 
+// rounds == 1: one workgroup per (head, 256-row block), ids mapped as in the other kernels.
+// rounds > 1 (persistent launch, 8 * kX2Slots workgroups, nqb a power of two): the workgroup
+// in slot r of XCD x works on ids x * (total / 8) + r + 32 j, j = 0 .. rounds - 1; the loads a
+// block starts with are issued while the previous block's output is being written.
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, int rounds,
+    float scale_log2e) {
   __shared__ __attribute__((aligned(1024))) char smem[kX2LdsBytes];
   const long long total = (long long)G * nqb;
-  const long long vid = xcd_contiguous_id(total);
-  if (vid >= total) return;
-  const int g = (int)(vid / nqb);
-  const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
+  int vid0, g0, qb0;
+  if (rounds > 1) {
+    vid0 = (int)((blockIdx.x % 8) * (total / 8) + blockIdx.x / 8);
+    g0 = vid0 / nqb;
+    qb0 = nqb - 1 - vid0 % nqb;
+  } else {
+    const long long vid = xcd_contiguous_id(total);
+    if (vid >= total) return;
+    vid0 = (int)vid;
+    g0 = (int)(vid / nqb);
+    qb0 = nqb - 1 - (int)(vid % nqb);  // longest rows first
+  }
+  const int lgnqb = 31 - __builtin_clz(nqb), nqbm1 = nqb - 1;  // used from the second round on
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, h = lane >> 5;
-  const int row0 = qb * kX2Rows;
   const unsigned lds0 = (unsigned)(size_t)smem;  // LDS byte address of the stage ring
 
   // K fragment (16 d-chunk 2kk+h of key row l32): row base and the kk-independent swizzle term
@@ -694,39 +709,35 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
   const unsigned qoff = (unsigned)(l32 * 256 + h * 16);
   const int lv = l32 - 4 * h;
   const unsigned l32x4 = l32 * 4, lanex16 = lane * 16;
-  // epilogue: a wave's two 32 x 128 output blocks go through its own 16 KB strip of LDS
-  const unsigned strip = lds0 + wave * 16384;
+  // epilogue: a wave's 32 x 128 output blocks go, one after the other, through its own 8 KB
+  // strip of LDS above the ring
+  const unsigned strip = lds0 + kX2RingBytes + wave * 8192;
   const unsigned strip_w = strip + l32 * 256 + 8 * h, x16 = (unsigned)((l32 & 15) << 4);
   const unsigned strip_r = strip + rr * 256, crr16 = (unsigned)((pc ^ rr) << 4);
 
-  // Rows: the 256-row block is cut into eight 32-row blocks; wave w owns blocks w ("block 0")
+  // Rows: a 256-row block is cut into eight 32-row blocks; wave w owns blocks w ("block 0")
   // and 7 - w ("block 1"), so that every wave has the same number of key tiles to go through
   // although the rows further down see more keys.
-  const size_t head = (size_t)g * n;
-  const int r0 = row0 + 32 * wave, r1 = row0 + 32 * (7 - wave);
-  const bf16_t* kg = K + head * 128;
-  const bf16_t* vg = V + head * 128;
-  const bf16_t* qw0 = Q + (head + r0) * 128;
-  const bf16_t* qw1 = Q + (head + r1) * 128;
-  bf16_t* ow0 = O + (head + r0) * 128;
-  bf16_t* ow1 = O + (head + r1) * 128;
-  float* lsew0 = LSE2 + head + r0;
-  float* lsew1 = LSE2 + head + r1;
-  const int tf0 = r0 >> 6, tf1 = r1 >> 6;  // last key tile of each block (the one with its diagonal)
-  const int ntmax = (row0 >> 6) + 4;       // key tiles the workgroup streams
-  const int wodd = wave & 1;
+  const int w32a = 32 * wave, w32b = 32 * (7 - wave), wodd = wave & 1;
   const unsigned wave_lds = lds0 + wave * 1024;
+  const unsigned long long qa = (unsigned long long)Q, ka = (unsigned long long)K,
+                           va = (unsigned long long)V, oa = (unsigned long long)O,
+                           la = (unsigned long long)LSE2;
 
   asm volatile(A2SF_FWD128X2_ASM
                :
                : [hx16] "v"(hx16), [krow] "v"(krow), [clvs16] "v"(clvs16), [vrow] "v"(vrow),
                  [kl0] "v"(kl0), [vl0] "v"(vl0), [qoff] "v"(qoff), [lv] "v"(lv),
                  [l32x4] "v"(l32x4), [lanex16] "v"(lanex16), [strip_w] "v"(strip_w),
-                 [x16] "v"(x16), [crr16] "v"(crr16), [strip_r] "v"(strip_r), [kg] "s"(kg),
-                 [vg] "s"(vg), [qw0] "s"(qw0), [qw1] "s"(qw1), [ow0] "s"(ow0), [ow1] "s"(ow1),
-                 [lsew0] "s"(lsew0), [lsew1] "s"(lsew1), [tf0] "s"(tf0), [tf1] "s"(tf1),
-                 [ntmax] "s"(ntmax), [wodd] "s"(wodd), [wave_lds] "s"(wave_lds),
-                 [scale] "s"(scale_log2e)
+                 [x16] "v"(x16), [crr16] "v"(crr16), [strip_r] "v"(strip_r),
+                 [qlo] "s"((unsigned)qa), [qhi] "s"((unsigned)(qa >> 32)),
+                 [klo] "s"((unsigned)ka), [khi] "s"((unsigned)(ka >> 32)),
+                 [vlo] "s"((unsigned)va), [vhi] "s"((unsigned)(va >> 32)),
+                 [olo] "s"((unsigned)oa), [ohi] "s"((unsigned)(oa >> 32)),
+                 [llo] "s"((unsigned)la), [lhi] "s"((unsigned)(la >> 32)),
+                 [n] "s"(n), [g0] "s"(g0), [qb0] "s"(qb0), [vid0] "s"(vid0), [rounds] "s"(rounds),
+                 [lgnqb] "s"(lgnqb), [nqbm1] "s"(nqbm1), [w32a] "s"(w32a), [w32b] "s"(w32b),
+                 [wodd] "s"(wodd), [wave_lds] "s"(wave_lds), [scale] "s"(scale_log2e)
                : A2SF_FWD128X2_CLOBBERS);
 }
 
@@ -836,11 +847,17 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
     // its start and end (measured crossover between n = 1024 and n = 2048).
-    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && n >= kX2MinRows) {
+    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && n >= kX2MinRows && (long long)G * n < (1ll << 31)) {
       const int nqb2 = n / kX2Rows;
-      const unsigned grid2 = (unsigned)((((long long)G * nqb2 + 7) / 8) * 8);
+      const long long items = (long long)G * nqb2;
+      // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
+      // number of full rounds (two rounds together cost every workgroup the same)
+      const bool persistent = (nqb2 & (nqb2 - 1)) == 0 && nqb2 <= kX2Slots &&
+                              items % (2 * 8 * kX2Slots) == 0;
+      const int rounds = persistent ? (int)(items / (8 * kX2Slots)) : 1;
+      const unsigned grid2 = persistent ? 8 * kX2Slots : (unsigned)(((items + 7) / 8) * 8);
       hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st, (const bf16_t*)q,
-                         (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G, nqb2,
+                         (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G, nqb2, rounds,
                          scale_log2e);
       return;
     }

@@ -199,3 +199,22 @@ def test_stream_barriers_are_wave_uniform(stream):
         elif ln.startswith("s_branch Lback"):
             in_slow = False
         assert not (in_slow and ln == "s_barrier")
+
+
+def test_stream_scc_consumers_see_their_producer(stream):
+    """s_addc_u32 must read the carry of the s_add_u32 just before it, s_cbranch_scc* and
+    s_cselect_* the result of an s_cmp_*: no other scalar op that writes SCC may have slipped in
+    between when instruction lists were interleaved."""
+    lines, _ = stream
+    writes_scc = ("s_add", "s_sub", "s_and", "s_or", "s_xor", "s_lshl", "s_lshr", "s_min", "s_max", "s_cmp")
+    last = None
+    for ln in lines:
+        if ln.endswith(":"):
+            continue   # a label: control may arrive from a branch, whose producer was checked there
+        op = ln.split()[0]
+        if op == "s_addc_u32":
+            assert last is not None and last.startswith("s_add_u32"), (last, ln)
+        elif op.startswith("s_cbranch_scc") or op.startswith("s_cselect"):
+            assert last is not None and last.startswith("s_cmp"), (last, ln)
+        if op.startswith(writes_scc):
+            last = ln
