@@ -665,6 +665,7 @@ constexpr int kX2Rows = 256;             // query rows per workgroup and block
 constexpr int kX2RingBytes = 4 * 32768;  // four stages of one K tile + one V tile
 constexpr int kX2LdsBytes = kX2RingBytes + 4 * 8192;  // + one 8 KB output strip per wave
 constexpr int kX2MinRows = 2048;
+constexpr int kX2MinRowsPersistent = 512;
 constexpr int kX2Slots = 32;             // persistent launch: workgroups per XCD (one per CU)
 
 // rounds == 1: one workgroup per (head, 256-row block), ids mapped as in the other kernels.
@@ -846,20 +847,23 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
     constexpr int NB = A2SF_FWD128_NB;
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
-    // its start and end (measured crossover between n = 1024 and n = 2048).
-    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && n >= kX2MinRows && (long long)G * n < (1ll << 31)) {
+    // the start and end of a row block: from n = 2048 with one workgroup per block, from
+    // n = 512 in the persistent form, which overlaps them with the neighbouring blocks.
+    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31)) {
       const int nqb2 = n / kX2Rows;
       const long long items = (long long)G * nqb2;
       // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
       // number of full rounds (two rounds together cost every workgroup the same)
       const bool persistent = (nqb2 & (nqb2 - 1)) == 0 && nqb2 <= kX2Slots &&
                               items % (2 * 8 * kX2Slots) == 0;
-      const int rounds = persistent ? (int)(items / (8 * kX2Slots)) : 1;
-      const unsigned grid2 = persistent ? 8 * kX2Slots : (unsigned)(((items + 7) / 8) * 8);
-      hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st, (const bf16_t*)q,
-                         (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G, nqb2, rounds,
-                         scale_log2e);
-      return;
+      if (n >= kX2MinRows || (persistent && n >= kX2MinRowsPersistent)) {
+        const int rounds = persistent ? (int)(items / (8 * kX2Slots)) : 1;
+        const unsigned grid2 = persistent ? 8 * kX2Slots : (unsigned)(((items + 7) / 8) * 8);
+        hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st,
+                           (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G,
+                           nqb2, rounds, scale_log2e);
+        return;
+      }
     }
     const long long total = (long long)G * nqb;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
