@@ -367,11 +367,11 @@ def qk_steps(fifo, s0, s1, odd, flip, next_reads, extra=None, blocks=(0, 1)):
     return steps
 
 
-def pv_steps(fifo, p0, p1, odd, flip, next_reads, blocks=(0, 1)):
+def pv_steps(fifo, p0, p1, odd, flip, next_reads, blocks=(0, 1), extra=None):
     """Matrix side of O0, O1 += V^T P^T over the 16 V fragments of a tile."""
     steps = []
     for j in range(0, 16, 2):
-        pre = []
+        pre = list((extra or {}).get(j // 2, []))
         for i in (j, j + 1):
             if i + PF < 16:
                 pre += v_read(i + PF, odd)
@@ -415,9 +415,10 @@ def dma_lines(j, base, lo, off):
     return ln
 
 
-def dma_pieces(out):
-    """The fetch of {K(t+4), V(t+3)}, to ride between the first matrix ops of phase X."""
-    return {1: dma_lines(KJ, KP, KL, 0), 3: dma_lines(VJ, VP, VL, 16384)}
+def dma_pieces(which):
+    """The fetch of K(t+4) (phase X) / V(t+3) (phase Y), to ride between the phase's first
+    matrix ops."""
+    return {1: dma_lines(KJ, KP, KL, 0) if which == "K" else dma_lines(VJ, VP, VL, 16384)}
 
 
 def dma(out, which):
@@ -498,7 +499,7 @@ def phase_x(out, fifo, par, blocks):
     # K(t+1) now; K address bit 16 flips after the last read when t+2 has another bit 1 than t+1;
     # then the first V(t) fragments
     steps = qk_steps(fifo, S0, S1[1 - par], 1 - par, par == 0, reader(fifo, "V", par),
-                     extra=dma_pieces(out), blocks=blocks)
+                     extra=dma_pieces("K"), blocks=blocks)
     valu, far = softmax(out, 1, S1[par], P1)
     out.far += far
     merge(out, steps, valu)
@@ -509,7 +510,8 @@ def phase_y(out, fifo, par, blocks, sm0):
     """Matrix ops: O += V(t)^T P(t) for `blocks` | vector ops: softmax of S0(t+1) (if sm0)."""
     out.e(f"; ---- Y phase, parity {par}, blocks {blocks}")
     # V(t) now, then the first K(t+2) fragments
-    steps = pv_steps(fifo, P0[par], P1, par, par == 1, reader(fifo, "K", par), blocks=blocks)
+    steps = pv_steps(fifo, P0[par], P1, par, par == 1, reader(fifo, "K", par), blocks=blocks,
+                     extra=dma_pieces("V"))
     if not sm0:
         merge(out, steps, [])
         return
@@ -681,9 +683,7 @@ def prologue(out):
     out.e(f"s_cbranch_scc0 {nomask}")
     out.ext(mask_block(out, 0, S0))
     out.e(f"{nomask}:")
-    valu, far = softmax(out, 0, S0, P0[0])
-    out.far += far
-    out.ext(valu)
+    out.ext(softmax_slow(0, S0, P0[0]))     # first tile: the maximum has to be found anyway
     # K(1) and V(0) have landed for every wave (K(2) V(1) K(3) V(2) may still be under way)
     out.e("s_waitcnt vmcnt(16)")
     out.e("s_barrier")
