@@ -674,22 +674,20 @@ constexpr int kX2Slots = 32;             // persistent launch: workgroups per XC
 // block starts with are issued while the previous block's output is being written.
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, int rounds,
-    float scale_log2e) {
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int nqb, int id_base, int ids,
+    int rounds, float scale_log2e) {
   __shared__ __attribute__((aligned(1024))) char smem[kX2LdsBytes];
-  const long long total = (long long)G * nqb;
-  int vid0, g0, qb0;
+  // this launch covers the ids id_base .. id_base + ids - 1; id = head * nqb + block position
+  int vid0;
   if (rounds > 1) {
-    vid0 = (int)((blockIdx.x % 8) * (total / 8) + blockIdx.x / 8);
-    g0 = vid0 / nqb;
-    qb0 = nqb - 1 - vid0 % nqb;
+    vid0 = id_base + (int)(blockIdx.x % 8) * (ids / 8) + (int)(blockIdx.x / 8);
   } else {
-    const long long vid = xcd_contiguous_id(total);
-    if (vid >= total) return;
-    vid0 = (int)vid;
-    g0 = (int)(vid / nqb);
-    qb0 = nqb - 1 - (int)(vid % nqb);  // longest rows first
+    const long long vid = xcd_contiguous_id(ids);
+    if (vid >= ids) return;
+    vid0 = id_base + (int)vid;
   }
+  const int g0 = vid0 / nqb;
+  const int qb0 = nqb - 1 - vid0 % nqb;  // longest rows first
   const int lgnqb = 31 - __builtin_clz(nqb), nqbm1 = nqb - 1;  // used from the second round on
 
   const int lane = threadIdx.x & 63;
@@ -855,13 +853,20 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
       // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
       // number of full rounds (two rounds together cost every workgroup the same)
       const bool persistent = (nqb2 & (nqb2 - 1)) == 0 && nqb2 <= kX2Slots &&
-                              items % (2 * 8 * kX2Slots) == 0;
+                              items >= 2 * 8 * kX2Slots && items < (1ll << 31);
       if (n >= kX2MinRows || (persistent && n >= kX2MinRowsPersistent)) {
-        const int rounds = persistent ? (int)(items / (8 * kX2Slots)) : 1;
-        const unsigned grid2 = persistent ? 8 * kX2Slots : (unsigned)(((items + 7) / 8) * 8);
-        hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st,
-                           (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n, G,
-                           nqb2, rounds, scale_log2e);
+        auto launch = [&](int id_base, int ids, int rounds) {
+          const unsigned grid2 = rounds > 1 ? 8 * kX2Slots : (unsigned)(((ids + 7) / 8) * 8);
+          hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st,
+                             (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
+                             nqb2, id_base, ids, rounds, scale_log2e);
+        };
+        // persistent part: an even number of full rounds; what is left over goes one workgroup
+        // per row block
+        const int chunk = 2 * 8 * kX2Slots;
+        const int main_ids = persistent ? (int)(items / chunk) * chunk : 0;
+        if (main_ids) launch(0, main_ids, main_ids / (8 * kX2Slots));
+        if (items > main_ids) launch(main_ids, (int)(items - main_ids), 1);
         return;
       }
     }

@@ -148,7 +148,8 @@ def test_prefill_optional_outputs(base, d, n):
 
 
 @pytest.mark.parametrize("d,n,G", [(128, 2048, 3), (128, 2304, 3), (128, 1024, 3), (128, 300, 3), (64, 320, 3),
-                                   (128, 2048, 128), (128, 1024, 128), (128, 512, 256)])   # several row blocks per workgroup
+                                   (128, 2048, 128), (128, 1024, 128), (128, 512, 256),   # several row blocks per workgroup
+                                   (128, 2048, 100)])                                     # ... plus a remainder launch
 @pytest.mark.parametrize("rise", [200.0, -60.0, 40.0])
 def test_prefill_moving_maximum(d, n, G, rise, say):
     """Logits that climb (or fall) by `rise` base-2 units over the sequence: the running maximum
