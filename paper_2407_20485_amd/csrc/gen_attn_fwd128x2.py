@@ -668,22 +668,23 @@ def prologue(out):
     out.e("s_barrier")             # also: every wave has left the last block's tiles
     stamp(out, 2)
     stamp(out, 4, 2)
-    # S0(0), S1(0); the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are issued on the way
+    # S0(0), then S1(0) with block 0's first softmax (the one that has to find a maximum)
+    # riding between its matrix ops; the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are
+    # issued on the way.  K(0)'s fragments are read once per block here: LDS is idle anyway.
     fifo = Fifo()
     for f in range(PF):
         out.ext(k_read(f, 0))
         fifo.push(("K", f))
-    extra = {i + 1: dma_lines(*((KJ, KP, KL, 0) if w == "K" else (VJ, VP, VL, 16384)))
-             for i, w in enumerate("KVKVKV")}
-    merge(out, qk_steps(fifo, S0, S1[0], 0, False, lambda i: [], extra=extra), [])
-    assert not fifo.q
-    out.ext(["s_nop 7", "s_nop 7", "s_nop 7"])
+    pieces = [dma_lines(*((KJ, KP, KL, 0) if w == "K" else (VJ, VP, VL, 16384))) for w in "KVKVKV"]
+    merge(out, qk_steps(fifo, S0, S1[0], 0, False, reader(fifo, "K", 0),
+                        extra={i + 1: pieces[i] for i in range(3)}, blocks=(0,)), [])
     nomask = out.label("nm")
-    out.e(f"s_cmp_eq_u32 s{TF0}, 0")
-    out.e(f"s_cbranch_scc0 {nomask}")
-    out.ext(mask_block(out, 0, S0))
-    out.e(f"{nomask}:")
-    out.ext(softmax_slow(0, S0, P0[0]))     # first tile: the maximum has to be found anyway
+    lead = (["s_nop 7", f"s_cmp_eq_u32 s{TF0}, 0", f"s_cbranch_scc0 {nomask}"]
+            + mask_block(out, 0, S0) + [f"{nomask}:"])
+    merge(out, qk_steps(fifo, S0, S1[0], 0, False, lambda i: [],
+                        extra={i + 1: pieces[3 + i] for i in range(3)}, blocks=(1,)),
+          softmax_slow(0, S0, P0[0]), lead=2, lead_lines=lead)
+    assert not fifo.q
     # K(1) and V(0) have landed for every wave (K(2) V(1) K(3) V(2) may still be under way)
     out.e("s_waitcnt vmcnt(16)")
     out.e("s_barrier")
