@@ -147,7 +147,7 @@ def stamps_store(out):
     for q in range(4):
         for k in range(4):
             out.e(f"v_mov_b32 {v(TMP + k)}, s{STAMP + 4 * q + k}")
-        out.e(f"global_store_dwordx4 {v(TMP + 15)}, {vr(TMP, 4)}, %[ow0] offset:{16 * q}")
+        out.e(f"global_store_dwordx4 {v(TMP + 15)}, {vr(TMP, 4)}, {sp(OW[0])} offset:{16 * q}")
     out.e("s_mov_b64 exec, -1")
 
 
@@ -547,7 +547,9 @@ def final(out, par):
     out.e(f"; ---- final, parity {par}")
     dma(out, "K")
     dma(out, "V")
-    next_block(out)     # Q registers and LDS stage 0 are free from here on
+    # Q registers and LDS stage 0 are free from here on: the next block's Q rows and first K
+    # tile are fetched between the instructions of this last tile
+    out.ext(next_block())
     out.e("s_waitcnt lgkmcnt(0)")
     out.ext(mask_block(out, 1, S1[par]))
     fifo = Fifo()
@@ -559,9 +561,10 @@ def final(out, par):
     out.ext(pre)
     valu, far = softmax(out, 1, S1[par], P1)
     out.far += far
-    out.ext(valu)
+    out.ext(weave(valu, q_loads()))
     rescale(out, 1, settle=False)
-    steps = pv_steps(fifo, P0[par], P1, par, False, lambda i: [], blocks=(1,))
+    k0 = k0_loads()
+    steps = pv_steps(fifo, P0[par], P1, par, False, lambda i: [], blocks=(1,), extra={1: k0[0], 3: k0[1]})
     merge(out, steps, [])
     assert not fifo.q
 
@@ -581,42 +584,57 @@ def block_rows():
             f"s_add_u32 s{ST1}, s{ST1}, s{SHEAD}", f"s_add_u32 s{PAIR}, s{PAIR}, s{SHEAD}"]
 
 
-def first_loads(out):
-    """Pointers of K, V and of this wave's Q rows for the block (s[SG], s[SQB]); then the loads
-    the first logits wait for: Q straight into the accumulation registers, K(0) into stage 0."""
-    out.ext(block_rows())
-    out.ext(pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8))
-    out.ext(pointer(QW[0], "q", ST1, 8) + pointer(QW[1], "q", PAIR, 8))
-    for b in (0, 1):
-        for kk in range(8):
-            out.e(f"global_load_dwordx4 {ar(Q[b] + 4 * kk, 4)}, %[qoff], {sp(QW[b])} offset:{kk * 32}")
-    for u in (1, 3):
-        out.ext([f"s_add_u32 m0, %[wave_lds], {u * 4096}", "s_nop 0",
-                 f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)} offset:-4096",
-                 f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)}"])
-FIRST_LOADS = 16 + 4   # memory instructions first_loads issues
+def first_load_pointers():
+    """Pointers of K, V and of this wave's Q rows for the block (s[SG], s[SQB])."""
+    return (block_rows() + pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8)
+            + pointer(QW[0], "q", ST1, 8) + pointer(QW[1], "q", PAIR, 8))
 
 
-def next_block(out):
-    """s[SG], s[SQB] of round s[J] + 1 (persistent launch: work id = vid0 + 32 round, the row
-    blocks of a head in turn from the long end and from the short end, so that two rounds
-    together cost every workgroup the same); s[HASNEXT] = 0 and nothing else if there is none."""
-    none = out.label("nn")
-    out.e(f"s_mov_b32 s{HASNEXT}, 0")
-    out.e(f"s_add_u32 s{ST0}, s{J}, 1")
-    out.e(f"s_cmp_lt_u32 s{ST0}, %[rounds]")
-    out.e(f"s_cbranch_scc0 {none}")
-    out.e(f"s_mov_b32 s{HASNEXT}, 1")
-    out.e(f"s_lshl_b32 s{ST1}, s{ST0}, 5")
-    out.e(f"s_add_u32 s{ST1}, s{ST1}, %[vid0]")
-    out.e(f"s_lshr_b32 s{SG}, s{ST1}, %[lgnqb]")
-    out.e(f"s_and_b32 s{SQB}, s{ST1}, %[nqbm1]")
-    out.e(f"s_sub_u32 s{ST1}, %[nqbm1], s{SQB}")
-    out.e(f"s_and_b32 s{ST0}, s{ST0}, 1")
-    out.e(f"s_cmp_eq_u32 s{ST0}, 1")                      # odd round: from the short end
-    out.e(f"s_cselect_b32 s{SQB}, s{SQB}, s{ST1}")
-    first_loads(out)
-    out.e(f"{none}:")
+def q_loads():
+    """Q straight into the accumulation registers (B-operand fragments)."""
+    return [f"global_load_dwordx4 {ar(Q[b] + 4 * kk, 4)}, %[qoff], {sp(QW[b])} offset:{kk * 32}"
+            for b in (0, 1) for kk in range(8)]
+
+
+def k0_loads():
+    """K(0) into LDS stage 0: two groups, each one M0 value and two loads."""
+    return [[f"s_add_u32 m0, %[wave_lds], {u * 4096}", "s_nop 0",
+             f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)} offset:-4096",
+             f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)}"] for u in (1, 3)]
+FIRST_LOADS = 16 + 4   # memory instructions q_loads() and k0_loads() issue
+
+
+def next_block():
+    """Scalar part of the early fetch: s[SG], s[SQB] become the block of round s[J] + 1
+    (persistent launch: work id = vid0 + 32 round, the row blocks of a head in turn from the long
+    end and from the short end, so that two rounds together cost every workgroup the same) and
+    s[HASNEXT] = 1; after the last round they stay what they are (that block's Q and first K
+    tile are then simply fetched once more) and s[HASNEXT] = 0.  Then the fetch pointers."""
+    return [f"s_add_u32 s{ST0}, s{J}, 1",
+            f"s_lshl_b32 s{ST1}, s{ST0}, 5",
+            f"s_add_u32 s{ST1}, s{ST1}, %[vid0]",
+            f"s_lshr_b32 s{PAIR}, s{ST1}, %[lgnqb]",
+            f"s_and_b32 s{ST1}, s{ST1}, %[nqbm1]",
+            f"s_sub_u32 s{OB}, %[nqbm1], s{ST1}",
+            f"s_and_b32 s{OB + 1}, s{ST0}, 1",
+            f"s_cmp_eq_u32 s{OB + 1}, 1",                     # odd round: from the short end
+            f"s_cselect_b32 s{ST1}, s{ST1}, s{OB}",
+            f"s_cmp_lt_u32 s{ST0}, %[rounds]",
+            f"s_cselect_b32 s{HASNEXT}, 1, 0",
+            f"s_cselect_b32 s{SG}, s{PAIR}, s{SG}",
+            f"s_cselect_b32 s{SQB}, s{ST1}, s{SQB}"] + first_load_pointers()
+
+
+def weave(base, extra, tail=8):
+    """`extra` spread evenly through `base`, none of it among the last `tail` lines."""
+    body = base[:len(base) - tail]
+    out, done = [], 0
+    for i, ln in enumerate(body):
+        out.append(ln)
+        upto = (len(extra) * (i + 1)) // len(body)
+        out += extra[done:upto]
+        done = upto
+    return out + base[len(base) - tail:]
 
 
 def setup(out):
@@ -631,7 +649,7 @@ def setup(out):
     out.e(f"s_mov_b32 s{J}, 0")
     out.e(f"s_mov_b32 s{SG}, %[g0]")
     out.e(f"s_mov_b32 s{SQB}, %[qb0]")
-    first_loads(out)
+    out.ext(first_load_pointers() + q_loads() + sum(k0_loads(), []))
 
 
 def prologue(out):
