@@ -841,7 +841,7 @@ template <int D>
 void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
                 hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  if (D == 128) {
+  if constexpr (D == 128) {
     constexpr int NB = A2SF_FWD128_NB;
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
@@ -880,21 +880,21 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
       hipLaunchKernelGGL((attn_fwd128_kernel<false, NB>), dim3(grid), dim3(kThreads), 0, st,
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
                          lse2, n, G, nqb, scale_log2e);
-    return;
+  } else {
+    constexpr int NB = A2SF_FWD_NB;
+    constexpr int BM = kWaves * 32 * NB;
+    const int nqb = (n + BM - 1) / BM;
+    const long long total = (long long)G * nqb;
+    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+    if (o)
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
+                         G, nqb, scale_log2e);
+    else
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, false>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
+                         lse2, n, G, nqb, scale_log2e);
   }
-  constexpr int NB = A2SF_FWD_NB;
-  constexpr int BM = kWaves * 32 * NB;
-  const int nqb = (n + BM - 1) / BM;
-  const long long total = (long long)G * nqb;
-  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-  if (o)
-    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
-                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
-                       G, nqb, scale_log2e);
-  else
-    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, false>), dim3(grid), dim3(kThreads), 0, st,
-                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
-                       lse2, n, G, nqb, scale_log2e);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1148,26 +1148,26 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   float l2a;
   const int first = first_contributing_row(n, alpha, &l2a);
-  if (D == 128 && n - (first / kTile) * kTile <= kTailTiles * kTile) {
-    hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
-                       (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e);
-    return;
-  }
-  if (D == 128) {
+  if constexpr (D == 128) {
+    if (n - (first / kTile) * kTile <= kTailTiles * kTile) {
+      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
+                         (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e);
+      return;
+    }
     constexpr int BC = kWaves * 32 * kStreamKB;
     const int ncb = (n + BC - 1) / BC;
     const unsigned grid = (unsigned)((((long long)G * ncb + 7) / 8) * 8);
     hipLaunchKernelGGL(col_scores_stream128_kernel, dim3(grid), dim3(kThreads), 0, st,
                        (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
                        alpha_heads, scale_log2e);
-    return;
+  } else {
+    const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
+    const long long total = (long long)G * ncb;
+    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+    hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
+                       alpha_heads, scale_log2e);
   }
-  const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
-  const long long total = (long long)G * ncb;
-  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-  hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st,
-                     (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
-                     alpha_heads, scale_log2e);
 }
 
 }  // namespace
