@@ -23,7 +23,10 @@ rare rescale of O by the running-maximum correction is deferred to the end of th
 
 K/V tiles arrive by global_load_lds DMA into a ring of four LDS stages; the barrier at the
 top of iteration t publishes the tiles of iteration t+1, so fragment reads may run ahead
-across phase and iteration boundaries.
+across phase and iteration boundaries.  A workgroup of the persistent launch works through
+several 256-row blocks, and the tile stream runs on across them: the last four iterations of
+a block fetch the first tiles of the next one, whose Q rows are loaded during the block's
+last tile.
 
 Hazards the hardware does not interlock are kept apart by construction: a vector op reads a
 matrix-op result only after two later matrix ops have been issued plus explicit s_nop, a
@@ -60,8 +63,7 @@ O = (0, 64)             # O^T accumulators: 4 blocks of 32 d x 16 registers each
 Q = (128, 160)          # Q fragments: 8 x 4 registers each
 NA = 192
 # ---- scalar registers -----------------------------------------------------------------
-KP, VP = 40, 42         # global pointers of the head's K and V
-NTM1 = 68               # NTMAX - 1
+KP, VP = 40, 42         # global pointers of the next K / V tile to fetch
 T, TF0, NTMAX = 44, 45, 46   # iteration, block 0's last tile, tiles the workgroup streams
 TF1 = 53                      # block 1's last tile
 KJ, VJ = 47, 48         # index of the next K / V tile to fetch
@@ -74,8 +76,10 @@ SHEAD, J, HASNEXT, SG, SQB = 49, 50, 51, 52, 69   # head * n (scratch), round, 1
 QW = (86, 88)           # Q row pointers of the two 32-row blocks
 OW = (90, 92)           # O row pointers
 LSEW = (94, 96)         # log-sum-exp pointers
-SLO, SHI = 40, 97
-STAMP = 70              # --stamps: eight timestamps (s_memtime) in s[70:85]
+KPN, VPN = 98, 82       # K / V pointers of the block after this one (this one again after the last)
+SGN, SQBN = 84, 85      # its head and row block
+SLO, SHI = 40, 99
+STAMP = 70              # --stamps: six timestamps (s_memtime) in s[70:81]
 STAMPS = False          # development aid: the stamps overwrite the first output row of the wave
 
 STAGE = 32768           # one LDS stage: K tile (16 KB) then V tile (16 KB)
@@ -394,77 +398,61 @@ def pv_steps(fifo, p0, p1, odd, flip, next_reads, blocks=(0, 1), extra=None):
     return steps
 
 
-def dma_lines(j, base, lo, off):
-    """Fetch of tile number s[j] (clamped to the last tile: past the end the last tile is
-    simply fetched again, which keeps the stream free of branches and the vmcnt bookkeeping
-    uniform) into LDS stage s[j] % NSTAGE; then s[j] += 1."""
-    ln = [f"s_min_u32 s{ST1}, s{j}, s{NTM1}",
-          f"s_lshl_b32 s{ST1}, s{ST1}, 14",
-          f"s_add_u32 s{PAIR}, s{base}, s{ST1}",
-          f"s_addc_u32 s{PAIR + 1}, s{base + 1}, 0",
-          f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
+def dma_lines(which):
+    """Fetch of the next K (or V) tile into LDS stage (tile number) % NSTAGE.  The tile stream
+    does not stop at the end of a 256-row block: after the block's last tile come the first
+    tiles of the next block (pointer s[KPN] / s[VPN]), whose tile 0 falls on stage 0 again
+    because a block always has a multiple of four tiles; so the fetch is the same instruction
+    sequence in every iteration, the vmcnt bookkeeping is uniform and the next block finds its
+    first tiles in LDS."""
+    j, p, pn, lo, off = (KJ, KP, KPN, KL, 0) if which == "K" else (VJ, VP, VPN, VL, 16384)
+    ln = [f"s_and_b32 s{ST1}, s{j}, {NSTAGE - 1}",
           f"s_lshl_b32 s{ST1}, s{ST1}, 15",
           f"s_add_u32 s{ST1}, s{ST1}, %[wave_lds]"]
     # the instruction's immediate offset moves the global and the LDS address alike, and the
     # four loads of a wave sit 4 KB apart in both: one M0 value serves two loads
     for u in (1, 3):
         ln += [f"s_add_u32 m0, s{ST1}, {off + u * 4096}", "s_nop 0",
-               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(PAIR)} offset:-4096",
-               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(PAIR)}"]
-    ln.append(f"s_add_u32 s{j}, s{j}, 1")
+               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)} offset:-4096",
+               f"global_load_lds_dwordx4 {v(lo + u)}, {sp(p)}"]
+    ln += [f"s_add_u32 s{p}, s{p}, 16384", f"s_addc_u32 s{p + 1}, s{p + 1}, 0",
+           f"s_add_u32 s{j}, s{j}, 1",
+           f"s_cmp_eq_u32 s{j}, s{NTMAX}",
+           f"s_cselect_b64 {sp(p)}, {sp(pn)}, {sp(p)}"]
     return ln
 
 
 def dma_pieces(which):
     """The fetch of K(t+4) (phase X) / V(t+3) (phase Y), to ride between the phase's first
     matrix ops."""
-    return {1: dma_lines(KJ, KP, KL, 0) if which == "K" else dma_lines(VJ, VP, VL, 16384)}
+    return {1: dma_lines(which)}
 
 
 def dma(out, which):
-    """Same fetch as one block, skipped when the tile does not exist (prologue, last tile,
-    drain: places where nothing is interleaved)."""
-    j, base, lo, off = (KJ, KP, KL, 0) if which == "K" else (VJ, VP, VL, 16384)
-    skip = out.label("nd")
-    out.e(f"s_cmp_lt_u32 s{j}, s{NTMAX}")
-    out.e(f"s_cbranch_scc0 {skip}")
-    out.ext(dma_lines(j, base, lo, off))
-    out.e(f"{skip}:")
+    out.ext(dma_lines(which))
 
 
 def top_drain(out):
-    """Top of an iteration for a wave that has finished its rows: its own outstanding fetches
-    are older than the next block's first loads, which may stay in flight."""
-    nonext, done = out.label("tn"), out.label("tm")
-    out.e(f"s_cmp_eq_u32 s{HASNEXT}, 1")
-    out.e(f"s_cbranch_scc0 {nonext}")
-    out.e(f"s_waitcnt vmcnt({FIRST_LOADS})")
-    out.e(f"s_branch {done}")
-    out.e(f"{nonext}:")
-    out.e("s_waitcnt vmcnt(0)")
-    out.e(f"{done}:")
+    """Top of an iteration for a wave that has finished its rows: besides the newest tile
+    group, the last tile's fetches and the next block's Q loads may stay in flight."""
+    out.e(f"s_waitcnt vmcnt({8 + 8 + Q_LOADS})")
     out.e("s_barrier")
     dma(out, "K")
     dma(out, "V")
 
 
-def top(out, fetch=True):
-    """Top of iteration t: the group {K(t+2), V(t+1)} has landed for every wave; then fetch
-    {K(t+4), V(t+3)} into the stages that held K(t) and V(t-1) (fetch=False: the caller
-    issues that fetch itself, right after)."""
-    tail, done = out.label("tl"), out.label("td")
-    out.e(f"s_add_u32 s{ST0}, s{T}, 3")
-    out.e(f"s_cmp_ge_u32 s{ST0}, s{NTMAX}")
-    out.e(f"s_cbranch_scc1 {tail}")
+def top(out, probe=False):
+    """Top of iteration t: the group {K(t+2), V(t+1)} has landed for every wave (only the
+    group fetched during iteration t-1 may still be in flight); the fetch of {K(t+4), V(t+3)},
+    into the stages that held K(t) and V(t-1), follows inside the iteration."""
+    if probe:
+        stamp(out, 0, 4)
     out.e("s_waitcnt vmcnt(8)")
-    out.e(f"s_branch {done}")
-    out.e(f"{tail}:")
-    out.e("s_waitcnt vmcnt(0)")
-    out.e(f"{done}:")
+    if probe:
+        stamp(out, 1, 4)
     out.e("s_barrier")
-    if fetch:
-        dma(out, "K")
-        dma(out, "V")
+    if probe:
+        stamp(out, 2, 4)
 
 
 def k_prefetch_tags():
@@ -547,8 +535,8 @@ def final(out, par):
     out.e(f"; ---- final, parity {par}")
     dma(out, "K")
     dma(out, "V")
-    # Q registers and LDS stage 0 are free from here on: the next block's Q rows and first K
-    # tile are fetched between the instructions of this last tile
+    # the Q registers are free from here on: the next block's Q rows are fetched between the
+    # instructions of this last tile
     out.ext(next_block())
     out.e("s_waitcnt lgkmcnt(0)")
     out.ext(mask_block(out, 1, S1[par]))
@@ -563,8 +551,7 @@ def final(out, par):
     out.far += far
     out.ext(weave(valu, q_loads()))
     rescale(out, 1, settle=False)
-    k0 = k0_loads()
-    steps = pv_steps(fifo, P0[par], P1, par, False, lambda i: [], blocks=(1,), extra={1: k0[0], 3: k0[1]})
+    steps = pv_steps(fifo, P0[par], P1, par, False, lambda i: [], blocks=(1,))
     merge(out, steps, [])
     assert not fifo.q
 
@@ -584,10 +571,14 @@ def block_rows():
             f"s_add_u32 s{ST1}, s{ST1}, s{SHEAD}", f"s_add_u32 s{PAIR}, s{PAIR}, s{SHEAD}"]
 
 
-def first_load_pointers():
-    """Pointers of K, V and of this wave's Q rows for the block (s[SG], s[SQB])."""
-    return (block_rows() + pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8)
-            + pointer(QW[0], "q", ST1, 8) + pointer(QW[1], "q", PAIR, 8))
+Q_LOADS = 16   # memory instructions q_loads() issues
+STORES = 18    # memory instructions the epilogue issues
+PROLOGUE_SKIPS_STORES = True
+
+
+def q_pointers():
+    """Pointers of this wave's Q rows for the block (s[SG], s[SQB])."""
+    return block_rows() + pointer(QW[0], "q", ST1, 8) + pointer(QW[1], "q", PAIR, 8)
 
 
 def q_loads():
@@ -596,20 +587,12 @@ def q_loads():
             for b in (0, 1) for kk in range(8)]
 
 
-def k0_loads():
-    """K(0) into LDS stage 0: two groups, each one M0 value and two loads."""
-    return [[f"s_add_u32 m0, %[wave_lds], {u * 4096}", "s_nop 0",
-             f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)} offset:-4096",
-             f"global_load_lds_dwordx4 {v(KL + u)}, {sp(KP)}"] for u in (1, 3)]
-FIRST_LOADS = 16 + 4   # memory instructions q_loads() and k0_loads() issue
-
-
-def next_block():
-    """Scalar part of the early fetch: s[SG], s[SQB] become the block of round s[J] + 1
-    (persistent launch: work id = vid0 + 32 round, the row blocks of a head in turn from the long
-    end and from the short end, so that two rounds together cost every workgroup the same) and
-    s[HASNEXT] = 1; after the last round they stay what they are (that block's Q and first K
-    tile are then simply fetched once more) and s[HASNEXT] = 0.  Then the fetch pointers."""
+def look_ahead():
+    """s[SGN], s[SQBN] = the block of round s[J] + 1 (persistent launch: work id = vid0 + 32
+    round, the row blocks of a head in turn from the long end and from the short end, so that
+    two rounds together cost every workgroup the same) and s[HASNEXT] = 1; after the last round
+    they are the current block again (whose first tiles are then simply fetched once more) and
+    s[HASNEXT] = 0.  s[KPN], s[VPN] = that block's K and V."""
     return [f"s_add_u32 s{ST0}, s{J}, 1",
             f"s_lshl_b32 s{ST1}, s{ST0}, 5",
             f"s_add_u32 s{ST1}, s{ST1}, %[vid0]",
@@ -621,8 +604,14 @@ def next_block():
             f"s_cselect_b32 s{ST1}, s{ST1}, s{OB}",
             f"s_cmp_lt_u32 s{ST0}, %[rounds]",
             f"s_cselect_b32 s{HASNEXT}, 1, 0",
-            f"s_cselect_b32 s{SG}, s{PAIR}, s{SG}",
-            f"s_cselect_b32 s{SQB}, s{ST1}, s{SQB}"] + first_load_pointers()
+            f"s_cselect_b32 s{SGN}, s{PAIR}, s{SG}",
+            f"s_cselect_b32 s{SQBN}, s{ST1}, s{SQB}",
+            f"s_mul_i32 s{SHEAD}, s{SGN}, %[n]"] + pointer(KPN, "k", SHEAD, 8) + pointer(VPN, "v", SHEAD, 8)
+
+
+def next_block():
+    """Scalar part of the early Q fetch: the next block becomes the current one."""
+    return [f"s_mov_b32 s{SG}, s{SGN}", f"s_mov_b32 s{SQB}, s{SQBN}"] + q_pointers()
 
 
 def weave(base, extra, tail=8):
@@ -638,7 +627,7 @@ def weave(base, extra, tail=8):
 
 
 def setup(out):
-    """Once per launch: constants and the first block's loads."""
+    """Once per launch: constants, the first block's Q and its first tiles."""
     out.e("; ---- setup")
     stamp(out, 0)
     stamp(out, 0, 2)
@@ -649,11 +638,21 @@ def setup(out):
     out.e(f"s_mov_b32 s{J}, 0")
     out.e(f"s_mov_b32 s{SG}, %[g0]")
     out.e(f"s_mov_b32 s{SQB}, %[qb0]")
-    out.ext(first_load_pointers() + q_loads() + sum(k0_loads(), []))
+    out.ext(q_pointers() + q_loads())
+    out.e(f"s_mul_i32 s{SHEAD}, s{SG}, %[n]")
+    out.ext(pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8))
+    out.ext(look_ahead())
+    out.e(f"s_lshl_b32 s{NTMAX}, s{SQB}, 2")
+    out.e(f"s_add_u32 s{NTMAX}, s{NTMAX}, 4")
+    out.e(f"s_mov_b32 s{KJ}, 0")
+    out.e(f"s_mov_b32 s{VJ}, 0")
+    for which in "KKVKVKV":
+        dma(out, which)
 
 
 def prologue(out):
-    """Start of a 256-row block: its Q and K(0) are already on their way."""
+    """Start of a 256-row block: its Q rows and its first tiles (K(0..3), V(0..2)) were
+    requested during the block before (or by setup)."""
     out.e("; ---- block start")
     out.ext(block_rows())
     out.ext(pointer(OW[0], "o", ST1, 8) + pointer(OW[1], "o", PAIR, 8))
@@ -664,10 +663,14 @@ def prologue(out):
     out.e(f"s_lshr_b32 s{TF1}, s{PAIR}, 6")
     out.e(f"s_lshr_b32 s{NTMAX}, s{ST0}, 6")
     out.e(f"s_add_u32 s{NTMAX}, s{NTMAX}, 4")
-    out.e(f"s_sub_u32 s{NTM1}, s{NTMAX}, 1")
     out.e(f"s_mov_b32 s{T}, 0")
-    out.e(f"s_mov_b32 s{KJ}, 1")
-    out.e(f"s_mov_b32 s{VJ}, 0")
+    out.e(f"s_mov_b32 s{KJ}, 4")      # K(0..3) and V(0..2) came with the tile stream
+    out.e(f"s_mov_b32 s{VJ}, 3")
+    out.ext(look_ahead())
+    # a block of four tiles has nothing left to fetch for itself: its K stream moves on to the
+    # next block right away (V still has tile 3 to go and switches in dma_lines)
+    out.e(f"s_cmp_eq_u32 s{NTMAX}, 4")
+    out.e(f"s_cselect_b64 {sp(KP)}, {sp(KPN)}, {sp(KP)}")
     for b in (0, 1):
         out.e(f"v_mov_b32 {v(M[b])}, {v(NEGINF)}")
         out.e(f"v_mov_b32 {v(L[b])}, 0")
@@ -682,32 +685,26 @@ def prologue(out):
         out.e(f"v_accvgpr_write_b32 a{i}, 0")
     stamp(out, 3, 2)
     stamp(out, 1)
-    out.e("s_waitcnt vmcnt(0)")    # Q and K(0): all the first logits need (and the last block's stores)
+    # this block's Q rows (and, long before them, its first tiles) have arrived; only the last
+    # block's output stores, which were issued after them, may still be under way
+    out.e(f"s_waitcnt vmcnt({STORES if PROLOGUE_SKIPS_STORES else 0})")
     out.e("s_barrier")             # also: every wave has left the last block's tiles
     stamp(out, 2)
     stamp(out, 4, 2)
     # S0(0), then S1(0) with block 0's first softmax (the one that has to find a maximum)
-    # riding between its matrix ops; the fetches of K(1), V(0), K(2), V(1), K(3), V(2) are
-    # issued on the way.  K(0)'s fragments are read once per block here: LDS is idle anyway.
+    # riding between its matrix ops.  K(0)'s fragments are read once per block here: LDS is
+    # idle anyway.
     fifo = Fifo()
     for f in range(PF):
         out.ext(k_read(f, 0))
         fifo.push(("K", f))
-    pieces = [dma_lines(*((KJ, KP, KL, 0) if w == "K" else (VJ, VP, VL, 16384))) for w in "KVKVKV"]
-    merge(out, qk_steps(fifo, S0, S1[0], 0, False, reader(fifo, "K", 0),
-                        extra={i + 1: pieces[i] for i in range(3)}, blocks=(0,)), [])
+    merge(out, qk_steps(fifo, S0, S1[0], 0, False, reader(fifo, "K", 0), blocks=(0,)), [])
     nomask = out.label("nm")
     lead = (["s_nop 7", f"s_cmp_eq_u32 s{TF0}, 0", f"s_cbranch_scc0 {nomask}"]
             + mask_block(out, 0, S0) + [f"{nomask}:"])
-    merge(out, qk_steps(fifo, S0, S1[0], 0, False, lambda i: [],
-                        extra={i + 1: pieces[3 + i] for i in range(3)}, blocks=(1,)),
+    merge(out, qk_steps(fifo, S0, S1[0], 0, False, reader(fifo, "K", 1), blocks=(1,)),
           softmax_slow(0, S0, P0[0]), lead=2, lead_lines=lead)
-    assert not fifo.q
-    # K(1) and V(0) have landed for every wave (K(2) V(1) K(3) V(2) may still be under way)
-    out.e("s_waitcnt vmcnt(16)")
-    out.e("s_barrier")
-    for f in range(PF):
-        out.ext(k_read(f, 1))
+    assert fifo.q == k_prefetch_tags()
 
 
 def epilogue(out):
@@ -746,8 +743,6 @@ def epilogue(out):
                 out.e(f"ds_write_b64 {v(adr)}, {vr(w, 2)}")
                 n += 1
         out.e("s_waitcnt lgkmcnt(0)")
-        if b == 1:
-            stamp(out, 6, 2)
         for u in range(8):
             out.e(f"v_xor_b32 {v(adr)}, {64 * (u & 3)}, %[crr16]")
             out.e(f"v_add_u32 {v(adr)}, {v(adr)}, %[strip_r]")
@@ -766,6 +761,7 @@ def generate():
     setup(out)
     block = out.label("blk")
     out.e(f"{block}:")
+    stamp(out, 0)
     prologue(out)
     la, lb_e, lb_o, sp_e, sp_o, fin_e, fin_o, drain, epi = (
         out.label(x) for x in ("la", "lbe", "lbo", "spe", "spo", "fe", "fo", "dr", "ep"))
@@ -773,7 +769,7 @@ def generate():
     def step(kind, par, last, target):
         if kind == "both" and par == 0:
             stamp(out, 0, 3)
-        top(out, fetch=False)
+        top(out, probe=(kind == "both" and par == 1))
         if kind == "both" and par == 1:
             stamp(out, 4, 3)
         out.e(f"s_cmp_eq_u32 s{T}, s{last}")
@@ -816,11 +812,8 @@ def generate():
     top_drain(out)
     out.e(f"s_branch {drain}")
     out.e(f"{epi}:")
-    stamp(out, 6)
     stamp(out, 5, 2)
     epilogue(out)
-    stamp(out, 7)
-    stamp(out, 7, 2)
     stamps_store(out)
     out.e(f"s_add_u32 s{J}, s{J}, 1")
     out.e(f"s_cmp_eq_u32 s{HASNEXT}, 1")
@@ -860,6 +853,9 @@ def main():
     if "--stamps3" in args:
         args.remove("--stamps3")
         globals()["STAMPS"] = 3
+    if "--stamps4" in args:
+        args.remove("--stamps4")
+        globals()["STAMPS"] = 4
     while "--drop" in args:  # e.g. --drop mfma --drop softmax: measures what the rest costs
         i = args.index("--drop")
         DROP.add(args[i + 1])

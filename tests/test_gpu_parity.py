@@ -186,6 +186,39 @@ def test_prefill_moving_maximum(d, n, G, rise, say):
     assert s_rel <= parity.SCORE_RTOL
 
 
+@pytest.mark.parametrize("n,G", [(1024, 256),    # four rounds of 256 workgroups, 4 .. 16 tiles per block
+                                 (512, 512),     # four rounds, every second block has only four tiles
+                                 (1024, 200)])   # two rounds plus a remainder launch
+def test_prefill_every_block_of_a_persistent_launch(n, G, say):
+    """A workgroup of the persistent attention launch works through several 256-row blocks and
+    fetches a block's first tiles and Q rows while it finishes the one before.  Every head, so
+    every block in every round, against the oracle (alpha small: the scores hang on the
+    log-sum-exp of the last rows, alpha = 1 on all of them)."""
+    d = 128
+    rng = np.random.Generator(np.random.Philox(key=[n, G]))
+    bits = [synth.round_to_bf16_bits(rng.standard_normal((G, n, d)).astype(np.float32)) for _ in range(3)]
+    host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+    dev = [parity.to_device(b, "bf16") for b in bits]
+    select = recent = 8
+    cache = a2sf.Cache(G, select + recent + 1, d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, n, select + recent + 1, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    P = [orc.causal_probabilities(host[0][g], host[1][g]) for g in range(G)]
+    o_ref = np.stack([orc.attention_output(P[g], host[2][g]) for g in range(G)])
+    for alpha in (0.1, 1.0):
+        o = torch.full((G, n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        sf = torch.full((G, n), float("nan"), dtype=torch.float32, device="cuda")
+        a2sf.a2sf_prefill(dev[0], dev[1], dev[2], n, alpha, select, recent, cache, o=o, scores_full=sf, workspace=ws)
+        torch.cuda.synchronize()
+        o_err = np.abs(parity.to_f64(o) - o_ref).max(axis=(1, 2))
+        S = np.stack([orc.forgotten_scores(P[g], alpha) for g in range(G)])
+        s_rel = (np.abs(parity.to_f64(sf) - S) / np.maximum(np.abs(S), 1e-30)).max(axis=1)
+        say(f"  [persistent launch n={n} G={G} alpha={alpha}] |o err|={o_err.max():.2e} (head {int(o_err.argmax())}) "
+            f"score rel={s_rel.max():.2e} (head {int(s_rel.argmax())})")
+        assert o_err.max() <= parity.O_TOL["bf16"]
+        assert s_rel.max() <= parity.SCORE_RTOL
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_small_fp32(d, say):
     w = variant(0, heads=3, d=d, n=150, T=5, select=9, recent=4, name=f"f32 d{d}")
