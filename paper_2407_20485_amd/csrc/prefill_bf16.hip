@@ -787,8 +787,13 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
 
   for (int t = t_begin; t < t_end; ++t) {
     const int buf = (t - t_begin) & 1;
-    if (t + 1 < t_end) stg.template load<false>(Qg, nullptr, (t + 1) * kTile, n);
     const int row0 = t * kTile;
+    // the rows' log-sum-exp values are requested before the matrix ops that they follow (and
+    // before the next tile's loads, so that waiting for them does not wait for those)
+    float lse_r[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) lse_r[qb] = lse[min(row0 + qb * 32 + l32, n - 1)];
+    if (t + 1 < t_end) stg.template load<false>(Qg, nullptr, (t + 1) * kTile, n);
     if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -804,7 +809,7 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
         // exponent offset of row r: -lse_r + (n-1-r) log2(alpha); rows past the end, and rows
         // whose weight is exactly 0 in fp32 (before first_row), add nothing
         const float bias = (r < n && r >= first_row)
-                               ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+                               ? lse_r[qb] - (float)(n - 1 - r) * log2_alpha : INFINITY;
         const bool diag = row0 + qb * 32 < wc0 + 31;  // block reaches above the diagonal
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -936,11 +941,14 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   for (int kk = 0; kk < KK; ++kk) qoff[kk] = l32 * 256 + (((2 * kk + h) ^ k_swizzle(l32)) << 4);
   // exponent offset of this lane's row in each 32-row block: lse_i - (n-1-i) log2 alpha;
   // +inf (probability 0) for rows past the end or before the window
+  // (all loads issued before the first is used: the address is clamped, not the load skipped)
   float bias[2 * kTailTiles];
+#pragma unroll
+  for (int rb = 0; rb < 2 * kTailTiles; ++rb) bias[rb] = lse[min(r_lo + rb * 32 + l32, n - 1)];
 #pragma unroll
   for (int rb = 0; rb < 2 * kTailTiles; ++rb) {
     const int r = r_lo + rb * 32 + l32;
-    bias[rb] = (r < n && r >= first_row) ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+    bias[rb] = (r < n && r >= first_row) ? bias[rb] - (float)(n - 1 - r) * log2_alpha : INFINITY;
   }
   // A wave owns kTailKB blocks of 32 keys at a time: every Q fragment read from LDS feeds
   // kTailKB matrix ops (one LDS kilobyte per matrix op is more than the LDS delivers).
@@ -1034,7 +1042,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
     float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
     const float* __restrict__ alpha_heads, float scale_log2e) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32 * kStreamKB;
-  __shared__ __attribute__((aligned(1024))) char smem[kStreamStages * kTileBytes];
+  // Q tiles, then per wave and stage the 64 log-sum-exp values of the tile's rows
+  __shared__ __attribute__((aligned(1024))) char smem[kStreamStages * kTileBytes + kWaves * kStreamStages * 256];
   lds_char* const qs = (lds_char*)smem;
 
   const long long total = (long long)G * ncb;
@@ -1054,8 +1063,18 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
 
   const int t_begin = max(c0, first_row) / kTile;
   const int t_end = (n + kTile - 1) / kTile;
-  auto fetch = [&](int t) {  // Q tile t into its ring stage (every wave a quarter of the rows)
-    if (t < t_end) dma_tile<false>(Qg, t * kTile, n, qs + ((t - t_begin) % kStreamStages) * kTileBytes);
+  lds_char* const lse_s = qs + kStreamStages * kTileBytes +
+                          __builtin_amdgcn_readfirstlane(wave) * (kStreamStages * 256);
+  // Q tile t into its ring stage (every wave a quarter of the rows) and the rows' log-sum-exp
+  // values into the wave's own strip of that stage: five loads per wave
+  auto fetch = [&](int t) {
+    if (t < t_end) {
+      const int stage = (t - t_begin) % kStreamStages;
+      dma_tile<false>(Qg, t * kTile, n, qs + stage * kTileBytes);
+      __builtin_amdgcn_global_load_lds((const void*)(lse + min(t * kTile + lane, n - 1)),
+                                       (__attribute__((address_space(3))) void*)(lse_s + stage * 256),
+                                       4, 0, 0);
+    }
   };
   fetch(t_begin);
   fetch(t_begin + 1);
@@ -1080,17 +1099,20 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
     for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 
   for (int t = t_begin; t < t_end; ++t) {
-    // tile t has landed: of this wave's fetches only those of tiles t+1 and t+2 (four loads
+    // tile t has landed: of this wave's fetches only those of tiles t+1 and t+2 (five loads
     // each, fewer at the end) may still be under way
     const int ahead = min(t_end - 1 - t, 2);
-    if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 8);        // vmcnt(8)
-    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 4);   // vmcnt(4)
+    if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 10);       // vmcnt(10)
+    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 5);   // vmcnt(5)
     else __builtin_amdgcn_s_waitcnt(0x0f70);                       // vmcnt(0)
     __syncthreads();
     fetch(t + 3);  // into the stage of tile t-1, which every wave has left
     const int row0 = t * kTile;
     if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
-      const lds_char* qt = qs + ((t - t_begin) % kStreamStages) * kTileBytes;
+      const int stage = (t - t_begin) % kStreamStages;
+      const lds_char* qt = qs + stage * kTileBytes;
+      const __attribute__((address_space(3))) float* lse_t =
+          (const __attribute__((address_space(3))) float*)(lse_s + stage * 256);
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
         f32x16 sacc[kStreamKB];
@@ -1108,7 +1130,7 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
         // exponent offset of row r: lse_r - (n-1-r) log2(alpha); rows past the end, and rows
         // whose weight is exactly 0 in fp32 (before first_row), add nothing
         const float bias = (r < n && r >= first_row)
-                               ? lse[r] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+                               ? lse_t[qb * 32 + l32] - (float)(n - 1 - r) * log2_alpha : INFINITY;
 #pragma unroll
         for (int b = 0; b < kStreamKB; ++b) {
           const int bk0 = wc0 + b * 32;
