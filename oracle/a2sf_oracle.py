@@ -25,6 +25,12 @@ Definitions followed
   score leave the cache so that a fixed budget stays; the budget is split into a
   score-selected part and a most-recent part (either may be 0).
 
+* Similarity to the Ideal mask (Section 4.3, Table 2): at every generation step the Ideal
+  computes the attention of the query over ALL earlier tokens (nothing is ever removed) and
+  keeps the entries of the tokens with the largest attention score, as many as the cache
+  allows; a pruning method's row has entries only on the tokens still in its cache.  The
+  figure of merit is the cosine between the two rows, averaged over steps.
+
 Readings where the paper is silent (all listed in the design notes of the repository):
 ties go to the lower original position; exactly ``len - budget`` tokens leave per step;
 selection after the prompt happens once, on the scores of the whole prompt.
@@ -41,6 +47,7 @@ __all__ = [
     "causal_probabilities", "attention_output", "forgotten_scores",
     "forgotten_scores_recurrence", "forgotten_scores_streamed", "select_keep",
     "HeadCache", "prefill", "attend_and_update", "evict", "decode_step",
+    "pruned_row", "ideal_row", "cosine_similarity", "similarity_to_ideal",
 ]
 
 
@@ -267,3 +274,63 @@ def decode_step(cache: HeadCache, q, k_new, v_new, t_pos: int, alpha: float,
     o, a = attend_and_update(cache, q, k_new, v_new, t_pos, alpha)
     gone, swaps = evict(cache, select, recent, forced_retained, margin)
     return o, a, gone, swaps
+
+
+# --------------------------------------------------------------------------- similarity to Ideal
+def _logits(q, K) -> np.ndarray:
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    return (K @ q) / np.sqrt(float(K.shape[1]))
+
+
+def pruned_row(q, K, retained) -> np.ndarray:
+    """Attention row of one query when only the tokens `retained` (positions, rows of K) can
+    be attended: softmax over those tokens (Section 2.2: after pruning the denominator runs
+    over what is left), zero everywhere else.  K: [L, d], all tokens so far; returns [L]."""
+    s = _logits(q, K)
+    idx = np.asarray(sorted(int(p) for p in retained), dtype=np.int64)
+    if len(idx) == 0 or idx[0] < 0 or idx[-1] >= len(s) or len(set(idx.tolist())) != len(idx):
+        raise ValueError("retained positions must be distinct rows of K")
+    e = np.exp(s[idx] - s[idx].max())
+    row = np.zeros(len(s), dtype=np.float64)
+    row[idx] = e / e.sum()
+    return row
+
+
+def ideal_row(q, K, keep: int) -> np.ndarray:
+    """Row of the Ideal mask (Section 4.3): the query attends all L tokens so far, the `keep`
+    tokens with the largest attention score are selected (tie -> lower position, as
+    everywhere here), and the row is the attention restricted to them.  Which tokens were
+    selected at earlier steps plays no role: nothing is removed for good."""
+    if keep < 1:
+        raise ValueError("keep must be at least 1")
+    s = _logits(q, K)
+    order = sorted(range(len(s)), key=lambda j: (-s[j], j))
+    return pruned_row(q, K, order[:min(int(keep), len(s))])
+
+
+def cosine_similarity(u, v) -> float:
+    u = np.asarray(u, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    return float(np.dot(u, v) / np.sqrt(np.dot(u, u) * np.dot(v, v)))
+
+
+def similarity_to_ideal(Q, K, V, alpha: float, select: int, recent: int, forced_retained=None,
+                        margin: float = 1e-6):
+    """Table 2 protocol on one head: the sequence is generated token by token from an empty
+    cache under the policy (alpha, select, recent); at step i the policy's row has entries on
+    its cached tokens and on token i itself, the Ideal row on equally many tokens.
+
+    forced_retained: optional list, per step i >= 1, of the positions the caller's cache holds
+    after that step (see ``evict``).  Returns (cos[n], cache after the last step)."""
+    Q, K, V = (np.asarray(x, dtype=np.float64) for x in (Q, K, V))
+    n = Q.shape[0]
+    _, _, cache = prefill(Q[:1], K[:1], V[:1], alpha, select, recent)
+    cos = np.ones(n, dtype=np.float64)     # step 0: one token, both rows are [1]
+    for i in range(1, n):
+        retained = [int(p) for p in cache.pos] + [i]
+        cos[i] = cosine_similarity(pruned_row(Q[i], K[:i + 1], retained),
+                                   ideal_row(Q[i], K[:i + 1], len(retained)))
+        decode_step(cache, Q[i], K[i], V[i], i, alpha, select, recent,
+                    None if forced_retained is None else forced_retained[i], margin)
+    return cos, cache

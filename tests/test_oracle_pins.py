@@ -340,6 +340,106 @@ class TestDecode:
 
 
 # ---------------------------------------------------------------- planted mistakes
+def brute_row(q, K, allowed):
+    """Softmax of q.k/sqrt(d) over the positions in `allowed`, explicit loops."""
+    d = len(q)
+    logit = {}
+    for j in allowed:
+        acc = 0.0
+        for c in range(d):
+            acc += q[c] * K[j][c]
+        logit[j] = acc / math.sqrt(d)
+    top = max(logit.values())
+    tot = math.fsum(math.exp(x - top) for x in logit.values())
+    row = [0.0] * len(K)
+    for j, x in logit.items():
+        row[j] = math.exp(x - top) / tot
+    return row
+
+
+class TestSimilarityToIdeal:
+    """Section 4.3 / Table 2: rows of a pruning method against rows of the Ideal mask."""
+
+    def test_no_pruning_is_the_full_attention_row_and_similarity_one(self):
+        Q, K, V = rand_head(40, 8)
+        P = orc.causal_probabilities(Q, K)        # pinned above
+        for i in (0, 5, 39):
+            np.testing.assert_allclose(orc.ideal_row(Q[i], K[:i + 1], keep=i + 1), P[i, :i + 1], rtol=1e-12)
+            np.testing.assert_allclose(orc.pruned_row(Q[i], K[:i + 1], range(i + 1)), P[i, :i + 1], rtol=1e-12)
+        cos, cache = orc.similarity_to_ideal(Q, K, V, 0.4, select=30, recent=30)
+        np.testing.assert_allclose(cos, 1.0, rtol=0, atol=1e-12)
+        assert len(cache) == 40
+
+    def test_rows_by_brute_force(self):
+        Q, K, _ = rand_head(14, 5, scale=1.5)
+        i, keep = 13, 4
+        full = brute_row(Q[i].tolist(), K.tolist(), range(i + 1))
+        best = sorted(range(i + 1), key=lambda j: (-full[j], j))[:keep]
+        np.testing.assert_allclose(orc.ideal_row(Q[i], K, keep), brute_row(Q[i].tolist(), K.tolist(), best),
+                                   rtol=1e-12, atol=1e-300)
+        some = [0, 3, 7, 13]
+        np.testing.assert_allclose(orc.pruned_row(Q[i], K, some), brute_row(Q[i].tolist(), K.tolist(), some),
+                                   rtol=1e-12, atol=1e-300)
+
+    def test_ideal_subset_holds_the_most_attention(self):
+        """"The Mask with the largest Attention Score given the Cache Size": no other subset of
+        that size collects more of the full row's probability (exhaustive search)."""
+        Q, K, _ = rand_head(9, 4, scale=2.0)
+        i, keep = 8, 3
+        full = np.asarray(brute_row(Q[i].tolist(), K.tolist(), range(i + 1)))
+        ideal = orc.ideal_row(Q[i], K, keep)
+        chosen = tuple(np.nonzero(ideal)[0])
+        assert len(chosen) == keep
+        best = max(itertools.combinations(range(i + 1), keep), key=lambda c: full[list(c)].sum())
+        assert chosen == best
+        # inside the subset the row is the full row renormalised
+        np.testing.assert_allclose(ideal[list(chosen)], full[list(chosen)] / full[list(chosen)].sum(), rtol=1e-12)
+
+    def test_uniform_attention_local_window_closed_form(self):
+        """All keys equal: every attention entry is 1/len.  The Ideal keeps the lowest positions
+        (tie rule), a pure recent window keeps the newest: with B cached tokens plus the current
+        one on either side, cos = max(0, 2B + 1 - i) / (B + 1) from step i = B on."""
+        n, d, B = 40, 4, 6
+        Q = RNG.standard_normal((n, d))
+        K = np.tile(RNG.standard_normal(d), (n, 1))
+        V = RNG.standard_normal((n, d))
+        cos, cache = orc.similarity_to_ideal(Q, K, V, 0.5, select=0, recent=B)
+        want = [1.0 if i <= B else max(0, 2 * B + 1 - i) / (B + 1) for i in range(n)]
+        np.testing.assert_allclose(cos, want, rtol=0, atol=1e-12)
+        assert sorted(cache.pos.tolist()) == list(range(n - B, n))
+
+    def test_tie_goes_to_lower_position(self):
+        q = np.array([1.0, 0.0])
+        K = np.array([[0.0, 1.0], [2.0, 0.0], [2.0, 5.0], [1.0, 0.0]])   # logits 0, 2, 2, 1 (times 1/sqrt 2)
+        row = orc.ideal_row(q, K, keep=1)
+        assert np.nonzero(row)[0].tolist() == [1] and row[1] == 1.0
+        assert np.nonzero(orc.ideal_row(q, K, keep=3))[0].tolist() == [1, 2, 3]
+
+    def test_cosine(self):
+        assert orc.cosine_similarity([1, 0, 0], [0, 3, 0]) == 0.0
+        assert abs(orc.cosine_similarity([0.2, 0.3, 0.5], [0.4, 0.6, 1.0]) - 1.0) < 1e-15
+        assert abs(orc.cosine_similarity([1, 1, 0, 0], [1, 0, 1, 0]) - 0.5) < 1e-15
+
+    def test_heavy_tokens_far_back_separate_score_policies_from_a_recent_window(self):
+        """Qualitative content of Table 2 on planted data: with a few heavy tokens far back, a
+        cache that selects by accumulated score stays much closer to the Ideal rows than a pure
+        recent window, which loses them."""
+        rng = np.random.default_rng(5)
+        n, d, B = 160, 16, 16
+        u = rng.standard_normal(d)
+        u /= np.linalg.norm(u)
+        Q = rng.standard_normal((n, d)) + 1.0 * u
+        K = rng.standard_normal((n, d))
+        K[[0, 7, 23, 40, 41, 77]] += 20.0 * u
+        V = rng.standard_normal((n, d))
+        local, _ = orc.similarity_to_ideal(Q, K, V, 0.3, select=0, recent=B)
+        scored, _ = orc.similarity_to_ideal(Q, K, V, 0.3, select=B // 2, recent=B // 2)
+        plain, _ = orc.similarity_to_ideal(Q, K, V, 1.0, select=B // 2, recent=B // 2)
+        assert local[100:].mean() < 0.2
+        assert scored[B + 1:].mean() > local[B + 1:].mean() + 0.2
+        assert plain[B + 1:].mean() > local[B + 1:].mean() + 0.2
+
+
 class TestPinsCatchMistakes:
     """Each case swaps one oracle function for a plausibly wrong one and requires that at
     least one of the pins above fails."""
@@ -357,6 +457,12 @@ class TestPinsCatchMistakes:
         (TestDecode, "test_no_eviction_matches_prompt_form", ()),
         (TestDecode, "test_step_invariants_with_eviction", ()),
         (TestDecode, "test_softmax_is_over_retained_tokens_only", ()),
+        (TestSimilarityToIdeal, "test_no_pruning_is_the_full_attention_row_and_similarity_one", ()),
+        (TestSimilarityToIdeal, "test_rows_by_brute_force", ()),
+        (TestSimilarityToIdeal, "test_ideal_subset_holds_the_most_attention", ()),
+        (TestSimilarityToIdeal, "test_uniform_attention_local_window_closed_form", ()),
+        (TestSimilarityToIdeal, "test_tie_goes_to_lower_position", ()),
+        (TestSimilarityToIdeal, "test_cosine", ()),
     ]
 
     def _some_pin_fails(self):
@@ -430,4 +536,45 @@ class TestPinsCatchMistakes:
         def bad(cache, q, k, v, t, alpha):
             return real(cache, q, k, v, t, 1.0)
         monkeypatch.setattr(orc, "attend_and_update", bad)
+        assert self._some_pin_fails()
+
+    def test_ideal_keeps_the_smallest(self, monkeypatch):
+        def bad(q, K, keep):
+            s = orc._logits(q, K)
+            order = sorted(range(len(s)), key=lambda j: (s[j], j))
+            return orc.pruned_row(q, K, order[:min(keep, len(s))])
+        monkeypatch.setattr(orc, "ideal_row", bad)
+        assert self._some_pin_fails()
+
+    def test_ideal_row_not_renormalised(self, monkeypatch):
+        def bad(q, K, keep):
+            s = orc._logits(q, K)
+            e = np.exp(s - s.max())
+            p = e / e.sum()
+            order = sorted(range(len(s)), key=lambda j: (-s[j], j))[:min(keep, len(s))]
+            row = np.zeros(len(s))
+            row[order] = p[order]
+            return row
+        monkeypatch.setattr(orc, "ideal_row", bad)
+        assert self._some_pin_fails()
+
+    def test_ideal_tie_to_higher_position(self, monkeypatch):
+        def bad(q, K, keep):
+            s = orc._logits(q, K)
+            order = sorted(range(len(s)), key=lambda j: (-s[j], -j))
+            return orc.pruned_row(q, K, order[:min(keep, len(s))])
+        monkeypatch.setattr(orc, "ideal_row", bad)
+        assert self._some_pin_fails()
+
+    def test_method_row_forgets_the_current_token(self, monkeypatch):
+        real = orc.pruned_row
+
+        def bad(q, K, retained):
+            r = sorted(int(p) for p in retained)
+            return real(q, K, r[:-1] if len(r) > 1 and r[-1] == len(K) - 1 else r)
+        monkeypatch.setattr(orc, "pruned_row", bad)
+        assert self._some_pin_fails()
+
+    def test_cosine_without_normalisation(self, monkeypatch):
+        monkeypatch.setattr(orc, "cosine_similarity", lambda u, v: float(np.dot(u, v)))
         assert self._some_pin_fails()
