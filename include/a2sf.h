@@ -164,6 +164,25 @@ a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* 
 a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32_t keep_stride,
                          const int32_t* n_keep, void* hip_stream);
 
+/* Diagnostic of Section 4.3 / Table 2: how close a pruning policy's attention row is to the
+ * row of the Ideal mask, for one generation step of every head.  The Ideal attends ALL
+ * tokens so far (nothing is ever removed) and keeps the entries of the tokens with the
+ * largest attention score (tie -> lower position), as many as the policy's row has; the
+ * policy's row has entries on the tokens in its cache and on the new token.  Either row is
+ * the softmax over its own tokens (Section 2.2), zero elsewhere; the result is their cosine.
+ *   q        [G, d] dtype: the step's query.
+ *   k_all    [G, n_stride, d] dtype, read only: the keys of all tokens so far, row = position,
+ *            rows 0 .. t_pos valid (row t_pos is the new token's key).
+ *   t_pos    position of the new token; t_pos + 1 <= A2SF_SIM_MAX_ROWS, t_pos < n_stride.
+ *   cache    the policy's cache BEFORE this step; only pos, len, capacity, G, d and dtype
+ *            are read.  Cached positions must be < t_pos.
+ *   cos_out  out [G] fp32, in [0, 1]; 1 when the two rows select the same tokens.
+ * Call it right before the a2sf_decode_step of the same token. */
+#define A2SF_SIM_MAX_ROWS 32768
+a2sf_status a2sf_ideal_similarity(const void* q, const void* k_all, int32_t n_stride,
+                                  int32_t t_pos, const a2sf_cache* cache, float* cos_out,
+                                  void* hip_stream);
+
 const char* a2sf_status_string(int32_t status);
 
 #ifdef __cplusplus

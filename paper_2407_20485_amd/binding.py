@@ -22,7 +22,7 @@ A2SF_MAX_CAPACITY = 12288
 
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",
            "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
-           "a2sf_decode_step_alpha_per_head")
+           "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity")
 
 
 class Budget(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.a2sf_select.argtypes = [vp, vp, vp, i32, i32, i32, Budget, vp, vp, vp]
         L.a2sf_compact.restype = i32
         L.a2sf_compact.argtypes = [ctypes.POINTER(CacheStruct), vp, i32, vp, vp]
+        L.a2sf_ideal_similarity.restype = i32
+        L.a2sf_ideal_similarity.argtypes = [vp, vp, i32, i32, ctypes.POINTER(CacheStruct), vp, vp]
         L.a2sf_status_string.restype = ctypes.c_char_p
         L.a2sf_status_string.argtypes = [i32]
         _lib = L
@@ -190,6 +192,12 @@ def a2sf_decode_step_alpha_per_head(q, k_new, v_new, t_pos, cache, alpha_heads, 
 def a2sf_select(scores, pos, length, G, L, stride, select, recent, keep_idx, n_keep, stream=None):
     _check(lib().a2sf_select(_ptr(scores), _ptr(pos), _ptr(length), G, L, stride,
                              Budget(select, recent), _ptr(keep_idx), _ptr(n_keep), _stream(stream)))
+
+
+def a2sf_ideal_similarity(q, k_all, n_stride, t_pos, cache, cos_out, stream=None):
+    cs = _cache_struct(cache)
+    _check(lib().a2sf_ideal_similarity(_ptr(q), _ptr(k_all), n_stride, t_pos, ctypes.byref(cs),
+                                       _ptr(cos_out), _stream(stream)))
 
 
 def a2sf_compact(cache, keep_idx, keep_stride, n_keep, stream=None):

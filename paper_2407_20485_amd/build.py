@@ -11,7 +11,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liba2sf.so")
-SOURCES = ["a2sf_api.hip", "decode.hip", "select_compact.hip", "prefill_f32.hip", "prefill_bf16.hip"]
+SOURCES = ["a2sf_api.hip", "decode.hip", "select_compact.hip", "prefill_f32.hip", "prefill_bf16.hip",
+           "similarity.hip"]
 # -packed-fp32-ops is switched off: packed fp32 forms have produced wrong results on the
 # target machines; the host pass does not know the feature and says so (harmless).
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

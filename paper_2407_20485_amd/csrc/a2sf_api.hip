@@ -200,6 +200,19 @@ a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32
   return launch_status();
 }
 
+a2sf_status a2sf_ideal_similarity(const void* q, const void* k_all, int32_t n_stride,
+                                  int32_t t_pos, const a2sf_cache* cache, float* cos_out,
+                                  void* hip_stream) {
+  a2sf_budget any = {1, 0};
+  a2sf_status s;
+  if ((s = check_cache(cache, any)) != A2SF_OK) return s;
+  if (!q || !k_all || !cos_out) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k_all)) return A2SF_EINVAL;
+  if (t_pos < 0 || t_pos >= A2SF_SIM_MAX_ROWS || n_stride <= t_pos) return A2SF_ESHAPE;
+  launch_ideal_similarity(q, k_all, n_stride, t_pos + 1, *cache, cos_out, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
 const char* a2sf_status_string(int32_t status) {
   switch (status) {
     case A2SF_OK: return "ok";

@@ -122,3 +122,16 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liba2sf.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         B.lib()
+
+
+def test_ideal_similarity_argument_errors():
+    f = B.lib().a2sf_ideal_similarity
+    ok_cache = fake_cache()
+    assert f(None, FAKE, 16, 3, ctypes.byref(ok_cache), FAKE, None) == B.A2SF_EINVAL
+    assert f(FAKE, FAKE, 16, 3, ctypes.byref(ok_cache), None, None) == B.A2SF_EINVAL
+    assert f(FAKE, FAKE + 4, 16, 3, ctypes.byref(ok_cache), FAKE, None) == B.A2SF_EINVAL      # misaligned
+    assert f(FAKE, FAKE, 16, 16, ctypes.byref(ok_cache), FAKE, None) == B.A2SF_ESHAPE         # row outside k_all
+    assert f(FAKE, FAKE, 1 << 20, 32768, ctypes.byref(ok_cache), FAKE, None) == B.A2SF_ESHAPE  # too long a row
+    assert f(FAKE, FAKE, 16, -1, ctypes.byref(ok_cache), FAKE, None) == B.A2SF_ESHAPE
+    assert f(FAKE, FAKE, 16, 3, ctypes.byref(fake_cache(d=96)), FAKE, None) == B.A2SF_ESHAPE
+    assert f(FAKE, FAKE, 16, 3, None, FAKE, None) == B.A2SF_EINVAL

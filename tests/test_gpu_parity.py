@@ -393,3 +393,127 @@ def test_cfg4_long_context(say):
             ls.step(t)
         say(f"  [cfg4 alpha={alpha}] decode max|o err|={ls.max_o_err:.2e} "
             f"max score rel={ls.max_s_rel:.2e} swaps={ls.swaps}")
+
+
+# ---------------------------------------------------------------- similarity to the Ideal mask
+SIM_TOL = 1e-4     # fp32 logits (error <= ~1e-5) exponentiated, squared and summed: see the design notes
+CUT_GAP = 1e-4     # a logit gap at the Ideal's cut below this may flip the choice in fp32
+
+
+def near_tie_at_cut(q, K, keep):
+    s = np.sort((K @ q) / math.sqrt(K.shape[1]))[::-1]
+    return keep < len(s) and s[keep - 1] - s[keep] < CUT_GAP
+
+
+@pytest.mark.parametrize("dtype,d,n,select,recent,alpha", [
+    ("bf16", 128, 200, 12, 12, 0.3),     # the split used by the other tests
+    ("f32", 64, 150, 0, 16, 0.5),        # recent window only (the paper's Local baseline)
+    ("bf16", 64, 160, 16, 0, 1.0),       # plain accumulation, no recent part
+    ("f32", 128, 90, 20, 0, 0.1),        # the paper's own split (no recent part), small alpha
+])
+def test_similarity_to_ideal_protocol(dtype, d, n, select, recent, alpha, say):
+    """Section 4.3 / Table 2 protocol, token by token from an empty cache: before every
+    generation step the library reports the cosine between the policy's row and the Ideal
+    row; the oracle runs the same protocol (following the GPU's retained sets inside the usual
+    margin)."""
+    G = 3
+    rng = np.random.Generator(np.random.Philox(key=[n, d]))
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    q = rng.standard_normal((G, n, d)) + u
+    k = rng.standard_normal((G, n, d))
+    k[:, [0, 5, 17, 40, 41, 77]] += 3.0 * math.sqrt(math.sqrt(d)) * u     # a sink and a few heavy tokens
+    v = rng.standard_normal((G, n, d))
+    if dtype == "bf16":
+        bits = [synth.round_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v)]
+        host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+        dev = [parity.to_device(b, "bf16") for b in bits]
+    else:
+        host = [x.astype(np.float32).astype(np.float64) for x in (q, k, v)]
+        dev = [parity.to_device(x.astype(np.float32), "f32") for x in (q, k, v)]
+    B = select + recent
+    code = a2sf.A2SF_F32 if dtype == "f32" else a2sf.A2SF_BF16
+    cache = a2sf.Cache(G, B + 1, d, parity.torch_dtype(dtype))
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, 1, B + 1, d, code, select, recent), dtype=torch.uint8, device="cuda")
+    first = [x[:, :1].contiguous() for x in dev]
+    a2sf.a2sf_prefill(first[0], first[1], first[2], 1, alpha, select, recent, cache, workspace=ws)
+    cos = torch.ones((n, G), dtype=torch.float32, device="cuda")
+    o = torch.empty((G, d), dtype=parity.torch_dtype(dtype), device="cuda")
+    retained = [None]
+    for i in range(1, n):
+        qi, ki, vi = (x[:, i].contiguous() for x in dev)
+        a2sf.a2sf_ideal_similarity(qi, dev[1], n, i, cache, cos[i])
+        a2sf.a2sf_decode_step(qi, ki, vi, i, cache, alpha, select, recent, o, workspace=ws)
+        L = cache.len.cpu().numpy()
+        P = cache.pos.cpu().numpy()
+        retained.append([P[g, :L[g]].tolist() for g in range(G)])
+    got = cos.cpu().numpy().astype(np.float64)
+    worst, skipped = 0.0, 0
+    for g in range(G):
+        want, oc = orc.similarity_to_ideal(host[0][g], host[1][g], host[2][g], alpha, select, recent,
+                                           forced_retained=[None if r is None else r[g] for r in retained])
+        for i in range(n):
+            keep = min(i, B) + 1
+            if near_tie_at_cut(host[0][g][i], host[1][g][:i + 1], keep):
+                skipped += 1
+                continue
+            worst = max(worst, abs(got[i, g] - want[i]))
+    say(f"  [similarity {dtype} d={d} n={n} {select}+{recent} alpha={alpha}] max |cos err|={worst:.2e}, "
+        f"{skipped} near-tie rows skipped, mean cos={got[B + 1:].mean():.3f}")
+    assert worst <= SIM_TOL
+    assert skipped <= 0.05 * n * G
+
+
+def test_similarity_to_ideal_longest_row(say):
+    """The largest row the call accepts (32768 tokens, the long-context configuration's
+    prompt length) with a cache of arbitrary earlier positions; and the shortest ones."""
+    G, d, L = 4, 128, 32768
+    rng = np.random.Generator(np.random.Philox(key=[L, 77]))
+    kb = synth.round_to_bf16_bits(rng.standard_normal((G, L, d)).astype(np.float32))
+    qb = synth.round_to_bf16_bits((1.5 * rng.standard_normal((G, d))).astype(np.float32))
+    K = synth.bf16_bits_to_f32(kb).astype(np.float64)
+    Q = synth.bf16_bits_to_f32(qb).astype(np.float64)
+    cap = 400
+    cache = a2sf.Cache(G, cap, d, torch.bfloat16)
+    lens = [399, 1, 0, 250]
+    pos = np.zeros((G, cap), dtype=np.int32)
+    for g in range(G):
+        pos[g, :lens[g]] = rng.choice(L - 1, size=lens[g], replace=False)
+    cache.pos.copy_(torch.from_numpy(pos))
+    cache.len.copy_(torch.tensor(lens, dtype=torch.int32))
+    out = torch.empty(G, dtype=torch.float32, device="cuda")
+    kd, qd = parity.to_device(kb, "bf16"), parity.to_device(qb, "bf16")
+    for t_pos in (L - 1, 0, 1):
+        if t_pos < L - 1:
+            cache.len.zero_()          # nothing cached yet at the very first tokens
+        a2sf.a2sf_ideal_similarity(qd, kd, L, t_pos, cache, out)
+        got = out.cpu().numpy()
+        for g in range(G):
+            held = pos[g, :lens[g]].tolist() if t_pos == L - 1 else []
+            want = orc.cosine_similarity(orc.pruned_row(Q[g], K[g, :t_pos + 1], held + [t_pos]),
+                                         orc.ideal_row(Q[g], K[g, :t_pos + 1], len(held) + 1))
+            say(f"  [similarity L={t_pos + 1} head {g} cache {len(held)}] cos={got[g]:.6f} oracle={want:.6f}")
+            if not near_tie_at_cut(Q[g], K[g, :t_pos + 1], len(held) + 1):
+                assert abs(got[g] - want) <= SIM_TOL
+
+
+def test_similarity_protocol_module(say):
+    """paper_2407_20485_amd.similarity_protocol.mask_similarity only sequences library calls."""
+    from paper_2407_20485_amd import similarity_protocol as sp
+    G, n, d, select, recent, alpha = 2, 72, 64, 5, 4, 0.5
+    rng = np.random.Generator(np.random.Philox(key=[n, 4321]))
+    q, k, v = (rng.standard_normal((G, n, d)).astype(np.float32) for _ in range(3))
+    k[:, [0, 9]] += 2.0
+    q += 0.25
+    cos = sp.mask_similarity(*(torch.from_numpy(x).cuda() for x in (q, k, v)), alpha, select, recent)
+    got = cos.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for g in range(G):
+        want, _ = orc.similarity_to_ideal(q[g].astype(np.float64), k[g].astype(np.float64),
+                                          v[g].astype(np.float64), alpha, select, recent)
+        for i in range(n):
+            if not near_tie_at_cut(q[g][i].astype(np.float64), k[g][:i + 1].astype(np.float64),
+                                   min(i, select + recent) + 1):
+                worst = max(worst, abs(got[i, g] - want[i]))
+    say(f"  [similarity protocol module] max |cos err|={worst:.2e}, mean cos={got.mean():.3f}")
+    assert worst <= SIM_TOL
