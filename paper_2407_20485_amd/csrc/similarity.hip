@@ -9,9 +9,10 @@
 // denominators cancel.
 //
 // One workgroup per head.  The logits of all L = t_pos + 1 tokens are formed once (the keys
-// are streamed from HBM exactly once, 16 bytes per lane) and stay in LDS; the Ideal's cut is
-// an exact radix select over 64-bit keys (ordered logit, then lower position first), so ties
-// need no special case.
+// are streamed from HBM exactly once, 16 bytes per lane) and stay in LDS (4 L bytes of dynamic
+// LDS, so short rows leave room for several workgroups per CU); the Ideal's cut is an exact
+// radix select over 64-bit keys (ordered logit, then lower position first), so ties need no
+// special case; it stops as soon as every key that still matches is known to be kept.
 #include "a2sf_dev.h"
 #include "a2sf_internal.h"
 
@@ -33,12 +34,11 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
   constexpr int EPL = Elem<T>::kPerLane;  // elements per 16-byte access
   constexpr int LPR = D / EPL;            // lanes per row
   constexpr int RPW = kWave / LPR;        // rows per wave-wide load
-  constexpr int U = 4;                    // loads in flight per lane
-  __shared__ float s[kSimMaxRows];
+  constexpr int U = 8;                    // loads in flight per lane
+  extern __shared__ __attribute__((aligned(16))) float s[];  // L logits
   __shared__ int hist[256];
   __shared__ float redf[8];
-  __shared__ int redi[8];
-  __shared__ unsigned long long pick[2];
+  __shared__ unsigned long long pick[3];
 
   const int g = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -92,11 +92,14 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
         while (above + hist[digit] < want) above += hist[digit--];
         pick[0] = (unsigned long long)digit;
         pick[1] = (unsigned long long)above;
+        pick[2] = (unsigned long long)hist[digit];
       }
       __syncthreads();
       prefix |= pick[0] << shift;
       want -= (int)pick[1];
+      const bool all_kept = (int)pick[2] == want;  // every key with this prefix is kept
       __syncthreads();
+      if (all_kept) break;                         // (the digits left are 0 in `prefix`)
     }
     cut = prefix;  // keys are distinct: exactly `keep` of them are >= cut
   }
@@ -128,7 +131,6 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
   qi = block_sum(qi, redf);
   qm = block_sum(qm, redf);
   dot = block_sum(dot, redf);
-  (void)redi;
   if (tid == 0) out[g] = dot / sqrtf(qi * qm);
 }
 
@@ -136,9 +138,16 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
 
 void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int L,
                              const a2sf_cache& c, float* out, hipStream_t st) {
-#define A2SF_SIM(T, D)                                                                        \
-  hipLaunchKernelGGL((ideal_similarity_kernel<T, D>), dim3(c.G), dim3(kThreads), 0, st,       \
-                     (const T*)q, (const T*)k_all, n_stride, L, c.pos, c.len, c.capacity, out)
+  const size_t lds = ((size_t)L * 4 + 1023) & ~(size_t)1023;
+#define A2SF_SIM(T, D)                                                                          \
+  do {                                                                                          \
+    static const hipError_t raised = hipFuncSetAttribute(                                       \
+        (const void*)ideal_similarity_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+        kSimMaxRows * 4);                                                                       \
+    (void)raised;                                                                               \
+    hipLaunchKernelGGL((ideal_similarity_kernel<T, D>), dim3(c.G), dim3(kThreads), lds, st,     \
+                       (const T*)q, (const T*)k_all, n_stride, L, c.pos, c.len, c.capacity, out); \
+  } while (0)
   if (c.dtype == A2SF_F32) {
     if (c.d == 64) A2SF_SIM(float, 64); else A2SF_SIM(float, 128);
   } else {

@@ -49,13 +49,40 @@ POLICIES = (   # name, alpha, share of the budget that is score-selected
 )
 
 
+def time_kernel(G, L, d=128, cached=200, reps=20):
+    """Time of one a2sf_ideal_similarity call over rows of length L against its algorithmic
+    bytes (the keys, read once: G * L * d * 2)."""
+    k = torch.randn((G, L, d), device="cuda").to(torch.bfloat16)
+    q = torch.randn((G, d), device="cuda").to(torch.bfloat16)
+    cache = B.Cache(G, cached + 1, d, torch.bfloat16)
+    cache.len.fill_(min(cached, L - 1))
+    cache.pos.copy_(torch.arange(cached + 1, dtype=torch.int32, device="cuda").expand(G, -1) % max(L - 1, 1))
+    out = torch.empty(G, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        B.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        B.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = G * L * d * 2
+    print(f"a2sf_ideal_similarity: {G} heads x {L} rows, d = {d}, bf16: {us:.1f} us per call, "
+          f"{nbytes / us / 1e3:.0f} GB/s of key bytes ({nbytes / us / 1e3 / 8000:.1%} of 8 TB/s)")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=1, help="synthetic workload (shapes and salience recipe)")
     ap.add_argument("--heads", type=int, default=32)
     ap.add_argument("--length", type=int, default=None, help="sequence length (default: the config's prompt)")
     ap.add_argument("--ratio", type=float, default=0.2, help="cache ratio, as in the paper's Section 4.3")
+    ap.add_argument("--time-kernel", action="store_true",
+                    help="instead: time a2sf_ideal_similarity alone at --heads x --length (bf16, d = 128)")
     a = ap.parse_args()
+    if a.time_kernel:
+        return time_kernel(a.heads, a.length or 4096)
     w = synth.CONFIGS[a.config]
     n = a.length or w.n
     heads = list(range(min(a.heads, w.G)))
