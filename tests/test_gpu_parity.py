@@ -395,6 +395,87 @@ def test_cfg4_long_context(say):
             f"max score rel={ls.max_s_rel:.2e} swaps={ls.swaps}")
 
 
+# ---------------------------------------------------------------- HIP graph capture
+@pytest.mark.parametrize("G,mode", [(48, "fast"), (48, "stable"), (1100, "fast"), (4200, "fast")])
+def test_decode_steps_replay_from_a_hip_graph(G, mode, say):
+    """The calls only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset), so a run of generation steps can be captured in a HIP graph.
+    Every replay -- with eager work and synchronisations in between -- must leave exactly
+    what the eager run left: outputs and the whole cache, bit for bit.  (Each launch path:
+    token-split, workgroup per head, wave per head; fast and stable eviction.)"""
+    d, n, T, select, recent, alpha = 128, 96, 6, 10, 10, 0.4
+    evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
+    gen = torch.Generator(device="cuda").manual_seed(G)
+    q, k, v = (torch.randn((G, n + T, d), device="cuda", generator=gen).bfloat16() for _ in range(3))
+    cache = a2sf.Cache(G, select + recent + 1, d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, n, select + recent + 1, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    a2sf.a2sf_prefill(q[:, :n].contiguous(), k[:, :n].contiguous(), v[:, :n].contiguous(), n, alpha,
+                      select, recent, cache, workspace=ws)
+    start = cache.snapshot()
+    steps = [tuple(x[:, n + t].contiguous() for x in (q, k, v)) for t in range(T)]
+    outs = torch.zeros((T, G, d), dtype=torch.bfloat16, device="cuda")
+
+    def run_steps():
+        for t, (qt, kt, vt) in enumerate(steps):
+            a2sf.a2sf_decode_step(qt, kt, vt, n + t, cache, alpha, select, recent, outs[t], mode=evict,
+                                  workspace=ws)
+
+    run_steps()
+    torch.cuda.synchronize()
+    want_o, want_cache = outs.clone(), cache.snapshot()
+
+    graph = torch.cuda.CUDAGraph()
+    cache.restore(start)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        run_steps()
+    for replay in range(3):
+        cache.restore(start)
+        outs.zero_()
+        (q[:, 0] * 2).sum().item()          # unrelated eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, want_o), f"replay {replay}: outputs differ"
+        for a, b in zip(cache.tensors(), want_cache):
+            assert torch.equal(a, b), f"replay {replay}: cache differs"
+    say(f"  [graph replay G={G} {mode}] {T} steps captured, 3 replays identical to the eager run")
+
+
+@pytest.mark.parametrize("n,G,d", [(512, 256, 128), (300, 5, 128), (200, 6, 64)])
+def test_prompt_phase_replays_from_a_hip_graph(n, G, d, say):
+    """The prompt phase (attention, column scores, selection, gather: up to five launches,
+    two of them the persistent attention kernel and its remainder) captured and replayed."""
+    select = recent = 20
+    gen = torch.Generator(device="cuda").manual_seed(n)
+    q, k, v = (torch.randn((G, n, d), device="cuda", generator=gen).bfloat16() for _ in range(3))
+    cache = a2sf.Cache(G, select + recent + 1, d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, n, select + recent + 1, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    o = torch.zeros_like(q)
+    sf = torch.zeros((G, n), dtype=torch.float32, device="cuda")
+
+    def run():
+        a2sf.a2sf_prefill(q, k, v, n, 0.6, select, recent, cache, o=o, scores_full=sf, workspace=ws)
+
+    run()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (o, sf, *cache.tensors())]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for replay in range(2):
+        for t in (o, sf, *cache.tensors()):
+            t.zero_()
+        ws.random_(0, 255)                   # the workspace's content may be anything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip((o, sf, *cache.tensors()), want):
+            assert torch.equal(a, b), f"replay {replay} differs"
+    say(f"  [graph replay prompt n={n} G={G} d={d}] 2 replays identical to the eager run")
+
+
 # ---------------------------------------------------------------- similarity to the Ideal mask
 SIM_TOL = 1e-4     # fp32 logits (error <= ~1e-5) exponentiated, squared and summed: see the design notes
 CUT_GAP = 1e-4     # a logit gap at the Ideal's cut below this may flip the choice in fp32
