@@ -573,7 +573,6 @@ def block_rows():
 
 Q_LOADS = 16   # memory instructions q_loads() issues
 STORES = 18    # memory instructions the epilogue issues
-PROLOGUE_SKIPS_STORES = True
 
 
 def q_pointers():
@@ -687,13 +686,13 @@ def prologue(out):
     stamp(out, 1)
     # this block's Q rows (and, long before them, its first tiles) have arrived; only the last
     # block's output stores, which were issued after them, may still be under way
-    out.e(f"s_waitcnt vmcnt({STORES if PROLOGUE_SKIPS_STORES else 0})")
+    out.e(f"s_waitcnt vmcnt({STORES})")
     out.e("s_barrier")             # also: every wave has left the last block's tiles
     stamp(out, 2)
     stamp(out, 4, 2)
     # S0(0), then S1(0) with block 0's first softmax (the one that has to find a maximum)
-    # riding between its matrix ops.  K(0)'s fragments are read once per block here: LDS is
-    # idle anyway.
+    # riding between its matrix ops.  K(0)'s fragments are read once per pass, i.e. twice per
+    # block, here: LDS is idle anyway.
     fifo = Fifo()
     for f in range(PF):
         out.ext(k_read(f, 0))

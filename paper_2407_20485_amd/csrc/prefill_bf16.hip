@@ -670,8 +670,9 @@ constexpr int kX2Slots = 32;             // persistent launch: workgroups per XC
 
 // rounds == 1: one workgroup per (head, 256-row block), ids mapped as in the other kernels.
 // rounds > 1 (persistent launch, 8 * kX2Slots workgroups, nqb a power of two): the workgroup
-// in slot r of XCD x works on ids x * (total / 8) + r + 32 j, j = 0 .. rounds - 1; the loads a
-// block starts with are issued while the previous block's output is being written.
+// in slot r of XCD x works on ids x * (total / 8) + r + 32 j, j = 0 .. rounds - 1; the K/V tile
+// stream runs on from one block into the next and a block's Q rows are loaded during the last
+// tile of the block before, so a block starts with its first tiles already in LDS.
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int nqb, int id_base, int ids,
