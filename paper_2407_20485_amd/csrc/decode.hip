@@ -629,9 +629,13 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
 
 DecodePlan plan_decode(int G, int capacity, int d) {
   DecodePlan p;
-  // Enough workgroups to cover the 256 compute units a few times over; a split never
-  // gets fewer than 64 rows.
-  int want = (1024 + G - 1) / G;
+  // Token split: enough workgroups to cover the 256 compute units a few times over; a split
+  // never gets fewer than 64 rows.  It costs a second launch (the combine kernel), which only
+  // pays when one workgroup per head would leave most of the chip idle for long: measured, the
+  // single fused kernel wins for short caches at any head count (12 us against 15 us per step
+  // at 32 heads x 205 slots), for a few hundred heads up to ~1000 slots, and from ~640 heads on.
+  const bool one_kernel = capacity <= 512 || (G >= 256 && capacity <= 1024) || G >= 640;
+  int want = one_kernel ? 1 : (1024 + G - 1) / G;
   int max_split = (capacity + 63) / 64;
   int ns = want < max_split ? want : max_split;
   if (ns < 1) ns = 1;

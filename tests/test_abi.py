@@ -87,8 +87,8 @@ def test_decode_argument_errors():
     assert decode_status(fake_cache(), mode=3) == B.A2SF_EINVAL
     assert decode_status(fake_cache(), t_pos=-1) == B.A2SF_EINVAL
     assert decode_status(fake_cache(capacity=8)) == B.A2SF_ECAPACITY
-    # few heads => split over tokens => needs the workspace; stable mode always does
-    assert decode_status(fake_cache(G=2, capacity=200, select=50, recent=50), select=50, recent=50,
+    # few heads with a long cache => split over tokens => needs the workspace; stable mode always does
+    assert decode_status(fake_cache(G=2, capacity=700, select=50, recent=50), select=50, recent=50,
                          ws=None) == B.A2SF_EWORKSPACE
     assert decode_status(fake_cache(G=4096), mode=1, ws=None) == B.A2SF_EWORKSPACE
 

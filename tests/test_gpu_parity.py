@@ -219,6 +219,19 @@ def test_prefill_every_block_of_a_persistent_launch(n, G, say):
         assert s_rel.max() <= parity.SCORE_RTOL
 
 
+@pytest.mark.parametrize("base,d", [(0, 64), (0, 128), (1, 64), (1, 128)])
+def test_token_split_decode_path(base, d, say):
+    """Few heads with room for more than 512 slots: the tokens of a head are split over
+    several workgroups and a second kernel combines them (short caches with few heads take the
+    one-kernel path instead).  fp32 and bf16, both head sizes, both eviction modes, one and
+    several evictions per step, per-head forgetting factors."""
+    w = variant(base, heads=5, d=d, n=700, T=6, select=330, recent=330, name=f"token split {CFG[base].dtype} d{d}")
+    run_lockstep(w, 0.4, capacity=700, say=say)
+    run_lockstep(w, 0.4, capacity=700, mode=a2sf.A2SF_EVICT_STABLE, say=say)
+    run_lockstep(w, np.array([0.0, 1.0, 0.3, 0.9, 0.6], dtype=np.float32), capacity=700, say=say)
+    run_lockstep(w, 0.4, capacity=700, select=200, recent=100, say=say)     # budget below the cache's fill
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_small_fp32(d, say):
     w = variant(0, heads=3, d=d, n=150, T=5, select=9, recent=4, name=f"f32 d{d}")
@@ -396,14 +409,16 @@ def test_cfg4_long_context(say):
 
 
 # ---------------------------------------------------------------- HIP graph capture
-@pytest.mark.parametrize("G,mode", [(48, "fast"), (48, "stable"), (1100, "fast"), (4200, "fast")])
-def test_decode_steps_replay_from_a_hip_graph(G, mode, say):
+@pytest.mark.parametrize("G,mode,select", [(48, "fast", 300), (48, "stable", 300), (48, "fast", 10),
+                                           (1100, "fast", 10), (4200, "fast", 10)])
+def test_decode_steps_replay_from_a_hip_graph(G, mode, select, say):
     """The calls only enqueue kernels on the caller's stream (no allocation, no
     synchronisation, no memset), so a run of generation steps can be captured in a HIP graph.
     Every replay -- with eager work and synchronisations in between -- must leave exactly
     what the eager run left: outputs and the whole cache, bit for bit.  (Each launch path:
-    token-split, workgroup per head, wave per head; fast and stable eviction.)"""
-    d, n, T, select, recent, alpha = 128, 96, 6, 10, 10, 0.4
+    token-split -- few heads with more than 512 slots --, workgroup per head, wave per head;
+    fast and stable eviction.)"""
+    d, n, T, recent, alpha = 128, 96, 6, select, 0.4
     evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
     gen = torch.Generator(device="cuda").manual_seed(G)
     q, k, v = (torch.randn((G, n + T, d), device="cuda", generator=gen).bfloat16() for _ in range(3))
@@ -439,7 +454,7 @@ def test_decode_steps_replay_from_a_hip_graph(G, mode, say):
         assert torch.equal(outs, want_o), f"replay {replay}: outputs differ"
         for a, b in zip(cache.tensors(), want_cache):
             assert torch.equal(a, b), f"replay {replay}: cache differs"
-    say(f"  [graph replay G={G} {mode}] {T} steps captured, 3 replays identical to the eager run")
+    say(f"  [graph replay G={G} {mode} budget={select + recent}] {T} steps captured, 3 replays identical to the eager run")
 
 
 @pytest.mark.parametrize("n,G,d", [(512, 256, 128), (300, 5, 128), (200, 6, 64)])
