@@ -17,7 +17,6 @@ namespace {
 
 struct SelectSmem {
   int hist[256];
-  int scan[256];
   int wave_tot[kWaves];
   uint32_t prefix;
   int k;
@@ -41,17 +40,19 @@ __device__ uint32_t radix_kth_largest(F f, int L, int k, SelectSmem& sm) {
       if (f(j, key) && (key & known_mask) == prefix) atomicAdd(&sm.hist[(key >> shift) & 255u], 1);
     }
     __syncthreads();
-    // suffix sums: above(t) = sum of hist[b] for b > t
-    int v = sm.hist[tid];
-    sm.scan[tid] = v;
-    __syncthreads();
-    for (int o = 1; o < 256; o <<= 1) {
-      int add = (tid + o < 256) ? sm.scan[tid + o] : 0;
-      __syncthreads();
-      sm.scan[tid] += add;
-      __syncthreads();
+    // suffix sums: above(t) = sum of hist[b] for b > t.  Inside a wave by shuffles, then the
+    // totals of the waves above: one barrier instead of a 256-wide scan through LDS.
+    const int v = sm.hist[tid];
+    const int lane = tid & 63, wave = tid >> 6;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int y = __shfl_down(incl, o, 64);
+      if (lane + o < 64) incl += y;
     }
-    const int incl = sm.scan[tid];   // sum over b >= tid
+    if (lane == 0) sm.wave_tot[wave] = incl;
+    __syncthreads();
+    for (int w = wave + 1; w < kWaves; ++w) incl += sm.wave_tot[w];  // sum over b >= tid
     const int above = incl - v;
     if (above < kk && kk <= incl) {  // exactly one thread
       sm.prefix = prefix | ((uint32_t)tid << shift);
