@@ -125,6 +125,10 @@ def main():
     ap.add_argument("--mode", choices=["fast", "stable"], default="fast")
     ap.add_argument("--alpha", type=float, default=None,
                     help="forgetting factor (default: the workload's; config 4 sweeps 0.1, 0.5, 0.9, 1.0)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the T generation steps of a pass from one HIP graph instead of launching "
+                         "them one by one (matters for the few-head configs, whose steps are shorter than "
+                         "a host launch)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -170,6 +174,13 @@ def main():
     o_pre = None if args.no_o else torch.empty((G, n, d), dtype=tdt, device="cuda")
     o_dec = torch.empty((G, d), dtype=tdt, device="cuda")
 
+    graph = None
+
+    def decode_steps():
+        for t in range(T):
+            a2sf.a2sf_decode_step(dev["qd"][t], dev["kd"][t], dev["vd"][t], n + t, cache, alpha,
+                                  w.select, w.recent, o_dec, mode=mode, workspace=ws)
+
     def one_pass(ev=None):
         if ev:
             ev[0].record()
@@ -177,9 +188,10 @@ def main():
                           o=o_pre, scores_full=None, workspace=ws)
         if ev:
             ev[1].record()
-        for t in range(T):
-            a2sf.a2sf_decode_step(dev["qd"][t], dev["kd"][t], dev["vd"][t], n + t, cache, alpha,
-                                  w.select, w.recent, o_dec, mode=mode, workspace=ws)
+        if graph is not None:
+            graph.replay()
+        else:
+            decode_steps()
         if ev:
             ev[2].record()
 
@@ -193,6 +205,13 @@ def main():
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()
+    if args.graph:   # the library only enqueues kernels: the T steps of a pass fit one HIP graph
+        one_pass()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            decode_steps()
+        torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -213,7 +232,8 @@ def main():
     flops = prefill_model_flops(G, n, d, with_o=not args.no_o)
     dec_gbs = dbytes / dec_s_per_step / 1e9
     pre_tflops = flops / pre_s / 1e12
-    nsplit_note = "one fused kernel per step" if G >= 1024 else "token-split partial + combine kernels per step"
+    one_kernel = capacity <= 256 or (G >= 256 and capacity <= 1024) or G >= 640   # the library's launch plan
+    nsplit_note = "one fused kernel per step" if one_kernel else "token-split partial + combine kernels per step"
 
     out = {
         "metric": "decode steps/s (fused attn+A2SF+evict) & HBM GB/s; prefill score TFLOP/s",
@@ -226,6 +246,7 @@ def main():
         "config": {"workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n, "head_dim": d,
                    "decode_steps": T, "budget": f"{w.select}+{w.recent}", "alpha": alpha,
                    "evict_mode": args.mode, "prefill_outputs": not args.no_o,
+                   "decode_launch": "hip graph of the T steps" if args.graph else "one launch per kernel",
                    "pass": "prefill + T decode steps"},
         "decode_us_per_step": dec_s_per_step * 1e6,
         "decode_hbm_gbs_algorithmic": dec_gbs,

@@ -630,11 +630,13 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
 DecodePlan plan_decode(int G, int capacity, int d) {
   DecodePlan p;
   // Token split: enough workgroups to cover the 256 compute units a few times over; a split
-  // never gets fewer than 64 rows.  It costs a second launch (the combine kernel), which only
-  // pays when one workgroup per head would leave most of the chip idle for long: measured, the
-  // single fused kernel wins for short caches at any head count (12 us against 15 us per step
-  // at 32 heads x 205 slots), for a few hundred heads up to ~1000 slots, and from ~640 heads on.
-  const bool one_kernel = capacity <= 512 || (G >= 256 && capacity <= 1024) || G >= 640;
+  // never gets fewer than 64 rows.  It costs a second kernel (the combine), which only pays
+  // when one workgroup per head would leave most of the chip idle for long.  Measured GPU
+  // time per step (steps replayed from a HIP graph, bf16, d = 128), one kernel / split:
+  // 32 heads x 205 slots 8.1 / 8.7 us, 8 x 512 11.2 / 9.0, 128 x 512 14.7 / 12.2,
+  // 64 x 1024 23.0 / 13.3, 256 x 1024 28.0 / 27.4, 320 x 410 17.0 / 18.2, 512 x 512 23.8 / 27.1,
+  // 900 x 256 21.2 / 26.5, 700 x 4096 257 / 291.
+  const bool one_kernel = capacity <= 256 || (G >= 256 && capacity <= 1024) || G >= 640;
   int want = one_kernel ? 1 : (1024 + G - 1) / G;
   int max_split = (capacity + 63) / 64;
   int ns = want < max_split ? want : max_split;

@@ -221,7 +221,7 @@ def test_prefill_every_block_of_a_persistent_launch(n, G, say):
 
 @pytest.mark.parametrize("base,d", [(0, 64), (0, 128), (1, 64), (1, 128)])
 def test_token_split_decode_path(base, d, say):
-    """Few heads with room for more than 512 slots: the tokens of a head are split over
+    """Few heads with room for more than 256 slots: the tokens of a head are split over
     several workgroups and a second kernel combines them (short caches with few heads take the
     one-kernel path instead).  fp32 and bf16, both head sizes, both eviction modes, one and
     several evictions per step, per-head forgetting factors."""
@@ -416,7 +416,7 @@ def test_decode_steps_replay_from_a_hip_graph(G, mode, select, say):
     synchronisation, no memset), so a run of generation steps can be captured in a HIP graph.
     Every replay -- with eager work and synchronisations in between -- must leave exactly
     what the eager run left: outputs and the whole cache, bit for bit.  (Each launch path:
-    token-split -- few heads with more than 512 slots --, workgroup per head, wave per head;
+    token-split -- few heads with more than 256 slots --, workgroup per head, wave per head;
     fast and stable eviction.)"""
     d, n, T, recent, alpha = 128, 96, 6, select, 0.4
     evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
