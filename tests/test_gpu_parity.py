@@ -492,7 +492,8 @@ def test_prompt_phase_replays_from_a_hip_graph(n, G, d, say):
 
 
 # ---------------------------------------------------------------- similarity to the Ideal mask
-SIM_TOL = 1e-4     # fp32 logits (error <= ~1e-5) exponentiated, squared and summed: see the design notes
+SIM_TOL = 1e-4     # fp32 logits carry <= ~1e-5 of error; exponentiated, squared and summed that is <= 4e-5
+                   # relative on each of the three sums the cosine is made of
 CUT_GAP = 1e-4     # a logit gap at the Ideal's cut below this may flip the choice in fp32
 
 
