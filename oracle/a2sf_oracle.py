@@ -31,7 +31,7 @@ Definitions followed
   allows; a pruning method's row has entries only on the tokens still in its cache.  The
   figure of merit is the cosine between the two rows, averaged over steps.
 
-Readings where the paper is silent (all listed in the design notes of the repository):
+Readings where the paper is silent:
 ties go to the lower original position; exactly ``len - budget`` tokens leave per step;
 selection after the prompt happens once, on the scores of the whole prompt.
 
