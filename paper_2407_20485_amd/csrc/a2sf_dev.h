@@ -160,6 +160,18 @@ __device__ __forceinline__ void head_window(const float* alpha_heads, int g, int
 }
 
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// 16 bytes that are read once and not again soon (the streamed rows of a KV cache): the
+// non-temporal hint keeps them from displacing other lines on their way through the caches.
+// Measured on MI355X with reads of 1.7 GB: 7.0-7.1 TB/s with the hint, 6.2-6.3 TB/s without.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <bool STREAM>
+__device__ __forceinline__ uint4 load16_as(const void* p) {
+  return STREAM ? load16_stream(p) : load16(p);
+}
 __device__ __forceinline__ void store16(void* p, const uint4& v) { *reinterpret_cast<uint4*>(p) = v; }
 
 }  // namespace a2sf

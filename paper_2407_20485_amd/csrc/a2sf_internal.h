@@ -25,6 +25,7 @@ struct DecodePlan {
   int nsplit;          // workgroups per head (1 = single fused kernel)
   int rows_per_split;  // multiple of 64
   int wave_slots;      // > 0: wave-per-head kernel holding 64*wave_slots slots in registers
+  bool stream;         // single-kernel paths: load the cache rows with the non-temporal hint
   size_t ws_bytes;     // split-K scratch
 };
 DecodePlan plan_decode(int G, int capacity, int d);
