@@ -14,9 +14,7 @@ import paper_2407_20485_amd as a2sf
 from oracle import a2sf_oracle as orc
 from paper_2407_20485_amd import synth
 
-O_TOL = {"bf16": 2e-2, "f32": 1e-5}
-SCORE_RTOL = 1e-4
-MARGIN = 1e-6
+from oracle_replay import MARGIN, O_TOL, SCORE_RTOL   # the tolerances, stated once
 
 
 def to_device(arr: np.ndarray, dtype: str) -> torch.Tensor:
@@ -38,14 +36,14 @@ class Problem:
     """A workload on the GPU plus what the oracle needs for a chosen sample of heads."""
 
     def __init__(self, w: synth.Workload, heads=None, sample=None, capacity=None, threads=None,
-                 progress=None):
+                 progress=None, host_copies=True):
         self.w = w
         self.heads = list(range(w.G)) if heads is None else list(heads)   # heads on the GPU
         self.G = len(self.heads)
         self.sample = list(range(self.G)) if sample is None else list(sample)  # indices into heads
         data = synth.generate(w, self.heads, threads=threads, progress=progress)
         self.host = {}
-        for i in self.sample:   # float64 copies for the oracle
+        for i in (self.sample if host_copies else []):   # float64 copies for the oracle
             self.host[i] = tuple(
                 np.concatenate([self._f32(data[k][i]), self._f32(data[k + "d"][:, i])]).astype(np.float64)
                 for k in ("q", "k", "v"))
@@ -209,3 +207,85 @@ class LockStep:
             assert err <= O_TOL[w.dtype], f"head {i} step {t}: output max-abs {err:.3e}"
             self.max_s_rel = max(self.max_s_rel, compare_cache(
                 p, i, oc, f"head {i} step {t}", ordered=self.ascending))
+
+
+class Replay:
+    """Record-and-replay comparison for the full-size configurations.
+
+    The GPU runs the prompt phase and every generation step for all heads without waiting for
+    the host; for a sample of heads everything the steps produce is recorded.  Afterwards one
+    worker process per head regenerates the head's inputs from its seed and runs the oracle over
+    the same prompt and steps (tests/oracle_replay.py), so hundreds of heads are checked element
+    by element -- outputs of every step, scores and retained set after every step, the cached
+    K/V rows at a few steps -- in the time a handful took in lock-step."""
+
+    def __init__(self, p: Problem, select=None, recent=None):
+        self.p = p
+        self.select = p.w.select if select is None else select
+        self.recent = p.w.recent if recent is None else recent
+        self.runs = {i: {} for i in p.sample}
+        self.idx = torch.as_tensor(p.sample, device="cuda")
+        self.o_err = self.s_rel = 0.0
+        self.swaps = 0
+
+    def _state(self, rows):
+        c, idx = self.p.cache, self.idx
+        lens = c.len[idx].cpu().numpy()
+        pos = c.pos[idx].cpu().numpy()
+        sc = c.scores[idx].cpu().numpy()
+        kv = (c.k[idx].float().cpu().numpy(), c.v[idx].float().cpu().numpy()) if rows else None
+        return lens, pos, sc, kv
+
+    def run_gpu(self, alpha, steps=None, mode=a2sf.A2SF_EVICT_FAST, row_steps=None, keep_o=True):
+        """One prompt phase + `steps` generation steps at forgetting factor `alpha`, recorded."""
+        p, w = self.p, self.p.w
+        T = w.T if steps is None else steps
+        row_steps = {0, T // 2, T - 1} if row_steps is None else set(row_steps)
+        o, s = p.gpu_prefill(alpha, select=self.select, recent=self.recent)
+        torch.cuda.synchronize()
+        lens, pos, sc, kv = self._state(True)
+        o_s = o[self.idx].float().cpu().numpy() if keep_o else None
+        s_s = s[self.idx].cpu().numpy()
+        for j, i in enumerate(p.sample):
+            L = int(lens[j])
+            self.runs[i][float(np.float32(alpha))] = {
+                "o": None if o_s is None else o_s[j], "s_full": s_s[j],
+                "pre": (pos[j, :L].copy(), sc[j, :L].copy(), (kv[0][j, :L].copy(), kv[1][j, :L].copy())),
+                "fast": mode != a2sf.A2SF_EVICT_STABLE, "steps": []}
+        self.s_full = s
+        del o
+        for t in range(T):
+            od = p.gpu_decode(t, alpha, mode=mode, select=self.select, recent=self.recent)
+            o_t = od[self.idx].float().cpu().numpy()
+            lens, pos, sc, kv = self._state(t in row_steps)
+            for j, i in enumerate(p.sample):
+                L = int(lens[j])
+                self.runs[i][float(np.float32(alpha))]["steps"].append(
+                    (o_t[j], pos[j, :L].copy(), sc[j, :L].copy(),
+                     None if kv is None else (kv[0][j, :L].copy(), kv[1][j, :L].copy())))
+        return s
+
+    def check(self, say=None, workers=None, threads=1):
+        """Runs the oracle over every recorded head in worker processes; raises on any mismatch."""
+        import multiprocessing as mp
+        import os
+
+        import oracle_replay
+
+        p = self.p
+        jobs = [{"w": p.w, "g": p.heads[i], "select": self.select, "recent": self.recent,
+                 "threads": threads, "runs": self.runs[i]} for i in p.sample]
+        if workers is None:
+            workers = max(1, min(16, len(os.sched_getaffinity(0)), len(jobs)))
+        failures = []
+        with mp.get_context("spawn").Pool(workers) as pool:
+            for k, r in enumerate(pool.imap_unordered(oracle_replay.replay_head, jobs)):
+                self.o_err = max(self.o_err, r["o_err"])
+                self.s_rel = max(self.s_rel, r["s_rel"])
+                self.swaps += r["swaps"]
+                if r["failure"]:
+                    failures.append(r["failure"])
+                if say and (k + 1) % 64 == 0:
+                    say(f"    oracle replay: {k + 1}/{len(jobs)} heads")
+        assert not failures, f"{len(failures)} of {len(jobs)} heads differ: " + "; ".join(failures[:5])
+        return self

@@ -331,81 +331,63 @@ def check_all_heads_invariants(p, s_full, alpha, steps_done):
 
 
 def test_cfg3_opt13b_shape(say):
+    """All 320 heads on the GPU; 48 seeded heads replayed by the oracle, every step."""
     w = CFG[3]
-    sample = [0, 77, 161, 319]
-    p = parity.Problem(w, sample=sample)
-    ls = parity.LockStep(p, w.alpha)
-    _, s = ls.prefill()
-    check_all_heads_invariants(p, s, w.alpha, 0)
-    for t in range(w.T):
-        ls.step(t)
+    sample = sorted(np.random.default_rng(3).choice(w.G, 48, replace=False).tolist())
+    p = parity.Problem(w, sample=sample, host_copies=False)
+    rp = parity.Replay(p)
+    s = rp.run_gpu(w.alpha)
     check_all_heads_invariants(p, s, w.alpha, w.T)
-    say(f"  [cfg3] max|o err|={ls.max_o_err:.2e} max score rel={ls.max_s_rel:.2e} swaps={ls.swaps}")
+    rp.check(say)
+    say(f"  [cfg3] {len(sample)} heads: max|o err|={rp.o_err:.2e} max score rel={rp.s_rel:.2e} swaps={rp.swaps}")
 
 
 def test_cfg2_full_size_sampled(say):
-    """All 16384 heads on the GPU in the benchmark's launch configuration; oracle on a sample."""
+    """All 16384 heads on the GPU in the benchmark's launch configuration.  1024 seeded heads,
+    32 from each of the 32 layers (so they are spread over the whole launch: every 16th head on
+    average, every workgroup position and round of the persistent prompt kernel), are replayed
+    by the oracle: prompt outputs and scores, then output, scores and retained set of every one
+    of the 128 steps.  Properties that need no oracle are checked on all heads."""
     w = CFG[2]
     rng = np.random.default_rng(2)
-    sample = sorted(rng.choice(w.G, 12, replace=False).tolist())
+    per_layer = w.batch * w.heads
+    sample = sorted(int(l * per_layer + j) for l in range(w.layers)
+                    for j in rng.choice(per_layer, 32, replace=False))
     say(f"  [cfg2] generating {w.G} heads ...")
-    p = parity.Problem(w, sample=sample, progress=lambda c, H: say(f"    {c}/{H} heads"))
-    ls = parity.LockStep(p, w.alpha)
-    _, s = ls.prefill()
-    check_all_heads_invariants(p, s, w.alpha, 0)
-    say("  [cfg2] prefill ok")
-    for t in range(w.T):
-        ls.step(t)
-        if t % 32 == 31:
-            say(f"    step {t + 1}/{w.T}")
+    p = parity.Problem(w, sample=sample, progress=lambda c, H: say(f"    {c}/{H} heads"), host_copies=False)
+    rp = parity.Replay(p)
+    s = rp.run_gpu(w.alpha)
+    say("  [cfg2] GPU pass recorded")
     check_all_heads_invariants(p, s, w.alpha, w.T)
     # newest `recent` positions are present in every head
     pos = p.cache.pos.cpu().numpy()
     newest = np.sort(pos, axis=1)[:, -w.recent:]
     assert np.array_equal(newest, np.tile(np.arange(w.n + w.T - w.recent, w.n + w.T), (w.G, 1)))
-    say(f"  [cfg2] max|o err|={ls.max_o_err:.2e} max score rel={ls.max_s_rel:.2e} swaps={ls.swaps}")
+    # every retained position is a real token and no head holds one twice
+    assert pos.min() >= 0 and pos.max() == w.n + w.T - 1
+    assert np.all(np.diff(np.sort(pos[:, :w.budget], axis=1), axis=1) > 0)
+    rp.check(say)
+    say(f"  [cfg2] {len(sample)} heads: max|o err|={rp.o_err:.2e} max score rel={rp.s_rel:.2e} swaps={rp.swaps}")
 
 
 def test_cfg4_long_context(say):
-    """n = 32768, alpha swept over {0.1, 0.5, 0.9, 1.0} on the same inputs: prompt scores and
-    outputs against the row-streamed oracle on two heads (the probabilities do not depend on
-    alpha, so one oracle sweep serves all four), the geometric total on all heads, then the
-    decode steps in lock-step on those two heads.  alpha = 1 is the plain accumulated score."""
+    """n = 32768, alpha swept over {0.1, 0.5, 0.9, 1.0} on the same inputs.  Eight heads are
+    replayed by the row-streamed oracle (the probabilities do not depend on alpha, so one sweep
+    per head serves all four factors): prompt outputs and scores, then every generation step.
+    The geometric total is checked on all heads.  alpha = 1 is the plain accumulated score."""
     w = CFG[4]
-    sample = [3, 30]
-    p = parity.Problem(w, sample=sample)
-    ref = {}
-    for i in sample:
-        Q, K, V = (x[: w.n] for x in p.host[i])
-        ref[i] = orc.forgotten_scores_streamed(Q, K, list(w.alphas), V=V, rows_per_chunk=1024)
-        say(f"  [cfg4] oracle prompt sweep of head {i} done")
+    sample = [0, 3, 9, 14, 19, 24, 30, 31]
+    p = parity.Problem(w, sample=sample, host_copies=False)
+    rp = parity.Replay(p)
     for alpha in w.alphas:
-        o, s = p.gpu_prefill(alpha)
-        torch.cuda.synchronize()
-        check_all_heads_invariants(p, s, alpha, 0)
-        p.fetch()
-        ls = parity.LockStep(p, alpha)
-        for i in sample:
-            Q, K, V = (x[: w.n] for x in p.host[i])
-            S_full, O = ref[i][0][float(alpha)], ref[i][1]
-            err = np.abs(parity.to_f64(o[i]) - O).max()
-            assert err <= parity.O_TOL["bf16"], f"head {i}: prefill output max-abs {err:.3e}"
-            rel = parity.compare_scores(s[i].cpu().numpy(), S_full, f"head {i} prompt scores")
-            _, gpos, _, _, _ = p.gpu_cache_of(i)
-            keep, sw = orc._resolve_keep(S_full, np.arange(w.n), w.select, w.recent, gpos.tolist(),
-                                         parity.MARGIN)
-            ls.swaps += sw
-            ls.oc[i] = orc.HeadCache(K[keep], V[keep], S_full[keep], keep)
-            parity.compare_cache(p, i, ls.oc[i], f"head {i} after prefill", ordered=True)
-            say(f"  [cfg4 alpha={alpha}] head {i}: prefill |o err|={err:.2e} score rel={rel:.2e} "
-                f"in-margin swaps={sw}")
+        s = rp.run_gpu(alpha)
+        check_all_heads_invariants(p, s, alpha, w.T)
         if alpha == 1.0:   # Section 3.1 Eq.4: the first token has been summed over every row
             assert float(s[:, 0].min()) > float(s[:, w.n // 2:].max())
-        del o
-        for t in range(w.T):
-            ls.step(t)
-        say(f"  [cfg4 alpha={alpha}] decode max|o err|={ls.max_o_err:.2e} "
-            f"max score rel={ls.max_s_rel:.2e} swaps={ls.swaps}")
+        say(f"  [cfg4 alpha={alpha}] GPU pass recorded")
+    rp.check(say, threads=2)
+    say(f"  [cfg4] {len(sample)} heads x {len(w.alphas)} factors: max|o err|={rp.o_err:.2e} "
+        f"max score rel={rp.s_rel:.2e} in-margin swaps={rp.swaps}")
 
 
 # ---------------------------------------------------------------- HIP graph capture
