@@ -128,6 +128,23 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
                              int32_t mode, void* o, void* workspace, size_t workspace_bytes,
                              void* hip_stream);
 
+/* a2sf_decode_step for callers that cannot provide or allocate a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Identical in every
+ * other respect (same kernels, same results); the scratch memory that a2sf_decode_step takes
+ * as `workspace` is a fixed array of A2SF_STATIC_WS_BYTES inside the library instead, one per
+ * GPU, held until the process ends.  Nothing is allocated or freed by this call.
+ *  - Returns A2SF_EWORKSPACE, launching nothing, when
+ *    a2sf_workspace_bytes(G, 0, capacity, d, dtype, budget) exceeds A2SF_STATIC_WS_BYTES.
+ *  - Every call on one GPU uses the same array: calls that overlap in time on one GPU (on
+ *    different streams) race.  The array keeps the previous call's content; every kernel
+ *    writes what it later reads, so nothing has to be cleared.
+ *  - The first call on a device looks the array's address up (hipGetSymbolAddress); make that
+ *    first call outside any stream capture. */
+#define A2SF_STATIC_WS_BYTES (16u << 20)
+a2sf_status a2sf_decode_step_static_ws(const void* q, const void* k_new, const void* v_new,
+                                       int32_t t_pos, const a2sf_cache* cache, float alpha,
+                                       a2sf_budget budget, int32_t mode, void* o, void* hip_stream);
+
 /* The same two calls with one forgetting factor per head (Section 6 of the paper names a
  * distinct factor per layer and head as the way to lift its limitation of a single one).
  *   alpha_heads  [G] fp32, device: head g uses alpha_heads[g], each in [0, 1].

@@ -19,10 +19,11 @@ A2SF_OK, A2SF_EINVAL, A2SF_ESHAPE, A2SF_EDTYPE, A2SF_ECAPACITY, A2SF_EWORKSPACE,
 A2SF_F32, A2SF_BF16 = 0, 1
 A2SF_EVICT_FAST, A2SF_EVICT_STABLE = 0, 1
 A2SF_MAX_CAPACITY = 12288
+A2SF_STATIC_WS_BYTES = 16 << 20
 
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",
            "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
-           "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity")
+           "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity", "a2sf_decode_step_static_ws")
 
 
 class Budget(ctypes.Structure):
@@ -56,6 +57,9 @@ def lib() -> ctypes.CDLL:
         L.a2sf_decode_step.restype = i32
         L.a2sf_decode_step.argtypes = [vp, vp, vp, i32, ctypes.POINTER(CacheStruct), f32, Budget, i32,
                                        vp, vp, sz, vp]
+        L.a2sf_decode_step_static_ws.restype = i32
+        L.a2sf_decode_step_static_ws.argtypes = [vp, vp, vp, i32, ctypes.POINTER(CacheStruct), f32, Budget,
+                                                 i32, vp, vp]
         L.a2sf_prefill_alpha_per_head.restype = i32
         L.a2sf_prefill_alpha_per_head.argtypes = [vp, vp, vp, i32, vp, f32, Budget,
                                                   ctypes.POINTER(CacheStruct), vp, vp, vp, sz, vp]
@@ -164,6 +168,13 @@ def a2sf_decode_step(q, k_new, v_new, t_pos, cache, alpha, select, recent, o,
     _check(lib().a2sf_decode_step(_ptr(q), _ptr(k_new), _ptr(v_new), t_pos, ctypes.byref(cs), alpha,
                                   Budget(select, recent), mode, _ptr(o), _ptr(workspace),
                                   workspace_bytes, _stream(stream)))
+
+
+def a2sf_decode_step_static_ws(q, k_new, v_new, t_pos, cache, alpha, select, recent, o,
+                               mode=A2SF_EVICT_FAST, stream=None):
+    cs = _cache_struct(cache)
+    _check(lib().a2sf_decode_step_static_ws(_ptr(q), _ptr(k_new), _ptr(v_new), t_pos, ctypes.byref(cs),
+                                            alpha, Budget(select, recent), mode, _ptr(o), _stream(stream)))
 
 
 def a2sf_prefill_alpha_per_head(q, k, v, n, alpha_heads, alpha_max, select, recent, cache, o=None,

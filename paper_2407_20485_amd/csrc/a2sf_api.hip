@@ -3,11 +3,36 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "a2sf_internal.h"
 
 using namespace a2sf;
 
+// Scratch memory of a2sf_decode_step_static_ws: one array per GPU, alive for the life of the
+// process.  In host code this name is only a handle for hipGetSymbolAddress; the device
+// address it yields (one per device) is what kernels and the carving code below are given.
+static __device__ __align__(256) unsigned char scratch[A2SF_STATIC_WS_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once known
+
+// Device address of this device's copy of `scratch` (looked up once per device).
+a2sf_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return A2SF_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return A2SF_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return A2SF_OK;
+}
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
@@ -165,6 +190,21 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
                              void* hip_stream) {
   return decode_impl(q, k_new, v_new, t_pos, cache, alpha, nullptr, budget, mode, o, workspace,
                      workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_decode_step_static_ws(const void* q, const void* k_new, const void* v_new,
+                                       int32_t t_pos, const a2sf_cache* cache, float alpha,
+                                       a2sf_budget budget, int32_t mode, void* o, void* hip_stream) {
+  // size check first (host only): what a2sf_decode_step would ask of its workspace argument
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (ws_layout(cache->G, 0, cache->capacity, cache->d, budget).total > (size_t)A2SF_STATIC_WS_BYTES)
+    return A2SF_EWORKSPACE;
+  void* ws = nullptr;
+  if ((s = static_scratch(&ws)) != A2SF_OK) return s;
+  return decode_impl(q, k_new, v_new, t_pos, cache, alpha, nullptr, budget, mode, o, ws,
+                     (size_t)A2SF_STATIC_WS_BYTES, hip_stream);
 }
 
 a2sf_status a2sf_decode_step_alpha_per_head(const void* q, const void* k_new, const void* v_new,

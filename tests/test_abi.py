@@ -93,6 +93,16 @@ def test_decode_argument_errors():
     assert decode_status(fake_cache(G=4096), mode=1, ws=None) == B.A2SF_EWORKSPACE
 
 
+def test_static_workspace_entry_point_checks_its_limit_on_the_host():
+    f = B.lib().a2sf_decode_step_static_ws
+    big = fake_cache(G=4096, capacity=2049, d=128, dtype=B.A2SF_BF16)       # 33 MB of keep indices
+    assert B.a2sf_workspace_bytes(4096, 0, 2049, 128, B.A2SF_BF16, 1024, 1024) > B.A2SF_STATIC_WS_BYTES
+    assert f(FAKE, FAKE, FAKE, 5, ctypes.byref(big), 0.3, B.Budget(1024, 1024), 0, FAKE, None) == B.A2SF_EWORKSPACE
+    assert f(FAKE, FAKE, FAKE, 5, ctypes.byref(fake_cache(capacity=8)), 0.3, B.Budget(4, 4), 0, FAKE,
+             None) == B.A2SF_ECAPACITY
+    assert f(FAKE, FAKE, FAKE, 5, None, 0.3, B.Budget(4, 4), 0, FAKE, None) == B.A2SF_EINVAL
+
+
 def test_per_head_alpha_argument_errors():
     lib = B.lib()
     c = fake_cache()
