@@ -127,6 +127,36 @@ def test_select_and_compact_argument_errors():
     assert lib.a2sf_compact(ctypes.byref(c), FAKE, 0, FAKE, None) == B.A2SF_ESHAPE
 
 
+def test_select_rejects_misaligned_pointers_and_index_overflow():
+    lib = B.lib()
+    b = B.Budget(2, 2)
+    assert lib.a2sf_select(FAKE + 4, None, None, 1, 8, 8, b, FAKE, FAKE, None) == B.A2SF_EINVAL     # scores: 16 bytes
+    assert lib.a2sf_select(FAKE, FAKE + 2, None, 1, 8, 8, b, FAKE, FAKE, None) == B.A2SF_EINVAL     # pos: 4 bytes
+    assert lib.a2sf_select(FAKE, None, None, 1, 8, 8, b, FAKE + 1, FAKE, None) == B.A2SF_EINVAL
+    assert lib.a2sf_select(FAKE, None, None, 1 << 20, 1 << 12, 1 << 12, b, FAKE, FAKE, None) == B.A2SF_ESHAPE
+
+
+def test_decode_plan_is_a_host_query():
+    assert B.a2sf_decode_plan(16384, 201, 128) == (1, 256, 4)        # one wave per head, 256 slots in registers
+    nsplit, rows, wave = B.a2sf_decode_plan(32, 3277, 128)           # few heads, long cache: tokens are split
+    assert nsplit > 1 and rows % 64 == 0 and nsplit * rows >= 3277 and wave == 0
+    assert B.a2sf_decode_plan(320, 410, 128)[0] == 1
+    lib = B.lib()
+    assert lib.a2sf_decode_plan(0, 10, 128, None, None, None) == B.A2SF_ESHAPE
+    assert lib.a2sf_decode_plan(4, 10, 100, None, None, None) == B.A2SF_ESHAPE
+    assert lib.a2sf_decode_plan(4, B.A2SF_MAX_CAPACITY + 1, 128, None, None, None) == B.A2SF_ECAPACITY
+    assert lib.a2sf_decode_plan(4, 10, 128, None, None, None) == B.A2SF_OK      # out pointers are optional
+
+
+def test_similarity_mean_argument_errors():
+    f = B.lib().a2sf_similarity_mean
+    assert f(None, 4, 2, 1, FAKE, None) == B.A2SF_EINVAL
+    assert f(FAKE, 4, 2, 1, None, None) == B.A2SF_EINVAL
+    assert f(FAKE + 2, 4, 2, 1, FAKE, None) == B.A2SF_EINVAL
+    assert f(FAKE, 0, 2, 0, FAKE, None) == B.A2SF_ESHAPE
+    assert f(FAKE, 4, 2, 5, FAKE, None) == B.A2SF_ESHAPE
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liba2sf.so")

@@ -184,6 +184,31 @@ def test_stream_registers_are_declared(stream):
     assert used <= declared, sorted(used - declared)[:10]
 
 
+def test_stream_special_registers(stream):
+    """Special registers the stream writes: vcc and scc are declared; exec is restored to all
+    ones wherever it is narrowed; M0 is written before the direct-to-LDS loads and is left out of
+    the clobber list on purpose (a reserved register: the compiler keeps nothing in it across a
+    statement and rejects it in a clobber list).  Nothing else may appear as a destination."""
+    lines, clob = stream
+    named = set(re.findall(r'"([a-z0-9]+)"', clob))
+    assert {"vcc", "scc", "memory"} <= named and "m0" not in named
+    written = set()
+    for ln in lines:
+        op, ops = split_operands(ln)
+        if not ops or op.startswith(("s_cmp", "s_cbranch", "s_branch", "s_waitcnt", "s_nop", "s_barrier")):
+            continue
+        if op.startswith("v_cmp") and not op.startswith("v_cmpx"):
+            written.add(ops[0])
+            continue
+        if classify(op) == "salu":
+            written.add(ops[0])
+    special = {w for w in written if not re.match(r"^s\d+$|^s\[\d+:\d+\]$", w)}
+    assert special <= {"m0", "vcc", "exec", "vcc_lo", "vcc_hi"}, sorted(special)
+    if "exec" in special:     # every narrowing of exec is undone before the stream ends
+        last = max(i for i, ln in enumerate(lines) if split_operands(ln)[1][:1] == ["exec"])
+        assert lines[last].replace(" ", "") in ("s_mov_b64exec,-1",), lines[last]
+
+
 def test_stream_barriers_are_wave_uniform(stream):
     """Every s_barrier sits in code all four waves of a workgroup run the same number of times:
     none may lie between a conditional branch on a per-wave quantity and its target.  The only

@@ -150,12 +150,18 @@ def test_prefill_optional_outputs(base, d, n):
 @pytest.mark.parametrize("d,n,G", [(128, 2048, 3), (128, 2304, 3), (128, 1024, 3), (128, 300, 3), (64, 320, 3),
                                    (128, 2048, 128), (128, 1024, 128), (128, 512, 256),   # several row blocks per workgroup
                                    (128, 2048, 100)])                                     # ... plus a remainder launch
-@pytest.mark.parametrize("rise", [200.0, -60.0, 40.0])
-def test_prefill_moving_maximum(d, n, G, rise, say):
+@pytest.mark.parametrize("rise,v_scale", [(200.0, 0.5), (-60.0, 0.5), (40.0, 0.5), (200.0, 1.0), (-60.0, 1.0)])
+def test_prefill_moving_maximum(d, n, G, rise, v_scale, say):
     """Logits that climb (or fall) by `rise` base-2 units over the sequence: the running maximum
     of the online softmax has to move again and again, in every phase of the tile loop, for
     both row blocks of a wave and in the tiles that hold the diagonal.  Outputs, and the scores
-    (which depend on the log-sum-exp the attention pass leaves behind), against the oracle."""
+    (which depend on the log-sum-exp the attention pass leaves behind), against the oracle.
+
+    Attention is nearly one-hot here, so an output row is close to a single V row.  With
+    V ~ 0.5 N(0,1) every |o| stays below 2.5 and the plain 2e-2 bound applies.  With V ~ N(0,1)
+    outputs reach |o| = 4..5, where bf16 values are 2^-5 apart: rounding the result to bf16
+    alone costs up to 2^-6 = 1.6e-2 there, so for |o| > 2 the bound grows with the magnitude
+    (2e-2 * |o| / 2, i.e. 1e-2 relative = 2.6 half-ulps of bf16); below 2 it stays 2e-2."""
     alpha = 0.97
     rng = np.random.Generator(np.random.Philox(key=[n, d + int(abs(rise))]))
     u = rng.standard_normal(d)
@@ -163,7 +169,7 @@ def test_prefill_moving_maximum(d, n, G, rise, say):
     a = math.sqrt(abs(rise) * math.log(2.0) * math.sqrt(d))      # q.k / sqrt(d) spans |rise| ln 2
     q = rng.standard_normal((G, n, d)) + a * u
     k = rng.standard_normal((G, n, d)) + math.copysign(a, rise) * (np.arange(n) / n)[None, :, None] * u
-    v = 0.5 * rng.standard_normal((G, n, d))   # attention is nearly one-hot here: keep |o| where a bf16 ulp is small
+    v = v_scale * rng.standard_normal((G, n, d))
     bits = [synth.round_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v)]
     host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
     dev = [parity.to_device(b, "bf16") for b in bits]
@@ -175,14 +181,21 @@ def test_prefill_moving_maximum(d, n, G, rise, say):
     sf = torch.full((G, n), float("nan"), dtype=torch.float32, device="cuda")
     a2sf.a2sf_prefill(dev[0], dev[1], dev[2], n, alpha, select, recent, cache, o=o, scores_full=sf, workspace=ws)
     torch.cuda.synchronize()
-    o_err = s_rel = 0.0
+    o_err = o_excess = o_max = s_rel = 0.0
     for g in (range(G) if G <= 8 else range(0, G, G // 8 + 1)):
         P = orc.causal_probabilities(host[0][g], host[1][g])
-        o_err = max(o_err, float(np.abs(parity.to_f64(o[g]) - orc.attention_output(P, host[2][g])).max()))
+        o_ref = orc.attention_output(P, host[2][g])
+        err = np.abs(parity.to_f64(o[g]) - o_ref)
+        o_err = max(o_err, float(err.max()))
+        o_max = max(o_max, float(np.abs(o_ref).max()))
+        o_excess = max(o_excess, float((err / np.maximum(1.0, np.abs(o_ref) / 2.0)).max()))
         S = orc.forgotten_scores(P, alpha)
         s_rel = max(s_rel, float((np.abs(parity.to_f64(sf[g]) - S) / np.maximum(np.abs(S), 1e-30)).max()))
-    say(f"  [moving maximum d={d} n={n} G={G} rise={rise}] |o err|={o_err:.2e} score rel={s_rel:.2e}")
-    assert o_err <= parity.O_TOL["bf16"]
+    say(f"  [moving maximum d={d} n={n} G={G} rise={rise} V x{v_scale}] |o err|={o_err:.2e} (max |o|={o_max:.2f}, "
+        f"scaled to |o|<=2: {o_excess:.2e}) score rel={s_rel:.2e}")
+    assert o_excess <= parity.O_TOL["bf16"]
+    if v_scale <= 0.5:
+        assert o_err <= parity.O_TOL["bf16"]
     assert s_rel <= parity.SCORE_RTOL
 
 
@@ -306,6 +319,81 @@ def test_alpha_per_head(base, G, d, n, say):
     # a narrow bound: every head below 0.5 (short-window score kernel on d = 128)
     low = np.minimum(alphas, 0.45).astype(np.float32)
     run_lockstep(w, low, sample=sample[:4], say=say)
+
+
+def test_alpha_above_the_bound_is_computed_as_the_bound(say):
+    """a2sf_prefill_alpha_per_head sizes its row window by alpha_max; a head whose own factor
+    is larger is documented to be computed with alpha_max."""
+    G, n, d = 6, 700, 128
+    w = variant(1, heads=G, d=d, n=n, T=1, select=10, recent=10, name="alpha above bound")
+    p = parity.Problem(w)
+    alphas = np.array([0.2, 0.5, 0.9, 1.0, 0.0, 0.35], dtype=np.float32)
+    bound = 0.5
+    ah = torch.tensor(alphas, device="cuda")
+    s = torch.empty((G, n), dtype=torch.float32, device="cuda")
+    a2sf.a2sf_prefill_alpha_per_head(p.dev["q"], p.dev["k"], p.dev["v"], n, ah, bound, w.select, w.recent,
+                                     p.cache, scores_full=s, workspace=p.ws)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for g in range(G):
+        Q, K, _ = (x[:n] for x in p.host[g])
+        eff = float(np.float32(min(alphas[g], np.float32(bound))))
+        S = orc.forgotten_scores(orc.causal_probabilities(Q, K), eff)
+        worst = max(worst, parity.compare_scores(s[g].cpu().numpy(), S, f"head {g} alpha {alphas[g]} -> {eff}"))
+    say(f"  [alpha above bound] factors {alphas.tolist()} under bound {bound}: max score rel={worst:.2e}")
+
+
+@pytest.mark.parametrize("G,cap", [(6, 40), (4200, 40), (5, 700)])
+def test_decode_flags_heads_with_an_invalid_length(G, cap, say):
+    """len[g] + 1 <= capacity is a precondition the host cannot check (the lengths live on the
+    device).  A head that breaks it is left untouched and its output row is NaN; every other
+    head is computed as if the bad ones were not there.  One case per launch path."""
+    d, select = 128, (cap - 1) // 2
+    recent = cap - 1 - select
+    gen = torch.Generator(device="cuda").manual_seed(G)
+    c = a2sf.Cache(G, cap, d, torch.bfloat16)
+    c.k.copy_(torch.randn((G, cap, d), device="cuda", generator=gen))
+    c.v.copy_(torch.randn((G, cap, d), device="cuda", generator=gen))
+    c.scores.copy_(torch.rand((G, cap), device="cuda", generator=gen))
+    c.pos.copy_(torch.arange(cap, dtype=torch.int32, device="cuda").repeat(G, 1))
+    c.len.fill_(cap - 1)
+    q, k, v = (torch.randn((G, d), device="cuda", generator=gen).bfloat16() for _ in range(3))
+    ws = torch.empty(max(256, a2sf.a2sf_workspace_bytes(G, 0, cap, d, a2sf.A2SF_BF16, select, recent)),
+                     dtype=torch.uint8, device="cuda")
+    start = c.snapshot()
+    o_good = torch.zeros((G, d), dtype=torch.bfloat16, device="cuda")
+    a2sf.a2sf_decode_step(q, k, v, cap, c, 0.5, select, recent, o_good, workspace=ws)
+    torch.cuda.synchronize()
+    good = c.snapshot()
+    c.restore(start)
+    bad = [1, G - 2]
+    c.len[bad[0]] = cap           # no free slot
+    c.len[bad[1]] = -1
+    start_bad = c.snapshot()
+    o = torch.zeros_like(o_good)
+    a2sf.a2sf_decode_step(q, k, v, cap, c, 0.5, select, recent, o, workspace=ws)
+    torch.cuda.synchronize()
+    ok = torch.ones(G, dtype=torch.bool, device="cuda")
+    ok[bad] = False
+    assert torch.isnan(o[bad].float()).all(), "the bad heads' output rows must be NaN"
+    assert torch.equal(o[ok], o_good[ok])
+    for now, before, clean in zip(c.tensors(), start_bad, good):
+        assert torch.equal(now[bad], before[bad]), "a bad head's cache was touched"
+        assert torch.equal(now[ok], clean[ok])
+    say(f"  [invalid length G={G} capacity={cap}] bad heads flagged with NaN, the others unchanged")
+
+
+def test_strong_sink_stays_in_the_cache(say):
+    """Section 4.3: a token that keeps receiving large attention (the sink at position 0) is
+    never evicted by the accumulated-score policy.  The long-context recipe (sink of magnitude
+    8) with the salient logits planted at their full magnitude; the whole run also matches the
+    oracle."""
+    w = variant(4, heads=8, n=400, T=40, select=20, recent=20, logit_shift=True, name="strong sink")
+    for alpha in (0.1, 0.3, 1.0):
+        ls = run_lockstep(w, alpha, say=say)
+        pos = ls.p.cache.pos.cpu().numpy()
+        lens = ls.p.cache.len.cpu().numpy()
+        assert all(0 in pos[g, :lens[g]] for g in range(w.G)), "the sink was evicted"
 
 
 def test_cfg1_llama_layer(say):
@@ -484,6 +572,30 @@ def near_tie_at_cut(q, K, keep):
     return keep < len(s) and s[keep - 1] - s[keep] < CUT_GAP
 
 
+def ideal_rows_near_cut(q, K, keep):
+    """The Ideal rows that an fp32 evaluation of the logits may legitimately produce: the
+    oracle's own, plus -- when tokens on either side of the cut have logits within CUT_GAP of
+    it -- every row that swaps one such token in for one such token out."""
+    L = K.shape[0]
+    s = (K @ q) / math.sqrt(K.shape[1])
+    order = sorted(range(L), key=lambda j: (-s[j], j))
+    rows = [orc.ideal_row(q, K, keep)]
+    if keep >= L:
+        return rows
+    cut = 0.5 * (s[order[keep - 1]] + s[order[keep]])
+    inside = [j for j in order[:keep] if s[j] - cut < CUT_GAP]
+    outside = [j for j in order[keep:] if cut - s[j] < CUT_GAP]
+    for a in inside:
+        for b in outside:
+            rows.append(orc.pruned_row(q, K, [j for j in order[:keep] if j != a] + [b]))
+    return rows
+
+
+def cosine_matches_a_valid_ideal(got, q, K, retained, keep):
+    pr = orc.pruned_row(q, K, retained)
+    return min(abs(got - orc.cosine_similarity(pr, ir)) for ir in ideal_rows_near_cut(q, K, keep))
+
+
 @pytest.mark.parametrize("dtype,d,n,select,recent,alpha", [
     ("bf16", 128, 200, 12, 12, 0.3),     # the split used by the other tests
     ("f32", 64, 150, 0, 16, 0.5),        # recent window only (the paper's Local baseline)
@@ -527,20 +639,25 @@ def test_similarity_to_ideal_protocol(dtype, d, n, select, recent, alpha, say):
         P = cache.pos.cpu().numpy()
         retained.append([P[g, :L[g]].tolist() for g in range(G)])
     got = cos.cpu().numpy().astype(np.float64)
-    worst, skipped = 0.0, 0
+    worst, near = 0.0, 0
     for g in range(G):
         want, oc = orc.similarity_to_ideal(host[0][g], host[1][g], host[2][g], alpha, select, recent,
                                            forced_retained=[None if r is None else r[g] for r in retained])
         for i in range(n):
             keep = min(i, B) + 1
             if near_tie_at_cut(host[0][g][i], host[1][g][:i + 1], keep):
-                skipped += 1
-                continue
-            worst = max(worst, abs(got[i, g] - want[i]))
+                # fp32 logits may order the two tokens at the cut the other way: the value must
+                # then be the cosine under one of the choices the gap allows
+                near += 1
+                held = ([0] if i == 1 else retained[i - 1][g]) if i >= 1 else []
+                err = cosine_matches_a_valid_ideal(got[i, g], host[0][g][i], host[1][g][:i + 1],
+                                                   list(held) + [i], keep)
+            else:
+                err = abs(got[i, g] - want[i])
+            worst = max(worst, err)
     say(f"  [similarity {dtype} d={d} n={n} {select}+{recent} alpha={alpha}] max |cos err|={worst:.2e}, "
-        f"{skipped} near-tie rows skipped, mean cos={got[B + 1:].mean():.3f}")
+        f"{near} near-tie rows checked against both cut choices, mean cos={got[B + 1:].mean():.3f}")
     assert worst <= SIM_TOL
-    assert skipped <= 0.05 * n * G
 
 
 def test_similarity_to_ideal_longest_row(say):
@@ -572,8 +689,8 @@ def test_similarity_to_ideal_longest_row(say):
             want = orc.cosine_similarity(orc.pruned_row(Q[g], K[g, :t_pos + 1], held + [t_pos]),
                                          orc.ideal_row(Q[g], K[g, :t_pos + 1], len(held) + 1))
             say(f"  [similarity L={t_pos + 1} head {g} cache {len(held)}] cos={got[g]:.6f} oracle={want:.6f}")
-            if not near_tie_at_cut(Q[g], K[g, :t_pos + 1], len(held) + 1):
-                assert abs(got[g] - want) <= SIM_TOL
+            assert cosine_matches_a_valid_ideal(got[g], Q[g], K[g, :t_pos + 1], held + [t_pos],
+                                                len(held) + 1) <= SIM_TOL
 
 
 def test_similarity_protocol_module(say):
@@ -588,11 +705,24 @@ def test_similarity_protocol_module(say):
     got = cos.cpu().numpy().astype(np.float64)
     worst = 0.0
     for g in range(G):
-        want, _ = orc.similarity_to_ideal(q[g].astype(np.float64), k[g].astype(np.float64),
-                                          v[g].astype(np.float64), alpha, select, recent)
-        for i in range(n):
-            if not near_tie_at_cut(q[g][i].astype(np.float64), k[g][:i + 1].astype(np.float64),
-                                   min(i, select + recent) + 1):
-                worst = max(worst, abs(got[i, g] - want[i]))
+        Q, K, V = (x[g].astype(np.float64) for x in (q, k, v))
+        want, _ = orc.similarity_to_ideal(Q, K, V, alpha, select, recent)
+        _, _, c = orc.prefill(Q[:1], K[:1], V[:1], alpha, select, recent)
+        for i in range(1, n):
+            held = [int(x) for x in c.pos]           # the policy's cache before step i
+            keep = min(i, select + recent) + 1
+            if near_tie_at_cut(Q[i], K[:i + 1], keep):
+                err = cosine_matches_a_valid_ideal(got[i, g], Q[i], K[:i + 1], held + [i], keep)
+            else:
+                err = abs(got[i, g] - want[i])
+            worst = max(worst, err)
+            orc.decode_step(c, Q[i], K[i], V[i], i, alpha, select, recent)
     say(f"  [similarity protocol module] max |cos err|={worst:.2e}, mean cos={got.mean():.3f}")
     assert worst <= SIM_TOL
+    # the Table 2 figure: mean over the steps past the budget and over heads, formed by the library
+    first = select + recent + 1
+    mean = torch.empty(1, dtype=torch.float32, device="cuda")
+    a2sf.a2sf_similarity_mean(cos, n, G, first, mean)
+    assert abs(float(mean.item()) - got[first:].mean()) <= 1e-6
+    a2sf.a2sf_similarity_mean(cos, n, G, n, mean)        # nothing left to average
+    assert float(mean.item()) == 1.0
