@@ -39,7 +39,6 @@ import os
 import sys
 
 PF = 4  # operand fragments in flight ahead of their matrix ops
-DROP = set()  # timing experiments only (--drop): instruction classes left out, results are wrong
 
 # ---- vector registers ----------------------------------------------------------------
 S0 = 0                  # logits of block 0 (32 registers: key sub-block 0, then 1)
@@ -79,8 +78,6 @@ LSEW = (94, 96)         # log-sum-exp pointers
 KPN, VPN = 98, 82       # K / V pointers of the block after this one (this one again after the last)
 SGN, SQBN = 84, 85      # its head and row block
 SLO, SHI = 40, 99
-STAMP = 70              # --stamps: six timestamps (s_memtime) in s[70:81]
-STAMPS = False          # development aid: the stamps overwrite the first output row of the wave
 
 STAGE = 32768           # one LDS stage: K tile (16 KB) then V tile (16 KB)
 NSTAGE = 4
@@ -137,24 +134,6 @@ class Fifo:
         return f"s_waitcnt lgkmcnt({left})"
 
 
-def stamp(out, k, mode=1):
-    if STAMPS == mode:
-        out.e(f"s_memtime {sp(STAMP + 2 * k)}")
-
-
-def stamps_store(out):
-    if not STAMPS:
-        return
-    out.e("s_waitcnt vmcnt(0) lgkmcnt(0)")
-    out.e("s_mov_b64 exec, 1")
-    out.e(f"v_mov_b32 {v(TMP + 15)}, 0")
-    for q in range(4):
-        for k in range(4):
-            out.e(f"v_mov_b32 {v(TMP + k)}, s{STAMP + 4 * q + k}")
-        out.e(f"global_store_dwordx4 {v(TMP + 15)}, {vr(TMP, 4)}, {sp(OW[0])} offset:{16 * q}")
-    out.e("s_mov_b64 exec, -1")
-
-
 def slot(f):
     return RING + 4 * (f % 8)
 
@@ -205,8 +184,6 @@ def softmax(out, b, s, p):
     itself); then the out-of-line slow path redoes the tile with a fresh maximum.  Returns
     (vector-op list, slow-path lines to be placed out of line)."""
     m, l, flag = M[b], L[b], FLAG[b]
-    if "softmax" in DROP:
-        return [f"s_mov_b64 {sp(FLAGO[b])}, 0"], []
     slow, back = out.label("slow"), out.label("back")
     t = [TMP + i for i in range(8)]
     o = [f"s_mov_b64 {sp(FLAGO[b])}, 0"]
@@ -441,18 +418,12 @@ def top_drain(out):
     dma(out, "V")
 
 
-def top(out, probe=False):
+def top(out):
     """Top of iteration t: the group {K(t+2), V(t+1)} has landed for every wave (only the
     group fetched during iteration t-1 may still be in flight); the fetch of {K(t+4), V(t+3)},
     into the stages that held K(t) and V(t-1), follows inside the iteration."""
-    if probe:
-        stamp(out, 0, 4)
     out.e("s_waitcnt vmcnt(8)")
-    if probe:
-        stamp(out, 1, 4)
     out.e("s_barrier")
-    if probe:
-        stamp(out, 2, 4)
 
 
 def k_prefetch_tags():
@@ -517,16 +488,8 @@ def iteration(out, par, kind):
     block 0's last tile: its logits are complete, only its last O update remains), "one"
     (only block 1 is still running)."""
     fifo = Fifo(k_prefetch_tags())
-    if kind == "both" and par == 0:
-        stamp(out, 1, 3)
     phase_x(out, fifo, par, (0, 1) if kind == "both" else (1,))
-    if kind == "both" and par == 0:
-        stamp(out, 2, 3)
     phase_y(out, fifo, par, (1,) if kind == "one" else (0, 1), sm0=(kind == "both"))
-    if kind == "both" and par == 0:
-        stamp(out, 3, 3)
-    if kind == "both" and par == 1:
-        stamp(out, 5, 3)
     assert fifo.q == k_prefetch_tags()
 
 
@@ -628,8 +591,6 @@ def weave(base, extra, tail=8):
 def setup(out):
     """Once per launch: constants, the first block's Q and its first tiles."""
     out.e("; ---- setup")
-    stamp(out, 0)
-    stamp(out, 0, 2)
     out.e(f"v_mov_b32 {v(NEGINF)}, 0xff800000")
     for u in range(4):
         out.e(f"v_add_u32 {v(KL + u)}, {u * 4096}, %[kl0]")
@@ -679,17 +640,12 @@ def prologue(out):
     for db in range(4):
         out.e(f"v_xor_b32 {v(VADDR + db)}, {db * 64}, %[clvs16]")
         out.e(f"v_add_u32 {v(VADDR + db)}, {v(VADDR + db)}, %[vrow]")
-    stamp(out, 2, 2)
     for i in range(128):
         out.e(f"v_accvgpr_write_b32 a{i}, 0")
-    stamp(out, 3, 2)
-    stamp(out, 1)
     # this block's Q rows (and, long before them, its first tiles) have arrived; only the last
     # block's output stores, which were issued after them, may still be under way
     out.e(f"s_waitcnt vmcnt({STORES})")
     out.e("s_barrier")             # also: every wave has left the last block's tiles
-    stamp(out, 2)
-    stamp(out, 4, 2)
     # S0(0), then S1(0) with block 0's first softmax (the one that has to find a maximum)
     # riding between its matrix ops.  K(0)'s fragments are read once per pass, i.e. twice per
     # block, here: LDS is idle anyway.
@@ -760,24 +716,18 @@ def generate():
     setup(out)
     block = out.label("blk")
     out.e(f"{block}:")
-    stamp(out, 0)
     prologue(out)
     la, lb_e, lb_o, sp_e, sp_o, fin_e, fin_o, drain, epi = (
         out.label(x) for x in ("la", "lbe", "lbo", "spe", "spo", "fe", "fo", "dr", "ep"))
 
     def step(kind, par, last, target):
-        if kind == "both" and par == 0:
-            stamp(out, 0, 3)
-        top(out, probe=(kind == "both" and par == 1))
-        if kind == "both" and par == 1:
-            stamp(out, 4, 3)
+        top(out)
         out.e(f"s_cmp_eq_u32 s{T}, s{last}")
         out.e(f"s_cbranch_scc1 {target}")
         iteration(out, par, kind)
         out.e(f"s_add_u32 s{T}, s{T}, 1")
 
     # both blocks running: until block 0 reaches its last tile
-    stamp(out, 3)
     out.e(f"{la}:")
     step("both", 0, TF0, sp_e)
     step("both", 1, TF0, sp_o)
@@ -797,23 +747,18 @@ def generate():
     step("one", 1, TF1, fin_o)
     out.e(f"s_branch {lb_e}")
     out.e(f"{fin_e}:")
-    stamp(out, 4)
     final(out, 0)
     out.e(f"s_branch {drain}")
     out.e(f"{fin_o}:")
-    stamp(out, 4)
     final(out, 1)
     out.e(f"{drain}:")
-    stamp(out, 5)
     out.e(f"s_add_u32 s{T}, s{T}, 1")
     out.e(f"s_cmp_lt_u32 s{T}, s{NTMAX}")
     out.e(f"s_cbranch_scc0 {epi}")
     top_drain(out)
     out.e(f"s_branch {drain}")
     out.e(f"{epi}:")
-    stamp(out, 5, 2)
     epilogue(out)
-    stamps_store(out)
     out.e(f"s_add_u32 s{J}, s{J}, 1")
     out.e(f"s_cmp_eq_u32 s{HASNEXT}, 1")
     out.e(f"s_cbranch_scc1 {block}")
@@ -825,42 +770,20 @@ def generate():
 
 
 def clobbers():
+    # M0 is written by the stream (before every direct-to-LDS load) but cannot be declared:
+    # it is a reserved register, which the compiler never keeps a value in across a statement
+    # -- it writes M0 itself right before each of its own uses -- and listing it only draws
+    # "clobber list contains reserved registers".  The stream is also the kernel's last statement.
     c = [f"v{i}" for i in range(NV)] + [f"a{i}" for i in range(NA)]
     c += [f"s{i}" for i in range(SLO, SHI + 1)] + ["vcc", "scc", "memory"]
     return ", ".join(f'"{x}"' for x in c)
 
 
-def dropped(ln):
-    op = ln.split()[0] if ln.split() else ""
-    return (("mfma" in DROP and op.startswith("v_mfma")) or ("exp" in DROP and op == "v_exp_f32")
-            or ("ds" in DROP and op.startswith("ds_read")) or ("barrier" in DROP and op == "s_barrier")
-            or ("dma" in DROP and op.startswith("global_load_lds"))
-            or ("vmwait" in DROP and op == "s_waitcnt" and "vmcnt" in ln)
-            or ("lgkmwait" in DROP and op == "s_waitcnt" and "lgkmcnt" in ln)
-            or ("slowbranch" in DROP and op == "s_cbranch_scc1" and "Lslow" in ln))
-
-
 def main():
     here = os.path.dirname(os.path.abspath(__file__))
     args = sys.argv[1:]
-    if "--stamps" in args:
-        args.remove("--stamps")
-        globals()["STAMPS"] = 1
-    if "--stamps2" in args:
-        args.remove("--stamps2")
-        globals()["STAMPS"] = 2
-    if "--stamps3" in args:
-        args.remove("--stamps3")
-        globals()["STAMPS"] = 3
-    if "--stamps4" in args:
-        args.remove("--stamps4")
-        globals()["STAMPS"] = 4
-    while "--drop" in args:  # e.g. --drop mfma --drop softmax: measures what the rest costs
-        i = args.index("--drop")
-        DROP.add(args[i + 1])
-        del args[i:i + 2]
     path = args[0] if args else os.path.join(here, "attn_fwd128x2_body.inc")
-    lines = [ln for ln in generate() if not dropped(ln)]
+    lines = generate()
     with open(path, "w") as f:
         f.write("// Written by gen_attn_fwd128x2.py; edit the generator, not this file.\n")
         f.write("#define A2SF_FWD128X2_ASM \\\n")

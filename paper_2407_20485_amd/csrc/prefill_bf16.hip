@@ -30,19 +30,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kTile = 64;  // keys (attn_fwd) or query rows (col_scores) per LDS tile
 constexpr float kLazyRescale = 8.0f;  // log2 units
-#ifndef A2SF_FWD_PREFETCH
-#define A2SF_FWD_PREFETCH 4
-#endif
-constexpr int kPrefetch = A2SF_FWD_PREFETCH;  // LDS fragment reads in flight ahead of their matrix op
-#ifndef A2SF_FWD_NB
-#define A2SF_FWD_NB 1      // 32-row query blocks per wave in attn_fwd
-#endif
-#ifndef A2SF_FWD128_X2
-#define A2SF_FWD128_X2 1   // d = 128: two query blocks per wave where the shape allows it
-#endif
-#ifndef A2SF_FWD_OCC
-#define A2SF_FWD_OCC 2     // workgroups per compute unit the register budget is sized for
-#endif
+constexpr int kPrefetch = 4;  // LDS fragment reads in flight ahead of their matrix op
+constexpr int kFwdNB = 1;     // 32-row query blocks per wave in attn_fwd_bf16_kernel / attn_fwd128_kernel
+constexpr int kFwdOcc = 2;    // workgroups per compute unit the register budget of attn_fwd_bf16_kernel is sized for
 
 __device__ __forceinline__ f32x16 mfma_bf16(const uint4& a, const uint4& b, const f32x16& c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
@@ -136,7 +126,7 @@ __device__ __forceinline__ long long xcd_contiguous_id(long long total) {
 
 // ---------------------------------------------------------------------------------------
 template <int D, int NB, bool WITH_O>
-__global__ __launch_bounds__(kThreads, A2SF_FWD_OCC) void attn_fwd_bf16_kernel(
+__global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
   constexpr int BM = kWaves * 32 * NB;
@@ -839,21 +829,17 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   }
 }
 
-#ifndef A2SF_FWD128_NB
-#define A2SF_FWD128_NB 1   // 32-row query blocks per wave of attn_fwd128_kernel
-#endif
-
 template <int D>
 void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
                 hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   if constexpr (D == 128) {
-    constexpr int NB = A2SF_FWD128_NB;
+    constexpr int NB = kFwdNB;
     const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
     // the start and end of a row block: from n = 2048 with one workgroup per block, from
     // n = 512 in the persistent form, which overlaps them with the neighbouring blocks.
-    if (A2SF_FWD128_X2 && o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31)) {
+    if (o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31)) {
       const int nqb2 = n / kX2Rows;
       const long long items = (long long)G * nqb2;
       // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
@@ -887,7 +873,7 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
                          lse2, n, G, nqb, scale_log2e);
   } else {
-    constexpr int NB = A2SF_FWD_NB;
+    constexpr int NB = kFwdNB;
     constexpr int BM = kWaves * 32 * NB;
     const int nqb = (n + BM - 1) / BM;
     const long long total = (long long)G * nqb;
