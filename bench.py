@@ -49,9 +49,15 @@ def prefill_model_flops(G, n, d, with_o=True):
     return G * one * (2 if with_o else 1)
 
 
+TRAFFIC_FILE = os.path.join("profiles", "traffic.txt")
+
+
 def read_traffic(name):
-    """HBM bytes per launch measured with rocprofv3 --pmc (profiles/traffic.txt), if recorded."""
-    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    """HBM bytes per launch as recorded in profiles/traffic.txt from two earlier `rocprofv3 --pmc`
+    runs of this benchmark (FETCH_SIZE, then WRITE_SIZE, scaled by a 1 GiB copy).  Counters
+    cannot be collected inside a timed run, so the figure is provenance, not a live measurement;
+    the JSON line says so in `traffic_source`."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -59,6 +65,36 @@ def read_traffic(name):
         if len(parts) >= 2 and parts[0] == name:
             return float(parts[1])
     return None
+
+
+def similarity_kernel(spec):
+    """`--similarity-kernel HEADSxROWS`: time of one a2sf_ideal_similarity call over rows of that
+    length against its algorithmic bytes (the keys, read once)."""
+    import torch
+
+    import paper_2407_20485_amd as a2sf
+    G, L = (int(x) for x in spec.lower().split("x"))
+    d, cached, reps = 128, 200, 20
+    k = torch.randn((G, L, d), device="cuda").to(torch.bfloat16)
+    q = torch.randn((G, d), device="cuda").to(torch.bfloat16)
+    cache = a2sf.Cache(G, cached + 1, d, torch.bfloat16)
+    cache.len.fill_(min(cached, L - 1))
+    cache.pos.copy_(torch.arange(cached + 1, dtype=torch.int32, device="cuda").expand(G, -1) % max(L - 1, 1))
+    out = torch.empty(G, dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        a2sf.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        a2sf.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = G * L * d * 2
+    print(json.dumps({"kernel": "a2sf_ideal_similarity", "heads": G, "rows": L, "head_dim": d, "dtype": "bf16",
+                      "us_per_call": us, "bytes_per_call": nbytes,
+                      "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBS,
+                                   "unit": "GB/s", "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
 
 
 def cpu_baseline(w, alpha, budget_s=12.0):
@@ -129,6 +165,11 @@ def main():
                     help="replay the T generation steps of a pass from one HIP graph instead of launching "
                          "them one by one (matters for the few-head configs, whose steps are shorter than "
                          "a host launch)")
+    ap.add_argument("--similarity-kernel", metavar="HEADSxROWS", default=None,
+                    help="instead of the pass: time the Ideal-mask similarity diagnostic alone (bf16, d = 128)")
+    ap.add_argument("--ceilings", choices=["hbm", "mfma", "all"], default=None,
+                    help="instead of the pass: run the stand-alone probe of the machine's ceilings "
+                         "(streaming reads in the generation step's access pattern; sustained matrix-core rate)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -136,6 +177,14 @@ def main():
         log("bench.py: this build runs on ONE GPU only (every head is an independent problem, so "
             "more GPUs would each take a share of the heads with no exchange). Run with --gpus 1.")
         sys.exit(2)
+
+    if args.ceilings:
+        import subprocess
+        exe = os.path.join(ROOT, "paper_2407_20485_amd", "ceilings")
+        if not os.path.exists(exe):
+            log(f"bench.py: {exe} is missing: build it with `python -m paper_2407_20485_amd.build`")
+            sys.exit(3)
+        sys.exit(subprocess.run([exe] + ([] if args.ceilings == "all" else [args.ceilings])).returncode)
 
     import numpy as np
     import torch
@@ -146,6 +195,8 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the HIP path has no CPU fallback.")
         sys.exit(3)
+    if args.similarity_kernel:
+        return similarity_kernel(args.similarity_kernel)
     w = synth.CONFIGS[args.config]
     alpha = w.alpha if args.alpha is None else args.alpha
     G, n, d, T = w.G, w.n, w.d, w.T
@@ -232,8 +283,13 @@ def main():
     flops = prefill_model_flops(G, n, d, with_o=not args.no_o)
     dec_gbs = dbytes / dec_s_per_step / 1e9
     pre_tflops = flops / pre_s / 1e12
-    one_kernel = capacity <= 256 or (G >= 256 and capacity <= 1024) or G >= 640   # the library's launch plan
-    nsplit_note = "one fused kernel per step" if one_kernel else "token-split partial + combine kernels per step"
+    nsplit, rows_per_split, wave_slots = a2sf.a2sf_decode_plan(G, capacity, d)   # the library's launch plan
+    if nsplit > 1:
+        nsplit_note = f"tokens of a head split over {nsplit} workgroups + combine kernel"
+    else:
+        nsplit_note = "one fused kernel, " + ("one wave per head" if wave_slots else "one workgroup per head")
+    if args.mode == "stable":
+        nsplit_note += ", then select + in-place compaction"
 
     out = {
         "metric": "decode steps/s (fused attn+A2SF+evict) & HBM GB/s; prefill score TFLOP/s",
@@ -255,14 +311,16 @@ def main():
         "roofline": {"kernel": f"decode step ({nsplit_note})", "bound": "hbm", "achieved": dec_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
                      "bytes_per_launch": dbytes, "avg_launch_us": dec_s_per_step * 1e6,
-                     "traffic": read_traffic(f"decode_cfg{w.cfg_id}")},
+                     "traffic": read_traffic(f"decode_cfg{w.cfg_id}" + ("_stable" if args.mode == "stable" else "")),
+                     "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"},
         "roofline_prefill": {"kernel": "a2sf_prefill (attention fwd + column scores + select + gather)",
                              "bound": "mfma", "achieved": pre_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                              "unit": "TFLOP/s", "frac": pre_tflops / MFMA_BF16_PEAK_TFLOPS,
                              "flops_per_launch": flops, "avg_launch_ms": pre_s * 1e3,
                              "flop_convention": "model flops: one causal QK^T sweep + one PV sweep; "
                                                 "the score kernel's recomputed QK^T is not counted",
-                             "traffic": read_traffic(f"prefill_cfg{w.cfg_id}")},
+                             "traffic": read_traffic(f"prefill_cfg{w.cfg_id}" + ("_no_o" if args.no_o else "")),
+                             "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"},
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the float64 oracle on the host cores ...")

@@ -115,7 +115,10 @@ a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n,
 /* One generation step (abstract; Section 2.2; Section 3.3).
  *   q, k_new, v_new  [G, d] dtype: the new token's query, key and value.
  *   t_pos            original position of the new token (larger than every cached one).
- *   cache            in/out.  Requires len[g] + 1 <= capacity.  The new token joins with
+ *   cache            in/out.  Requires 0 <= len[g] and len[g] + 1 <= capacity; a head that
+ *                    violates this is left untouched and its row of o is filled with NaN
+ *                    (the lengths live on the device, so the host cannot check them).
+ *                    The new token joins with
  *                    score 0; a = softmax(K_c q / sqrt(d)) over the len+1 cached tokens;
  *                    o = a^T V_c; every score becomes alpha*S + a; then, if len+1 > B,
  *                    the len+1-B lowest-score tokens outside the `recent` newest
@@ -149,8 +152,8 @@ a2sf_status a2sf_decode_step_static_ws(const void* q, const void* k_new, const v
  * distinct factor per layer and head as the way to lift its limitation of a single one).
  *   alpha_heads  [G] fp32, device: head g uses alpha_heads[g], each in [0, 1].
  *   alpha_max    (prefill only) an upper bound of alpha_heads, checked like alpha; it sizes
- *                the row window of the score pass.  A head whose factor exceeds it gets
- *                scores that miss the rows outside that window.
+ *                the row window of the score pass.  A head whose factor exceeds it is
+ *                computed with alpha_max instead of its own factor.
  * Everything else as in a2sf_prefill / a2sf_decode_step. */
 a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void* v, int32_t n,
                                         const float* alpha_heads, float alpha_max,
@@ -174,8 +177,10 @@ a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* 
                         int32_t L, int32_t stride, a2sf_budget budget, int32_t* keep_idx,
                         int32_t* n_keep, void* hip_stream);
 
-/* In-place stable compaction of a cache: for every head, row keep_idx[g][r] of K, V,
- * scores and pos moves to row r for r < n_keep[g], and len[g] = n_keep[g].
+/* Removal of the tokens that were not selected (Section 2.2: tokens with a small accumulated
+ * score are removed from the KV cache; Section 3.1 after Eq.2), as an in-place stable
+ * compaction: for every head, row keep_idx[g][r] of K, V, scores and pos moves to row r for
+ * r < n_keep[g], and len[g] = n_keep[g].
  *   keep_idx  [G, keep_stride] strictly ascending slot indices (as a2sf_select writes).
  *   n_keep    [G] device. */
 a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32_t keep_stride,
@@ -199,6 +204,24 @@ a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32
 a2sf_status a2sf_ideal_similarity(const void* q, const void* k_all, int32_t n_stride,
                                   int32_t t_pos, const a2sf_cache* cache, float* cos_out,
                                   void* hip_stream);
+
+/* Average of the similarities over the steps from first_step on and over all heads: the
+ * figure Table 2 reports (Section 4.3; steps before the budget is reached prune nothing and
+ * are left out by the caller through first_step).
+ *   cos       [steps, G] fp32, device, as successive a2sf_ideal_similarity calls wrote it.
+ *   mean_out  out [1] fp32, device; 1 when no step is left to average. */
+a2sf_status a2sf_similarity_mean(const float* cos, int32_t steps, int32_t G, int32_t first_step,
+                                 float* mean_out, void* hip_stream);
+
+/* How a2sf_decode_step will launch for these sizes (host only, launches nothing; for
+ * benchmarks and profiles that have to name the kernels they measure).  Any out pointer may
+ * be NULL.
+ *   nsplit          workgroups per head; 1 = one fused kernel, > 1 = the tokens of a head are
+ *                   split over that many workgroups and a second kernel combines them.
+ *   rows_per_split  cached tokens per workgroup when nsplit > 1.
+ *   wave_slots      > 0: the one-wave-per-head kernel (64 * wave_slots slots in registers). */
+a2sf_status a2sf_decode_plan(int32_t G, int32_t capacity, int32_t d, int32_t* nsplit,
+                             int32_t* rows_per_split, int32_t* wave_slots);
 
 const char* a2sf_status_string(int32_t status);
 

@@ -23,7 +23,8 @@ A2SF_STATIC_WS_BYTES = 16 << 20
 
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",
            "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
-           "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity", "a2sf_decode_step_static_ws")
+           "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity", "a2sf_decode_step_static_ws",
+           "a2sf_similarity_mean", "a2sf_decode_plan")
 
 
 class Budget(ctypes.Structure):
@@ -72,6 +73,11 @@ def lib() -> ctypes.CDLL:
         L.a2sf_compact.argtypes = [ctypes.POINTER(CacheStruct), vp, i32, vp, vp]
         L.a2sf_ideal_similarity.restype = i32
         L.a2sf_ideal_similarity.argtypes = [vp, vp, i32, i32, ctypes.POINTER(CacheStruct), vp, vp]
+        L.a2sf_similarity_mean.restype = i32
+        L.a2sf_similarity_mean.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.a2sf_decode_plan.restype = i32
+        L.a2sf_decode_plan.argtypes = [i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                       ctypes.POINTER(i32)]
         L.a2sf_status_string.restype = ctypes.c_char_p
         L.a2sf_status_string.argtypes = [i32]
         _lib = L
@@ -209,6 +215,17 @@ def a2sf_ideal_similarity(q, k_all, n_stride, t_pos, cache, cos_out, stream=None
     cs = _cache_struct(cache)
     _check(lib().a2sf_ideal_similarity(_ptr(q), _ptr(k_all), n_stride, t_pos, ctypes.byref(cs),
                                        _ptr(cos_out), _stream(stream)))
+
+
+def a2sf_similarity_mean(cos, steps, G, first_step, mean_out, stream=None):
+    _check(lib().a2sf_similarity_mean(_ptr(cos), steps, G, first_step, _ptr(mean_out), _stream(stream)))
+
+
+def a2sf_decode_plan(G, capacity, d):
+    """(nsplit, rows_per_split, wave_slots) of a2sf_decode_step for these sizes."""
+    a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().a2sf_decode_plan(G, capacity, d, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
 
 
 def a2sf_compact(cache, keep_idx, keep_stride, n_keep, stream=None):

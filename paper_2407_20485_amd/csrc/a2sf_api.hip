@@ -80,6 +80,10 @@ a2sf_status check_cache(const a2sf_cache* c, a2sf_budget b) {
   return A2SF_OK;
 }
 
+// A launch error is read with hipGetLastError(), which also returns (and clears) an error an
+// unrelated earlier call left behind on this thread: every entry point clears that stale
+// state before its first launch, so A2SF_EHIP speaks of this call's launches only.
+inline void clear_stale_error() { (void)hipGetLastError(); }
 inline a2sf_status launch_status() {
   return hipGetLastError() == hipSuccess ? A2SF_OK : A2SF_EHIP;
 }
@@ -101,6 +105,7 @@ a2sf_status prefill_impl(const void* q, const void* k, const void* v, int32_t n,
   if (!workspace || misaligned(workspace) || workspace_bytes < w.total) return A2SF_EWORKSPACE;
 
   hipStream_t st = (hipStream_t)hip_stream;
+  clear_stale_error();
   char* ws = (char*)workspace;
   float* lse2 = (float*)(ws + w.lse2);
   float* s_full = scores_full ? scores_full : (float*)(ws + w.s_full);
@@ -140,6 +145,7 @@ a2sf_status decode_impl(const void* q, const void* k_new, const void* v_new, int
     return A2SF_EWORKSPACE;
 
   hipStream_t st = (hipStream_t)hip_stream;
+  clear_stale_error();
   char* ws = (char*)workspace;
   launch_decode(q, k_new, v_new, t_pos, *cache, alpha, alpha_heads, budget.select, budget.recent,
                 mode == A2SF_EVICT_FAST, o, ws ? ws + w.split : nullptr, plan, st);
@@ -223,7 +229,12 @@ a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* 
   a2sf_status s;
   if ((s = check_budget(budget)) != A2SF_OK) return s;
   if (!scores || !keep_idx || !n_keep) return A2SF_EINVAL;
+  if (misaligned(scores) || ((uintptr_t)pos & 3u) || ((uintptr_t)len & 3u) ||
+      ((uintptr_t)keep_idx & 3u) || ((uintptr_t)n_keep & 3u))
+    return A2SF_EINVAL;
   if (G < 1 || L < 1 || stride < L) return A2SF_ESHAPE;
+  if ((long long)G * stride > 0x7FFFFFFFLL) return A2SF_ESHAPE;   // slots are indexed with 32 bits
+  clear_stale_error();
   launch_select(scores, pos, len, G, L, stride, budget.select, budget.recent, keep_idx, n_keep,
                 (hipStream_t)hip_stream);
   return launch_status();
@@ -236,6 +247,8 @@ a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32
   if ((s = check_cache(cache, any)) != A2SF_OK) return s;
   if (!keep_idx || !n_keep) return A2SF_EINVAL;
   if (keep_stride < 1) return A2SF_ESHAPE;
+  if (((uintptr_t)keep_idx & 3u) || ((uintptr_t)n_keep & 3u)) return A2SF_EINVAL;
+  clear_stale_error();
   launch_compact(*cache, keep_idx, keep_stride, n_keep, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -249,8 +262,30 @@ a2sf_status a2sf_ideal_similarity(const void* q, const void* k_all, int32_t n_st
   if (!q || !k_all || !cos_out) return A2SF_EINVAL;
   if (misaligned(q) || misaligned(k_all)) return A2SF_EINVAL;
   if (t_pos < 0 || t_pos >= A2SF_SIM_MAX_ROWS || n_stride <= t_pos) return A2SF_ESHAPE;
+  clear_stale_error();
   launch_ideal_similarity(q, k_all, n_stride, t_pos + 1, *cache, cos_out, (hipStream_t)hip_stream);
   return launch_status();
+}
+
+a2sf_status a2sf_similarity_mean(const float* cos, int32_t steps, int32_t G, int32_t first_step,
+                                 float* mean_out, void* hip_stream) {
+  if (!cos || !mean_out || ((uintptr_t)cos & 3u) || ((uintptr_t)mean_out & 3u)) return A2SF_EINVAL;
+  if (steps < 1 || G < 1 || first_step < 0 || first_step > steps) return A2SF_ESHAPE;
+  clear_stale_error();
+  launch_similarity_mean(cos, (long long)first_step * G, (long long)steps * G, mean_out,
+                         (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+a2sf_status a2sf_decode_plan(int32_t G, int32_t capacity, int32_t d, int32_t* nsplit,
+                             int32_t* rows_per_split, int32_t* wave_slots) {
+  if (G < 1 || (d != 64 && d != 128)) return A2SF_ESHAPE;
+  if (capacity < 1 || capacity > A2SF_MAX_CAPACITY) return A2SF_ECAPACITY;
+  const DecodePlan p = plan_decode(G, capacity, d);
+  if (nsplit) *nsplit = p.nsplit;
+  if (rows_per_split) *rows_per_split = p.rows_per_split;
+  if (wave_slots) *wave_slots = p.wave_slots;
+  return A2SF_OK;
 }
 
 const char* a2sf_status_string(int32_t status) {

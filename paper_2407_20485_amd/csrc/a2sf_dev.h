@@ -145,15 +145,20 @@ __device__ __forceinline__ unsigned long long block_min_u64(unsigned long long v
 
 // Row window and exponent slope of one head's forgotten score (Section 3.3 Eq.5): rows before
 // `first_row` have a weight alpha^(n-1-i) below the smallest fp32 subnormal and add exactly 0.
-// With alpha_heads the head's own factor narrows the window the host sized for the bound.
+// On entry first_row / log2_alpha are the host's values for its bound alpha_max (log2_alpha is 0
+// for both alpha_max = 1, with first_row 0, and alpha_max = 0, with first_row n-1).  With
+// alpha_heads the head's own factor narrows the window; a factor above the bound is computed
+// as the bound.
 __device__ __forceinline__ void head_window(const float* alpha_heads, int g, int n, int& first_row,
                                             float& log2_alpha) {
   if (!alpha_heads) return;  // host values apply to every head
   const float a = alpha_heads[g];
-  if (!(a > 0.f)) { first_row = n - 1; log2_alpha = 0.f; return; }
-  if (!(a < 1.f)) { log2_alpha = 0.f; return; }
-  const float l2 = log2f(a);
+  if (!(a > 0.f)) { first_row = n - 1; log2_alpha = 0.f; return; }   // alpha = 0: the newest row only
+  if (log2_alpha == 0.f && first_row >= n - 1) return;               // bound is 0 (or n = 1)
+  float l2 = a < 1.f ? log2f(a) : 0.f;
+  if (log2_alpha < 0.f) l2 = fminf(l2, log2_alpha);                  // bound below 1: clamp
   log2_alpha = l2;
+  if (l2 == 0.f) return;                                             // alpha = 1 under a bound of 1: all rows
   const float rows = 160.0f / (-l2);
   const int own = rows >= (float)n ? 0 : n - ((int)rows + 1);
   first_row = own > first_row ? own : first_row;

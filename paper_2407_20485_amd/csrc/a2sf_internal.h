@@ -39,6 +39,9 @@ void launch_decode(const void* q, const void* k_new, const void* v_new, int t_po
 void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int L,
                              const a2sf_cache& c, float* out, hipStream_t st);
 
+void launch_similarity_mean(const float* cos, long long begin, long long end, float* out,
+                            hipStream_t st);
+
 // prefill_f32.hip / prefill_bf16.hip
 // lse2[g][i] = log2(sum_j exp(s_ij)) of the masked row i (s already scaled by 1/sqrt(d)).
 void launch_prefill_f32(const float* q, const float* k, const float* v, int G, int n, int d,

@@ -165,6 +165,13 @@ __device__ __forceinline__ void copy_kv_row(T* kdst, const T* ksrc, T* vdst, con
     store16(vdst + (t - Gm::LPR) * Gm::EPL, load16(vsrc + (t - Gm::LPR) * Gm::EPL));
 }
 
+// A head whose stored length breaks the call's precondition (0 <= len, len + 1 <= capacity) is
+// left untouched; its output row is filled with NaN so that the caller can see it.
+template <typename T, int D>
+__device__ __forceinline__ void flag_bad_head(T* og, int tid, int nthreads) {
+  for (int c = tid; c < D; c += nthreads) Elem<T>::store(og + c, __int_as_float(0x7FC00000));
+}
+
 __device__ __forceinline__ unsigned long long evict_key(float score, int pos) {
   // smallest key = lowest score; among equal scores the highest position
   return ((unsigned long long)ordered_key(score) << 32) | (unsigned)(0x7FFFFFFF - pos);
@@ -307,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
   const int g = blockIdx.x, tid = threadIdx.x;
   if (alpha_heads) alpha = alpha_heads[g];
   const int n_old = len[g];
-  if (n_old < 0 || n_old >= capacity) return;  // precondition len+1 <= capacity violated
+  if (n_old < 0 || n_old >= capacity) { flag_bad_head<T, D>(o + (size_t)g * D, tid, kThreads); return; }
   const int L = n_old + 1;
   T* Kg = K + (size_t)g * capacity * D;
   T* Vg = V + (size_t)g * capacity * D;
@@ -363,7 +370,10 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   const int g = blockIdx.x * kWaves + wave;
   if (g >= G) return;
   const int n_old = len[g];
-  if (n_old < 0 || n_old >= capacity) return;
+  if (n_old < 0 || n_old >= capacity) {
+    flag_bad_head<T, D>(o + (size_t)g * D, lane, kWave);
+    return;
+  }
   const int L = n_old + 1;
   if (alpha_heads) alpha = alpha_heads[g];
   float* z = zs[wave];
@@ -553,7 +563,7 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
   const int g = blockIdx.x, tid = threadIdx.x;
   if (alpha_heads) alpha = alpha_heads[g];
   const int n_old = len[g];
-  if (n_old < 0 || n_old >= capacity) return;
+  if (n_old < 0 || n_old >= capacity) { flag_bad_head<T, D>(o + (size_t)g * D, tid, kThreads); return; }
   const int L = n_old + 1;
   // merge the per-split (max, sum): one lane per split (nsplit <= 64), wave reductions
   __shared__ float wsplit[kWave];

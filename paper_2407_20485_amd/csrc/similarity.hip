@@ -26,7 +26,7 @@ __device__ __forceinline__ unsigned long long rank_key(float s, int j) {
   return ((unsigned long long)ordered_key(s) << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)j);
 }
 
-template <typename T, int D>
+template <typename T, int D, bool STREAM>
 __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
     const T* __restrict__ Q, const T* __restrict__ Kall, int n_stride, int L,
     const int32_t* __restrict__ cache_pos, const int32_t* __restrict__ cache_len, int capacity,
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int r = base + (u * kWaves + wave) * RPW + rgrp;
-      x[u] = load16(Kg + (size_t)(r < L ? r : L - 1) * D + sub * EPL);
+      x[u] = load16_as<STREAM>(Kg + (size_t)(r < L ? r : L - 1) * D + sub * EPL);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -134,19 +134,49 @@ __global__ __launch_bounds__(kThreads) void ideal_similarity_kernel(
   if (tid == 0) out[g] = dot / sqrtf(qi * qm);
 }
 
+// Mean of cos[first_step .. steps) x [0 .. G): the figure Table 2 reports (average over the
+// steps past the budget and over heads).  One workgroup; fp64 accumulation, fixed order.
+__global__ __launch_bounds__(kThreads) void similarity_mean_kernel(const float* __restrict__ cos,
+                                                                   long long begin, long long end,
+                                                                   float* __restrict__ out) {
+  __shared__ double part[kThreads];
+  double acc = 0.0;
+  for (long long i = begin + threadIdx.x; i < end; i += kThreads) acc += (double)cos[i];
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = kThreads / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = end > begin ? (float)(part[0] / (double)(end - begin)) : 1.0f;
+}
+
 }  // namespace
+
+void launch_similarity_mean(const float* cos, long long begin, long long end, float* out,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(similarity_mean_kernel, dim3(1), dim3(kThreads), 0, st, cos, begin, end, out);
+}
 
 void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int L,
                              const a2sf_cache& c, float* out, hipStream_t st) {
   const size_t lds = ((size_t)L * 4 + 1023) & ~(size_t)1023;
-#define A2SF_SIM(T, D)                                                                          \
-  do {                                                                                          \
-    static const hipError_t raised = hipFuncSetAttribute(                                       \
-        (const void*)ideal_similarity_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-        kSimMaxRows * 4);                                                                       \
-    (void)raised;                                                                               \
-    hipLaunchKernelGGL((ideal_similarity_kernel<T, D>), dim3(c.G), dim3(kThreads), lds, st,     \
-                       (const T*)q, (const T*)k_all, n_stride, L, c.pos, c.len, c.capacity, out); \
+  // keys that cannot stay in the 256 MB last-level cache until the next step are read with the
+  // non-temporal hint (see load16_stream)
+  const bool stream = (double)c.G * L * c.d * (c.dtype == A2SF_F32 ? 4 : 2) > 512e6;
+#define A2SF_SIM_(T, D, S)                                                                         \
+  do {                                                                                             \
+    static const hipError_t raised = hipFuncSetAttribute(                                          \
+        (const void*)ideal_similarity_kernel<T, D, S>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+        kSimMaxRows * 4);                                                                          \
+    (void)raised;                                                                                  \
+    hipLaunchKernelGGL((ideal_similarity_kernel<T, D, S>), dim3(c.G), dim3(kThreads), lds, st,     \
+                       (const T*)q, (const T*)k_all, n_stride, L, c.pos, c.len, c.capacity, out);  \
+  } while (0)
+#define A2SF_SIM(T, D)              \
+  do {                              \
+    if (stream) A2SF_SIM_(T, D, true); \
+    else A2SF_SIM_(T, D, false);    \
   } while (0)
   if (c.dtype == A2SF_F32) {
     if (c.d == 64) A2SF_SIM(float, 64); else A2SF_SIM(float, 128);
@@ -154,6 +184,7 @@ void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int
     if (c.d == 64) A2SF_SIM(bf16_t, 64); else A2SF_SIM(bf16_t, 128);
   }
 #undef A2SF_SIM
+#undef A2SF_SIM_
 }
 
 }  // namespace a2sf

@@ -11,6 +11,7 @@ All arithmetic happens in liba2sf.so; this file only sequences the calls.
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import time
 
 import torch
@@ -49,54 +50,34 @@ POLICIES = (   # name, alpha, share of the budget that is score-selected
 )
 
 
-def time_kernel(G, L, d=128, cached=200, reps=20):
-    """Time of one a2sf_ideal_similarity call over rows of length L against its algorithmic
-    bytes (the keys, read once: G * L * d * 2)."""
-    k = torch.randn((G, L, d), device="cuda").to(torch.bfloat16)
-    q = torch.randn((G, d), device="cuda").to(torch.bfloat16)
-    cache = B.Cache(G, cached + 1, d, torch.bfloat16)
-    cache.len.fill_(min(cached, L - 1))
-    cache.pos.copy_(torch.arange(cached + 1, dtype=torch.int32, device="cuda").expand(G, -1) % max(L - 1, 1))
-    out = torch.empty(G, dtype=torch.float32, device="cuda")
-    for _ in range(3):
-        B.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        B.a2sf_ideal_similarity(q, k, L, L - 1, cache, out)
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / reps
-    nbytes = G * L * d * 2
-    print(f"a2sf_ideal_similarity: {G} heads x {L} rows, d = {d}, bf16: {us:.1f} us per call, "
-          f"{nbytes / us / 1e3:.0f} GB/s of key bytes ({nbytes / us / 1e3 / 8000:.1%} of 8 TB/s)")
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=1, help="synthetic workload (shapes and salience recipe)")
     ap.add_argument("--heads", type=int, default=32)
     ap.add_argument("--length", type=int, default=None, help="sequence length (default: the config's prompt)")
     ap.add_argument("--ratio", type=float, default=0.2, help="cache ratio, as in the paper's Section 4.3")
-    ap.add_argument("--time-kernel", action="store_true",
-                    help="instead: time a2sf_ideal_similarity alone at --heads x --length (bf16, d = 128)")
+    ap.add_argument("--salience-logit-shift", action="store_true",
+                    help="plant the salient tokens so that their logits stand out by their full magnitude "
+                         "(strongly peaked attention, as trained models show) instead of magnitude / sqrt(d)")
     a = ap.parse_args()
-    if a.time_kernel:
-        return time_kernel(a.heads, a.length or 4096)
     w = synth.CONFIGS[a.config]
+    if a.salience_logit_shift:
+        w = dataclasses.replace(w, logit_shift=True)
     n = a.length or w.n
     heads = list(range(min(a.heads, w.G)))
     rows = [synth.head_arrays(w, g, length=n) for g in heads]
     dt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     q, k, v = (torch.stack([torch.from_numpy(r[j]) for r in rows]).to("cuda", dt) for j in range(3))
     budget = int(a.ratio * n)
-    print(f"workload {w.name}: {len(heads)} heads, n = {n}, d = {w.d}, {w.dtype}; cache {budget} tokens "
+    print(f"workload {w.name}{' (salient logits shifted)' if w.logit_shift else ''}: {len(heads)} heads, n = {n}, d = {w.d}, {w.dtype}; cache {budget} tokens "
           f"({a.ratio:.0%}); average cosine to the Ideal rows over the steps past the budget")
     for name, alpha, share in POLICIES:
         select = int(round(share * budget))
         t0 = time.time()
         cos = mask_similarity(q, k, v, alpha, select, budget - select)
-        mean = float(cos[budget + 1:].mean())
+        mean_dev = torch.empty(1, dtype=torch.float32, device=cos.device)
+        B.a2sf_similarity_mean(cos, n, len(heads), budget + 1, mean_dev)
+        mean = float(mean_dev.item())
         print(f"  {name:9s} alpha={alpha:<4} select={select:4d} recent={budget - select:4d}  "
               f"cosine {mean:.3f}   ({time.time() - t0:.1f} s)")
 

@@ -14,7 +14,9 @@ Recipe per head (lengths n + T: rows < n are the prompt, row n+t feeds decode st
   Q_i += u for every i;  K_j += m_j * u for salient j, where m_j = 3 ("fixed") or
   m_j = min(1 + Pareto(1.5), 8) ("pareto"; token 0 gets 8 when the config asks for a sink);
   for bf16 configs the three arrays are then rounded to bf16 (round to nearest even) and
-  both sides consume the rounded values.
+  both sides consume the rounded values.  `logit_shift` (off in the five configurations)
+  multiplies the planted component by d^(1/4) on Q and K, which makes the salient logits
+  stand out by m instead of m / sqrt(d).
 """
 from __future__ import annotations
 
@@ -43,6 +45,7 @@ class Workload:
     magnitude: str        # "fixed" or "pareto"
     sink: bool = False
     seed: int = 0
+    logit_shift: bool = False   # planted component times d^(1/4) on Q and K: shifts in logit units
 
     @property
     def G(self) -> int:
@@ -103,8 +106,12 @@ def head_arrays(w: Workload, g: int, length: int | None = None):
         if w.sink:
             m[0] = 8.0
     Q, K, V = x[0], x[1], x[2]
-    Q += u[None, :]
-    K[salient] += m[salient, None] * u[None, :]
+    # The literal recipe moves a salient logit by only m / sqrt(d) after the 1/sqrt(d) scale
+    # (0.27 at d = 128 for m = 3).  With logit_shift the planted component is scaled by d^(1/4)
+    # on both sides, so the shift is m in logit units: strongly peaked attention.
+    boost = np.float32(w.d ** 0.25) if w.logit_shift else np.float32(1.0)
+    Q += boost * u[None, :]
+    K[salient] += boost * m[salient, None] * u[None, :]
     if w.dtype == "bf16":
         Q = bf16_bits_to_f32(round_to_bf16_bits(Q))
         K = bf16_bits_to_f32(round_to_bf16_bits(K))
