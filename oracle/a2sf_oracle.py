@@ -25,6 +25,16 @@ Definitions followed
   score leave the cache so that a fixed budget stays; the budget is split into a
   score-selected part and a most-recent part (either may be 0).
 
+* Prompt processed in chunks (beyond the paper, which evicts once per generation step): a chunk
+  of m tokens is m generation steps without eviction in between -- each row attends the cached
+  tokens and the chunk's tokens up to itself, S <- alpha*S + a row by row -- followed by ONE
+  eviction down to the budget.  Written here in matrix form; the tests tie it to the
+  step-by-step form, to ``prefill`` (one chunk, empty cache) and to ``decode_step`` (m = 1).
+* Grouped-query heads (beyond the paper, whose models are all multi-head): r query heads share
+  one K/V head, so a token is kept or evicted for the whole group.  Reading: the group's score
+  of a token is the SUM of its query heads' accumulated scores, as Eq.1 of the paper sums over
+  heads where one pruning decision serves all of them.
+
 * Similarity to the Ideal mask (Section 4.3, Table 2): at every generation step the Ideal
   computes the attention of the query over ALL earlier tokens (nothing is ever removed) and
   keeps the entries of the tokens with the largest attention score, as many as the cache
@@ -48,6 +58,8 @@ __all__ = [
     "forgotten_scores_recurrence", "forgotten_scores_streamed", "select_keep",
     "HeadCache", "prefill", "attend_and_update", "evict", "decode_step",
     "pruned_row", "ideal_row", "cosine_similarity", "similarity_to_ideal",
+    "chunk_attend_and_update", "prefill_chunk", "gqa_prefill", "gqa_attend_and_update",
+    "gqa_decode_step",
 ]
 
 
@@ -272,6 +284,95 @@ def decode_step(cache: HeadCache, q, k_new, v_new, t_pos: int, alpha: float,
     the cache in between.  Returns (o[d], a[L], evicted_positions, n_swapped).
     """
     o, a = attend_and_update(cache, q, k_new, v_new, t_pos, alpha)
+    gone, swaps = evict(cache, select, recent, forced_retained, margin)
+    return o, a, gone, swaps
+
+
+# --------------------------------------------------------------------------- chunks of a prompt
+def chunk_attend_and_update(cache: HeadCache, Qc, Kc, Vc, pos0: int, alpha: float):
+    """A chunk of m new tokens against a cache of L earlier ones, in place, no eviction yet.
+
+    Row i of the chunk attends every cached token and the chunk's tokens 0..i (softmax over
+    exactly those: Section 2.2, Section 3.1 Eq.3 for the masked part); O = P [V_c; Vc].
+    Scores: the recurrence S <- alpha*S + a (abstract; Section 3.3) applied once per row, i.e.
+    a cached token ends with alpha^m S_j + sum_i alpha^(m-1-i) P[i, j] and chunk token c with
+    sum_{i>=c} alpha^(m-1-i) P[i, L+c] (Eq.5 restricted to the rows that exist).  The chunk's
+    tokens get positions pos0 .. pos0+m-1.  Returns (O[m, d], P[m, L+m])."""
+    Qc, Kc, Vc = (np.asarray(x, dtype=np.float64) for x in (Qc, Kc, Vc))
+    m, d = Qc.shape
+    L = len(cache)
+    K_all = np.vstack([cache.K.reshape(L, d), Kc])
+    V_all = np.vstack([cache.V.reshape(L, d), Vc])
+    s = (Qc @ K_all.T) / np.sqrt(float(d))
+    rows = np.arange(m)[:, None]
+    cols = np.arange(L + m)[None, :]
+    s[cols > L + rows] = -np.inf            # chunk token c is visible to chunk rows i >= c only
+    s -= s.max(axis=1, keepdims=True)
+    e = np.exp(s)
+    P = e / e.sum(axis=1, keepdims=True)
+    O = P @ V_all
+    S_old = np.concatenate([cache.S, np.zeros(m, dtype=np.float64)])
+    decay = float(alpha) ** m               # 0**m = 0 for m >= 1: alpha = 0 forgets everything older
+    cache.S = decay * S_old + _weights(m, alpha) @ P
+    cache.K, cache.V = K_all, V_all
+    cache.pos = np.concatenate([cache.pos, np.arange(pos0, pos0 + m, dtype=np.int64)])
+    return O, P
+
+
+def prefill_chunk(cache: HeadCache, Qc, Kc, Vc, pos0: int, alpha: float, select: int, recent: int,
+                  forced_retained=None, margin: float = 1e-6):
+    """chunk_attend_and_update, then one eviction down to the budget (``evict``).
+    Returns (O[m, d], evicted_positions, n_swapped)."""
+    O, _ = chunk_attend_and_update(cache, Qc, Kc, Vc, pos0, alpha)
+    gone, swaps = evict(cache, select, recent, forced_retained, margin)
+    return O, gone, swaps
+
+
+# --------------------------------------------------------------------------- grouped-query heads
+def gqa_prefill(Qs, K, V, alpha: float, select: int, recent: int, forced_retained=None,
+                margin: float = 1e-6):
+    """Prompt phase of one K/V head shared by r query heads.  Qs: [r, n, d]; K, V: [n, d].
+
+    Every query head has its own masked softmax and output; the score of a token is the sum of
+    the r heads' Eq.5 scores, and one selection on that sum serves the whole group.
+    Returns (O[r, n, d], S_full[n], HeadCache)."""
+    Qs = np.asarray(Qs, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    r, n, _ = Qs.shape
+    O = np.zeros((r, n, V.shape[1]), dtype=np.float64)
+    S_full = np.zeros(n, dtype=np.float64)
+    for h in range(r):
+        P = causal_probabilities(Qs[h], K)
+        O[h] = attention_output(P, V)
+        S_full += forgotten_scores(P, alpha)
+    keep, _ = _resolve_keep(S_full, np.arange(n), select, recent, forced_retained, margin)
+    return O, S_full, HeadCache(K[keep], V[keep], S_full[keep], keep)
+
+
+def gqa_attend_and_update(cache: HeadCache, qs, k_new, v_new, t_pos: int, alpha: float):
+    """First half of a generation step of one K/V head with r query heads (qs: [r, d]), in
+    place: every query head takes its own softmax over the cached tokens and its own output;
+    the forgetting update adds the SUM of the r probability rows.  Returns (o[r, d], a[r, L])."""
+    qs = np.asarray(qs, dtype=np.float64)
+    r, d = qs.shape
+    cache.K = np.vstack([cache.K.reshape(-1, d), np.asarray(k_new, dtype=np.float64)[None, :]])
+    cache.V = np.vstack([cache.V.reshape(-1, d), np.asarray(v_new, dtype=np.float64)[None, :]])
+    cache.S = np.append(cache.S, 0.0)
+    cache.pos = np.append(cache.pos, int(t_pos))
+    z = (qs @ cache.K.T) / np.sqrt(float(d))
+    z -= z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    a = e / e.sum(axis=1, keepdims=True)
+    o = a @ cache.V
+    cache.S = float(alpha) * cache.S + a.sum(axis=0)
+    return o, a
+
+
+def gqa_decode_step(cache: HeadCache, qs, k_new, v_new, t_pos: int, alpha: float, select: int,
+                    recent: int, forced_retained=None, margin: float = 1e-6):
+    """gqa_attend_and_update, then ``evict``.  Returns (o[r, d], a[r, L], evicted, n_swapped)."""
+    o, a = gqa_attend_and_update(cache, qs, k_new, v_new, t_pos, alpha)
     gone, swaps = evict(cache, select, recent, forced_retained, margin)
     return o, a, gone, swaps
 

@@ -172,6 +172,29 @@ class TestForgottenScore:
         bound = alpha ** W / (1 - alpha) * P[: n - W].max(axis=0)
         assert np.all(full - cut >= 0) and np.all(full - cut <= bound + 1e-18)
 
+    @pytest.mark.parametrize("alpha", [0.1, 0.5, 0.9])
+    @pytest.mark.parametrize("spread", [1.0, 4.0])
+    def test_window_from_the_newest_row_keeps_the_relative_error(self, alpha, spread):
+        """The a-priori row window of a2sf_prefill_windowed, stated on the oracle: all rows before
+        n - W add at most alpha^W / (1 - alpha) to any score while S_j >= P[n-1, j], so with
+        alpha^W <= tol (1 - alpha) min_j P[n-1, j] (the minimum over a group of keys) every score
+        of the group keeps a relative error <= tol when those rows are dropped."""
+        n, d, tol, group = 600, 16, 2.5e-5, 64
+        rng = np.random.default_rng(int(alpha * 100 + spread))
+        Q = spread * rng.standard_normal((n, d))
+        K = rng.standard_normal((n, d))
+        P = orc.causal_probabilities(Q, K)
+        full = orc.forgotten_scores(P, alpha)
+        for j0 in range(0, n, group):
+            p_min = P[n - 1, j0:j0 + group].min()
+            W = int(np.ceil(np.log(tol * (1 - alpha) * p_min) / np.log(alpha)))
+            assert W >= 1
+            Pt = P.copy()
+            Pt[: max(0, n - W)] = 0.0
+            cut = orc.forgotten_scores(Pt, alpha)[j0:j0 + group]
+            rel = (full[j0:j0 + group] - cut) / full[j0:j0 + group]
+            assert np.all(rel >= 0) and rel.max() <= tol, (j0, W, rel.max())
+
     def test_streamed_equals_matrix_form(self):
         Q, K, V = rand_head(300, 16)
         P = orc.causal_probabilities(Q, K)
@@ -339,6 +362,186 @@ class TestDecode:
             orc.evict(c.copy(), 2, 1, forced_retained=[0, 3])        # wrong size
 
 
+
+# ---------------------------------------------------------------- chunks of a prompt
+def brute_chunk(cacheK, cacheV, cacheS, Qc, Kc, Vc, alpha):
+    """A chunk against a cache with explicit loops: row i attends the L cached tokens and the
+    chunk's tokens 0..i; the scores follow S <- alpha*S + a once per row (abstract, Section 3.3)."""
+    L, m, d = len(cacheK), len(Qc), len(Qc[0])
+    keys = [list(r) for r in cacheK] + [list(r) for r in Kc]
+    vals = [list(r) for r in cacheV] + [list(r) for r in Vc]
+    S = [float(x) for x in cacheS] + [0.0] * m
+    O = []
+    for i in range(m):
+        vis = L + i + 1
+        logit = [sum(Qc[i][c] * keys[j][c] for c in range(d)) / math.sqrt(d) for j in range(vis)]
+        top = max(logit)
+        ex = [math.exp(x - top) for x in logit]
+        tot = math.fsum(ex)
+        a = [x / tot for x in ex]
+        O.append([math.fsum(a[j] * vals[j][c] for j in range(vis)) for c in range(len(vals[0]))])
+        S = [alpha * S[j] + (a[j] if j < vis else 0.0) for j in range(L + m)]
+    return O, S
+
+
+class TestChunks:
+    def _cache(self, L, d, rng):
+        K, V = rng.standard_normal((L, d)), rng.standard_normal((L, d))
+        S = rng.random(L)
+        pos = np.sort(rng.choice(5 * L + 3, size=L, replace=False))
+        return orc.HeadCache(K, V, S, pos)
+
+    @pytest.mark.parametrize("alpha", [0.0, 0.3, 1.0])
+    def test_brute_force_chunk(self, alpha):
+        rng = np.random.default_rng(11)
+        L, m, d = 7, 5, 4
+        c = self._cache(L, d, rng)
+        Qc, Kc, Vc = (rng.standard_normal((m, d)) for _ in range(3))
+        O_ref, S_ref = brute_chunk(c.K.tolist(), c.V.tolist(), c.S.tolist(), Qc.tolist(), Kc.tolist(),
+                                   Vc.tolist(), alpha)
+        first = int(c.pos.max()) + 1
+        O, P = orc.chunk_attend_and_update(c, Qc, Kc, Vc, first, alpha)
+        assert np.abs(O - np.array(O_ref)).max() < 1e-13
+        assert np.abs(c.S - np.array(S_ref)).max() < 1e-13
+        assert np.all(P[np.arange(m)[:, None] + L < np.arange(L + m)[None, :]] == 0.0)   # masked part
+        assert np.allclose(P.sum(axis=1), 1.0, rtol=0, atol=1e-14)
+        assert list(c.pos[L:]) == list(range(first, first + m))
+
+    @pytest.mark.parametrize("alpha", [0.0, 0.4, 1.0])
+    def test_chunk_is_steps_without_eviction_then_one_eviction(self, alpha):
+        """The matrix form against the generation-step form: m calls of attend_and_update with
+        no eviction in between, then evict -- same outputs, scores and survivors."""
+        rng = np.random.default_rng(5)
+        L, m, d, sel, rec = 20, 9, 8, 8, 6
+        c1 = self._cache(L, d, rng)
+        c2 = c1.copy()
+        Qc, Kc, Vc = (rng.standard_normal((m, d)) for _ in range(3))
+        first = int(c1.pos.max()) + 1
+        O, gone, _ = orc.prefill_chunk(c1, Qc, Kc, Vc, first, alpha, sel, rec)
+        for i in range(m):
+            o, _ = orc.attend_and_update(c2, Qc[i], Kc[i], Vc[i], first + i, alpha)
+            assert np.abs(o - O[i]).max() < 1e-13
+        gone2, _ = orc.evict(c2, sel, rec)
+        assert gone == gone2 and len(gone) == L + m - (sel + rec)
+        assert list(c1.pos) == list(c2.pos)
+        assert np.abs(c1.S - c2.S).max() < 1e-13
+        assert np.array_equal(c1.K, c2.K) and np.array_equal(c1.V, c2.V)
+
+    def test_chunk_of_one_is_a_generation_step(self):
+        rng = np.random.default_rng(6)
+        c1 = self._cache(15, 8, rng)
+        c2 = c1.copy()
+        q, k, v = (rng.standard_normal(8) for _ in range(3))
+        t = int(c1.pos.max()) + 4
+        O, gone, _ = orc.prefill_chunk(c1, q[None], k[None], v[None], t, 0.6, 5, 5)
+        o, _, gone2, _ = orc.decode_step(c2, q, k, v, t, 0.6, 5, 5)
+        assert np.abs(O[0] - o).max() < 1e-14 and gone == gone2
+        assert list(c1.pos) == list(c2.pos) and np.abs(c1.S - c2.S).max() < 1e-14
+
+    @pytest.mark.parametrize("alpha", [0.0, 0.25, 1.0])
+    def test_one_chunk_on_an_empty_cache_is_the_prompt_phase(self, alpha):
+        n, d, sel, rec = 48, 8, 7, 5
+        Q, K, V = rand_head(n, d)
+        O_ref, S_full, c_ref = orc.prefill(Q, K, V, alpha, sel, rec)
+        c = orc.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64))
+        O, P = orc.chunk_attend_and_update(c, Q, K, V, 0, alpha)
+        assert np.abs(O - O_ref).max() < 1e-13
+        assert np.abs(c.S - S_full).max() < 1e-13
+        assert np.abs(P - orc.causal_probabilities(Q, K)).max() < 1e-14
+        orc.evict(c, sel, rec)
+        assert list(c.pos) == list(c_ref.pos) and np.abs(c.S - c_ref.S).max() < 1e-13
+
+    @pytest.mark.parametrize("sizes", [(30, 18), (1, 47), (24, 1, 23), (16, 16, 16)])
+    def test_chunks_without_eviction_equal_the_whole_prompt(self, sizes):
+        """With a budget that never binds, any split of the prompt into chunks gives the rows
+        and the Eq.5 scores of the whole prompt."""
+        n, d, alpha = sum(sizes), 8, 0.45
+        Q, K, V = rand_head(n, d)
+        P = orc.causal_probabilities(Q, K)
+        c = orc.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64))
+        at = 0
+        for m in sizes:
+            O, gone, _ = orc.prefill_chunk(c, Q[at:at + m], K[at:at + m], V[at:at + m], at, alpha, n, 0)
+            assert gone == []
+            assert np.abs(O - orc.attention_output(P, V)[at:at + m]).max() < 1e-13
+            at += m
+        assert np.abs(c.S - orc.forgotten_scores(P, alpha)).max() < 1e-13
+
+    @pytest.mark.parametrize("alpha", [0.3, 1.0])
+    def test_chunk_score_total(self, alpha):
+        """Rows sum to 1, so the chunk adds sum_i alpha^(m-1-i) to the decayed total."""
+        rng = np.random.default_rng(8)
+        c = self._cache(12, 4, rng)
+        before = c.S.sum()
+        m = 6
+        Qc, Kc, Vc = (rng.standard_normal((m, 4)) for _ in range(3))
+        orc.chunk_attend_and_update(c, Qc, Kc, Vc, int(c.pos.max()) + 1, alpha)
+        add = float(m) if alpha == 1.0 else (1 - alpha ** m) / (1 - alpha)
+        assert math.isclose(c.S.sum(), alpha ** m * before + add, rel_tol=1e-13)
+
+
+# ---------------------------------------------------------------- grouped-query heads
+class TestGroupedQueryHeads:
+    def test_group_of_one_is_the_plain_path(self):
+        n, T, d, alpha, sel, rec = 40, 9, 8, 0.3, 6, 4
+        Q, K, V = rand_head(n + T, d)
+        O1, S1, c1 = orc.prefill(Q[:n], K[:n], V[:n], alpha, sel, rec)
+        O2, S2, c2 = orc.gqa_prefill(Q[None, :n], K[:n], V[:n], alpha, sel, rec)
+        assert np.array_equal(O1, O2[0]) and np.array_equal(S1, S2) and list(c1.pos) == list(c2.pos)
+        for t in range(T):
+            o1, _, g1, _ = orc.decode_step(c1, Q[n + t], K[n + t], V[n + t], n + t, alpha, sel, rec)
+            o2, _, g2, _ = orc.gqa_decode_step(c2, Q[None, n + t], K[n + t], V[n + t], n + t, alpha, sel, rec)
+            assert np.abs(o1 - o2[0]).max() < 1e-15 and g1 == g2
+        assert np.abs(c1.S - c2.S).max() < 1e-15
+
+    def test_group_score_is_the_sum_over_its_query_heads(self):
+        """Each query head's output is what that head computes alone on the shared K/V; the
+        group's score is the sum of the single-head scores (prompt and generation steps, no
+        eviction so that the single-head caches stay comparable)."""
+        r, n, T, d, alpha = 3, 30, 6, 8, 0.5
+        rng = np.random.default_rng(13)
+        Qs = rng.standard_normal((r, n + T, d))
+        K, V = rng.standard_normal((n + T, d)), rng.standard_normal((n + T, d))
+        big = n + T
+        O, S, c = orc.gqa_prefill(Qs[:, :n], K[:n], V[:n], alpha, big, 0)
+        singles = [orc.prefill(Qs[h, :n], K[:n], V[:n], alpha, big, 0) for h in range(r)]
+        assert np.abs(S - sum(x[1] for x in singles)).max() < 1e-13
+        for h in range(r):
+            assert np.abs(O[h] - singles[h][0]).max() < 1e-14
+        caches = [x[2] for x in singles]
+        for t in range(T):
+            o, a, _, _ = orc.gqa_decode_step(c, Qs[:, n + t], K[n + t], V[n + t], n + t, alpha, big, 0)
+            for h in range(r):
+                oh, ah, _, _ = orc.decode_step(caches[h], Qs[h, n + t], K[n + t], V[n + t], n + t, alpha, big, 0)
+                assert np.abs(o[h] - oh).max() < 1e-14 and np.abs(a[h] - ah).max() < 1e-15
+            assert np.abs(c.S - sum(x.S for x in caches)).max() < 1e-13
+
+    def test_group_totals(self):
+        """r rows of probabilities are added per step: total_after = alpha * total_before + r."""
+        r, n, d, alpha = 4, 25, 8, 0.3
+        rng = np.random.default_rng(14)
+        Qs = rng.standard_normal((r, n + 1, d))
+        K, V = rng.standard_normal((n + 1, d)), rng.standard_normal((n + 1, d))
+        _, S, c = orc.gqa_prefill(Qs[:, :n], K[:n], V[:n], alpha, 6, 6)
+        assert math.isclose(S.sum(), r * (1 - alpha ** n) / (1 - alpha), rel_tol=1e-12)
+        before = c.S.sum()
+        orc.gqa_attend_and_update(c, Qs[:, n], K[n], V[n], n, alpha)
+        assert math.isclose(c.S.sum(), alpha * before + r, rel_tol=1e-13)
+
+    def test_one_eviction_serves_the_group(self):
+        """The token with the smallest SUMMED score leaves, even where a single query head
+        would have evicted another one."""
+        d = 4
+        K = np.eye(4)[:3].astype(float) * 6.0          # three tokens along different axes
+        V = np.zeros((3, d))
+        cache = orc.HeadCache(K, V, np.zeros(3), np.arange(3))
+        qs = np.array([[6.0, 0, 0, 0], [0, 0, 6.0, 0]])            # head 0 likes token 0, head 1 token 2
+        _, a, gone, _ = orc.gqa_decode_step(cache, qs, np.zeros(d), np.zeros(d), 3, 1.0, 3, 0)
+        assert gone == [1] or gone == [3]              # token 1 (no head likes it) or the new token
+        assert a[0].argmax() == 0 and a[1].argmax() == 2
+        assert 0 in cache.pos and 2 in cache.pos
+
+
 # ---------------------------------------------------------------- planted mistakes
 def brute_row(q, K, allowed):
     """Softmax of q.k/sqrt(d) over the positions in `allowed`, explicit loops."""
@@ -463,6 +666,13 @@ class TestPinsCatchMistakes:
         (TestSimilarityToIdeal, "test_uniform_attention_local_window_closed_form", ()),
         (TestSimilarityToIdeal, "test_tie_goes_to_lower_position", ()),
         (TestSimilarityToIdeal, "test_cosine", ()),
+        (TestChunks, "test_brute_force_chunk", (0.3,)),
+        (TestChunks, "test_chunk_is_steps_without_eviction_then_one_eviction", (0.4,)),
+        (TestChunks, "test_one_chunk_on_an_empty_cache_is_the_prompt_phase", (0.25,)),
+        (TestChunks, "test_chunk_score_total", (0.3,)),
+        (TestGroupedQueryHeads, "test_group_score_is_the_sum_over_its_query_heads", ()),
+        (TestGroupedQueryHeads, "test_group_totals", ()),
+        (TestGroupedQueryHeads, "test_one_eviction_serves_the_group", ()),
     ]
 
     def _some_pin_fails(self):
@@ -577,4 +787,45 @@ class TestPinsCatchMistakes:
 
     def test_cosine_without_normalisation(self, monkeypatch):
         monkeypatch.setattr(orc, "cosine_similarity", lambda u, v: float(np.dot(u, v)))
+        assert self._some_pin_fails()
+
+    def test_chunk_decay_forgotten(self, monkeypatch):
+        """A chunk that does not decay the cached scores by alpha^m."""
+        real = orc.chunk_attend_and_update
+
+        def bad(cache, Qc, Kc, Vc, pos0, alpha):
+            old = cache.S.copy()
+            out = real(cache, Qc, Kc, Vc, pos0, alpha)
+            m = len(np.asarray(Qc))
+            cache.S[:len(old)] += (1.0 - float(alpha) ** m) * old
+            return out
+        monkeypatch.setattr(orc, "chunk_attend_and_update", bad)
+        assert self._some_pin_fails()
+
+    def test_chunk_rows_see_the_whole_chunk(self, monkeypatch):
+        """A chunk whose rows also attend the chunk's LATER tokens (mask forgotten)."""
+        def bad(cache, Qc, Kc, Vc, pos0, alpha):
+            Qc, Kc, Vc = (np.asarray(x, float) for x in (Qc, Kc, Vc))
+            m, d = Qc.shape
+            L = len(cache)
+            K_all, V_all = np.vstack([cache.K.reshape(L, d), Kc]), np.vstack([cache.V.reshape(L, d), Vc])
+            s = Qc @ K_all.T / np.sqrt(d)
+            e = np.exp(s - s.max(axis=1, keepdims=True))
+            P = e / e.sum(axis=1, keepdims=True)
+            cache.S = float(alpha) ** m * np.concatenate([cache.S, np.zeros(m)]) + orc._weights(m, alpha) @ P
+            cache.K, cache.V = K_all, V_all
+            cache.pos = np.concatenate([cache.pos, np.arange(pos0, pos0 + m)])
+            return P @ V_all, P
+        monkeypatch.setattr(orc, "chunk_attend_and_update", bad)
+        assert self._some_pin_fails()
+
+    def test_group_score_averaged_instead_of_summed(self, monkeypatch):
+        real = orc.gqa_attend_and_update
+
+        def bad(cache, qs, k_new, v_new, t_pos, alpha):
+            old = np.append(cache.S, 0.0)
+            o, a = real(cache, qs, k_new, v_new, t_pos, alpha)
+            cache.S = float(alpha) * old + a.mean(axis=0)
+            return o, a
+        monkeypatch.setattr(orc, "gqa_attend_and_update", bad)
         assert self._some_pin_fails()
