@@ -1,0 +1,275 @@
+// Machine ceilings that the roofline figures of this build are compared with, measured on the
+// box itself.  A stand-alone program (not part of liba2sf.so); bench.py --ceilings runs it,
+// and so can rocprofv3:
+//
+//     ceilings hbm     streaming reads of the generation step's K/V bytes (16384 heads x 201 rows
+//                      of 256 bytes, K then V) in the step's own access pattern (one wave per
+//                      head) and as a plain linear sweep, with and without the non-temporal
+//                      hint; then the same reads plus the step's small per-head accesses (score
+//                      row read and written, two 256-byte row writes, one 256-byte output row)
+//     ceilings mfma    sustained rate of v_mfma_f32_32x32x16_bf16 from registers, for operands
+//                      that are all zero, N(0,1)-like, and probability-like (in [0,1)): the chip
+//                      lowers its clock with the switching activity of the operands, so the
+//                      rate real data can reach is well below the nominal peak
+//
+// Every access is inside its allocation by construction (indices are clamped to the extent);
+// kernels do no work beyond the loads / matrix ops being measured.  One JSON object per line.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#define CK(x)                                                                       \
+  do {                                                                              \
+    hipError_t e_ = (x);                                                            \
+    if (e_ != hipSuccess) {                                                         \
+      fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
+      exit(1);                                                                      \
+    }                                                                               \
+  } while (0)
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ uint4 ld16(const uint4* p) {
+  if (NT) {
+    const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+  }
+  return *p;
+}
+__device__ __forceinline__ float sum4(uint4 x) {
+  return __uint_as_float(x.x) + __uint_as_float(x.y) + __uint_as_float(x.z) + __uint_as_float(x.w);
+}
+
+// ---- HBM ------------------------------------------------------------------------------
+// linear sweep over n 16-byte units, U loads in flight per lane
+template <int U, bool NT>
+__global__ __launch_bounds__(256) void sweep_linear(const uint4* __restrict__ A, size_t n, float* out) {
+  float acc = 0.f;
+  const size_t stride = (size_t)gridDim.x * 256 * U;
+  for (size_t i = (size_t)blockIdx.x * 256 * U + threadIdx.x; i < n; i += stride) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t j = i + (size_t)u * 256;
+      x[u] = ld16<NT>(A + (j < n ? j : 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += sum4(x[u]);
+  }
+  if (acc == 12345.678f) out[blockIdx.x] = acc;   // never true: keeps the loads alive
+}
+
+// One wave per head: the head's K region (units x 16 bytes), a wave reduction, then its V region.
+// SMALL adds the generation step's other per-head traffic: a score row of `slots` floats read
+// up front and written at the end, one 256-byte row written into each of the two regions at a
+// slot that changes from launch to launch, and a 256-byte output row.
+template <int U, bool NT, bool SMALL>
+__global__ __launch_bounds__(256) void sweep_heads(uint4* __restrict__ A, uint4* __restrict__ B, int units,
+                                                   int heads, float* __restrict__ S, int slots,
+                                                   uint4* __restrict__ O, int launch, float* out) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (g >= heads) return;
+  const uint4* a = A + (size_t)g * units;
+  const uint4* b = B + (size_t)g * units;
+  float sv[4] = {0.f, 0.f, 0.f, 0.f};
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = lane + 64 * k;
+      if (j < slots) sv[k] = S[(size_t)g * slots + j];
+    }
+  }
+  float acc = 0.f;
+  for (int i = lane; i < units; i += 64 * U) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = i + u * 64;
+      x[u] = ld16<NT>(a + (j < units ? j : 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc += sum4(x[u]);
+  }
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  float acc2 = 0.f;
+  for (int i = lane; i < units; i += 64 * U) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = i + u * 64;
+      x[u] = ld16<NT>(b + (j < units ? j : 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc2 += acc * sum4(x[u]);
+  }
+  if (SMALL) {
+    for (int o = 32; o > 0; o >>= 1) acc2 += __shfl_xor(acc2, o, 64);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = lane + 64 * k;
+      if (j < slots - 1) S[(size_t)g * slots + j] = 0.5f * sv[k] + 1e-30f * acc2;
+    }
+    const int rows = units / 16;                                // 256-byte rows of a region
+    const int v = (int)(((unsigned)g * 7u + (unsigned)launch * 13u) % (unsigned)rows);
+    const uint4 w = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, __float_as_uint(acc2) & 0x3f803f80u);
+    if (lane < 16) A[(size_t)g * units + v * 16 + lane] = w;
+    else if (lane < 32) B[(size_t)g * units + v * 16 + lane - 16] = w;
+    else if (lane < 48) O[(size_t)g * 16 + lane - 32] = w;
+  } else if (acc2 == 12345.678f) {
+    out[g] = acc2;
+  }
+}
+
+static void run_hbm() {
+  const int heads = 16384, rows = 201, units = rows * 16;       // 16-byte units per head and region
+  const size_t bytes = (size_t)heads * units * 16;              // one region set (K or V): 843 MB
+  const size_t n = bytes / 16;
+  uint4 *A[2], *B[2], *O;
+  float *out, *S;
+  for (int i = 0; i < 2; ++i) {   // two buffer sets, used in turn, so that nothing is served by the 256 MB cache
+    CK(hipMalloc(&A[i], bytes));
+    CK(hipMalloc(&B[i], bytes));
+    CK(hipMemset(A[i], 0x3f, bytes));
+    CK(hipMemset(B[i], 0x3f, bytes));
+  }
+  CK(hipMalloc(&out, heads * sizeof(float)));
+  CK(hipMalloc(&S, (size_t)heads * rows * sizeof(float)));
+  CK(hipMemset(S, 0, (size_t)heads * rows * sizeof(float)));
+  CK(hipMalloc(&O, (size_t)heads * 256));
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  const char* names[] = {"linear sweep", "linear sweep, non-temporal", "one wave per head (K then V)",
+                         "one wave per head, non-temporal", "one wave per head + the step's small accesses",
+                         "one wave per head, non-temporal + the step's small accesses"};
+  const double small_bytes = (double)heads * (8.0 * rows + 3 * 256.0);
+  for (int variant = 0; variant < 6; ++variant) {
+    float best = 1e30f;
+    const int launches = 10;
+    for (int rep = 0; rep < 3; ++rep) {
+      CK(hipEventRecord(e0));
+      for (int it = 0; it < launches; ++it) {
+        uint4* a = A[it & 1];
+        uint4* b = B[it & 1];
+        const dim3 gh(heads / 4), bl(256);
+        switch (variant) {
+          case 0:
+            hipLaunchKernelGGL((sweep_linear<8, false>), dim3(2048), bl, 0, 0, a, n, out);
+            hipLaunchKernelGGL((sweep_linear<8, false>), dim3(2048), bl, 0, 0, b, n, out);
+            break;
+          case 1:
+            hipLaunchKernelGGL((sweep_linear<8, true>), dim3(2048), bl, 0, 0, a, n, out);
+            hipLaunchKernelGGL((sweep_linear<8, true>), dim3(2048), bl, 0, 0, b, n, out);
+            break;
+          case 2: hipLaunchKernelGGL((sweep_heads<8, false, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 3: hipLaunchKernelGGL((sweep_heads<8, true, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 4: hipLaunchKernelGGL((sweep_heads<8, false, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 5: hipLaunchKernelGGL((sweep_heads<8, true, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+        }
+      }
+      CK(hipEventRecord(e1));
+      CK(hipEventSynchronize(e1));
+      float ms;
+      CK(hipEventElapsedTime(&ms, e0, e1));
+      if (ms < best) best = ms;
+    }
+    const double us = best * 1e3 / launches;
+    const double kv = 2.0 * bytes;
+    const double total = kv + (variant >= 4 ? small_bytes : 0.0);
+    printf("{\"probe\": \"hbm\", \"pattern\": \"%s\", \"bytes\": %.0f, \"us\": %.1f, \"GBps\": %.0f, "
+           "\"frac_of_8TBps\": %.3f}\n", names[variant], total, us, total / us / 1e3, total / us / 1e3 / 8000.0);
+    fflush(stdout);
+  }
+}
+
+// ---- matrix cores ---------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// NACC independent accumulators per wave, operands resident in registers: nothing but matrix ops
+template <int NACC>
+__global__ __launch_bounds__(256) void mfma_loop(const uint4* __restrict__ in, float* out, int iters) {
+  const uint4 a = in[threadIdx.x], b = in[threadIdx.x + 256];
+  const bf16x8 va = __builtin_bit_cast(bf16x8, a), vb = __builtin_bit_cast(bf16x8, b);
+  f32x16 acc[NACC];
+#pragma unroll
+  for (int j = 0; j < NACC; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < NACC; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, vb, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < NACC; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[j][i];
+  if (s == 1234.5f) out[threadIdx.x] = s;
+}
+
+static uint16_t to_bf16(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+static void run_mfma() {
+  uint4* in;
+  float* out;
+  CK(hipMalloc(&in, 512 * 16));
+  CK(hipMalloc(&out, 4096));
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  const char* names[] = {"all zero", "N(0,1)", "probabilities in [0,1) times N(0,1)"};
+  const int iters = 20000, nacc = 4, grid = 512;     // 2 workgroups per CU, 8 waves per CU
+  uint64_t state = 0x9E3779B97F4A7C15ull;
+  auto uni = [&]() {
+    state = state * 6364136223846793005ull + 1442695040888963407ull;
+    return (double)((state >> 11) + 1) / 9007199254740994.0;   // (0, 1)
+  };
+  auto gauss = [&]() { return std::sqrt(-2.0 * std::log(uni())) * std::cos(6.283185307179586 * uni()); };
+  for (int kind = 0; kind < 3; ++kind) {
+    std::vector<uint16_t> h(512 * 8);
+    for (int i = 0; i < 512 * 8; ++i) {
+      float x = 0.f;
+      if (kind == 1) x = (float)gauss();
+      if (kind == 2) x = i < 256 * 8 ? (float)gauss() : (float)uni();   // A = values, B = probabilities
+      h[i] = to_bf16(x);
+    }
+    CK(hipMemcpy(in, h.data(), 512 * 16, hipMemcpyHostToDevice));
+    float best = 1e30f;
+    for (int rep = 0; rep < 4; ++rep) {
+      CK(hipEventRecord(e0));
+      hipLaunchKernelGGL(mfma_loop<nacc>, dim3(grid), dim3(256), 0, 0, in, out, iters);
+      CK(hipEventRecord(e1));
+      CK(hipEventSynchronize(e1));
+      float ms;
+      CK(hipEventElapsedTime(&ms, e0, e1));
+      if (rep && ms < best) best = ms;
+    }
+    const double flop = (double)grid * 4 * iters * nacc * 2.0 * 32 * 32 * 16;
+    const double tf = flop / best / 1e9;
+    // a matrix op occupies its pipe for 32 cycles (16 passes of 2): implied clock
+    const double ghz = (double)iters * nacc * (grid / 256) * 32 / (best * 1e-3) / 1e9;
+    printf("{\"probe\": \"mfma\", \"instruction\": \"v_mfma_f32_32x32x16_bf16\", \"operands\": \"%s\", \"ms\": %.3f, "
+           "\"TFLOPps\": %.0f, \"frac_of_2500\": %.3f, \"implied_GHz\": %.2f}\n",
+           names[kind], best, tf, tf / 2500.0, ghz);
+    fflush(stdout);
+  }
+}
+
+int main(int argc, char** argv) {
+  const bool all = argc < 2;
+  if (all || !strcmp(argv[1], "hbm")) run_hbm();
+  if (all || !strcmp(argv[1], "mfma")) run_mfma();
+  return 0;
+}
