@@ -161,6 +161,10 @@ def main():
     ap.add_argument("--mode", choices=["fast", "stable"], default="fast")
     ap.add_argument("--alpha", type=float, default=None,
                     help="forgetting factor (default: the workload's; config 4 sweeps 0.1, 0.5, 0.9, 1.0)")
+    ap.add_argument("--score-tol", type=float, default=2.5e-5,
+                    help="relative tolerance of the prompt scores (a2sf_prefill_windowed: rows that provably "
+                         "cannot change a score by more are skipped); 0 = a2sf_prefill, every row of nonzero "
+                         "fp32 weight.  The scores are held to 1e-4 against the full-sum oracle either way")
     ap.add_argument("--graph", action="store_true",
                     help="replay the T generation steps of a pass from one HIP graph instead of launching "
                          "them one by one (matters for the few-head configs, whose steps are shorter than "
@@ -235,8 +239,12 @@ def main():
     def one_pass(ev=None):
         if ev:
             ev[0].record()
-        a2sf.a2sf_prefill(dev["q"], dev["k"], dev["v"], n, alpha, w.select, w.recent, cache,
-                          o=o_pre, scores_full=None, workspace=ws)
+        if args.score_tol > 0:
+            a2sf.a2sf_prefill_windowed(dev["q"], dev["k"], dev["v"], n, alpha, args.score_tol, w.select,
+                                       w.recent, cache, o=o_pre, scores_full=None, workspace=ws)
+        else:
+            a2sf.a2sf_prefill(dev["q"], dev["k"], dev["v"], n, alpha, w.select, w.recent, cache,
+                              o=o_pre, scores_full=None, workspace=ws)
         if ev:
             ev[1].record()
         if graph is not None:
@@ -302,6 +310,8 @@ def main():
         "config": {"workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n, "head_dim": d,
                    "decode_steps": T, "budget": f"{w.select}+{w.recent}", "alpha": alpha,
                    "evict_mode": args.mode, "prefill_outputs": not args.no_o,
+                   "prefill_call": (f"a2sf_prefill_windowed, score_rel_tol {args.score_tol:g}" if args.score_tol > 0
+                                    else "a2sf_prefill"),
                    "decode_launch": "hip graph of the T steps" if args.graph else "one launch per kernel",
                    "pass": "prefill + T decode steps"},
         "decode_us_per_step": dec_s_per_step * 1e6,

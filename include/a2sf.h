@@ -112,6 +112,44 @@ a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n,
                          float* scores_full, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
 
+/* a2sf_prefill with a relative tolerance on the Eq.5 scores (Section 3.3: the forgetting
+ * factor sends the contribution of old rows to 0, so for alpha < 1 only the newest rows of
+ * the prompt matter).  Rows whose whole remaining contribution to S_j is PROVABLY at most
+ * score_rel_tol * S_j are not computed.  The bound needs nothing but the newest row: all rows
+ * before n - W together add at most alpha^W / (1 - alpha) to any score (probabilities are
+ * <= 1) while S_j >= P[n-1, j]; the kernel reads the smallest P[n-1, j] of each group of 64
+ * keys off the newest row, which it processes first, and walks back W rows with
+ * alpha^W <= score_rel_tol * (1 - alpha) * min_j P[n-1, j].
+ *   score_rel_tol  in [0, 1); 0 = every row of nonzero fp32 weight, exactly a2sf_prefill.
+ * Everything else as in a2sf_prefill.  The window is applied to bf16 prompts with d = 128;
+ * other shapes compute every row (the result is then a2sf_prefill's).  alpha = 1 has no
+ * window, alpha = 0 only the newest row either way. */
+a2sf_status a2sf_prefill_windowed(const void* q, const void* k, const void* v, int32_t n,
+                                  float alpha, float score_rel_tol, a2sf_budget budget,
+                                  const a2sf_cache* cache, void* o, float* scores_full,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* A further chunk of a prompt that is too long to be processed at once (beyond the paper,
+ * which evicts once per generation step, Section 3.1): the chunk's m tokens are m generation
+ * steps whose eviction is deferred to the end of the chunk, so that their rows go through the
+ * matrix cores together.
+ *   q, k, v   [G, m, d] dtype: the chunk's queries, keys and values; its tokens have
+ *             positions pos0 .. pos0 + m - 1 (larger than every cached one).
+ *   cache     in/out; requires len[g] + m <= capacity (so capacity > m).  Row i of the chunk
+ *             attends the head's cached tokens and the chunk's tokens 0 .. i (softmax over
+ *             exactly those, Section 2.2); o_i is that row's output; every cached token's score
+ *             becomes alpha^m * S + sum_i alpha^(m-1-i) P[i, .] and a chunk token gets
+ *             sum_{i >= its own row} alpha^(m-1-i) P[i, .] (Section 3.3 Eq.5 over the rows
+ *             that exist); then ONE eviction as in a2sf_decode_step's stable mode brings the
+ *             head down to min(len + m, B) tokens, slot order preserved.
+ *             A head without room for the chunk is left untouched, its rows of o are NaN.
+ *   o         out [G, m, d] dtype, may be NULL.
+ * The first chunk of a prompt is a2sf_prefill (or this call on an empty cache, len = 0).
+ * Workspace: a2sf_workspace_bytes(G, m, capacity, d, dtype, budget). */
+a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int32_t m, int32_t pos0,
+                               float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* One generation step (abstract; Section 2.2; Section 3.3).
  *   q, k_new, v_new  [G, d] dtype: the new token's query, key and value.
  *   t_pos            original position of the new token (larger than every cached one).

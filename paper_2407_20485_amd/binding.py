@@ -24,7 +24,8 @@ A2SF_STATIC_WS_BYTES = 16 << 20
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",
            "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
            "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity", "a2sf_decode_step_static_ws",
-           "a2sf_similarity_mean", "a2sf_decode_plan")
+           "a2sf_similarity_mean", "a2sf_decode_plan", "a2sf_prefill_windowed",
+           "a2sf_prefill_chunk")
 
 
 class Budget(ctypes.Structure):
@@ -55,6 +56,12 @@ def lib() -> ctypes.CDLL:
         L.a2sf_prefill.restype = i32
         L.a2sf_prefill.argtypes = [vp, vp, vp, i32, f32, Budget, ctypes.POINTER(CacheStruct), vp, vp,
                                    vp, sz, vp]
+        L.a2sf_prefill_windowed.restype = i32
+        L.a2sf_prefill_windowed.argtypes = [vp, vp, vp, i32, f32, f32, Budget, ctypes.POINTER(CacheStruct), vp,
+                                            vp, vp, sz, vp]
+        L.a2sf_prefill_chunk.restype = i32
+        L.a2sf_prefill_chunk.argtypes = [vp, vp, vp, i32, i32, f32, Budget, ctypes.POINTER(CacheStruct), vp,
+                                         vp, sz, vp]
         L.a2sf_decode_step.restype = i32
         L.a2sf_decode_step.argtypes = [vp, vp, vp, i32, ctypes.POINTER(CacheStruct), f32, Budget, i32,
                                        vp, vp, sz, vp]
@@ -164,6 +171,26 @@ def a2sf_prefill(q, k, v, n, alpha, select, recent, cache, o=None, scores_full=N
     _check(lib().a2sf_prefill(_ptr(q), _ptr(k), _ptr(v), n, alpha, Budget(select, recent),
                               ctypes.byref(cs), _ptr(o), _ptr(scores_full), _ptr(workspace),
                               workspace_bytes, _stream(stream)))
+
+
+def a2sf_prefill_windowed(q, k, v, n, alpha, score_rel_tol, select, recent, cache, o=None, scores_full=None,
+                          workspace=None, workspace_bytes=None, stream=None):
+    cs = _cache_struct(cache)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().a2sf_prefill_windowed(_ptr(q), _ptr(k), _ptr(v), n, alpha, score_rel_tol,
+                                       Budget(select, recent), ctypes.byref(cs), _ptr(o), _ptr(scores_full),
+                                       _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def a2sf_prefill_chunk(q, k, v, m, pos0, alpha, select, recent, cache, o=None, workspace=None,
+                       workspace_bytes=None, stream=None):
+    cs = _cache_struct(cache)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().a2sf_prefill_chunk(_ptr(q), _ptr(k), _ptr(v), m, pos0, alpha, Budget(select, recent),
+                                    ctypes.byref(cs), _ptr(o), _ptr(workspace), workspace_bytes,
+                                    _stream(stream)))
 
 
 def a2sf_decode_step(q, k_new, v_new, t_pos, cache, alpha, select, recent, o,

@@ -89,7 +89,7 @@ inline a2sf_status launch_status() {
 }
 
 a2sf_status prefill_impl(const void* q, const void* k, const void* v, int32_t n, float alpha,
-                         const float* alpha_heads, a2sf_budget budget, const a2sf_cache* cache,
+                         const float* alpha_heads, float tol, a2sf_budget budget, const a2sf_cache* cache,
                          void* o, float* scores_full, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
   a2sf_status s;
@@ -119,7 +119,7 @@ a2sf_status prefill_impl(const void* q, const void* k, const void* v, int32_t n,
     launch_scores_f32((const float*)q, (const float*)k, lse2, G, n, d, alpha, alpha_heads, s_full, st);
   } else {
     launch_prefill_bf16(q, k, v, G, n, d, o, lse2, st);
-    launch_scores_bf16(q, k, lse2, G, n, d, alpha, alpha_heads, s_full, st);
+    launch_scores_bf16(q, k, lse2, G, n, d, alpha, alpha_heads, tol, s_full, st);
   }
   launch_select(s_full, nullptr, nullptr, G, n, n, budget.select, budget.recent, keep_idx, n_keep, st);
   launch_gather_prompt(k, v, s_full, n, keep_idx, B, n_keep, *cache, st);
@@ -176,8 +176,59 @@ a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n,
                          a2sf_budget budget, const a2sf_cache* cache, void* o,
                          float* scores_full, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
-  return prefill_impl(q, k, v, n, alpha, nullptr, budget, cache, o, scores_full, workspace,
+  return prefill_impl(q, k, v, n, alpha, nullptr, 0.0f, budget, cache, o, scores_full, workspace,
                       workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_prefill_windowed(const void* q, const void* k, const void* v, int32_t n,
+                                  float alpha, float score_rel_tol, a2sf_budget budget,
+                                  const a2sf_cache* cache, void* o, float* scores_full,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!(score_rel_tol >= 0.0f && score_rel_tol < 1.0f)) return A2SF_EINVAL;   // also rejects NaN
+  return prefill_impl(q, k, v, n, alpha, nullptr, score_rel_tol, budget, cache, o, scores_full,
+                      workspace, workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int32_t m, int32_t pos0,
+                               float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_alpha(alpha)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (!q || !k || !v) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o)) return A2SF_EINVAL;
+  if (m < 1 || pos0 < 0 || (long long)pos0 + m > 0x7FFFFFFFLL) return A2SF_ESHAPE;
+  if (m >= cache->capacity) return A2SF_ECAPACITY;   // a chunk needs room beside at least one slot
+  if ((long long)cache->G * m > 0x7FFFFFFFLL) return A2SF_ESHAPE;
+  const WsLayout w = ws_layout(cache->G, m, 0, cache->d, budget);
+  if (!workspace || misaligned(workspace) || workspace_bytes < w.total) return A2SF_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  clear_stale_error();
+  char* ws = (char*)workspace;
+  float* lse2 = (float*)(ws + w.lse2);
+  int32_t* len_old = (int32_t*)(ws + w.s_full);   // G ints fit where G * m floats would go
+  int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
+  int32_t* n_keep = (int32_t*)(ws + w.n_keep);
+  const int G = cache->G, d = cache->d, C = cache->capacity;
+  const AttnRect rc{m, C, len_old};
+  const float decay = alpha > 0.f ? powf(alpha, (float)m) : 0.f;   // 0^m = 0 for m >= 1
+
+  launch_chunk_append(k, v, m, pos0, *cache, len_old, st);
+  if (cache->dtype == A2SF_F32) {
+    launch_attn_f32((const float*)q, (const float*)cache->k, (const float*)cache->v, G, rc, d,
+                    (float*)o, lse2, st);
+    launch_colscores_f32((const float*)q, (const float*)cache->k, lse2, G, rc, C, d, alpha, nullptr,
+                         cache->scores, C, true, decay, st);
+  } else {
+    launch_attn_bf16(q, cache->k, cache->v, G, rc, d, o, lse2, st);
+    launch_colscores_bf16(q, cache->k, lse2, G, rc, C, d, alpha, cache->scores, C, true, decay, st);
+  }
+  launch_select(cache->scores, cache->pos, cache->len, G, C, C, budget.select, budget.recent,
+                keep_idx, n_keep, st);
+  launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
+  return launch_status();
 }
 
 a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void* v, int32_t n,
@@ -186,8 +237,8 @@ a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void
                                         float* scores_full, void* workspace,
                                         size_t workspace_bytes, void* hip_stream) {
   if (!alpha_heads || ((uintptr_t)alpha_heads & 3u)) return A2SF_EINVAL;
-  return prefill_impl(q, k, v, n, alpha_max, alpha_heads, budget, cache, o, scores_full, workspace,
-                      workspace_bytes, hip_stream);
+  return prefill_impl(q, k, v, n, alpha_max, alpha_heads, 0.0f, budget, cache, o, scores_full,
+                      workspace, workspace_bytes, hip_stream);
 }
 
 a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new, int32_t t_pos,

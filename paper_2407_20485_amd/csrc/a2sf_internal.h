@@ -34,6 +34,17 @@ void launch_decode(const void* q, const void* k_new, const void* v_new, int t_po
                    int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
                    hipStream_t st);
 
+// Generation step of G K/V heads with `group` (2, 4 or 8) query heads each: q, o are
+// [G, group, d]; group * capacity floats of LDS per workgroup.
+void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int t_pos,
+                       const a2sf_cache& c, int group, float alpha, int select, int recent,
+                       bool evict_here, void* o, hipStream_t st);
+
+// chunk.hip: the chunk's K/V rows go behind each head's cached tokens (len grows by m, the old
+// lengths are left in len_old, -1 where the chunk does not fit)
+void launch_chunk_append(const void* k, const void* v, int m, int pos0, const a2sf_cache& c,
+                         int32_t* len_old, hipStream_t st);
+
 // similarity.hip: cosine between the policy's attention row (cache positions + the new token)
 // and the Ideal row over the first L rows of k_all, per head.
 void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int L,
@@ -41,6 +52,20 @@ void launch_ideal_similarity(const void* q, const void* k_all, int n_stride, int
 
 void launch_similarity_mean(const float* cos, long long begin, long long end, float* out,
                             hipStream_t st);
+
+// Geometry of one attention call: m query rows per head against keys that lie kv_stride rows
+// apart from head to head; row i sees keys 0 .. off + i.  The prompt phase is the square case
+// (off = 0, kv_stride = m); a chunk of a prompt runs against the head's cache, off = the tokens
+// cached before the chunk (off_heads[g] < 0 marks a head to be skipped).
+// kv_group > 1: grouped-query heads.  The attention kernels then run over G * kv_group query
+// heads, query head g reading the K/V rows of head g / kv_group; the column-score kernels run
+// over the G K/V heads and sum the scores of each head's kv_group query heads.
+struct AttnRect {
+  int m;
+  int kv_stride;
+  const int32_t* off_heads;  // [G] device, or null: 0 for every head
+  int kv_group = 1;
+};
 
 // prefill_f32.hip / prefill_bf16.hip
 // lse2[g][i] = log2(sum_j exp(s_ij)) of the masked row i (s already scaled by 1/sqrt(d)).
@@ -50,10 +75,27 @@ void launch_prefill_f32(const float* q, const float* k, const float* v, int G, i
 // upper bound of the per-head factors.
 void launch_scores_f32(const float* q, const float* k, const float* lse2, int G, int n, int d,
                        float alpha, const float* alpha_heads, float* scores, hipStream_t st);
+// The general (rectangular) forms, used for chunks of a prompt.  keys_per_head: upper bound of
+// off + m over the heads (the grid is sized by it).  accumulate: the new column sums are added
+// to decay * scores[] (the cached tokens' older scores) instead of replacing it.
+void launch_attn_f32(const float* q, const float* k, const float* v, int G, const AttnRect& rc,
+                     int d, float* o, float* lse2, hipStream_t st);
+void launch_colscores_f32(const float* q, const float* k, const float* lse2, int G,
+                          const AttnRect& rc, int keys_per_head, int d, float alpha,
+                          const float* alpha_heads, float* scores, int s_stride, bool accumulate,
+                          float decay, hipStream_t st);
+void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const AttnRect& rc, int d,
+                      void* o, float* lse2, hipStream_t st);
+void launch_colscores_bf16(const void* q, const void* k, const float* lse2, int G,
+                           const AttnRect& rc, int keys_per_head, int d, float alpha, float* scores,
+                           int s_stride, bool accumulate, float decay, hipStream_t st);
 void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
                          void* o, float* lse2, hipStream_t st);
+// tol > 0 (d = 128 only): rows whose whole remaining contribution is provably below tol * S_j
+// are skipped (see RowWindow in prefill_bf16.hip); tol = 0 computes every row of nonzero weight.
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
-                        float alpha, const float* alpha_heads, float* scores, hipStream_t st);
+                        float alpha, const float* alpha_heads, float tol, float* scores,
+                        hipStream_t st);
 
 // Rows i < first_row contribute exactly 0 to every fp32 score (their weight alpha^(n-1-i)
 // is below the smallest fp32 subnormal while P <= 1), so the score kernels skip them.

@@ -350,6 +350,131 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
                          recent, evict_here != 0, sm);
 }
 
+// ---- grouped-query heads: one workgroup per K/V head, R query heads ---------------------
+// The K and V rows of the head are streamed once and serve all R queries (R logits per row in
+// the K sweep, R output accumulators in the V sweep); every query head has its own softmax.
+// The score update adds the SUM of the R probability rows (a token is kept or evicted for the
+// whole group, as Eq.1 of the paper sums over heads that share one pruning decision).
+template <typename T, int D, int R, bool STREAM>
+__global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int capacity, float alpha, int select,
+    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+  using Gm = RowGeom<T, D>;
+  constexpr int U = kBlockUnroll;
+  constexpr int ROWS_PER_ITER = kWaves * Gm::RPW * U;
+  extern __shared__ float a[];  // [R][capacity]: logits, then probabilities, of each query head
+  __shared__ StepSmem sm;
+  __shared__ float part[kWaves][128];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) {
+    for (int r = 0; r < R; ++r) flag_bad_head<T, D>(o + ((size_t)g * R + r) * D, tid, kThreads);
+    return;
+  }
+  const int L = n_old + 1;
+  T* Kg = K + (size_t)g * capacity * D;
+  T* Vg = V + (size_t)g * capacity * D;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+
+  float qv[R][Gm::EPL];
+#pragma unroll
+  for (int r = 0; r < R; ++r) load_query<T, D>(q + ((size_t)g * R + r) * D, scale_log2e, qv[r]);
+
+  // ---- K sweep: R logits per row
+  for (int base = 0; base < L; base += ROWS_PER_ITER) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      const T* p = (row == n_old) ? knew : Kg + (size_t)(row < L ? row : 0) * D;
+      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[r][e], f[e], dot);
+        dot = group_sum<Gm::LPR>(dot);
+        if (sub == 0 && row < L) a[r * capacity + row] = dot;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- R softmaxes
+#pragma unroll 1
+  for (int r = 0; r < R; ++r) {
+    float* ar = a + r * capacity;
+    float mx = -INFINITY;
+    for (int j = tid; j < L; j += kThreads) mx = fmaxf(mx, ar[j]);
+    mx = block_max(mx, sm.redf);
+    float sum = 0.f;
+    for (int j = tid; j < L; j += kThreads) {
+      const float p = exp2f(ar[j] - mx);
+      ar[j] = p;
+      sum += p;
+    }
+    sum = block_sum(sum, sm.redf);
+    const float inv = 1.0f / sum;
+    for (int j = tid; j < L; j += kThreads) ar[j] *= inv;
+  }
+  __syncthreads();
+
+  // ---- V sweep: R output rows
+  float acc[R][Gm::EPL];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = 0.f;
+  for (int base = 0; base < L; base += ROWS_PER_ITER) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      const T* p = (row == n_old) ? vnew : Vg + (size_t)(row < L ? row : 0) * D;
+      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float wr = row < L ? a[r * capacity + row] : 0.f;
+#pragma unroll
+        for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = fmaf(wr, f[e], acc[r][e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    v_fold_row_groups<T, D>(acc[r]);
+    reduce_output<T, D>(acc[r], part);
+    if (tid < D) Elem<T>::store(o + ((size_t)g * R + r) * D + tid, part[0][tid]);
+  }
+
+  // ---- S <- alpha*S + sum of the R probability rows, eviction as for a single head
+  update_and_evict<T, D>(
+      [&](int j) {
+        float p = 0.f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) p += a[r * capacity + j];
+        return p;
+      },
+      a, n_old, Kg, Vg, S + (size_t)g * capacity, P + (size_t)g * capacity, len + g, knew, vnew, t_pos,
+      alpha, select, recent, evict_here != 0, sm);
+}
+
 // ---- one wave per head ----------------------------------------------------------------
 // For many heads with short caches (capacity <= 64*NJ).  No workgroup barrier anywhere: a
 // wave streams its head's K rows, keeps logits / probabilities in its own LDS strip, the
@@ -639,7 +764,43 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                      zbuf, ml, po, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o);
 }
 
+template <typename T, int D>
+void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t_pos,
+                      const a2sf_cache& c, int group, float alpha, int select, int recent,
+                      bool evict_here, void* o, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  const size_t lds = (size_t)group * c.capacity * sizeof(float);
+  const bool stream = 4.0 * c.G * c.capacity * D > 512e6;   // as in plan_decode
+#define A2SF_GQA_(R, STREAM)                                                                      \
+  hipLaunchKernelGGL((decode_gqa_kernel<T, D, R, STREAM>), dim3(c.G), dim3(kThreads), lds, st,    \
+                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,      \
+                     c.scores, c.pos, c.len, c.capacity, alpha, select, recent, (int)evict_here,  \
+                     (T*)o, scale_log2e)
+#define A2SF_GQA(R)              \
+  do {                           \
+    if (stream) A2SF_GQA_(R, true); \
+    else A2SF_GQA_(R, false);    \
+  } while (0)
+  if (group == 2) A2SF_GQA(2);
+  else if (group == 4) A2SF_GQA(4);
+  else A2SF_GQA(8);
+#undef A2SF_GQA
+#undef A2SF_GQA_
+}
+
 }  // namespace
+
+void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int t_pos,
+                       const a2sf_cache& c, int group, float alpha, int select, int recent,
+                       bool evict_here, void* o, hipStream_t st) {
+  if (c.dtype == A2SF_F32) {
+    if (c.d == 64) launch_gqa_typed<float, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+    else launch_gqa_typed<float, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+  } else {
+    if (c.d == 64) launch_gqa_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+    else launch_gqa_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+  }
+}
 
 DecodePlan plan_decode(int G, int capacity, int d) {
   DecodePlan p;

@@ -125,10 +125,12 @@ __device__ __forceinline__ long long xcd_contiguous_id(long long total) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Geometry as in AttnRect: n = rc.m query rows per head; row i sees keys 0 .. off + i of the nk =
+// off + n keys of its head (the prompt phase: off = 0, the keys are the rows' own).
 template <int D, int NB, bool WITH_O>
 __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, AttnRect rc, int G, int nqb, float scale_log2e) {
   constexpr int BM = kWaves * 32 * NB;
   constexpr int CPR = D / 8;
   constexpr int KK = D / 16;   // k-steps of the first product
@@ -144,10 +146,20 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
-  const bf16_t* Qg = Q + (size_t)g * n * D;
-  const bf16_t* Kg = K + (size_t)g * n * D;
-  const bf16_t* Vg = V + (size_t)g * n * D;
+  const int n = rc.m;
+  const int gk = g / rc.kv_group;  // the K/V head this query head reads
+  const int off = rc.off_heads ? rc.off_heads[gk] : 0;
   const int row0 = qb * BM;
+  if (off < 0) {  // a head the caller's precondition excludes: its rows are flagged with NaN
+    if (WITH_O)
+      for (int e = tid; e < min(BM, n - row0) * D; e += kThreads)
+        O[((size_t)g * n + row0) * D + e] = (bf16_t)0x7FC0;
+    return;
+  }
+  const int nk = off + n;  // keys of this head
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)gk * rc.kv_stride * D;
+  const bf16_t* Vg = V + (size_t)gk * rc.kv_stride * D;
   const int wrow0 = row0 + wave * 32 * NB;  // first query row of this wave
 
   // Q fragments (B operand): lane (query l32, half h) holds Q[query][16kk + 8h .. +7]
@@ -172,18 +184,18 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
       for (int i = 0; i < 16; ++i) oacc[nb][db][i] = 0.f;
   }
 
-  const int last_row = min(n, row0 + BM) - 1;
-  const int ntiles = last_row / kTile + 1;
+  const int last_key = off + min(n, row0 + BM) - 1;  // newest key the block's rows see
+  const int ntiles = last_key / kTile + 1;
   Stage<D> stg;
-  stg.template load<WITH_O>(Kg, Vg, 0, n);
+  stg.template load<WITH_O>(Kg, Vg, 0, nk);
   stg.template store<WITH_O>(ks[0], vt[0]);
   __syncthreads();
 
   for (int t = 0; t < ntiles; ++t) {
     const int buf = t & 1;
-    if (t + 1 < ntiles) stg.template load<WITH_O>(Kg, Vg, (t + 1) * kTile, n);
+    if (t + 1 < ntiles) stg.template load<WITH_O>(Kg, Vg, (t + 1) * kTile, nk);
     const int key0 = t * kTile;
-    if (key0 <= wrow0 + 32 * NB - 1) {  // some key of the tile is visible to this wave
+    if (key0 <= off + wrow0 + 32 * NB - 1) {  // some key of the tile is visible to this wave
       // ---- S^T = K Q^T
       f32x16 sacc[NB][2];
 #pragma unroll
@@ -212,11 +224,11 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
           __builtin_amdgcn_sched_group_barrier(0x008, NB, 0); // then this step's matrix ops
         }
       }
-      const bool diag = key0 + kTile - 1 > wrow0;  // tile reaches past the wave's first row
+      const bool diag = key0 + kTile - 1 > off + wrow0;  // tile reaches past the wave's first row
       uint4 pf[NB][2][2];
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const int qrow = wrow0 + nb * 32 + l32;
+        const int qrow = off + wrow0 + nb * 32 + l32;   // newest key this lane's row sees
         if (diag) {
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
@@ -732,11 +744,14 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
+// Geometry as in AttnRect (n = rc.m rows, keys 0 .. off + n - 1, row i sees keys <= off + i).
+// accumulate: the column sums are added to decay * S[] (a chunk: the cached tokens' older scores
+// decayed by alpha^m) instead of replacing it.
 template <int D>
 __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
-    float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
-    const float* __restrict__ alpha_heads, float scale_log2e) {
+    float* __restrict__ S, AttnRect rc, int s_stride, bool accumulate, float decay, int G, int ncb,
+    int first_row, float log2_alpha, const float* __restrict__ alpha_heads, float scale_log2e) {
   constexpr int BC = kWaves * 32;  // key columns per workgroup
   constexpr int CPR = D / 8;
   constexpr int KK = D / 16;
@@ -747,21 +762,23 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   if (vid >= total) return;
   const int g = (int)(vid / ncb);
   const int cb = (int)(vid % ncb);  // column block 0 has the most rows: first
+  const int n = rc.m;
+  const int off = rc.off_heads ? rc.off_heads[g] : 0;
+  const int nk = off + n;  // keys of this head
+  const int c0 = cb * BC;
+  if (off < 0 || c0 >= nk) return;
   head_window(alpha_heads, g, n, first_row, log2_alpha);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, h = lane >> 5;
-  const bf16_t* Qg = Q + (size_t)g * n * D;
-  const bf16_t* Kg = K + (size_t)g * n * D;
-  const float* lse = LSE2 + (size_t)g * n;
-  const int c0 = cb * BC;
+  const bf16_t* Kg = K + (size_t)g * rc.kv_stride * D;
   const int wc0 = c0 + wave * 32;  // first key of this wave
 
   // K fragments (A operand): lane (key l32, half h) holds K[key][16kk + 8h .. +7]
   uint4 kf[KK];
   {
     int r = wc0 + l32;
-    r = r < n ? r : n - 1;
+    r = r < nk ? r : nk - 1;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) kf[kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
   }
@@ -769,50 +786,55 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 
-  const int t_begin = max(c0, first_row) / kTile;
+  const int t_begin = max(max(c0 - off, first_row), 0) / kTile;   // first row tile that sees a key of the block
   const int t_end = (n + kTile - 1) / kTile;
-  Stage<D> stg;
-  stg.template load<false>(Qg, nullptr, t_begin * kTile, n);
-  stg.template store<false>(qs[0], nullptr);
-  __syncthreads();
+  for (int hq = 0; hq < rc.kv_group; ++hq) {  // the query heads that share this K/V head
+    const bf16_t* Qg = Q + ((size_t)g * rc.kv_group + hq) * n * D;
+    const float* lse = LSE2 + ((size_t)g * rc.kv_group + hq) * n;
+    Stage<D> stg;
+    stg.template load<false>(Qg, nullptr, t_begin * kTile, n);
+    __syncthreads();  // the previous query head's last tile has been read by every wave
+    stg.template store<false>(qs[0], nullptr);
+    __syncthreads();
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const int buf = (t - t_begin) & 1;
-    const int row0 = t * kTile;
-    // the rows' log-sum-exp values are requested before the matrix ops that they follow (and
-    // before the next tile's loads, so that waiting for them does not wait for those)
-    float lse_r[2];
+    for (int t = t_begin; t < t_end; ++t) {
+      const int buf = (t - t_begin) & 1;
+      const int row0 = t * kTile;
+      // the rows' log-sum-exp values are requested before the matrix ops that they follow (and
+      // before the next tile's loads, so that waiting for them does not wait for those)
+      float lse_r[2];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) lse_r[qb] = lse[min(row0 + qb * 32 + l32, n - 1)];
-    if (t + 1 < t_end) stg.template load<false>(Qg, nullptr, (t + 1) * kTile, n);
-    if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
+      for (int qb = 0; qb < 2; ++qb) lse_r[qb] = lse[min(row0 + qb * 32 + l32, n - 1)];
+      if (t + 1 < t_end) stg.template load<false>(Qg, nullptr, (t + 1) * kTile, n);
+      if (off + row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        f32x16 sacc;
+        for (int qb = 0; qb < 2; ++qb) {
+          f32x16 sacc;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+          for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const uint4 b = qs[buf][row_tile_unit<D>(qb * 32 + l32, 2 * kk + h)];
-          sacc = mfma_bf16(kf[kk], b, sacc);
-        }
-        const int r = row0 + qb * 32 + l32;
-        // exponent offset of row r: -lse_r + (n-1-r) log2(alpha); rows past the end, and rows
-        // whose weight is exactly 0 in fp32 (before first_row), add nothing
-        const float bias = (r < n && r >= first_row)
-                               ? lse_r[qb] - (float)(n - 1 - r) * log2_alpha : INFINITY;
-        const bool diag = row0 + qb * 32 < wc0 + 31;  // block reaches above the diagonal
+          for (int kk = 0; kk < KK; ++kk) {
+            const uint4 b = qs[buf][row_tile_unit<D>(qb * 32 + l32, 2 * kk + h)];
+            sacc = mfma_bf16(kf[kk], b, sacc);
+          }
+          const int r = row0 + qb * 32 + l32;
+          // exponent offset of row r: -lse_r + (n-1-r) log2(alpha); rows past the end, and rows
+          // whose weight is exactly 0 in fp32 (before first_row), add nothing
+          const float bias = (r < n && r >= first_row)
+                                 ? lse_r[qb] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+          const bool diag = off + row0 + qb * 32 < wc0 + 31;  // block reaches above the diagonal
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
-          float p = fast_exp2(fmaf(sacc[i], scale_log2e, -bias));
-          if (diag && key > r) p = 0.f;
-          acc[i] += p;
+          for (int i = 0; i < 16; ++i) {
+            const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            float p = fast_exp2(fmaf(sacc[i], scale_log2e, -bias));
+            if (diag && key > off + r) p = 0.f;
+            acc[i] += p;
+          }
         }
       }
+      if (t + 1 < t_end) stg.template store<false>(qs[buf ^ 1], nullptr);
+      __syncthreads();
     }
-    if (t + 1 < t_end) stg.template store<false>(qs[buf ^ 1], nullptr);
-    __syncthreads();
   }
   // sum over the 32 queries (lanes with the same half)
 #pragma unroll
@@ -824,9 +846,33 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = wc0 + 8 * (i >> 2) + 4 * h + (i & 3);
-      if (key < n) S[(size_t)g * n + key] = acc[i];
+      if (key < nk) {
+        float* out = S + (size_t)g * s_stride + key;
+        *out = accumulate ? fmaf(decay, *out, acc[i]) : acc[i];
+      }
     }
   }
+}
+
+// attn_fwd_bf16_kernel for any head size and geometry
+template <int D>
+void launch_fwd_rect(const void* q, const void* k, const void* v, int G, const AttnRect& rc, void* o,
+                     float* lse2, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  constexpr int NB = kFwdNB;
+  constexpr int BM = kWaves * 32 * NB;
+  const int nqb = (rc.m + BM - 1) / BM;
+  const int GQ = G * rc.kv_group;  // query heads
+  const long long total = (long long)GQ * nqb;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+  if (o)
+    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, rc, GQ,
+                       nqb, scale_log2e);
+  else
+    hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, false>), dim3(grid), dim3(kThreads), 0, st,
+                       (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr, lse2,
+                       rc, GQ, nqb, scale_log2e);
 }
 
 template <int D>
@@ -873,19 +919,7 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
                          lse2, n, G, nqb, scale_log2e);
   } else {
-    constexpr int NB = kFwdNB;
-    constexpr int BM = kWaves * 32 * NB;
-    const int nqb = (n + BM - 1) / BM;
-    const long long total = (long long)G * nqb;
-    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-    if (o)
-      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, true>), dim3(grid), dim3(kThreads), 0, st,
-                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
-                         G, nqb, scale_log2e);
-    else
-      hipLaunchKernelGGL((attn_fwd_bf16_kernel<D, NB, false>), dim3(grid), dim3(kThreads), 0, st,
-                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
-                         lse2, n, G, nqb, scale_log2e);
+    launch_fwd_rect<D>(q, k, v, G, AttnRect{n, n, nullptr}, o, lse2, st);
   }
 }
 
@@ -900,10 +934,34 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
 constexpr int kTailTiles = 4;
 constexpr int kTailKB = 2;  // 32-key blocks per wave and step
 
+// Row window for a relative tolerance on the scores (Section 3.3: the forgetting factor makes
+// old rows' contributions go to 0).  All rows before n - W together add at most
+// alpha^W / (1 - alpha) to any S_j (probabilities are <= 1), while S_j >= P[n-1, j]; so for a
+// group of keys whose smallest P[n-1, j] is p_min every S_j of the group is exact to a
+// relative `tol` once  alpha^W <= tol (1 - alpha) p_min.  p_min is read off the newest row,
+// which a wave processes first; zmin is log2 of the probabilities a lane saw there.
+struct RowWindow {
+  bool on;
+  float tl2, inv_l2a;
+  __device__ RowWindow(float tol, float log2_alpha) {
+    on = tol > 0.f && log2_alpha < 0.f;
+    tl2 = on ? log2f(tol * (1.f - exp2f(log2_alpha))) : 0.f;
+    inv_l2a = on ? 1.f / log2_alpha : 0.f;
+  }
+  // first row a wave has to process; zmin as held by the lanes `lane_last` and `lane_last + 32`
+  // (the two halves of the newest row)
+  __device__ __forceinline__ int first_row(int n, float zmin, int lane_last) const {
+    const float z0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zmin), lane_last));
+    const float z1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zmin), lane_last + 32));
+    const float need = (tl2 + fminf(z0, z1)) * inv_l2a;   // rows needed (both factors negative)
+    return need >= (float)n ? 0 : n - ((int)need + 2);
+  }
+};
+
 __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
     float* __restrict__ S, int n, int first_row, float log2_alpha,
-    const float* __restrict__ alpha_heads, float scale_log2e) {
+    const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
   __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
   lds_char* const qs = (lds_char*)smem;
@@ -945,6 +1003,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
       int r = c0 + (wave * kTailKB + b) * 32 + l32;
       r = r < n ? r : n - 1;
 #pragma unroll
+      // (plain loads: a lane takes 32 bytes of its key's row per instruction, so every 128-byte
+      // line is shared by four instructions and has to stay in the cache between them)
       for (int kk = 0; kk < KK; ++kk) kf[b][kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
     }
   };
@@ -953,18 +1013,24 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
+  const RowWindow win(tol, log2_alpha);
+  const int rb_last = (n - 1 - r_lo) >> 5;   // the row block that holds the newest row
+  const int lane_last = (n - 1 - r_lo) & 31;
   constexpr int STEP = BC * kTailKB;  // keys per workgroup step
   for (int c0 = 0; c0 < n; c0 += STEP) {
     const int wc0 = c0 + wave * kTailKB * 32;  // first key of this wave in this step
+    int lim = max(wc0, first_row);             // rows before `lim` add nothing to this wave's keys
+    bool pending = c0 + STEP < n;              // the next step's keys still have to be fetched
     float acc[kTailKB][16];
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+    // newest rows first: the block of the last row tells how far back this wave has to go
 #pragma unroll
-    for (int rb = 0; rb < 2 * kTailTiles; ++rb) {
+    for (int rb = 2 * kTailTiles - 1; rb >= 0; --rb) {
       const int rr0 = r_lo + rb * 32;
-      if (rb < 2 * ntile && rr0 + 31 >= wc0 && rr0 + 31 >= first_row) {  // wave-uniform
+      if (rb <= rb_last && rr0 + 31 >= lim) {  // wave-uniform
         f32x16 sacc[kTailKB];
 #pragma unroll
         for (int b = 0; b < kTailKB; ++b)
@@ -977,8 +1043,20 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
 #pragma unroll
           for (int b = 0; b < kTailKB; ++b) sacc[b] = mfma_bf16(kf[b][kk], qf, sacc[b]);
         }
-        if (rb == 2 * ntile - 1 && c0 + STEP < n) load_keys(c0 + STEP, kf);  // last use of kf is behind us
+        // last use of kf is behind us once no older row block follows
+        if (pending && rb != rb_last && (rb == 0 || rr0 - 1 < lim)) {
+          load_keys(c0 + STEP, kf);
+          pending = false;
+        }
         const int r = rr0 + l32;
+        if (win.on && rb == rb_last) {   // log2 of the newest row's smallest probability, per lane
+          float zmin = INFINITY;
+#pragma unroll
+          for (int b = 0; b < kTailKB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) zmin = fminf(zmin, fmaf(sacc[b][i], scale_log2e, -bias[rb]));
+          lim = max(lim, win.first_row(n, zmin, lane_last));
+        }
 #pragma unroll
         for (int b = 0; b < kTailKB; ++b) {
           const int bk0 = wc0 + b * 32;
@@ -994,10 +1072,9 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
             for (int i = 0; i < 16; ++i) acc[b][i] += fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias[rb]));
           }
         }
-      } else if (rb == 2 * ntile - 1 && c0 + STEP < n) {
-        load_keys(c0 + STEP, kf);
       }
     }
+    if (pending) load_keys(c0 + STEP, kf);
     // sum over the 32 rows held by the lanes of one half
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b) {
@@ -1027,10 +1104,11 @@ constexpr int kStreamKB = 2;  // 32-key blocks per wave
 __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
     float* __restrict__ S, int n, int G, int ncb, int first_row, float log2_alpha,
-    const float* __restrict__ alpha_heads, float scale_log2e) {
+    const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32 * kStreamKB;
   // Q tiles, then per wave and stage the 64 log-sum-exp values of the tile's rows
   __shared__ __attribute__((aligned(1024))) char smem[kStreamStages * kTileBytes + kWaves * kStreamStages * 256];
+  __shared__ int wave_lim[kWaves];
   lds_char* const qs = (lds_char*)smem;
 
   const long long total = (long long)G * ncb;
@@ -1048,24 +1126,27 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
   const int c0 = cb * BC;
   const int wc0 = c0 + wave * 32 * kStreamKB;  // first key of this wave
 
-  const int t_begin = max(c0, first_row) / kTile;
-  const int t_end = (n + kTile - 1) / kTile;
+  // Tiles are walked from the newest rows down: with a tolerance the newest row tells how far
+  // back the workgroup has to go (RowWindow), and without one the order does not matter.
+  const int t_last = (n + kTile - 1) / kTile - 1;
+  int t_first = max(c0, first_row) / kTile;      // oldest tile any wave of the workgroup needs
   lds_char* const lse_s = qs + kStreamStages * kTileBytes +
                           __builtin_amdgcn_readfirstlane(wave) * (kStreamStages * 256);
   // Q tile t into its ring stage (every wave a quarter of the rows) and the rows' log-sum-exp
-  // values into the wave's own strip of that stage: five loads per wave
+  // values into the wave's own strip of that stage: five loads per wave, always issued (a tile
+  // below the window is clamped onto tile t_first and never used), so that the wait counts in
+  // the loop are the same for every tile
   auto fetch = [&](int t) {
-    if (t < t_end) {
-      const int stage = (t - t_begin) % kStreamStages;
-      dma_tile<false>(Qg, t * kTile, n, qs + stage * kTileBytes);
-      __builtin_amdgcn_global_load_lds((const void*)(lse + min(t * kTile + lane, n - 1)),
-                                       (__attribute__((address_space(3))) void*)(lse_s + stage * 256),
-                                       4, 0, 0);
-    }
+    const int stage = (t_last - t) % kStreamStages;
+    const int tt = max(t, 0);
+    dma_tile<false>(Qg, tt * kTile, n, qs + stage * kTileBytes);
+    __builtin_amdgcn_global_load_lds((const void*)(lse + min(tt * kTile + lane, n - 1)),
+                                     (__attribute__((address_space(3))) void*)(lse_s + stage * 256),
+                                     4, 0, 0);
   };
-  fetch(t_begin);
-  fetch(t_begin + 1);
-  fetch(t_begin + 2);
+  fetch(t_last);
+  fetch(t_last - 1);
+  fetch(t_last - 2);
 
   // K fragments (A operand): lane (key l32, half h) holds K[key][16kk + 8h .. +7]
   uint4 kf[kStreamKB][KK];
@@ -1085,23 +1166,23 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 
-  for (int t = t_begin; t < t_end; ++t) {
-    // tile t has landed: of this wave's fetches only those of tiles t+1 and t+2 (five loads
-    // each, fewer at the end) may still be under way
-    const int ahead = min(t_end - 1 - t, 2);
-    if (ahead == 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 10);       // vmcnt(10)
-    else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 5);   // vmcnt(5)
-    else __builtin_amdgcn_s_waitcnt(0x0f70);                       // vmcnt(0)
+  const RowWindow win(tol, log2_alpha);
+  int lim = max(wc0, first_row);   // rows before `lim` add nothing to this wave's keys
+  for (int t = t_last; t >= t_first; --t) {
+    // tile t has landed: of this wave's fetches only those of tiles t-1 and t-2 (five loads
+    // each) may still be under way
+    __builtin_amdgcn_s_waitcnt(0x0f70 | 10);  // vmcnt(10)
     __syncthreads();
-    fetch(t + 3);  // into the stage of tile t-1, which every wave has left
+    fetch(t - 3);  // into the stage of tile t+1, which every wave has left
     const int row0 = t * kTile;
-    if (row0 + kTile - 1 >= wc0) {  // some row of the tile sees a key of this wave
-      const int stage = (t - t_begin) % kStreamStages;
+    if (row0 + kTile - 1 >= lim) {  // some row of the tile counts for a key of this wave
+      const int stage = (t_last - t) % kStreamStages;
       const lds_char* qt = qs + stage * kTileBytes;
       const __attribute__((address_space(3))) float* lse_t =
           (const __attribute__((address_space(3))) float*)(lse_s + stage * 256);
+      float zmin[2] = {INFINITY, INFINITY};
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 1; qb >= 0; --qb) {
         f32x16 sacc[kStreamKB];
 #pragma unroll
         for (int b = 0; b < kStreamKB; ++b)
@@ -1118,6 +1199,14 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
         // whose weight is exactly 0 in fp32 (before first_row), add nothing
         const float bias = (r < n && r >= first_row)
                                ? lse_t[qb * 32 + l32] - (float)(n - 1 - r) * log2_alpha : INFINITY;
+        if (win.on && t == t_last) {   // log2 of the newest row's smallest probability, per lane
+          float zm = INFINITY;
+#pragma unroll
+          for (int b = 0; b < kStreamKB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) zm = fminf(zm, fmaf(sacc[b][i], scale_log2e, -bias));
+          zmin[qb] = zm;
+        }
 #pragma unroll
         for (int b = 0; b < kStreamKB; ++b) {
           const int bk0 = wc0 + b * 32;
@@ -1134,8 +1223,19 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
           }
         }
       }
+      if (win.on && t == t_last) {
+        const int rl = n - 1 - row0;   // the newest row inside this tile
+        lim = max(lim, win.first_row(n, rl >= 32 ? zmin[1] : zmin[0], rl & 31));
+      }
+    }
+    if (win.on && t == t_last) {   // the workgroup stops at the oldest tile one of its waves needs
+      if (lane == 0) wave_lim[wave] = lim;
+      __syncthreads();
+      const int wl = min(min(wave_lim[0], wave_lim[1]), min(wave_lim[2], wave_lim[3]));
+      t_first = max(t_first, wl / kTile);
     }
   }
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // tiles fetched ahead of the last one used: let them land
   // sum over the 32 rows held by the lanes of one half
 #pragma unroll
   for (int b = 0; b < kStreamKB; ++b) {
@@ -1151,16 +1251,32 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
   }
 }
 
+// col_scores_bf16_kernel for any head size and geometry
+template <int D>
+void launch_cols_rect(const void* q, const void* k, const float* lse2, int G, const AttnRect& rc,
+                      int keys_per_head, float alpha, const float* alpha_heads, float* scores,
+                      int s_stride, bool accumulate, float decay, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  float l2a;
+  const int first = first_contributing_row(rc.m, alpha, &l2a);
+  const int ncb = (keys_per_head + kWaves * 32 - 1) / (kWaves * 32);
+  const long long total = (long long)G * ncb;
+  const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+  hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st, (const bf16_t*)q,
+                     (const bf16_t*)k, lse2, scores, rc, s_stride, accumulate, decay, G, ncb, first, l2a,
+                     alpha_heads, scale_log2e);
+}
+
 template <int D>
 void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, float alpha,
-                 const float* alpha_heads, float* scores, hipStream_t st) {
+                 const float* alpha_heads, float tol, float* scores, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   float l2a;
   const int first = first_contributing_row(n, alpha, &l2a);
   if constexpr (D == 128) {
     if (n - (first / kTile) * kTile <= kTailTiles * kTile) {
       hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
-                         (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e);
+                         (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e, tol);
       return;
     }
     constexpr int BC = kWaves * 32 * kStreamKB;
@@ -1168,18 +1284,29 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
     const unsigned grid = (unsigned)((((long long)G * ncb + 7) / 8) * 8);
     hipLaunchKernelGGL(col_scores_stream128_kernel, dim3(grid), dim3(kThreads), 0, st,
                        (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
-                       alpha_heads, scale_log2e);
+                       alpha_heads, scale_log2e, tol);
   } else {
-    const int ncb = (n + kWaves * 32 - 1) / (kWaves * 32);
-    const long long total = (long long)G * ncb;
-    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-    hipLaunchKernelGGL((col_scores_bf16_kernel<D>), dim3(grid), dim3(kThreads), 0, st,
-                       (const bf16_t*)q, (const bf16_t*)k, lse2, scores, n, G, ncb, first, l2a,
-                       alpha_heads, scale_log2e);
+    launch_cols_rect<D>(q, k, lse2, G, AttnRect{n, n, nullptr}, n, alpha, alpha_heads, scores, n, false,
+                        0.f, st);
   }
 }
 
 }  // namespace
+
+void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const AttnRect& rc, int d,
+                      void* o, float* lse2, hipStream_t st) {
+  if (d == 64) launch_fwd_rect<64>(q, k, v, G, rc, o, lse2, st);
+  else launch_fwd_rect<128>(q, k, v, G, rc, o, lse2, st);
+}
+
+void launch_colscores_bf16(const void* q, const void* k, const float* lse2, int G,
+                           const AttnRect& rc, int keys_per_head, int d, float alpha, float* scores,
+                           int s_stride, bool accumulate, float decay, hipStream_t st) {
+  if (d == 64)
+    launch_cols_rect<64>(q, k, lse2, G, rc, keys_per_head, alpha, nullptr, scores, s_stride, accumulate, decay, st);
+  else
+    launch_cols_rect<128>(q, k, lse2, G, rc, keys_per_head, alpha, nullptr, scores, s_stride, accumulate, decay, st);
+}
 
 void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
                          void* o, float* lse2, hipStream_t st) {
@@ -1188,9 +1315,10 @@ void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int
 }
 
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
-                        float alpha, const float* alpha_heads, float* scores, hipStream_t st) {
-  if (d == 64) launch_cols<64>(q, k, lse2, G, n, alpha, alpha_heads, scores, st);
-  else launch_cols<128>(q, k, lse2, G, n, alpha, alpha_heads, scores, st);
+                        float alpha, const float* alpha_heads, float tol, float* scores,
+                        hipStream_t st) {
+  if (d == 64) launch_cols<64>(q, k, lse2, G, n, alpha, alpha_heads, tol, scores, st);
+  else launch_cols<128>(q, k, lse2, G, n, alpha, alpha_heads, tol, scores, st);
 }
 
 }  // namespace a2sf

@@ -4,6 +4,12 @@
 // with plain fp32 FMA arithmetic.  One workgroup per attention row, then one per column.
 // The probability matrix is recomputed, never stored.  The bf16 matrix-core path lives in
 // prefill_bf16.hip; this one exists for fp32 inputs, where exact fp32 products are wanted.
+//
+// Both kernels take the geometry of a2sf_internal.h's AttnRect: m query rows per head against
+// keys that lie kv_stride rows apart from head to head; row i sees keys 0 .. off + i, where
+// off (per head, or 0) is the number of older tokens in front of the rows' own.  The prompt
+// phase is the square case (off = 0, kv_stride = m); a chunk of a prompt runs against the
+// head's cache (off = tokens cached before the chunk).
 #include <math.h>
 
 #include "a2sf_dev.h"
@@ -29,21 +35,29 @@ __device__ __forceinline__ float dot_row(const float* __restrict__ a, const floa
 
 template <int D>
 __global__ __launch_bounds__(kThreads) void attn_rows_f32_kernel(
-    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v, int n,
-    float* __restrict__ o, float* __restrict__ lse2, float scale_log2e) {
+    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
+    AttnRect rc, float* __restrict__ o, float* __restrict__ lse2, float scale_log2e) {
   __shared__ float z[kChunk];
   __shared__ float part[kThreads / D][D];
   __shared__ float red[8];
+  const int n = rc.m;
   const int g = blockIdx.x / n, i = blockIdx.x % n, tid = threadIdx.x;
+  const int gk = g / rc.kv_group;  // the K/V head this query head reads
+  const int off = rc.off_heads ? rc.off_heads[gk] : 0;
+  if (off < 0) {  // a head the caller's precondition excludes: its rows are flagged
+    if (o && tid < D) o[((size_t)g * n + i) * D + tid] = __int_as_float(0x7FC00000);
+    return;
+  }
   const float* qi = q + ((size_t)g * n + i) * D;
-  const float* kg = k + (size_t)g * n * D;
-  const float* vg = v + (size_t)g * n * D;
+  const float* kg = k + (size_t)gk * rc.kv_stride * D;
+  const float* vg = v + (size_t)gk * rc.kv_stride * D;
   constexpr int PARTS = kThreads / D;
   const int c = tid % D, part_id = tid / D;
+  const int last = off + i;  // newest key this row sees
 
   float m = -INFINITY, l = 0.f, acc = 0.f;
-  for (int c0 = 0; c0 <= i; c0 += kChunk) {
-    const int c1 = min(i + 1, c0 + kChunk);
+  for (int c0 = 0; c0 <= last; c0 += kChunk) {
+    const int c1 = min(last + 1, c0 + kChunk);
     float mx = -INFINITY;
     for (int j = c0 + tid; j < c1; j += kThreads) {
       const float s = dot_row<D>(qi, kg + (size_t)j * D) * scale_log2e;
@@ -81,24 +95,35 @@ __global__ __launch_bounds__(kThreads) void attn_rows_f32_kernel(
   if (tid == 0) lse2[(size_t)g * n + i] = m + log2f(l);
 }
 
+// `accumulate`: the result is added to `decay` times what scores[] holds (a chunk: the cached
+// tokens' older scores, decayed by alpha^m); otherwise it replaces it.
 template <int D>
 __global__ __launch_bounds__(kThreads) void scores_f32_kernel(
-    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ lse2, int n,
-    int first_row, float log2_alpha, const float* __restrict__ alpha_heads,
-    float* __restrict__ scores, float scale_log2e) {
+    const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ lse2,
+    AttnRect rc, int keys_per_head, int first_row, float log2_alpha,
+    const float* __restrict__ alpha_heads, float* __restrict__ scores, int s_stride, bool accumulate,
+    float decay, float scale_log2e) {
   __shared__ float red[8];
-  const int g = blockIdx.x / n, j = blockIdx.x % n, tid = threadIdx.x;
+  const int n = rc.m;
+  const int g = blockIdx.x / keys_per_head, j = blockIdx.x % keys_per_head, tid = threadIdx.x;
+  const int off = rc.off_heads ? rc.off_heads[g] : 0;
+  if (off < 0 || j >= off + n) return;
   head_window(alpha_heads, g, n, first_row, log2_alpha);
-  const float* kj = k + ((size_t)g * n + j) * D;
-  const float* qg = q + (size_t)g * n * D;
-  const float* lg = lse2 + (size_t)g * n;
+  const float* kj = k + ((size_t)g * rc.kv_stride + j) * D;
   float sum = 0.f;
-  for (int i = max(j, first_row) + tid; i < n; i += kThreads) {
-    const float s = dot_row<D>(qg + (size_t)i * D, kj) * scale_log2e;
-    sum += exp2f(s - lg[i] + (float)(n - 1 - i) * log2_alpha);
+  for (int hq = 0; hq < rc.kv_group; ++hq) {  // the query heads that share this K/V head
+    const float* qg = q + ((size_t)g * rc.kv_group + hq) * n * D;
+    const float* lg = lse2 + ((size_t)g * rc.kv_group + hq) * n;
+    for (int i = max(max(j - off, first_row), 0) + tid; i < n; i += kThreads) {
+      const float s = dot_row<D>(qg + (size_t)i * D, kj) * scale_log2e;
+      sum += exp2f(s - lg[i] + (float)(n - 1 - i) * log2_alpha);
+    }
   }
   sum = block_sum(sum, red);
-  if (tid == 0) scores[(size_t)g * n + j] = sum;
+  if (tid == 0) {
+    float* out = scores + (size_t)g * s_stride + j;
+    *out = accumulate ? fmaf(decay, *out, sum) : sum;
+  }
 }
 
 }  // namespace
@@ -115,26 +140,41 @@ int first_contributing_row(int n, float alpha, float* log2_alpha) {
   return n - w < 0 ? 0 : n - w;
 }
 
+void launch_attn_f32(const float* q, const float* k, const float* v, int G, const AttnRect& rc,
+                     int d, float* o, float* lse2, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
+  dim3 grid((unsigned)G * (unsigned)rc.kv_group * (unsigned)rc.m);
+  if (d == 64)
+    hipLaunchKernelGGL(attn_rows_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, v, rc, o, lse2, scale_log2e);
+  else
+    hipLaunchKernelGGL(attn_rows_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, v, rc, o, lse2, scale_log2e);
+}
+
+void launch_colscores_f32(const float* q, const float* k, const float* lse2, int G,
+                          const AttnRect& rc, int keys_per_head, int d, float alpha,
+                          const float* alpha_heads, float* scores, int s_stride, bool accumulate,
+                          float decay, hipStream_t st) {
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
+  float l2a;
+  const int first = first_contributing_row(rc.m, alpha, &l2a);
+  dim3 grid((unsigned)G * (unsigned)keys_per_head);
+  if (d == 64)
+    hipLaunchKernelGGL(scores_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, lse2, rc, keys_per_head,
+                       first, l2a, alpha_heads, scores, s_stride, accumulate, decay, scale_log2e);
+  else
+    hipLaunchKernelGGL(scores_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, lse2, rc, keys_per_head,
+                       first, l2a, alpha_heads, scores, s_stride, accumulate, decay, scale_log2e);
+}
+
 void launch_prefill_f32(const float* q, const float* k, const float* v, int G, int n, int d,
                         float* o, float* lse2, hipStream_t st) {
-  const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
-  dim3 grid((unsigned)G * (unsigned)n);
-  if (d == 64)
-    hipLaunchKernelGGL(attn_rows_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, v, n, o, lse2, scale_log2e);
-  else
-    hipLaunchKernelGGL(attn_rows_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, v, n, o, lse2, scale_log2e);
+  launch_attn_f32(q, k, v, G, AttnRect{n, n, nullptr}, d, o, lse2, st);
 }
 
 void launch_scores_f32(const float* q, const float* k, const float* lse2, int G, int n, int d,
                        float alpha, const float* alpha_heads, float* scores, hipStream_t st) {
-  const float scale_log2e = 1.4426950408889634f / sqrtf((float)d);
-  float l2a;
-  const int first = first_contributing_row(n, alpha, &l2a);
-  dim3 grid((unsigned)G * (unsigned)n);
-  if (d == 64)
-    hipLaunchKernelGGL(scores_f32_kernel<64>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, alpha_heads, scores, scale_log2e);
-  else
-    hipLaunchKernelGGL(scores_f32_kernel<128>, grid, dim3(kThreads), 0, st, q, k, lse2, n, first, l2a, alpha_heads, scores, scale_log2e);
+  launch_colscores_f32(q, k, lse2, G, AttnRect{n, n, nullptr}, n, d, alpha, alpha_heads, scores, n,
+                       false, 0.f, st);
 }
 
 }  // namespace a2sf

@@ -68,7 +68,7 @@ def replay_head(job):
     """One head, every forgetting factor that was run on it.
 
     job: dict(w=Workload, g=head id, select, recent, threads,
-              runs={alpha: dict(o=[n,d] float32 | None, s_full=[n] float32,
+              runs={alpha: dict(o=[n,d] float32 | None, s_full=[n] float32, s_full_alt=[n] | None,
                                 pre=(pos, scores, (K, V) | None), fast=bool,
                                 steps=[(o[d], pos, scores, (K, V) | None), ...])})
     Returns dict(g, o_err, s_rel, swaps, failure | None).
@@ -103,11 +103,12 @@ def replay_head(job):
                 res["o_err"] = max(res["o_err"], err)
                 if err > O_TOL[w.dtype]:
                     raise Mismatch(f"{what}: prompt output max-abs {err:.3e}")
-            if run.get("s_full") is not None:
-                rel = rel_err(run["s_full"], S_full)
-                res["s_rel"] = max(res["s_rel"], rel)
-                if rel > SCORE_RTOL:
-                    raise Mismatch(f"{what}: prompt score rel error {rel:.3e}")
+            for key in ("s_full", "s_full_alt"):
+                if run.get(key) is not None:
+                    rel = rel_err(run[key], S_full)
+                    res["s_rel"] = max(res["s_rel"], rel)
+                    if rel > SCORE_RTOL:
+                        raise Mismatch(f"{what}: prompt score ({key}) rel error {rel:.3e}")
             pos_g, s_g, rows_g = run["pre"]
             keep, sw = orc._resolve_keep(S_full, np.arange(n), select, recent,
                                          [int(p) for p in pos_g], MARGIN)

@@ -61,14 +61,18 @@ class Problem:
         return a if self.w.dtype == "f32" else synth.bf16_bits_to_f32(a)
 
     # ---- GPU calls
-    def gpu_prefill(self, alpha, want_o=True, want_scores=True, select=None, recent=None):
-        """alpha: one factor, or a sequence of G per-head factors."""
+    def gpu_prefill(self, alpha, want_o=True, want_scores=True, select=None, recent=None, tol=None):
+        """alpha: one factor, or a sequence of G per-head factors.  tol: relative tolerance of the
+        scores (a2sf_prefill_windowed); None = a2sf_prefill."""
         w = self.w
         select = w.select if select is None else select
         recent = w.recent if recent is None else recent
         o = torch.empty_like(self.dev["q"]) if want_o else None
         s = torch.empty((self.G, w.n), dtype=torch.float32, device="cuda") if want_scores else None
-        if np.ndim(alpha) == 0:
+        if tol is not None:
+            a2sf.a2sf_prefill_windowed(self.dev["q"], self.dev["k"], self.dev["v"], w.n, float(alpha), tol,
+                                       select, recent, self.cache, o=o, scores_full=s, workspace=self.ws)
+        elif np.ndim(alpha) == 0:
             a2sf.a2sf_prefill(self.dev["q"], self.dev["k"], self.dev["v"], w.n, float(alpha), select,
                               recent, self.cache, o=o, scores_full=s, workspace=self.ws)
         else:
@@ -236,12 +240,20 @@ class Replay:
         kv = (c.k[idx].float().cpu().numpy(), c.v[idx].float().cpu().numpy()) if rows else None
         return lens, pos, sc, kv
 
-    def run_gpu(self, alpha, steps=None, mode=a2sf.A2SF_EVICT_FAST, row_steps=None, keep_o=True):
-        """One prompt phase + `steps` generation steps at forgetting factor `alpha`, recorded."""
+    def run_gpu(self, alpha, steps=None, mode=a2sf.A2SF_EVICT_FAST, row_steps=None, keep_o=True, tol=None,
+                also_exact_scores=False):
+        """One prompt phase + `steps` generation steps at forgetting factor `alpha`, recorded.
+        tol: the prompt phase runs as a2sf_prefill_windowed with that tolerance; with
+        also_exact_scores the scores of a plain a2sf_prefill are recorded beside it."""
         p, w = self.p, self.p.w
         T = w.T if steps is None else steps
         row_steps = {0, T // 2, T - 1} if row_steps is None else set(row_steps)
-        o, s = p.gpu_prefill(alpha, select=self.select, recent=self.recent)
+        s_alt = None
+        if also_exact_scores:
+            _, s_exact = p.gpu_prefill(alpha, want_o=False, select=self.select, recent=self.recent)
+            s_alt = s_exact[self.idx].cpu().numpy()
+            del s_exact
+        o, s = p.gpu_prefill(alpha, select=self.select, recent=self.recent, tol=tol)
         torch.cuda.synchronize()
         lens, pos, sc, kv = self._state(True)
         o_s = o[self.idx].float().cpu().numpy() if keep_o else None
@@ -250,6 +262,7 @@ class Replay:
             L = int(lens[j])
             self.runs[i][float(np.float32(alpha))] = {
                 "o": None if o_s is None else o_s[j], "s_full": s_s[j],
+                "s_full_alt": None if s_alt is None else s_alt[j],
                 "pre": (pos[j, :L].copy(), sc[j, :L].copy(), (kv[0][j, :L].copy(), kv[1][j, :L].copy())),
                 "fast": mode != a2sf.A2SF_EVICT_STABLE, "steps": []}
         self.s_full = s

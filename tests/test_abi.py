@@ -136,6 +136,19 @@ def test_select_rejects_misaligned_pointers_and_index_overflow():
     assert lib.a2sf_select(FAKE, None, None, 1 << 20, 1 << 12, 1 << 12, b, FAKE, FAKE, None) == B.A2SF_ESHAPE
 
 
+def test_prefill_chunk_argument_errors():
+    f = B.lib().a2sf_prefill_chunk
+    c = fake_cache(capacity=40)
+    b = B.Budget(4, 4)
+    assert f(None, FAKE, FAKE, 8, 0, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_EINVAL
+    assert f(FAKE, FAKE, FAKE, 0, 0, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_ESHAPE
+    assert f(FAKE, FAKE, FAKE, 8, -1, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_ESHAPE
+    assert f(FAKE, FAKE, FAKE, 40, 0, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_ECAPACITY
+    assert f(FAKE, FAKE, FAKE, 8, 0, 1.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_EINVAL
+    assert f(FAKE, FAKE, FAKE, 8, 0, 0.3, b, ctypes.byref(c), None, None, 0, None) == B.A2SF_EWORKSPACE
+    assert f(FAKE, FAKE, FAKE, 8, 0, 0.3, b, ctypes.byref(c), None, FAKE, 64, None) == B.A2SF_EWORKSPACE
+
+
 def test_decode_plan_is_a_host_query():
     assert B.a2sf_decode_plan(16384, 201, 128) == (1, 256, 4)        # one wave per head, 256 slots in registers
     nsplit, rows, wave = B.a2sf_decode_plan(32, 3277, 128)           # few heads, long cache: tokens are split
