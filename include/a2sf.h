@@ -169,6 +169,29 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
                              int32_t mode, void* o, void* workspace, size_t workspace_bytes,
                              void* hip_stream);
 
+/* Grouped-query heads (beyond the paper, whose models are all multi-head): `group` query heads
+ * share each of the G K/V heads of the cache, so a token is kept or evicted for the whole
+ * group.  The group's score of a token is the SUM of its query heads' accumulated scores -- as
+ * the paper's Eq.1 sums over the heads that one pruning decision serves.  Every query head has
+ * its own softmax and its own output.
+ *   group        1, 2, 4 or 8 (1 = the plain calls).
+ *   q            prefill: [G, group, n, d]; decode: [G, group, d].
+ *   k, v / k_new, v_new   as in the plain calls: one row per K/V head.
+ *   o            prefill: [G, group, n, d] (may be NULL); decode: [G, group, d].
+ *   scores_full  [G, n] (prefill, may be NULL): the summed scores.
+ * Workspace: a2sf_workspace_bytes(G * group, n, capacity, d, dtype, budget) for the prefill
+ * (one log-sum-exp row per query head); the decode step needs one only in stable mode.  The
+ * decode step holds group * capacity logits in LDS: group * capacity <= A2SF_GQA_MAX_LOGITS. */
+#define A2SF_GQA_MAX_LOGITS 16384
+a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_t n, int32_t group,
+                             float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
+                             float* scores_full, void* workspace, size_t workspace_bytes,
+                             void* hip_stream);
+a2sf_status a2sf_decode_step_gqa(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                                 const a2sf_cache* cache, int32_t group, float alpha,
+                                 a2sf_budget budget, int32_t mode, void* o, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+
 /* a2sf_decode_step for callers that cannot provide or allocate a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation.  Identical in every
  * other respect (same kernels, same results); the scratch memory that a2sf_decode_step takes

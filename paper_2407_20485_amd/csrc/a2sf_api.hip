@@ -231,6 +231,85 @@ a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int3
   return launch_status();
 }
 
+namespace {
+inline bool bad_group(int32_t group) { return group != 1 && group != 2 && group != 4 && group != 8; }
+}  // namespace
+
+a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_t n, int32_t group,
+                             float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
+                             float* scores_full, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_alpha(alpha)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (!q || !k || !v) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(scores_full))
+    return A2SF_EINVAL;
+  if (n < 1 || bad_group(group)) return A2SF_ESHAPE;
+  if ((long long)cache->G * group * n > 0x7FFFFFFFLL) return A2SF_ESHAPE;
+  const int G = cache->G, d = cache->d;
+  const WsLayout w = ws_layout(G * group, n, 0, d, budget);   // one log-sum-exp row per QUERY head
+  if (!workspace || misaligned(workspace) || workspace_bytes < w.total) return A2SF_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  clear_stale_error();
+  char* ws = (char*)workspace;
+  float* lse2 = (float*)(ws + w.lse2);
+  float* s_full = scores_full ? scores_full : (float*)(ws + w.s_full);
+  int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
+  int32_t* n_keep = (int32_t*)(ws + w.n_keep);
+  AttnRect rc{n, n, nullptr};
+  rc.kv_group = group;
+  if (cache->dtype == A2SF_F32) {
+    launch_attn_f32((const float*)q, (const float*)k, (const float*)v, G, rc, d, (float*)o, lse2, st);
+    launch_colscores_f32((const float*)q, (const float*)k, lse2, G, rc, n, d, alpha, nullptr, s_full, n,
+                         false, 0.f, st);
+  } else {
+    launch_attn_bf16(q, k, v, G, rc, d, o, lse2, st);
+    launch_colscores_bf16(q, k, lse2, G, rc, n, d, alpha, s_full, n, false, 0.f, st);
+  }
+  launch_select(s_full, nullptr, nullptr, G, n, n, budget.select, budget.recent, keep_idx, n_keep, st);
+  launch_gather_prompt(k, v, s_full, n, keep_idx, budget.select + budget.recent, n_keep, *cache, st);
+  return launch_status();
+}
+
+a2sf_status a2sf_decode_step_gqa(const void* q, const void* k_new, const void* v_new, int32_t t_pos,
+                                 const a2sf_cache* cache, int32_t group, float alpha,
+                                 a2sf_budget budget, int32_t mode, void* o, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  if (group == 1)
+    return decode_impl(q, k_new, v_new, t_pos, cache, alpha, nullptr, budget, mode, o, workspace,
+                       workspace_bytes, hip_stream);
+  a2sf_status s;
+  if ((s = check_budget(budget)) != A2SF_OK) return s;
+  if ((s = check_alpha(alpha)) != A2SF_OK) return s;
+  if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
+  if (!q || !k_new || !v_new || !o) return A2SF_EINVAL;
+  if (misaligned(q) || misaligned(k_new) || misaligned(v_new) || misaligned(o)) return A2SF_EINVAL;
+  if (t_pos < 0) return A2SF_EINVAL;
+  if (mode != A2SF_EVICT_FAST && mode != A2SF_EVICT_STABLE) return A2SF_EINVAL;
+  if (bad_group(group)) return A2SF_ESHAPE;
+  if ((long long)group * cache->capacity > A2SF_GQA_MAX_LOGITS) return A2SF_ECAPACITY;
+  const WsLayout w = ws_layout(cache->G, 0, cache->capacity, cache->d, budget);
+  if (mode == A2SF_EVICT_STABLE && (!workspace || misaligned(workspace) || workspace_bytes < w.total))
+    return A2SF_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)hip_stream;
+  clear_stale_error();
+  launch_decode_gqa(q, k_new, v_new, t_pos, *cache, group, alpha, budget.select, budget.recent,
+                    mode == A2SF_EVICT_FAST, o, st);
+  if (mode == A2SF_EVICT_STABLE) {
+    char* ws = (char*)workspace;
+    int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
+    int32_t* n_keep = (int32_t*)(ws + w.n_keep);
+    launch_select(cache->scores, cache->pos, cache->len, cache->G, cache->capacity, cache->capacity,
+                  budget.select, budget.recent, keep_idx, n_keep, st);
+    launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
+  }
+  return launch_status();
+}
+
 a2sf_status a2sf_prefill_alpha_per_head(const void* q, const void* k, const void* v, int32_t n,
                                         const float* alpha_heads, float alpha_max,
                                         a2sf_budget budget, const a2sf_cache* cache, void* o,

@@ -99,6 +99,17 @@ __device__ __forceinline__ void sweep_k(const T* __restrict__ Kg, const T* __res
   }
 }
 
+// sum of the per-row-group partial outputs of a wave: valid in the lanes with rgrp == 0
+template <typename T, int D>
+__device__ __forceinline__ void v_fold_row_groups(float* acc) {
+  using Gm = RowGeom<T, D>;
+#pragma unroll
+  for (int e = 0; e < Gm::EPL; ++e) {
+#pragma unroll
+    for (int o = Gm::LPR; o < kWave; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+  }
+}
+
 // acc[e] = sum_r w[r] * V[r][sub*EPL + e] over this wave's share of rows [row_begin, row_end),
 // summed over the row groups of the wave: valid in the lanes with rgrp == 0.
 template <typename Grp, int U, bool STREAM, typename T, int D>
@@ -129,11 +140,7 @@ __device__ __forceinline__ void sweep_v(const T* __restrict__ Vg, const T* __res
       for (int e = 0; e < Gm::EPL; ++e) acc[e] = fmaf(wr, f[e], acc[e]);
     }
   }
-#pragma unroll
-  for (int e = 0; e < Gm::EPL; ++e) {
-#pragma unroll
-    for (int o = Gm::LPR; o < kWave; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
-  }
+  v_fold_row_groups<T, D>(acc);
 }
 
 // Workgroup-wide sum of the per-wave partial outputs; result in part[0][0..D).

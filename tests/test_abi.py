@@ -149,6 +149,27 @@ def test_prefill_chunk_argument_errors():
     assert f(FAKE, FAKE, FAKE, 8, 0, 0.3, b, ctypes.byref(c), None, FAKE, 64, None) == B.A2SF_EWORKSPACE
 
 
+def test_grouped_query_argument_errors():
+    lib = B.lib()
+    c = fake_cache(capacity=40)
+    b = B.Budget(4, 4)
+    assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 3, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
+                                None) == B.A2SF_ESHAPE                                   # group of 3
+    assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 4, 0.3, b, ctypes.byref(c), None, None, FAKE, 64,
+                                None) == B.A2SF_EWORKSPACE
+    assert lib.a2sf_prefill_gqa(None, FAKE, FAKE, 16, 4, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
+                                None) == B.A2SF_EINVAL
+    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 5, 0.3, b, 0, FAKE, None, 0,
+                                    None) == B.A2SF_ESHAPE
+    big = fake_cache(capacity=4096)
+    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(big), 8, 0.3, b, 0, FAKE, None, 0,
+                                    None) == B.A2SF_ECAPACITY                            # 8 * 4096 logits
+    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 4, 0.3, b, 1, FAKE, None, 0,
+                                    None) == B.A2SF_EWORKSPACE                           # stable mode needs one
+    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 4, 0.3, b, 0, None, None, 0,
+                                    None) == B.A2SF_EINVAL
+
+
 def test_decode_plan_is_a_host_query():
     assert B.a2sf_decode_plan(16384, 201, 128) == (1, 256, 4)        # one wave per head, 256 slots in registers
     nsplit, rows, wave = B.a2sf_decode_plan(32, 3277, 128)           # few heads, long cache: tokens are split

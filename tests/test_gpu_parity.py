@@ -512,6 +512,80 @@ def test_chunk_without_room_is_flagged():
     assert c.len.tolist() == [15, 31, 39, 10]
 
 
+@pytest.mark.parametrize("dtype,d,group,n", [("bf16", 128, 4, 300), ("bf16", 64, 8, 200), ("f32", 64, 2, 130),
+                                             ("f32", 128, 4, 70), ("bf16", 128, 2, 64), ("bf16", 128, 8, 257)])
+@pytest.mark.parametrize("alpha", [0.0, 0.5, 1.0])
+def test_grouped_query_heads(dtype, d, group, n, alpha, say):
+    """a2sf_prefill_gqa / a2sf_decode_step_gqa: `group` query heads per K/V head; own softmax and
+    output per query head, scores summed over the group, one eviction per K/V head.  Both
+    eviction modes, against the oracle's gqa_prefill / gqa_decode_step."""
+    G, T, select, recent = 3, 6, 14, 10
+    rng = np.random.Generator(np.random.Philox(key=[n, d * 16 + group]))
+    total = n + T
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    q = rng.standard_normal((G, group, total, d)) + u
+    k = rng.standard_normal((G, total, d))
+    k[:, ::17] += 3.0 * u
+    v = rng.standard_normal((G, total, d))
+    if dtype == "bf16":
+        bits = [synth.round_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v)]
+        host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+        dev = [parity.to_device(b, "bf16") for b in bits]
+    else:
+        host = [x.astype(np.float32).astype(np.float64) for x in (q, k, v)]
+        dev = [parity.to_device(x.astype(np.float32), "f32") for x in (q, k, v)]
+    tdt = parity.torch_dtype(dtype)
+    code = a2sf.A2SF_F32 if dtype == "f32" else a2sf.A2SF_BF16
+    B = select + recent
+    alpha32 = float(np.float32(alpha))
+    for mode in (a2sf.A2SF_EVICT_FAST, a2sf.A2SF_EVICT_STABLE):
+        cache = a2sf.Cache(G, B + 1, d, tdt)
+        ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, n, B + 1, d, code, select, recent),
+                         dtype=torch.uint8, device="cuda")
+        o = torch.full((G, group, n, d), float("nan"), dtype=tdt, device="cuda")
+        sf = torch.full((G, n), float("nan"), dtype=torch.float32, device="cuda")
+        a2sf.a2sf_prefill_gqa(dev[0][:, :, :n].contiguous(), dev[1][:, :n].contiguous(), dev[2][:, :n].contiguous(),
+                              n, group, alpha, select, recent, cache, o=o, scores_full=sf, workspace=ws)
+        torch.cuda.synchronize()
+        o_err = s_rel = 0.0
+        oc = []
+        pos = cache.pos.cpu().numpy()
+        lens = cache.len.cpu().numpy()
+        for g in range(G):
+            O, S_full, c = orc.gqa_prefill(host[0][g, :, :n], host[1][g, :n], host[2][g, :n], alpha32, select, recent,
+                                           forced_retained=pos[g, :lens[g]].tolist(), margin=parity.MARGIN)
+            oc.append(c)
+            o_err = max(o_err, float(np.abs(parity.to_f64(o[g]) - O).max()))
+            s_rel = max(s_rel, parity.compare_scores(sf[g].cpu().numpy(), S_full, f"kv head {g} prompt scores"))
+            assert np.array_equal(pos[g, :lens[g]], c.pos)
+            assert np.array_equal(parity.to_f64(cache.k[g, :lens[g]]), c.K)
+        assert o_err <= parity.O_TOL[dtype]
+        od = torch.empty((G, group, d), dtype=tdt, device="cuda")
+        for t in range(T):
+            r = n + t
+            a2sf.a2sf_decode_step_gqa(dev[0][:, :, r].contiguous(), dev[1][:, r].contiguous(), dev[2][:, r].contiguous(),
+                                      r, cache, group, alpha, select, recent, od, mode=mode, workspace=ws)
+            torch.cuda.synchronize()
+            pos = cache.pos.cpu().numpy()
+            lens = cache.len.cpu().numpy()
+            sc = cache.scores.cpu().numpy()
+            for g in range(G):
+                o_ref, _, _, _ = orc.gqa_decode_step(oc[g], host[0][g, :, r], host[1][g, r], host[2][g, r], r, alpha32,
+                                                     select, recent, forced_retained=pos[g, :lens[g]].tolist(),
+                                                     margin=parity.MARGIN)
+                o_err = max(o_err, float(np.abs(parity.to_f64(od[g]) - o_ref).max()))
+                order = np.argsort(pos[g, :lens[g]])
+                oo = oc[g].sorted_by_pos()
+                assert np.array_equal(pos[g, :lens[g]][order], oo.pos), f"kv head {g} step {t}: retained sets differ"
+                if mode == a2sf.A2SF_EVICT_STABLE:
+                    assert np.all(np.diff(pos[g, :lens[g]]) > 0)
+                s_rel = max(s_rel, parity.compare_scores(sc[g, :lens[g]][order], oo.S, f"kv head {g} step {t}"))
+                assert np.array_equal(parity.to_f64(cache.v[g, :lens[g]])[order], oo.V)
+            assert o_err <= parity.O_TOL[dtype]
+    say(f"  [grouped-query {dtype} d={d} group={group} n={n} alpha={alpha}] max|o err|={o_err:.2e} max score rel={s_rel:.2e}")
+
+
 WINDOW_TOL = 2.5e-5     # a quarter of the 1e-4 the scores are held to; the rest is for fp32 rounding
 
 
