@@ -288,6 +288,11 @@ def main():
 
     L = min(n, w.budget) + 1     # tokens a steady-state generation step reads
     dbytes = decode_bytes_per_step(G, L, d, e)
+    if args.mode == "stable" and n + T > w.budget:
+        # keeping the slots in ascending position costs row moves that the method itself does not
+        # need: the victim is never one of the `recent` newest tokens, so at least those rows of K
+        # and V move down one slot (read + write) in every step
+        dbytes += G * 4 * w.recent * d * e
     flops = prefill_model_flops(G, n, d, with_o=not args.no_o)
     dec_gbs = dbytes / dec_s_per_step / 1e9
     pre_tflops = flops / pre_s / 1e12
@@ -321,6 +326,9 @@ def main():
         "roofline": {"kernel": f"decode step ({nsplit_note})", "bound": "hbm", "achieved": dec_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS,
                      "bytes_per_launch": dbytes, "avg_launch_us": dec_s_per_step * 1e6,
+                     "bytes_convention": ("K and V rows read once, scores read and written, q / o / new rows"
+                                          + ("; plus the rows of the recent window moved down one slot "
+                                             "(a lower bound of the stable mode's row moves)" if args.mode == "stable" else "")),
                      "traffic": read_traffic(f"decode_cfg{w.cfg_id}" + ("_stable" if args.mode == "stable" else "")),
                      "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"},
         "roofline_prefill": {"kernel": "a2sf_prefill (attention fwd + column scores + select + gather)",

@@ -88,7 +88,8 @@ typedef struct {
   int32_t dtype;  /* a2sf_dtype */
 } a2sf_cache;
 
-#define A2SF_MAX_CAPACITY 12288
+/* One float per slot is kept in the 160 KB of LDS of a compute unit by the generation step. */
+#define A2SF_MAX_CAPACITY 36864
 
 /* Bytes of device workspace that any of the calls below may need for these sizes
  * (n_max = longest prompt, 0 if a2sf_prefill is not used; capacity as in a2sf_cache).
@@ -242,7 +243,8 @@ a2sf_status a2sf_select(const float* scores, const int32_t* pos, const int32_t* 
  * score are removed from the KV cache; Section 3.1 after Eq.2), as an in-place stable
  * compaction: for every head, row keep_idx[g][r] of K, V, scores and pos moves to row r for
  * r < n_keep[g], and len[g] = n_keep[g].
- *   keep_idx  [G, keep_stride] strictly ascending slot indices (as a2sf_select writes).
+ *   keep_idx  [G, keep_stride] strictly ascending indices of valid slots, i.e. below len[g]
+ *             (as a2sf_select writes).
  *   n_keep    [G] device. */
 a2sf_status a2sf_compact(const a2sf_cache* cache, const int32_t* keep_idx, int32_t keep_stride,
                          const int32_t* n_keep, void* hip_stream);

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liba2sf.so")
 A2SF_OK, A2SF_EINVAL, A2SF_ESHAPE, A2SF_EDTYPE, A2SF_ECAPACITY, A2SF_EWORKSPACE, A2SF_EHIP = range(7)
 A2SF_F32, A2SF_BF16 = 0, 1
 A2SF_EVICT_FAST, A2SF_EVICT_STABLE = 0, 1
-A2SF_MAX_CAPACITY = 12288
+A2SF_MAX_CAPACITY = 36864
 A2SF_STATIC_WS_BYTES = 16 << 20
 
 EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_select",

@@ -179,6 +179,32 @@ __device__ __forceinline__ void flag_bad_head(T* og, int tid, int nthreads) {
   for (int c = tid; c < D; c += nthreads) Elem<T>::store(og + c, __int_as_float(0x7FC00000));
 }
 
+// Stable eviction of slot v by one wave: rows v+1 .. n_old-1 of X move down one slot and the
+// new token's row goes to slot n_old-1 (slot order, i.e. ascending position, is kept).  In
+// place: a batch's source rows (dst + 1) are all requested before its stores, a store only
+// writes rows below every source still outstanding, and the next batch reads beyond everything
+// written so far.
+template <typename T, int D, int U>
+__device__ __forceinline__ void shift_rows_down(T* Xg, const T* xnew, int v, int n_old) {
+  using Gm = RowGeom<T, D>;
+  const int lane = threadIdx.x & 63;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+  for (int base = v; base < n_old; base += Gm::RPW * U) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int src = base + u * Gm::RPW + rgrp + 1;
+      const T* p = (src == n_old) ? xnew : Xg + (size_t)(src < n_old ? src : v) * D;
+      x[u] = load16(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int dst = base + u * Gm::RPW + rgrp;
+      if (dst < n_old) store16(Xg + (size_t)dst * D + sub * Gm::EPL, x[u]);
+    }
+  }
+}
+
 __device__ __forceinline__ unsigned long long evict_key(float score, int pos) {
   // smallest key = lowest score; among equal scores the highest position
   return ((unsigned long long)ordered_key(score) << 32) | (unsigned)(0x7FFFFFFF - pos);
@@ -236,7 +262,7 @@ __device__ void evict_general(float* a, int n_old, int excess, T* Kg, T* Vg, flo
 // Score update and eviction of one head by a whole workgroup.  prob(j) returns the
 // probability of slot j (slot n_old = the new token, not yet stored in the cache); the
 // updated scores are left in LDS a[0..L).  All 256 threads call this.  One pass reads the
-// scores and positions (independent loads, batched four deep), one pass writes the scores.
+// scores and positions (independent loads, eight per thread issued together), one pass writes the scores.
 template <typename T, int D, typename ProbFn>
 __device__ void update_and_evict(ProbFn prob, float* a, int n_old, T* Kg, T* Vg, float* Sg,
                                  int32_t* Pg, int32_t* len_g, const T* knew, const T* vnew,
@@ -252,18 +278,34 @@ __device__ void update_and_evict(ProbFn prob, float* a, int n_old, T* Kg, T* Vg,
   const int thr = t_pos - recent;
   int cnt = 0, best_slot = n_old;
   unsigned long long best = ~0ull;
-#pragma unroll 4
-  for (int j = tid; j < L; j += kThreads) {
-    const float pj = prob(j);
-    const float s_old = j < n_old ? Sg[j] : 0.f;
-    const int p = j < n_old ? Pg[j] : t_pos;
-    const float s = fmaf(alpha, s_old, pj);  // the forgetting update
-    a[j] = s;
-    if (p > thr) {
-      ++cnt;
-    } else {
-      const unsigned long long key = evict_key(s, p);
-      if (key < best) { best = key; best_slot = j; }
+  constexpr int NB = 8;  // slots per thread whose loads are issued together
+  for (int j0 = tid; j0 < L; j0 += kThreads * NB) {
+    float s_old[NB], pj[NB];
+    int p[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int j = j0 + b * kThreads;
+      s_old[b] = j < n_old ? Sg[j] : 0.f;
+      p[b] = j < n_old ? Pg[j] : t_pos;
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int j = j0 + b * kThreads;
+      pj[b] = j < L ? prob(j) : 0.f;
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      const int j = j0 + b * kThreads;
+      if (j < L) {
+        const float s = fmaf(alpha, s_old[b], pj[b]);  // the forgetting update
+        a[j] = s;
+        if (p[b] > thr) {
+          ++cnt;
+        } else {
+          const unsigned long long key = evict_key(s, p[b]);
+          if (key < best) { best = key; best_slot = j; }
+        }
+      }
     }
   }
   __syncthreads();
@@ -305,7 +347,12 @@ __device__ __forceinline__ void load_query(const T* qg, float scale_log2e, float
   for (int e = 0; e < Gm::EPL; ++e) qv[e] *= scale_log2e;
 }
 
-constexpr int kBlockUnroll = 4;  // loads in flight per lane, workgroup-per-head kernels
+// What a kernel does when the step overfills the budget.
+constexpr int kEvictNone = 0;   // nothing: the token is appended (selection / compaction kernels follow)
+constexpr int kEvictInSlot = 1; // fast mode: the new token's rows go into the evicted slot
+constexpr int kEvictShift = 2;  // stable mode, one-wave-per-head kernel: the slots behind the victim move down
+
+constexpr int kBlockUnroll = 8;  // loads in flight per lane, workgroup-per-head kernels
 constexpr int kWaveUnroll = 8;   // loads in flight per lane, wave-per-head kernel
 
 // ---- one workgroup per head ---------------------------------------------------------
@@ -488,7 +535,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
 // scores and positions of its head in registers (slot j = lane + 64k), and finishes the
 // softmax, the score update and the single eviction with wave shuffles only, so the four
 // heads of a workgroup never wait for each other and loads of different heads overlap.
-template <typename T, int D, int NJ>
+template <typename T, int D, int NJ, bool STABLE>
 __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
     const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
     T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha,
@@ -497,6 +544,9 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   using Gm = RowGeom<T, D>;
   using Grp = WaveGroup;
   __shared__ float zs[kWaves][NJ * 64];
+  // scores and positions, for the slot shift of the stable mode
+  __shared__ float szs[STABLE ? kWaves : 1][STABLE ? NJ * 64 : 1];
+  __shared__ int pzs[STABLE ? kWaves : 1][STABLE ? NJ * 64 : 1];
   __shared__ StepSmem sms[kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.x * kWaves + wave;
@@ -557,6 +607,109 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   }
   Grp::sync();
 
+  if constexpr (STABLE) {
+    // Stable mode: slots stay in ascending position, so the slots behind the victim move down by
+    // one and the new token takes the last one.  The victim depends on the scores only, so it is
+    // chosen BEFORE the V sweep: scores, positions and K rows (re-read: the K sweep is over) are
+    // shifted first, and the V rows are written one slot down as the V sweep loads them, which
+    // saves reading them a second time.
+    float s_new[NJ];
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], zr[k]);
+    const int excess = L - (select + recent);
+    int v = -1;  // >= 0: the slot that is evicted
+    if (excess == 1) {
+      const int thr = t_pos - recent;
+      int cnt = 0;
+      unsigned long long best = ~0ull;
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j < L) {
+          if (pos[k] > thr) {
+            ++cnt;
+          } else {
+            const unsigned long long key = evict_key(s_new[k], pos[k]);
+            best = key < best ? key : best;
+          }
+        }
+      }
+      cnt = wave_sum_i(cnt);
+      if (cnt == recent) {
+        const unsigned long long win = wave_min_u64(best);
+#pragma unroll
+        for (int k = 0; k < NJ; ++k) {
+          const int j = lane + 64 * k;
+          if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
+      }
+    }
+    if (v >= 0) {
+      float* sz = szs[wave];
+      int* pz = pzs[wave];
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j < L) { sz[j] = s_new[k]; pz[j] = pos[k]; }   // slot n_old there is the new token
+      }
+      Grp::sync();
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j < n_old) {
+          const int src = j < v ? j : j + 1;
+          Sg[j] = sz[src];
+          if (j >= v) Pg[j] = pz[src];
+        }
+      }
+      shift_rows_down<T, D, kWaveUnroll>(Kg, knew, v, n_old);
+      // len stays n_old
+    } else {
+      // room left, or a step the single shift cannot do (several evictions, gaps in the newest
+      // positions): the token is appended; the selection and compaction kernels that follow
+      // bring the head down to its budget
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j < L) Sg[j] = s_new[k];
+      }
+      if (lane == 0) { Pg[n_old] = t_pos; len[g] = L; }
+      if (lane < Gm::LPR) store16(Kg + (size_t)n_old * D + lane * Gm::EPL, load16(knew + lane * Gm::EPL));
+    }
+    // V sweep; with a victim, every row behind it is written one slot down as it passes
+    constexpr int VROWS = Gm::RPW * kWaveUnroll;
+    float acc[Gm::EPL];
+#pragma unroll
+    for (int e = 0; e < Gm::EPL; ++e) acc[e] = 0.f;
+    for (int base = 0; base < L; base += VROWS) {
+      uint4 x[kWaveUnroll];
+#pragma unroll
+      for (int u = 0; u < kWaveUnroll; ++u) {
+        const int r = base + u * Gm::RPW + rgrp;
+        const T* p = (r == n_old) ? vnew : Vg + (size_t)(r < L ? r : 0) * D;
+        x[u] = load16_stream(p + sub * Gm::EPL);
+      }
+#pragma unroll
+      for (int u = 0; u < kWaveUnroll; ++u) {
+        const int r = base + u * Gm::RPW + rgrp;
+        const float wr = r < L ? z[r] : 0.f;
+        float f[Gm::EPL];
+        Elem<T>::unpack(x[u], f);
+#pragma unroll
+        for (int e = 0; e < Gm::EPL; ++e) acc[e] = fmaf(wr, f[e], acc[e]);
+        // rows v+1 .. n_old (the new token) go to slots v .. n_old-1; without a victim the new
+        // token's row goes to slot n_old
+        if (v >= 0 ? (r > v && r <= n_old) : r == n_old)
+          store16(Vg + (size_t)(v >= 0 ? r - 1 : r) * D + sub * Gm::EPL, x[u]);
+      }
+    }
+    v_fold_row_groups<T, D>(acc);
+    if (rgrp == 0) store16(o + (size_t)g * D + sub * Gm::EPL, pack16(acc, T()));
+    return;
+  }
+
   float acc[Gm::EPL];
   sweep_v<Grp, kWaveUnroll, true, T, D>(Vg, vnew, n_old, 0, L, z, 0, acc);
   if (rgrp == 0) store16(o + (size_t)g * D + sub * Gm::EPL, pack16(acc, T()));
@@ -565,8 +718,8 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   float s_new[NJ];
 #pragma unroll
   for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], zr[k]);
-  const int excess = evict_here ? L - (select + recent) : 0;
-  if (excess <= 0) {  // room left: plain append
+  const int excess = evict_here != kEvictNone ? L - (select + recent) : 0;
+  auto append_only = [&]() {  // the new token takes slot n_old, nothing leaves
 #pragma unroll
     for (int k = 0; k < NJ; ++k) {
       const int j = lane + 64 * k;
@@ -574,6 +727,9 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
     }
     if (lane == 0) { Pg[n_old] = t_pos; len[g] = L; }
     copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
+  };
+  if (excess <= 0) {  // room left
+    append_only();
     return;
   }
   const int thr = t_pos - recent;
@@ -734,24 +890,38 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   if (plan.nsplit <= 1 && plan.wave_slots > 0) {
     const dim3 grid((c.G + kWaves - 1) / kWaves);
-#define A2SF_WAVE(NJ)                                                                            \
-  hipLaunchKernelGGL((decode_wave_kernel<T, D, NJ>), grid, dim3(kThreads), 0, st, (const T*)q,   \
-                     (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, \
-                     c.len, c.G, c.capacity, alpha, alpha_heads, select, recent, (int)evict_here, \
-                     (T*)o, scale_log2e)
+#define A2SF_WAVE_(NJ, STABLE)                                                                        \
+  hipLaunchKernelGGL((decode_wave_kernel<T, D, NJ, STABLE>), grid, dim3(kThreads), 0, st, (const T*)q, \
+                     (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos,       \
+                     c.len, c.G, c.capacity, alpha, alpha_heads, select, recent,                       \
+                     evict_here ? kEvictInSlot : kEvictShift, (T*)o, scale_log2e)
+#define A2SF_WAVE(NJ)                       \
+  do {                                      \
+    if (evict_here) A2SF_WAVE_(NJ, false);  \
+    else A2SF_WAVE_(NJ, true);              \
+  } while (0)
     if (plan.wave_slots == 2) A2SF_WAVE(2);
     else if (plan.wave_slots == 4) A2SF_WAVE(4);
     else A2SF_WAVE(8);
 #undef A2SF_WAVE
+#undef A2SF_WAVE_
     return;
   }
+  // the kernels that keep one float per slot in LDS may ask for more than the default 64 KB
+  constexpr int kMaxLds = A2SF_MAX_CAPACITY * (int)sizeof(float);
   if (plan.nsplit <= 1) {
-#define A2SF_FUSED(STREAM)                                                                        \
-  hipLaunchKernelGGL((decode_fused_kernel<T, D, STREAM>), dim3(c.G), dim3(kThreads),              \
-                     (size_t)c.capacity * sizeof(float), st, (const T*)q, (const T*)k_new,        \
-                     (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,            \
-                     c.capacity, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o,      \
-                     scale_log2e)
+#define A2SF_FUSED(STREAM)                                                                          \
+  do {                                                                                              \
+    static const hipError_t raised = hipFuncSetAttribute(                                           \
+        (const void*)decode_fused_kernel<T, D, STREAM>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+        kMaxLds);                                                                                   \
+    (void)raised;                                                                                   \
+    hipLaunchKernelGGL((decode_fused_kernel<T, D, STREAM>), dim3(c.G), dim3(kThreads),              \
+                       (size_t)c.capacity * sizeof(float), st, (const T*)q, (const T*)k_new,        \
+                       (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,            \
+                       c.capacity, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o,      \
+                       scale_log2e);                                                                \
+  } while (0)
     if (plan.stream) A2SF_FUSED(true);
     else A2SF_FUSED(false);
 #undef A2SF_FUSED
@@ -765,6 +935,9 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                      (const T*)q, (const T*)k_new, (const T*)v_new, (const T*)c.k,
                      (const T*)c.v, c.len, c.capacity, plan.nsplit, plan.rows_per_split, zbuf, ml,
                      po, scale_log2e);
+  static const hipError_t raised = hipFuncSetAttribute(
+      (const void*)decode_combine_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+  (void)raised;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(c.G), dim3(kThreads),
                      (size_t)c.capacity * sizeof(float), st, (const T*)k_new, (const T*)v_new,
                      t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len, c.capacity, plan.nsplit,

@@ -175,6 +175,8 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(
   int nk = n_keep[g];
   nk = nk < 0 ? 0 : (nk > capacity ? capacity : nk);
   nk = nk > keep_stride ? keep_stride : nk;
+  // as many strictly ascending indices of valid slots as there are valid slots: the identity
+  if (nk == len[g]) return;
   const int32_t* keep = keep_idx + (size_t)g * keep_stride;
   uint4* Kg = K + (size_t)g * capacity * ROW_UNITS;
   uint4* Vg = V + (size_t)g * capacity * ROW_UNITS;

@@ -272,6 +272,68 @@ def test_wave_per_head_slot_counts(select, recent, d, dtype, say):
     run_lockstep(w, 0.5, sample=[0, 1, 2, 3, 2049, 4099], say=say)
 
 
+@pytest.mark.parametrize("G,budget,mode", [(3, 26214, "fast"), (3, 26214, "stable"), (650, 16384, "fast"),
+                                           (2, 36863, "fast")])
+def test_large_budgets(G, budget, mode, say):
+    """Budgets of half the long-context prompt and more (cache ratios 0.5 and 0.8 of 32768 tokens,
+    and the largest capacity the library takes): the generation step keeps one float per slot in
+    LDS, up to 144 KB.  Few heads (tokens split over workgroups) and many (one workgroup per
+    head).  The caches are drawn directly (a prompt phase over 32768 tokens per head costs the
+    oracle half a minute each); three steps against the oracle on a sample of heads."""
+    d, T = 128, 3
+    select = budget // 2
+    recent = budget - select
+    cap = budget + 1
+    evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
+    sample = sorted(set([0, G // 2, G - 1]))
+    rng = np.random.Generator(np.random.Philox(key=[G, budget]))
+    cache = a2sf.Cache(G, cap, d, torch.bfloat16)
+    gen = torch.Generator(device="cuda").manual_seed(budget)
+    cache.k[:, :budget].copy_(torch.randn((G, budget, d), device="cuda", generator=gen))
+    cache.v[:, :budget].copy_(torch.randn((G, budget, d), device="cuda", generator=gen))
+    cache.scores[:, :budget].copy_(torch.rand((G, budget), device="cuda", generator=gen) * 1e-3)
+    cache.pos[:, :budget].copy_(torch.arange(budget, dtype=torch.int32, device="cuda") * 2)   # ascending, with gaps
+    cache.len.fill_(budget)
+    idx = torch.as_tensor(sample, device="cuda")
+    oc = [orc.HeadCache(parity.to_f64(cache.k[g, :budget]), parity.to_f64(cache.v[g, :budget]),
+                        cache.scores[g, :budget].double().cpu().numpy(), cache.pos[g, :budget].cpu().numpy())
+          for g in sample]
+    qkv = [synth.round_to_bf16_bits(rng.standard_normal((T, G, d)).astype(np.float32)) for _ in range(3)]
+    host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in qkv]
+    dev = [parity.to_device(b, "bf16") for b in qkv]
+    ws = torch.empty(max(256, a2sf.a2sf_workspace_bytes(G, 0, cap, d, a2sf.A2SF_BF16, select, recent)),
+                     dtype=torch.uint8, device="cuda")
+    o = torch.empty((G, d), dtype=torch.bfloat16, device="cuda")
+    o_err = s_rel = 0.0
+    for t in range(T):
+        t_pos = 2 * budget + t
+        a2sf.a2sf_decode_step(dev[0][t], dev[1][t], dev[2][t], t_pos, cache, 0.7, select, recent, o, mode=evict,
+                              workspace=ws)
+        torch.cuda.synchronize()
+        lens = cache.len[idx].cpu().numpy()
+        pos = cache.pos[idx].cpu().numpy()
+        sc = cache.scores[idx].cpu().numpy()
+        og = parity.to_f64(o[idx])
+        for i, g in enumerate(sample):
+            o_ref, _ = orc.attend_and_update(oc[i], host[0][t, g], host[1][t, g], host[2][t, g], t_pos,
+                                             float(np.float32(0.7)))
+            orc.evict(oc[i], select, recent, forced_retained=pos[i, :lens[i]].tolist(), margin=parity.MARGIN)
+            o_err = max(o_err, float(np.abs(og[i] - o_ref).max()))
+            assert lens[i] == budget
+            order = np.argsort(pos[i, :lens[i]])
+            oo = oc[i].sorted_by_pos()
+            assert np.array_equal(pos[i, :lens[i]][order], oo.pos)
+            if mode == "stable":
+                assert np.all(np.diff(pos[i, :lens[i]]) > 0)
+            s_rel = max(s_rel, parity.compare_scores(sc[i, :lens[i]][order], oo.S, f"head {g} step {t}"))
+        assert o_err <= parity.O_TOL["bf16"]
+    g = sample[-1]
+    lg = int(cache.len[g])
+    order = np.argsort(cache.pos[g, :lg].cpu().numpy())
+    assert np.array_equal(parity.to_f64(cache.k[g, :lg])[order], oc[-1].sorted_by_pos().K)
+    say(f"  [large budget G={G} budget={budget} {mode}] max|o err|={o_err:.2e} max score rel={s_rel:.2e}")
+
+
 @pytest.mark.parametrize("select,recent", [(10, 0), (0, 10), (1, 0), (0, 1), (200, 200)])
 def test_budget_shapes(select, recent, say):
     """recent = 0 (the paper's own A2SF split), select = 0 (local window), a budget of one,
