@@ -97,6 +97,97 @@ def similarity_kernel(spec):
                                    "unit": "GB/s", "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
 
 
+def chunked_prompt(w, alpha, m):
+    """`--chunked M`: the workload's prompt processed as n / M chunks with a2sf_prefill_chunk (the
+    first into an empty cache), one eviction per chunk.  Model flops: a chunk row attends the
+    tokens cached before the chunk and the chunk's tokens up to itself (QK^T + PV)."""
+    import torch
+
+    import paper_2407_20485_amd as a2sf
+    from paper_2407_20485_amd import synth
+    G, n, d = w.G, w.n, w.d
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    code = a2sf.A2SF_F32 if w.dtype == "f32" else a2sf.A2SF_BF16
+    data = synth.generate(w)
+    q, k, v = (torch.from_numpy(data[x]) for x in ("q", "k", "v"))
+    if w.dtype == "bf16":
+        q, k, v = (t.view(torch.int16).view(torch.bfloat16) for t in (q, k, v))
+    q, k, v = q.cuda(), k.cuda(), v.cuda()
+    del data
+    cap = w.budget + m + 1
+    cache = a2sf.Cache(G, cap, d, tdt)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, m, cap, d, code, w.select, w.recent), dtype=torch.uint8, device="cuda")
+    chunks = [(a, min(m, n - a)) for a in range(0, n, m)]
+    parts = [tuple(x[:, a:a + mm].contiguous() for x in (q, k, v)) for a, mm in chunks]
+    o = torch.empty((G, m, d), dtype=tdt, device="cuda")
+
+    def run():
+        cache.len.zero_()
+        for (a, mm), (qc, kc, vc) in zip(chunks, parts):
+            a2sf.a2sf_prefill_chunk(qc, kc, vc, mm, a, alpha, w.select, w.recent, cache, o=o, workspace=ws)
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 3
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    flops, cached = 0, 0
+    for a, mm in chunks:
+        flops += G * 2 * 2 * d * (mm * cached + mm * (mm + 1) // 2)
+        cached = min(cached + mm, w.budget)
+    tf = flops / ms / 1e9
+    print(json.dumps({"kernel": "a2sf_prefill_chunk", "workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n,
+                      "chunk": m, "budget": f"{w.select}+{w.recent}", "alpha": alpha, "dtype": w.dtype,
+                      "ms_per_prompt": ms, "flops_model": flops,
+                      "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                   "frac": tf / MFMA_BF16_PEAK_TFLOPS}}), flush=True)
+
+
+def grouped_query_step(w, alpha, group, steps=60):
+    """`--group R`: generation steps of the workload's shape with R query heads per K/V head (G / R
+    K/V heads; random rows).  Algorithmic bytes: K and V rows once per K/V head, scores read and
+    written, R query and output rows, the new K/V rows."""
+    import torch
+
+    import paper_2407_20485_amd as a2sf
+    d, B = w.d, w.budget
+    G = max(1, w.G // group)
+    e = 4 if w.dtype == "f32" else 2
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    cap = B + 1
+    c = a2sf.Cache(G, cap, d, tdt)
+    c.k.copy_(torch.randn(G, cap, d, device="cuda"))
+    c.v.copy_(torch.randn(G, cap, d, device="cuda"))
+    c.scores.copy_(torch.rand(G, cap, device="cuda"))
+    c.pos.copy_(torch.arange(cap, dtype=torch.int32, device="cuda").repeat(G, 1))
+    c.len.fill_(B)
+    q = torch.randn(G, group, d, device="cuda").to(tdt)
+    kn, vn = (torch.randn(G, d, device="cuda").to(tdt) for _ in range(2))
+    o = torch.empty((G, group, d), dtype=tdt, device="cuda")
+
+    def run(t0, cnt):
+        for t in range(t0, t0 + cnt):
+            a2sf.a2sf_decode_step_gqa(q, kn, vn, B + t, c, group, alpha, w.select, w.recent, o)
+    run(0, 5)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    run(5, steps)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    L = B + 1
+    nbytes = G * (2 * L * d * e + 8 * L + (2 * group + 2) * d * e)
+    print(json.dumps({"kernel": "a2sf_decode_step_gqa", "kv_heads": G, "group": group, "slots": L, "head_dim": d,
+                      "dtype": w.dtype, "us_per_step": us, "bytes_per_step": nbytes,
+                      "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
+
+
 def cpu_baseline(w, alpha, budget_s=12.0):
     """The oracle, as it stands, on this machine's host cores: prompt phase of two heads, then
     generation steps head by head until about `budget_s` seconds have been spent."""
@@ -171,6 +262,10 @@ def main():
                          "a host launch)")
     ap.add_argument("--similarity-kernel", metavar="HEADSxROWS", default=None,
                     help="instead of the pass: time the Ideal-mask similarity diagnostic alone (bf16, d = 128)")
+    ap.add_argument("--chunked", type=int, metavar="M", default=None,
+                    help="instead of the pass: the prompt phase as chunks of M tokens (a2sf_prefill_chunk)")
+    ap.add_argument("--group", type=int, metavar="R", default=None,
+                    help="instead of the pass: generation steps with R query heads per K/V head (a2sf_decode_step_gqa)")
     ap.add_argument("--ceilings", choices=["hbm", "mfma", "all"], default=None,
                     help="instead of the pass: run the stand-alone probe of the machine's ceilings "
                          "(streaming reads in the generation step's access pattern; sustained matrix-core rate)")
@@ -203,6 +298,10 @@ def main():
         return similarity_kernel(args.similarity_kernel)
     w = synth.CONFIGS[args.config]
     alpha = w.alpha if args.alpha is None else args.alpha
+    if args.chunked:
+        return chunked_prompt(w, alpha, args.chunked)
+    if args.group:
+        return grouped_query_step(w, alpha, args.group)
     G, n, d, T = w.G, w.n, w.d, w.T
     e = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
