@@ -259,15 +259,36 @@ __device__ void evict_general(float* a, int n_old, int excess, T* Kg, T* Vg, flo
   if (tid == 0) *len_g = live;
 }
 
-// Score update and eviction of one head by a whole workgroup.  prob(j) returns the
+// The first slots a thread handles in update_and_evict (slot tid + b * kThreads): their old
+// scores and positions, and one more value per slot for the caller's probability function.
+// A kernel can request them long before the update needs them.
+constexpr int kSlotBatch = 8;
+struct SlotBatch {
+  float s[kSlotBatch], aux[kSlotBatch];
+  int p[kSlotBatch];
+};
+template <typename AuxFn>
+__device__ __forceinline__ void load_slot_batch(SlotBatch& sb, AuxFn aux, const float* Sg,
+                                                const int32_t* Pg, int j0, int n_old, int t_pos) {
+#pragma unroll
+  for (int b = 0; b < kSlotBatch; ++b) {
+    const int j = j0 + b * kThreads;
+    sb.s[b] = j < n_old ? Sg[j] : 0.f;
+    sb.p[b] = j < n_old ? Pg[j] : t_pos;
+    sb.aux[b] = j <= n_old ? aux(j) : 0.f;
+  }
+}
+
+// Score update and eviction of one head by a whole workgroup.  prob(j, aux(j)) returns the
 // probability of slot j (slot n_old = the new token, not yet stored in the cache); the
 // updated scores are left in LDS a[0..L).  All 256 threads call this.  One pass reads the
-// scores and positions (independent loads, eight per thread issued together), one pass writes the scores.
-template <typename T, int D, typename ProbFn>
-__device__ void update_and_evict(ProbFn prob, float* a, int n_old, T* Kg, T* Vg, float* Sg,
-                                 int32_t* Pg, int32_t* len_g, const T* knew, const T* vnew,
-                                 int t_pos, float alpha, int select, int recent, bool evict_here,
-                                 StepSmem& sm) {
+// scores and positions (independent loads, eight per thread issued together; PRE: the first
+// eight were loaded by the caller into `first`), one pass writes the scores.
+template <typename T, int D, bool PRE, typename AuxFn, typename ProbFn>
+__device__ void update_and_evict(AuxFn aux, ProbFn prob, const SlotBatch& first, float* a, int n_old,
+                                 T* Kg, T* Vg, float* Sg, int32_t* Pg, int32_t* len_g,
+                                 const T* knew, const T* vnew, int t_pos, float alpha, int select,
+                                 int recent, bool evict_here, StepSmem& sm) {
   using Grp = BlockGroup;
   const int tid = threadIdx.x;
   const int L = n_old + 1;
@@ -278,31 +299,20 @@ __device__ void update_and_evict(ProbFn prob, float* a, int n_old, T* Kg, T* Vg,
   const int thr = t_pos - recent;
   int cnt = 0, best_slot = n_old;
   unsigned long long best = ~0ull;
-  constexpr int NB = 8;  // slots per thread whose loads are issued together
-  for (int j0 = tid; j0 < L; j0 += kThreads * NB) {
-    float s_old[NB], pj[NB];
-    int p[NB];
+  for (int j0 = tid; j0 < L; j0 += kThreads * kSlotBatch) {
+    SlotBatch sb;
+    if (PRE && j0 == tid) sb = first;
+    else load_slot_batch(sb, aux, Sg, Pg, j0, n_old, t_pos);
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const int j = j0 + b * kThreads;
-      s_old[b] = j < n_old ? Sg[j] : 0.f;
-      p[b] = j < n_old ? Pg[j] : t_pos;
-    }
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      const int j = j0 + b * kThreads;
-      pj[b] = j < L ? prob(j) : 0.f;
-    }
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
+    for (int b = 0; b < kSlotBatch; ++b) {
       const int j = j0 + b * kThreads;
       if (j < L) {
-        const float s = fmaf(alpha, s_old[b], pj[b]);  // the forgetting update
+        const float s = fmaf(alpha, sb.s[b], prob(j, sb.aux[b]));  // the forgetting update
         a[j] = s;
-        if (p[b] > thr) {
+        if (sb.p[b] > thr) {
           ++cnt;
         } else {
-          const unsigned long long key = evict_key(s, p[b]);
+          const unsigned long long key = evict_key(s, sb.p[b]);
           if (key < best) { best = key; best_slot = j; }
         }
       }
@@ -375,6 +385,13 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
   const T* knew = k_new + (size_t)g * D;
   const T* vnew = v_new + (size_t)g * D;
 
+  // old scores and positions of the first slots: requested now, used after the V sweep
+  const auto no_aux = [](int) { return 0.f; };
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  SlotBatch first;
+  load_slot_batch(first, no_aux, Sg, Pg, tid, n_old, t_pos);
+
   float qv[RowGeom<T, D>::EPL];
   load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
   sweep_k<BlockGroup, kBlockUnroll, STREAM, T, D>(Kg, knew, n_old, 0, L, qv, a, 0);
@@ -399,9 +416,9 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
   reduce_output<T, D>(acc, part);
   if (tid < D) Elem<T>::store(o + (size_t)g * D + tid, part[0][tid]);
 
-  update_and_evict<T, D>([&](int j) { return a[j]; }, a, n_old, Kg, Vg, S + (size_t)g * capacity,
-                         P + (size_t)g * capacity, len + g, knew, vnew, t_pos, alpha, select,
-                         recent, evict_here != 0, sm);
+  update_and_evict<T, D, true>(no_aux, [&](int j, float) { return a[j]; }, first, a, n_old, Kg, Vg, Sg,
+                               Pg, len + g, knew, vnew, t_pos, alpha, select, recent, evict_here != 0,
+                               sm);
 }
 
 // ---- grouped-query heads: one workgroup per K/V head, R query heads ---------------------
@@ -433,6 +450,13 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
   T* Vg = V + (size_t)g * capacity * D;
   const T* knew = k_new + (size_t)g * D;
   const T* vnew = v_new + (size_t)g * D;
+
+  // old scores and positions of the first slots: requested now, used after the V sweep
+  const auto no_aux = [](int) { return 0.f; };
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  SlotBatch first;
+  load_slot_batch(first, no_aux, Sg, Pg, tid, n_old, t_pos);
 
   float qv[R][Gm::EPL];
 #pragma unroll
@@ -518,15 +542,16 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
   }
 
   // ---- S <- alpha*S + sum of the R probability rows, eviction as for a single head
-  update_and_evict<T, D>(
-      [&](int j) {
+  update_and_evict<T, D, true>(
+      no_aux,
+      [&](int j, float) {
         float p = 0.f;
 #pragma unroll
         for (int r = 0; r < R; ++r) p += a[r * capacity + j];
         return p;
       },
-      a, n_old, Kg, Vg, S + (size_t)g * capacity, P + (size_t)g * capacity, len + g, knew, vnew, t_pos,
-      alpha, select, recent, evict_here != 0, sm);
+      first, a, n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos, alpha, select, recent,
+      evict_here != 0, sm);
 }
 
 // ---- one wave per head ----------------------------------------------------------------
@@ -852,13 +877,19 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
   if (alpha_heads) alpha = alpha_heads[g];
   const int n_old = len[g];
   if (n_old < 0 || n_old >= capacity) { flag_bad_head<T, D>(o + (size_t)g * D, tid, kThreads); return; }
-  const int L = n_old + 1;
-  // merge the per-split (max, sum): one lane per split (nsplit <= 64), wave reductions
-  __shared__ float wsplit[kWave];
+  // everything the merge reads is requested at once: the per-split (max, sum), the first
+  // slots' logits, scores and positions, the per-split outputs
+  const float* zg = zbuf + (size_t)g * capacity;
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
   const float* mlg = ml + (size_t)g * nsplit * 2;
-  if (tid < kWave) {
-    const float mc = tid < nsplit ? mlg[2 * tid] : -INFINITY;
-    const float lc = tid < nsplit ? mlg[2 * tid + 1] : 0.f;
+  const float mc = tid < nsplit ? mlg[2 * tid] : -INFINITY;       // nsplit <= 64
+  const float lc = tid < nsplit ? mlg[2 * tid + 1] : 0.f;
+  const auto logit = [&](int j) { return zg[j]; };
+  SlotBatch first;
+  load_slot_batch(first, logit, Sg, Pg, tid, n_old, t_pos);
+  __shared__ float wsplit[kWave];
+  if (tid < kWave) {  // one lane per split, wave reductions
     const float mw = wave_max(mc);
     const float w = exp2f(mc - mw);  // 0 for empty splits
     const float sw = wave_sum(lc * w);
@@ -874,12 +905,10 @@ __global__ __launch_bounds__(kThreads) void decode_combine_kernel(
     for (int c = 0; c < nsplit; ++c) acc = fmaf(po[((size_t)g * nsplit + c) * D + tid], wsplit[c], acc);
     Elem<T>::store(o + (size_t)g * D + tid, acc * inv);
   }
-  const float* zg = zbuf + (size_t)g * capacity;
-  update_and_evict<T, D>([&](int j) { return exp2f(zg[j] - mx) * inv; }, a, n_old,
-                         K + (size_t)g * capacity * D, V + (size_t)g * capacity * D,
-                         S + (size_t)g * capacity, P + (size_t)g * capacity, len + g,
-                         k_new + (size_t)g * D, v_new + (size_t)g * D, t_pos, alpha, select,
-                         recent, evict_here != 0, sm);
+  update_and_evict<T, D, true>(logit, [&](int, float z) { return exp2f(z - mx) * inv; }, first, a, n_old,
+                               K + (size_t)g * capacity * D, V + (size_t)g * capacity * D, Sg, Pg,
+                               len + g, k_new + (size_t)g * D, v_new + (size_t)g * D, t_pos, alpha,
+                               select, recent, evict_here != 0, sm);
 }
 
 template <typename T, int D>
