@@ -554,6 +554,89 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
       evict_here != 0, sm);
 }
 
+// Tail of a one-wave-per-head step: S <- alpha*S + prob on the head's slots held in registers
+// (slot j = lane + 64k; slot n_old is the new token), then the eviction.  z = the wave's LDS
+// strip of at least n_old + 1 floats (used by the rare general path).
+template <typename T, int D, int NJ>
+__device__ __forceinline__ void wave_update_and_evict(const float (&s_old)[NJ], const float (&prob)[NJ],
+                                                      const int (&pos)[NJ], float* z, int n_old, T* Kg,
+                                                      T* Vg, float* Sg, int32_t* Pg, int32_t* len_g,
+                                                      const T* knew, const T* vnew, int t_pos,
+                                                      float alpha, int select, int recent,
+                                                      bool evict_here, StepSmem& sm) {
+  using Grp = WaveGroup;
+  const int lane = threadIdx.x & 63;
+  const int L = n_old + 1;
+  float s_new[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], prob[k]);
+  const int excess = evict_here ? L - (select + recent) : 0;
+  if (excess <= 0) {  // room left: the new token takes slot n_old, nothing leaves
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < L) Sg[j] = s_new[k];
+    }
+    if (lane == 0) { Pg[n_old] = t_pos; *len_g = L; }
+    copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
+    return;
+  }
+  const int thr = t_pos - recent;
+  int cnt = 0;
+  unsigned long long best = ~0ull;
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    if (j < L) {
+      if (pos[k] > thr) {
+        ++cnt;
+      } else {
+        const unsigned long long key = evict_key(s_new[k], pos[k]);
+        best = key < best ? key : best;
+      }
+    }
+  }
+  cnt = wave_sum_i(cnt);
+  if (excess == 1 && cnt == recent) {
+    const unsigned long long win = wave_min_u64(best);
+    int v = -1;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
+    if (v < 0) v = n_old;  // cannot happen for valid input: drop the new token rather than write out of range
+    // the new token's updated score (= its probability) sits with lane n_old%64, slot n_old/64
+    float s_tok = 0.f;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k)
+      if (k == n_old / 64) s_tok = s_new[k];
+    s_tok = __shfl(s_tok, n_old & 63, 64);
+    // one contiguous store of the scores; the victim's slot receives the new token's
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      if (j < n_old) Sg[j] = (j == v) ? s_tok : s_new[k];
+    }
+    if (v != n_old) {
+      if (lane == 63) Pg[v] = t_pos;
+      copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, knew, Vg + (size_t)v * D, vnew);
+    }
+    // len stays n_old (= select + recent): nothing to write
+    return;
+  }
+  // rare: several evictions or gaps in the newest positions
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    if (j < L) z[j] = s_new[k];
+  }
+  Grp::sync();
+  evict_general<Grp, T, D>(z, n_old, excess, Kg, Vg, Sg, Pg, len_g, knew, vnew, t_pos, recent, sm);
+}
+
 // ---- one wave per head ----------------------------------------------------------------
 // For many heads with short caches (capacity <= 64*NJ).  No workgroup barrier anywhere: a
 // wave streams its head's K rows, keeps logits / probabilities in its own LDS strip, the
@@ -739,78 +822,153 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
   sweep_v<Grp, kWaveUnroll, true, T, D>(Vg, vnew, n_old, 0, L, z, 0, acc);
   if (rgrp == 0) store16(o + (size_t)g * D + sub * Gm::EPL, pack16(acc, T()));
 
-  // ---- S <- alpha*S + a, in registers
-  float s_new[NJ];
-#pragma unroll
-  for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], zr[k]);
-  const int excess = evict_here != kEvictNone ? L - (select + recent) : 0;
-  auto append_only = [&]() {  // the new token takes slot n_old, nothing leaves
-#pragma unroll
-    for (int k = 0; k < NJ; ++k) {
-      const int j = lane + 64 * k;
-      if (j < L) Sg[j] = s_new[k];
-    }
-    if (lane == 0) { Pg[n_old] = t_pos; len[g] = L; }
-    copy_kv_row<Grp, T, D>(Kg + (size_t)n_old * D, knew, Vg + (size_t)n_old * D, vnew);
-  };
-  if (excess <= 0) {  // room left
-    append_only();
+  wave_update_and_evict<T, D, NJ>(s_old, zr, pos, z, n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos,
+                                  alpha, select, recent, evict_here != kEvictNone, sm);
+}
+
+// ---- grouped-query heads, one wave per K/V head ------------------------------------------
+// Many K/V heads with short caches (capacity <= 64*NJ): as decode_wave_kernel, no workgroup
+// barrier; a K row loaded once gives R logits, a V row R output contributions.  The R
+// probability rows live in the wave's LDS strip, their sum per slot in registers.
+// Registers: 160 (R = 2) and 200 (R = 4) per lane when the compiler is left alone; bounding
+// them to raise the occupancy spills into the sweeps and is slower (R = 4: 182 us per step
+// instead of 100 at 4096 K/V heads x 201 slots); R = 8 is held to 256, which two waves per SIMD
+// need, and is faster for it (76 us instead of 99 at 2048 K/V heads).
+template <typename T, int D, int NJ, int R, bool STREAM>
+__global__ __launch_bounds__(kThreads, R <= 4 ? 1 : 2) void decode_gqa_wave_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha, int select,
+    int recent, int evict_here, T* __restrict__ o, float scale_log2e) {
+  using Gm = RowGeom<T, D>;
+  using Grp = WaveGroup;
+  constexpr int U = kWaveUnroll, ROWS = Gm::RPW * U, NS = NJ * 64;
+  __shared__ float zs[kWaves][R][NS];
+  __shared__ StepSmem sms[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.x * kWaves + wave;
+  if (g >= G) return;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) {
+    for (int r = 0; r < R; ++r) flag_bad_head<T, D>(o + ((size_t)g * R + r) * D, lane, kWave);
     return;
   }
-  const int thr = t_pos - recent;
-  int cnt = 0;
-  unsigned long long best = ~0ull;
+  const int L = n_old + 1;
+  float (*z)[NS] = zs[wave];
+  T* Kg = K + (size_t)g * capacity * D;
+  T* Vg = V + (size_t)g * capacity * D;
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+
+  float s_old[NJ];
+  int pos[NJ];
 #pragma unroll
   for (int k = 0; k < NJ; ++k) {
     const int j = lane + 64 * k;
-    if (j < L) {
-      if (pos[k] > thr) {
-        ++cnt;
-      } else {
-        const unsigned long long key = evict_key(s_new[k], pos[k]);
-        best = key < best ? key : best;
+    s_old[k] = j < n_old ? Sg[j] : 0.f;
+    pos[k] = j < n_old ? Pg[j] : t_pos;
+  }
+  float qv[R][Gm::EPL];
+#pragma unroll
+  for (int r = 0; r < R; ++r) load_query<T, D>(q + ((size_t)g * R + r) * D, scale_log2e, qv[r]);
+
+  // ---- K sweep: R logits per row
+  for (int base = 0; base < L; base += ROWS) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + u * Gm::RPW + rgrp;
+      const T* p = (row == n_old) ? knew : Kg + (size_t)(row < L ? row : 0) * D;
+      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + u * Gm::RPW + rgrp;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[r][e], f[e], dot);
+        dot = group_sum<Gm::LPR>(dot);
+        if (sub == 0 && row < L) z[r][row] = dot;
       }
     }
   }
-  cnt = wave_sum_i(cnt);
-  if (excess == 1 && cnt == recent) {
-    const unsigned long long win = wave_min_u64(best);
-    int v = -1;
+  Grp::sync();
+
+  // ---- R softmaxes; psum = the group's probability of each slot
+  float psum[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) psum[k] = 0.f;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    float zr[NJ];
+    float mx = -INFINITY;
 #pragma unroll
     for (int k = 0; k < NJ; ++k) {
       const int j = lane + 64 * k;
-      if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
+      zr[k] = j < L ? z[r][j] : -INFINITY;
+      mx = fmaxf(mx, zr[k]);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
-    if (v < 0) v = n_old;  // cannot happen for valid input: drop the new token rather than write out of range
-    // the new token's updated score (= its probability) sits with lane n_old%64, slot n_old/64
-    float s_tok = 0.f;
-#pragma unroll
-    for (int k = 0; k < NJ; ++k)
-      if (k == n_old / 64) s_tok = s_new[k];
-    s_tok = __shfl(s_tok, n_old & 63, 64);
-    // one contiguous store of the scores; the victim's slot receives the new token's
+    mx = wave_max(mx);
+    float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < NJ; ++k) {
-      const int j = lane + 64 * k;
-      if (j < n_old) Sg[j] = (j == v) ? s_tok : s_new[k];
+      zr[k] = exp2f(zr[k] - mx);  // 0 for j >= L
+      sum += zr[k];
     }
-    if (v != n_old) {
-      if (lane == 63) Pg[v] = t_pos;
-      copy_kv_row<Grp, T, D>(Kg + (size_t)v * D, knew, Vg + (size_t)v * D, vnew);
-    }
-    // len stays n_old (= select + recent): nothing to write
-    return;
-  }
-  // rare: several evictions or gaps in the newest positions
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
 #pragma unroll
-  for (int k = 0; k < NJ; ++k) {
-    const int j = lane + 64 * k;
-    if (j < L) z[j] = s_new[k];
+    for (int k = 0; k < NJ; ++k) {
+      zr[k] *= inv;
+      psum[k] += zr[k];
+      const int j = lane + 64 * k;
+      if (j < L) z[r][j] = zr[k];
+    }
   }
   Grp::sync();
-  evict_general<Grp, T, D>(z, n_old, excess, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos, recent, sm);
+
+  // ---- V sweep: R output rows
+  float acc[R][Gm::EPL];
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = 0.f;
+  for (int base = 0; base < L; base += ROWS) {
+    uint4 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + u * Gm::RPW + rgrp;
+      const T* p = (row == n_old) ? vnew : Vg + (size_t)(row < L ? row : 0) * D;
+      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + u * Gm::RPW + rgrp;
+      float f[Gm::EPL];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float wr = row < L ? z[r][row] : 0.f;
+#pragma unroll
+        for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = fmaf(wr, f[e], acc[r][e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    v_fold_row_groups<T, D>(acc[r]);
+    if (rgrp == 0) store16(o + ((size_t)g * R + r) * D + sub * Gm::EPL, pack16(acc[r], T()));
+  }
+  Grp::sync();  // the strip's first row is reused by the rare general eviction
+
+  wave_update_and_evict<T, D, NJ>(s_old, psum, pos, z[0], n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew,
+                                  t_pos, alpha, select, recent, evict_here != 0, sms[wave]);
 }
 
 // ---- split over tokens ----------------------------------------------------------------
@@ -980,6 +1138,36 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const size_t lds = (size_t)group * c.capacity * sizeof(float);
   const bool stream = 4.0 * c.G * c.capacity * D > 512e6;   // as in plan_decode
+  // Many K/V heads with short caches: one wave per K/V head (its strip of R probability rows
+  // must fit: 4 waves x R x 64*NJ floats <= 32 KB)
+  const int nj = c.capacity <= 128 ? 2 : (c.capacity <= 256 ? 4 : 8);
+  if (c.G >= 1024 && c.capacity <= 512 && group * nj <= 32) {
+    const dim3 grid((c.G + kWaves - 1) / kWaves);
+#define A2SF_GQAW__(NJ, R, STREAM)                                                                   \
+  hipLaunchKernelGGL((decode_gqa_wave_kernel<T, D, NJ, R, STREAM>), grid, dim3(kThreads), 0, st,     \
+                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,         \
+                     c.scores, c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, \
+                     (T*)o, scale_log2e)
+#define A2SF_GQAW_(NJ, R)                   \
+  do {                                      \
+    if (stream) A2SF_GQAW__(NJ, R, true);   \
+    else A2SF_GQAW__(NJ, R, false);         \
+  } while (0)
+#define A2SF_GQAW(R)                        \
+  do {                                      \
+    if (nj == 2) A2SF_GQAW_(2, R);          \
+    else if (nj == 4) A2SF_GQAW_(4, R);     \
+    else A2SF_GQAW_(8, R);                  \
+  } while (0)
+    if (group == 2) A2SF_GQAW(2);
+    else if (group == 4) A2SF_GQAW(4);
+    else if (nj == 2) A2SF_GQAW_(2, 8);   // group 8: 64*NJ <= 256 slots
+    else A2SF_GQAW_(4, 8);
+#undef A2SF_GQAW
+#undef A2SF_GQAW_
+#undef A2SF_GQAW__
+    return;
+  }
 #define A2SF_GQA_(R, STREAM)                                                                      \
   hipLaunchKernelGGL((decode_gqa_kernel<T, D, R, STREAM>), dim3(c.G), dim3(kThreads), lds, st,    \
                      (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,      \

@@ -581,8 +581,25 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
     """a2sf_prefill_gqa / a2sf_decode_step_gqa: `group` query heads per K/V head; own softmax and
     output per query head, scores summed over the group, one eviction per K/V head.  Both
     eviction modes, against the oracle's gqa_prefill / gqa_decode_step."""
-    G, T, select, recent = 3, 6, 14, 10
+    grouped_query_case(dtype, d, group, n, alpha, 3, 6, 14, 10, say)
+
+
+@pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 4, 30, 14, 10),    # 64*2 slots per wave
+                                                           ("bf16", 128, 8, 160, 80, 70),   # 64*4 slots, 8 query heads
+                                                           ("f32", 64, 2, 310, 150, 150),   # 64*8 slots
+                                                           ("bf16", 64, 4, 200, 0, 190),    # recent tokens only
+                                                           ("bf16", 128, 2, 140, 129, 0)])  # scores only
+def test_grouped_query_heads_many_kv_heads(dtype, d, group, n, select, recent, say):
+    """The same with 1024 K/V heads and short caches: the generation step runs one wave per
+    K/V head."""
+    grouped_query_case(dtype, d, group, n, 0.5, 1024, 4, select, recent, say)
+
+
+def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say):
     rng = np.random.Generator(np.random.Philox(key=[n, d * 16 + group]))
+    # heads the oracle follows: all of them, or the first and last workgroups plus a seeded sample
+    heads = list(range(G)) if G <= 16 else sorted(set(range(8)) | set(range(G - 8, G)) |
+                                                  set(rng.choice(G, 80, replace=False).tolist()))
     total = n + T
     u = rng.standard_normal(d)
     u /= np.linalg.norm(u)
@@ -611,13 +628,14 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
                               n, group, alpha, select, recent, cache, o=o, scores_full=sf, workspace=ws)
         torch.cuda.synchronize()
         o_err = s_rel = 0.0
-        oc = []
+        oc = {}
         pos = cache.pos.cpu().numpy()
         lens = cache.len.cpu().numpy()
-        for g in range(G):
+        assert np.all(lens == min(n, B))
+        for g in heads:
             O, S_full, c = orc.gqa_prefill(host[0][g, :, :n], host[1][g, :n], host[2][g, :n], alpha32, select, recent,
                                            forced_retained=pos[g, :lens[g]].tolist(), margin=parity.MARGIN)
-            oc.append(c)
+            oc[g] = c
             o_err = max(o_err, float(np.abs(parity.to_f64(o[g]) - O).max()))
             s_rel = max(s_rel, parity.compare_scores(sf[g].cpu().numpy(), S_full, f"kv head {g} prompt scores"))
             assert np.array_equal(pos[g, :lens[g]], c.pos)
@@ -632,7 +650,8 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
             pos = cache.pos.cpu().numpy()
             lens = cache.len.cpu().numpy()
             sc = cache.scores.cpu().numpy()
-            for g in range(G):
+            assert np.all(lens == min(r + 1, B))
+            for g in heads:
                 o_ref, _, _, _ = orc.gqa_decode_step(oc[g], host[0][g, :, r], host[1][g, r], host[2][g, r], r, alpha32,
                                                      select, recent, forced_retained=pos[g, :lens[g]].tolist(),
                                                      margin=parity.MARGIN)
@@ -645,7 +664,7 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
                 s_rel = max(s_rel, parity.compare_scores(sc[g, :lens[g]][order], oo.S, f"kv head {g} step {t}"))
                 assert np.array_equal(parity.to_f64(cache.v[g, :lens[g]])[order], oo.V)
             assert o_err <= parity.O_TOL[dtype]
-    say(f"  [grouped-query {dtype} d={d} group={group} n={n} alpha={alpha}] max|o err|={o_err:.2e} max score rel={s_rel:.2e}")
+    say(f"  [grouped-query {dtype} d={d} group={group} kv heads={G} n={n} budget={select}+{recent} alpha={alpha}] max|o err|={o_err:.2e} max score rel={s_rel:.2e}")
 
 
 WINDOW_TOL = 2.5e-5     # a quarter of the 1e-4 the scores are held to; the rest is for fp32 rounding
