@@ -144,7 +144,8 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
   const int g = (int)(vid / nqb);
   const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
   const int n = rc.m;
   const int gk = g / rc.kv_group;  // the K/V head this query head reads
@@ -421,13 +422,21 @@ __device__ __forceinline__ void dma_full_tile(const bf16_t* __restrict__ Mg, int
                                      16, 0, 0);
 }
 
+constexpr int kScoreOnlyNB = 1;   // 32-row query blocks per wave when no outputs are wanted
+constexpr int kScoreOnlyOcc = 4;  // workgroups per compute unit then (32 KB of LDS each: K tiles only)
+
 template <bool WITH_O, int NB>
-__global__ __launch_bounds__(kThreads, (NB == 1 || !WITH_O) ? 2 : 1) void attn_fwd128_kernel(
+__global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 1)) void attn_fwd128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
   constexpr int D = 128, BM = kWaves * 32 * NB, KK = D / 16, DB = D / 32;
-  // [buffer][K tile | V tile]
-  __shared__ __attribute__((aligned(1024))) char smem[2 * 2 * kTileBytes];
+  // [stage][K tile | V tile]; without outputs there are no V tiles.  A deeper ring (tiles
+  // fetched three steps ahead) was measured for that pass and is slower: it costs occupancy.
+  constexpr int kBuf = (WITH_O ? 2 : 1) * kTileBytes;
+  constexpr int RING = 2;                        // tiles are fetched RING - 1 steps ahead
+  constexpr int kLoadsPerTile = WITH_O ? 8 : 4;  // direct-to-LDS loads a wave issues per fetch
+  static_assert((RING - 2) * kLoadsPerTile <= 15, "pending loads must fit the wait count used below");
+  __shared__ __attribute__((aligned(1024))) char smem[RING * kBuf];
   lds_char* const lds = (lds_char*)smem;
 
   const long long total = (long long)G * nqb;
@@ -436,7 +445,8 @@ __global__ __launch_bounds__(kThreads, (NB == 1 || !WITH_O) ? 2 : 1) void attn_f
   const int g = (int)(vid / nqb);
   const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)g * n * D;
@@ -492,8 +502,18 @@ __global__ __launch_bounds__(kThreads, (NB == 1 || !WITH_O) ? 2 : 1) void attn_f
       if (WITH_O) dma_tile<true>(Vg, t * kTile, n, buf + kTileBytes);
     }
   };
-  fetch(0, lds);
-  __builtin_amdgcn_s_waitcnt(0);
+  // a wave's loads complete in order: tile t has landed once at most the loads of the tiles
+  // fetched after it are outstanding
+  // `later` = tiles fetched after the one that is needed (at most RING - 2)
+  auto wait_all_but = [&](int later) {
+    if (later >= 2 && RING > 2) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * kLoadsPerTile));
+    else if (later == 1 && RING > 2) __builtin_amdgcn_s_waitcnt(0x0f70 | kLoadsPerTile);
+    else __builtin_amdgcn_s_waitcnt(0x0f70);
+  };
+#pragma unroll
+  for (int i = 0; i < RING - 1; ++i)
+    if (i < ntiles) fetch(i, lds + i * kBuf);
+  wait_all_but(min(RING - 2, ntiles - 1));  // tile 0; tiles 1 .. RING-2 may still be on their way
   __syncthreads();
 
   auto tile_step = [&](int t, const lds_char* kt, const lds_char* vt_) {
@@ -539,6 +559,35 @@ __global__ __launch_bounds__(kThreads, (NB == 1 || !WITH_O) ? 2 : 1) void attn_f
             const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
             if (key > qrow) sacc[nb][kb][i] = -INFINITY;
           }
+      }
+      if constexpr (!WITH_O) {
+        // Statistics only.  The exponentials are taken against the running maximum as it is,
+        // without looking for the tile's own: floating point keeps their relative precision
+        // whatever their size, so the maximum has to move only when a sum leaves the range
+        // (>= 2^30, or not a number: the first tile, whose running maximum is -inf).
+        float rs = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) rs += fast_exp2(fmaf(sacc[nb][kb][i], scale_log2e, -m[nb]));
+        if (__any(!(rs < 1073741824.f))) {
+          float mx = sacc[nb][0][0];
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          const float m_new = fmaxf(m[nb], fmaxf(mx * scale_log2e, -1e30f));
+          lsum[nb] *= fast_exp2(m[nb] - m_new);  // 0 on the first tile
+          m[nb] = m_new;
+          rs = 0.f;
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) rs += fast_exp2(fmaf(sacc[nb][kb][i], scale_log2e, -m_new));
+        }
+        lsum[nb] += rs;
+        continue;
       }
       float mx = sacc[nb][0][0];
 #pragma unroll
@@ -602,17 +651,19 @@ __global__ __launch_bounds__(kThreads, (NB == 1 || !WITH_O) ? 2 : 1) void attn_f
     }
   };
 
-  for (int t = 0; t < ntiles; t += 2) {
-    // even tile in buffer 0, odd tile in buffer 1: all LDS offsets are immediates
-    if (t + 1 < ntiles) fetch(t + 1, lds + 2 * kTileBytes);
-    tile_step(t, lds, lds + kTileBytes);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (t + 1 >= ntiles) break;
-    if (t + 2 < ntiles) fetch(t + 2, lds);
-    tile_step(t + 1, lds + 2 * kTileBytes, lds + 3 * kTileBytes);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
+  for (int t0 = 0; t0 < ntiles; t0 += RING) {
+    // tile t in stage t % RING: unrolled over the ring, all LDS offsets are immediates
+#pragma unroll
+    for (int b = 0; b < RING; ++b) {
+      const int t = t0 + b;
+      if (t >= ntiles) break;
+      // the stage of tile t - 1 is free: every wave passed the barrier that ended its step
+      if (t + RING - 1 < ntiles) fetch(t + RING - 1, lds + ((b + RING - 1) % RING) * kBuf);
+      tile_step(t, lds + b * kBuf, lds + b * kBuf + kTileBytes);
+      // tile t + 1 for every wave of the workgroup
+      wait_all_but(min(RING - 2, ntiles - 2 - t));
+      __syncthreads();
+    }
   }
 
   // ---- epilogue.  The accumulator layout gives a lane 4 consecutive d of one row at a time:
@@ -769,7 +820,8 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   if (off < 0 || c0 >= nk) return;
   head_window(alpha_heads, g, n, first_row, log2_alpha);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Kg = K + (size_t)g * rc.kv_stride * D;
   const int wc0 = c0 + wave * 32;  // first key of this wave
@@ -915,10 +967,11 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
                          (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
                          G, nqb, scale_log2e);
     } else {
-      // Without outputs there are no O accumulators, so a wave has the registers for two
-      // 32-row query blocks: every K fragment read from LDS then feeds two matrix ops
-      // (64 heads of n = 32768: 11.0 -> 10.0 ms for the whole call).
-      constexpr int NBL = 2;
+      // Without outputs the pass is bound by the vector ALU as much as by the matrix cores
+      // (fma + exp + add per logit against 1/16 matrix op): one 32-row block per wave at four
+      // workgroups per compute unit overlaps the two better than two blocks per wave at two
+      // (16384 heads of n = 2048: 11.1 ms against 12.75).
+      constexpr int NBL = kScoreOnlyNB;
       const int nqbl = (n + kWaves * 32 * NBL - 1) / (kWaves * 32 * NBL);
       const long long total = (long long)G * nqbl;
       const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
@@ -975,7 +1028,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   lds_char* const qs = (lds_char*)smem;
 
   const int g = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)g * n * D;
@@ -1126,7 +1180,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
   const int cb = (int)(vid % ncb);  // column block 0 has the most rows: first
   head_window(alpha_heads, g, n, first_row, log2_alpha);
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)g * n * D;
