@@ -135,3 +135,98 @@ def replay_head(job):
         if limiter is not None:
             limiter.unregister() if hasattr(limiter, "unregister") else None
     return res
+
+
+def _sorted_state(pos_g, s_g, oc, what):
+    """Retained set and scores of a GPU head (any slot order) against the oracle's cache."""
+    pos_g = np.asarray(pos_g, dtype=np.int64)
+    if len(pos_g) != len(oc):
+        raise Mismatch(f"{what}: len {len(pos_g)} vs oracle {len(oc)}")
+    order = np.argsort(pos_g)
+    oo = oc.sorted_by_pos()
+    if not np.array_equal(pos_g[order], oo.pos):
+        raise Mismatch(f"{what}: retained sets differ")
+    rel = rel_err(np.asarray(s_g)[order], oo.S)
+    if rel > SCORE_RTOL:
+        raise Mismatch(f"{what}: score rel error {rel:.3e}")
+    return rel, order, oo
+
+
+def replay_head_chunks(job):
+    """A prompt processed in chunks (one eviction per chunk) on one head.
+
+    job: dict(w, g, select, recent, alpha, m, threads,
+              chunks=[(o[m,d] float32, pos, scores), ...] one per chunk, rows=(K, V) after the last)
+    Returns dict(g, o_err, s_rel, swaps, failure | None)."""
+    from paper_2407_20485_amd import synth
+    w, g = job["w"], job["g"]
+    res = {"g": g, "o_err": 0.0, "s_rel": 0.0, "swaps": 0, "failure": None}
+    try:
+        Q, K, V = (x.astype(np.float64) for x in synth.head_arrays(w, g))
+        m, d = job["m"], Q.shape[1]
+        oc = orc.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64))
+        for c, (o_g, pos_g, s_g) in enumerate(job["chunks"]):
+            r0 = c * m
+            O, _, sw = orc.prefill_chunk(oc, Q[r0:r0 + m], K[r0:r0 + m], V[r0:r0 + m], r0, job["alpha"],
+                                         job["select"], job["recent"],
+                                         forced_retained=[int(p) for p in pos_g], margin=MARGIN)
+            res["swaps"] += sw
+            err = float(np.abs(np.asarray(o_g, dtype=np.float64) - O).max())
+            res["o_err"] = max(res["o_err"], err)
+            if err > O_TOL[w.dtype]:
+                raise Mismatch(f"head {g} chunk {c}: output max-abs {err:.3e}")
+            rel, order, oo = _sorted_state(pos_g, s_g, oc, f"head {g} chunk {c}")
+            res["s_rel"] = max(res["s_rel"], rel)
+            if not np.all(np.diff(np.asarray(pos_g)) > 0):
+                raise Mismatch(f"head {g} chunk {c}: slots not in ascending position")
+        Kg, Vg = job["rows"]
+        if not (np.array_equal(np.asarray(Kg, dtype=np.float64)[order], oo.K)
+                and np.array_equal(np.asarray(Vg, dtype=np.float64)[order], oo.V)):
+            raise Mismatch(f"head {g}: cached rows differ after the last chunk")
+    except (Mismatch, ValueError) as e:
+        res["failure"] = f"{type(e).__name__}: {e}"
+    return res
+
+
+def replay_kv_head_group(job):
+    """Grouped-query heads: `group` consecutive heads of the workload act as the query heads of
+    one K/V head (keys and values of the first of them).
+
+    job: dict(w, g (K/V head), group, select, recent, alpha,
+              o=[group, rows, d] float32 (the last `rows` prompt rows), s_full=[n],
+              pre=(pos, scores), steps=[(o[group, d], pos, scores), ...])"""
+    from paper_2407_20485_amd import synth
+    w, g, R = job["w"], job["g"], job["group"]
+    res = {"g": g, "o_err": 0.0, "s_rel": 0.0, "swaps": 0, "failure": None}
+    try:
+        heads = [synth.head_arrays(w, g * R + r) for r in range(R)]
+        Qs = np.stack([h[0].astype(np.float64) for h in heads])            # [R, n + T, d]
+        K, V = heads[0][1].astype(np.float64), heads[0][2].astype(np.float64)
+        n = w.n
+        pos_g, s_g = job["pre"]
+        O, S_full, oc = orc.gqa_prefill(Qs[:, :n], K[:n], V[:n], job["alpha"], job["select"], job["recent"],
+                                        forced_retained=[int(p) for p in pos_g], margin=MARGIN)
+        rows = job["o"].shape[1]
+        err = float(np.abs(np.asarray(job["o"], dtype=np.float64) - O[:, n - rows:]).max())
+        res["o_err"] = err
+        if err > O_TOL[w.dtype]:
+            raise Mismatch(f"K/V head {g}: prompt output max-abs {err:.3e}")
+        rel = rel_err(job["s_full"], S_full)
+        res["s_rel"] = rel
+        if rel > SCORE_RTOL:
+            raise Mismatch(f"K/V head {g}: prompt score rel error {rel:.3e}")
+        res["s_rel"] = max(res["s_rel"], _sorted_state(pos_g, s_g, oc, f"K/V head {g} after the prompt")[0])
+        for t, (o_g, pos_g, s_g) in enumerate(job["steps"]):
+            r = n + t
+            o_ref, _, _, sw = orc.gqa_decode_step(oc, Qs[:, r], K[r], V[r], r, job["alpha"], job["select"],
+                                                  job["recent"], forced_retained=[int(p) for p in pos_g],
+                                                  margin=MARGIN)
+            res["swaps"] += sw
+            err = float(np.abs(np.asarray(o_g, dtype=np.float64) - o_ref).max())
+            res["o_err"] = max(res["o_err"], err)
+            if err > O_TOL[w.dtype]:
+                raise Mismatch(f"K/V head {g} step {t}: output max-abs {err:.3e}")
+            res["s_rel"] = max(res["s_rel"], _sorted_state(pos_g, s_g, oc, f"K/V head {g} step {t}")[0])
+    except (Mismatch, ValueError) as e:
+        res["failure"] = f"{type(e).__name__}: {e}"
+    return res

@@ -762,7 +762,132 @@ def test_cfg3_opt13b_shape(say):
     say(f"  [cfg3] {len(sample)} heads: max|o err|={rp.o_err:.2e} max score rel={rp.s_rel:.2e} swaps={rp.swaps}")
 
 
-def test_cfg2_full_size_sampled(say):
+@pytest.fixture(scope="module")
+def cfg2_inputs():
+    """configs[2] on the GPU (all 16384 heads), generated once for the tests that run at full size."""
+    box = {}
+
+    def get(say):
+        if "p" not in box:
+            say(f"  [cfg2] generating {CFG[2].G} heads ...")
+            box["p"] = parity.Problem(CFG[2], sample=[], progress=lambda c, H: say(f"    {c}/{H} heads"),
+                                      host_copies=False)
+        return box["p"]
+    yield get
+    box.clear()
+
+
+def run_workers(fn, jobs, say, what):
+    """The oracle over the recorded heads in worker processes (numpy only there)."""
+    import multiprocessing as mp
+    import os
+    workers = max(1, min(16, len(os.sched_getaffinity(0)), len(jobs)))
+    o_err = s_rel = 0.0
+    swaps, failures = 0, []
+    with mp.get_context("spawn").Pool(workers) as pool:
+        for r in pool.imap_unordered(fn, jobs):
+            o_err, s_rel, swaps = max(o_err, r["o_err"]), max(s_rel, r["s_rel"]), swaps + r["swaps"]
+            if r["failure"]:
+                failures.append(r["failure"])
+    assert not failures, f"{len(failures)} of {len(jobs)} heads differ: " + "; ".join(failures[:5])
+    say(f"  [{what}] {len(jobs)} heads: max|o err|={o_err:.2e} max score rel={s_rel:.2e} in-margin swaps={swaps}")
+
+
+def test_cfg2_chunked_prompt_full_size_sampled(cfg2_inputs, say):
+    """The benchmark's chunked leg (bench.py --chunked 256): the prompt of all 16384 heads in eight
+    chunks of 256 tokens, one eviction per chunk.  64 seeded heads are replayed by the oracle's
+    prefill_chunk: every chunk's outputs, scores and retained set, the cached rows at the end;
+    on all heads the lengths and the presence of the newest tokens."""
+    import oracle_replay
+    w = CFG[2]
+    p = cfg2_inputs(say)
+    m = 256
+    rng = np.random.default_rng(22)
+    sample = sorted(rng.choice(w.G, 64, replace=False).tolist())
+    idx = torch.as_tensor(sample, device="cuda")
+    cap = w.budget + m + 1
+    cache = a2sf.Cache(w.G, cap, w.d, torch.bfloat16)
+    cache.len.zero_()
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(w.G, m, cap, w.d, a2sf.A2SF_BF16, w.select, w.recent),
+                     dtype=torch.uint8, device="cuda")
+    o = torch.empty((w.G, m, w.d), dtype=torch.bfloat16, device="cuda")
+    rec = {g: [] for g in sample}
+    for a in range(0, w.n, m):
+        qc, kc, vc = (p.dev[x][:, a:a + m].contiguous() for x in ("q", "k", "v"))
+        a2sf.a2sf_prefill_chunk(qc, kc, vc, m, a, w.alpha, w.select, w.recent, cache, o=o, workspace=ws)
+        torch.cuda.synchronize()
+        L = min(a + m, w.budget)
+        assert bool((cache.len == L).all())
+        og = o[idx].float().cpu().numpy()
+        pg = cache.pos[idx, :L].cpu().numpy()
+        sg = cache.scores[idx, :L].cpu().numpy()
+        for j, g in enumerate(sample):
+            rec[g].append((og[j], pg[j], sg[j]))
+    pos = cache.pos[:, :w.budget].cpu().numpy()
+    assert np.array_equal(pos[:, -w.recent:], np.tile(np.arange(w.n - w.recent, w.n), (w.G, 1)))
+    assert np.all(np.diff(pos, axis=1) > 0)
+    kg, vg = parity.to_f64(cache.k[idx, :w.budget]), parity.to_f64(cache.v[idx, :w.budget])
+    jobs = [{"w": w, "g": g, "select": w.select, "recent": w.recent, "alpha": float(np.float32(w.alpha)), "m": m,
+             "chunks": rec[g], "rows": (kg[j], vg[j])} for j, g in enumerate(sample)]
+    del cache, ws, o
+    run_workers(oracle_replay.replay_head_chunks, jobs, say, "cfg2 in chunks of 256")
+
+
+def test_cfg2_grouped_query_full_size_sampled(cfg2_inputs, say):
+    """The benchmark's grouped-query leg (bench.py --group 4) on the config's inputs: 4096 K/V
+    heads (keys and values of every fourth head) with the four heads from there on as their query
+    heads.  a2sf_prefill_gqa and 16 generation steps (one wave per K/V head) on all of them; 24
+    seeded K/V heads are replayed by the oracle: the last 64 prompt rows of every query head, the
+    prompt scores, then outputs, scores and retained set of every step."""
+    import oracle_replay
+    w = CFG[2]
+    p = cfg2_inputs(say)
+    R, T, rows = 4, 16, 64
+    Gk = w.G // R
+    rng = np.random.default_rng(23)
+    sample = sorted(rng.choice(Gk, 24, replace=False).tolist())
+    idx = torch.as_tensor(sample, device="cuda")
+    q = p.dev["q"].view(Gk, R, w.n, w.d)
+    k, v = (p.dev[x].view(Gk, R, w.n, w.d)[:, 0].contiguous() for x in ("k", "v"))
+    cache = a2sf.Cache(Gk, w.budget + 1, w.d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(w.G, w.n, w.budget + 1, w.d, a2sf.A2SF_BF16, w.select, w.recent),
+                     dtype=torch.uint8, device="cuda")
+    o = torch.empty((Gk, R, w.n, w.d), dtype=torch.bfloat16, device="cuda")
+    sf = torch.empty((Gk, w.n), dtype=torch.float32, device="cuda")
+    a2sf.a2sf_prefill_gqa(q, k, v, w.n, R, w.alpha, w.select, w.recent, cache, o=o, scores_full=sf, workspace=ws)
+    torch.cuda.synchronize()
+    assert bool((cache.len == w.budget).all())
+    total = sf.double().sum(dim=1).cpu().numpy()      # R heads' geometric totals (Eq.5 summed over keys)
+    want = R * (1 - w.alpha ** w.n) / (1 - w.alpha)
+    assert np.abs(total / want - 1).max() < 1e-4
+    jobs = {g: {"w": w, "g": g, "group": R, "select": w.select, "recent": w.recent,
+                "alpha": float(np.float32(w.alpha)), "steps": []} for g in sample}
+    og = o[idx, :, w.n - rows:].float().cpu().numpy()
+    sfg = sf[idx].cpu().numpy()
+    pg, sg = cache.pos[idx, :w.budget].cpu().numpy(), cache.scores[idx, :w.budget].cpu().numpy()
+    for j, g in enumerate(sample):
+        jobs[g].update(o=og[j], s_full=sfg[j], pre=(pg[j], sg[j]))
+    del o
+    od = torch.empty((Gk, R, w.d), dtype=torch.bfloat16, device="cuda")
+    qd = p.dev["qd"].view(w.T, Gk, R, w.d)
+    kd, vd = (p.dev[x].view(w.T, Gk, R, w.d)[:, :, 0].contiguous() for x in ("kd", "vd"))
+    for t in range(T):
+        a2sf.a2sf_decode_step_gqa(qd[t], kd[t], vd[t], w.n + t, cache, R, w.alpha, w.select, w.recent, od,
+                                  workspace=ws)
+        torch.cuda.synchronize()
+        og = od[idx].float().cpu().numpy()
+        pg, sg = cache.pos[idx, :w.budget].cpu().numpy(), cache.scores[idx, :w.budget].cpu().numpy()
+        for j, g in enumerate(sample):
+            jobs[g]["steps"].append((og[j], pg[j], sg[j]))
+    assert bool((cache.len == w.budget).all())
+    pos = cache.pos[:, :w.budget].cpu().numpy()
+    newest = np.sort(pos, axis=1)[:, -w.recent:]
+    assert np.array_equal(newest, np.tile(np.arange(w.n + T - w.recent, w.n + T), (Gk, 1)))
+    del cache, ws, sf
+    run_workers(oracle_replay.replay_kv_head_group, [jobs[g] for g in sample], say, "cfg2 as 4096 K/V heads x 4")
+
+
+def test_cfg2_full_size_sampled(cfg2_inputs, say):
     """All 16384 heads on the GPU in the benchmark's launch configuration.  1024 seeded heads,
     32 from each of the 32 layers (so they are spread over the whole launch: every 16th head on
     average, every workgroup position and round of the persistent prompt kernel), are replayed
@@ -773,8 +898,8 @@ def test_cfg2_full_size_sampled(say):
     per_layer = w.batch * w.heads
     sample = sorted(int(l * per_layer + j) for l in range(w.layers)
                     for j in rng.choice(per_layer, 32, replace=False))
-    say(f"  [cfg2] generating {w.G} heads ...")
-    p = parity.Problem(w, sample=sample, progress=lambda c, H: say(f"    {c}/{H} heads"), host_copies=False)
+    p = cfg2_inputs(say)
+    p.sample = sample
     rp = parity.Replay(p)
     # the benchmark's prompt phase is a2sf_prefill_windowed at WINDOW_TOL; the scores of the
     # plain a2sf_prefill are recorded and compared too
