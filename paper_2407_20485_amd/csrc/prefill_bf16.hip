@@ -428,7 +428,7 @@ constexpr int kScoreOnlyOcc = 4;  // workgroups per compute unit then (32 KB of 
 template <bool WITH_O, int NB>
 __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 1)) void attn_fwd128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
-    bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int G, int nqb, float scale_log2e) {
+    bf16_t* __restrict__ O, float* __restrict__ LSE2, AttnRect rc, int G, int nqb, float scale_log2e) {
   constexpr int D = 128, BM = kWaves * 32 * NB, KK = D / 16, DB = D / 32;
   // [stage][K tile | V tile]; without outputs there are no V tiles.  A deeper ring (tiles
   // fetched three steps ahead) was measured for that pass and is slower: it costs occupancy.
@@ -448,10 +448,20 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
-  const bf16_t* Qg = Q + (size_t)g * n * D;
-  const bf16_t* Kg = K + (size_t)g * n * D;
-  const bf16_t* Vg = V + (size_t)g * n * D;
+  const int n = rc.m;
+  const int gk = g / rc.kv_group;  // the K/V head this query head reads
+  const int off = rc.off_heads ? rc.off_heads[gk] : 0;  // older tokens in front of the rows' own
   const int row0 = qb * BM;
+  if (off < 0) {  // a head the caller's precondition excludes: its rows are flagged with NaN
+    if (WITH_O)
+      for (int e = tid; e < min(BM, n - row0) * D; e += kThreads)
+        O[((size_t)g * n + row0) * D + e] = (bf16_t)0x7FC0;
+    return;
+  }
+  const int nk = off + n;  // keys of this head
+  const bf16_t* Qg = Q + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)gk * rc.kv_stride * D;
+  const bf16_t* Vg = V + (size_t)gk * rc.kv_stride * D;
   const int wrow0 = row0 + wave * 32 * NB;  // first query row of this wave
 
   // Q fragments (B operand): lane (query l32, half h) holds Q[query][16kk + 8h .. +7]
@@ -488,18 +498,18 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
       for (int i = 0; i < 16; ++i) oacc[nb][db][i] = 0.f;
   }
 
-  const int last_row = min(n, row0 + BM) - 1;
-  const int ntiles = last_row / kTile + 1;
+  const int last_key = off + min(n, row0 + BM) - 1;  // newest key the block's rows see
+  const int ntiles = last_key / kTile + 1;
   int k_loff[4], v_loff[4];
   dma_offsets<false>(k_loff);
   dma_offsets<true>(v_loff);
   auto fetch = [&](int t, lds_char* buf) {  // K tile t and V tile t into buf | buf + 16 KB
-    if ((t + 1) * kTile <= n) {
+    if ((t + 1) * kTile <= nk) {
       dma_full_tile(Kg, t * kTile, k_loff, buf);
       if (WITH_O) dma_full_tile(Vg, t * kTile, v_loff, buf + kTileBytes);
     } else {
-      dma_tile<false>(Kg, t * kTile, n, buf);
-      if (WITH_O) dma_tile<true>(Vg, t * kTile, n, buf + kTileBytes);
+      dma_tile<false>(Kg, t * kTile, nk, buf);
+      if (WITH_O) dma_tile<true>(Vg, t * kTile, nk, buf + kTileBytes);
     }
   };
   // a wave's loads complete in order: tile t has landed once at most the loads of the tiles
@@ -518,7 +528,7 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
 
   auto tile_step = [&](int t, const lds_char* kt, const lds_char* vt_) {
     const int key0 = t * kTile;
-    if (key0 > wrow0 + 32 * NB - 1) return;  // no key of the tile is visible to this wave
+    if (key0 > off + wrow0 + 32 * NB - 1) return;  // no key of the tile is visible to this wave
     f32x16 sacc[NB][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -546,18 +556,18 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
         if (i + kPrefetch < NF) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
     }
-    const bool diag = key0 + kTile - 1 > wrow0;  // tile reaches past the wave's first row
+    const bool diag = key0 + kTile - 1 > off + wrow0;  // tile reaches past the wave's first row
     uint4 pf[NB][2][2];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       if (diag) {  // causal mask
-        const int qrow = wrow0 + nb * 32 + l32;
+        const int newest = off + wrow0 + nb * 32 + l32;  // newest key this lane's row sees
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = key0 + kb * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-            if (key > qrow) sacc[nb][kb][i] = -INFINITY;
+            if (key > newest) sacc[nb][kb][i] = -INFINITY;
           }
       }
       if constexpr (!WITH_O) {
@@ -911,10 +921,26 @@ template <int D>
 void launch_fwd_rect(const void* q, const void* k, const void* v, int G, const AttnRect& rc, void* o,
                      float* lse2, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  const int GQ = G * rc.kv_group;  // query heads
+  if constexpr (D == 128) {
+    // direct-to-LDS tiles and transposing LDS reads; without outputs one row block per wave
+    const int nb = o ? 1 : kScoreOnlyNB;
+    const int nqb = (rc.m + kWaves * 32 * nb - 1) / (kWaves * 32 * nb);
+    const long long total = (long long)GQ * nqb;
+    const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
+    if (o)
+      hipLaunchKernelGGL((attn_fwd128_kernel<true, 1>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, rc, GQ,
+                         nqb, scale_log2e);
+    else
+      hipLaunchKernelGGL((attn_fwd128_kernel<false, kScoreOnlyNB>), dim3(grid), dim3(kThreads), 0, st,
+                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr, lse2,
+                         rc, GQ, nqb, scale_log2e);
+    return;
+  }
   constexpr int NB = kFwdNB;
   constexpr int BM = kWaves * 32 * NB;
   const int nqb = (rc.m + BM - 1) / BM;
-  const int GQ = G * rc.kv_group;  // query heads
   const long long total = (long long)GQ * nqb;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
   if (o)
@@ -932,8 +958,6 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
                 hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   if constexpr (D == 128) {
-    constexpr int NB = kFwdNB;
-    const int nqb = (n + kWaves * 32 * NB - 1) / (kWaves * 32 * NB);
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
     // the start and end of a row block: from n = 2048 with one workgroup per block, from
     // n = 512 in the persistent form, which overlaps them with the neighbouring blocks.
@@ -960,25 +984,11 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
         return;
       }
     }
-    if (o) {
-      const long long total = (long long)G * nqb;
-      const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-      hipLaunchKernelGGL((attn_fwd128_kernel<true, NB>), dim3(grid), dim3(kThreads), 0, st,
-                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
-                         G, nqb, scale_log2e);
-    } else {
-      // Without outputs the pass is bound by the vector ALU as much as by the matrix cores
-      // (fma + exp + add per logit against 1/16 matrix op): one 32-row block per wave at four
-      // workgroups per compute unit overlaps the two better than two blocks per wave at two
-      // (16384 heads of n = 2048: 11.1 ms against 12.75).
-      constexpr int NBL = kScoreOnlyNB;
-      const int nqbl = (n + kWaves * 32 * NBL - 1) / (kWaves * 32 * NBL);
-      const long long total = (long long)G * nqbl;
-      const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
-      hipLaunchKernelGGL((attn_fwd128_kernel<false, NBL>), dim3(grid), dim3(kThreads), 0, st,
-                         (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)nullptr,
-                         lse2, n, G, nqbl, scale_log2e);
-    }
+    // Without outputs the pass is bound by the vector ALU as much as by the matrix cores
+    // (fma + exp + add per logit against 1/16 matrix op): one 32-row block per wave at four
+    // workgroups per compute unit overlaps the two better than two blocks per wave at two
+    // (16384 heads of n = 2048: 11.1 ms against 12.75).
+    launch_fwd_rect<D>(q, k, v, G, AttnRect{n, n, nullptr}, o, lse2, st);
   } else {
     launch_fwd_rect<D>(q, k, v, G, AttnRect{n, n, nullptr}, o, lse2, st);
   }
@@ -1021,8 +1031,8 @@ struct RowWindow {
 
 __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
-    float* __restrict__ S, int n, int first_row, float log2_alpha,
-    const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
+    float* __restrict__ S, AttnRect rc, int s_stride, bool accumulate, float decay, int first_row,
+    float log2_alpha, const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
   __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
   lds_char* const qs = (lds_char*)smem;
@@ -1031,10 +1041,16 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
+  // n query rows; row i sees keys 0 .. off + i of the head's nk = off + n keys (the prompt
+  // phase: off = 0; a chunk of a prompt: off = tokens cached before it)
+  const int n = rc.m;
+  const int off = rc.off_heads ? rc.off_heads[g] : 0;
+  if (off < 0) return;  // a head the caller's precondition excludes
+  const int nk = off + n;
   const bf16_t* Qg = Q + (size_t)g * n * D;
-  const bf16_t* Kg = K + (size_t)g * n * D;
+  const bf16_t* Kg = K + (size_t)g * rc.kv_stride * D;
   const float* lse = LSE2 + (size_t)g * n;
-  float* Sg = S + (size_t)g * n;
+  float* Sg = S + (size_t)g * s_stride;
 
   const int r_lo = (first_row / kTile) * kTile;          // first staged row (sized by the host)
   head_window(alpha_heads, g, n, first_row, log2_alpha);  // this head's own window inside it
@@ -1063,7 +1079,7 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b) {
       int r = c0 + (wave * kTailKB + b) * 32 + l32;
-      r = r < n ? r : n - 1;
+      r = r < nk ? r : nk - 1;
 #pragma unroll
       // (plain loads: a lane takes 32 bytes of its key's row per instruction, so every 128-byte
       // line is shared by four instructions and has to stay in the cache between them)
@@ -1079,10 +1095,10 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   const int rb_last = (n - 1 - r_lo) >> 5;   // the row block that holds the newest row
   const int lane_last = (n - 1 - r_lo) & 31;
   constexpr int STEP = BC * kTailKB;  // keys per workgroup step
-  for (int c0 = 0; c0 < n; c0 += STEP) {
+  for (int c0 = 0; c0 < nk; c0 += STEP) {
     const int wc0 = c0 + wave * kTailKB * 32;  // first key of this wave in this step
-    int lim = max(wc0, first_row);             // rows before `lim` add nothing to this wave's keys
-    bool pending = c0 + STEP < n;              // the next step's keys still have to be fetched
+    int lim = max(wc0 - off, first_row);       // rows before `lim` add nothing to this wave's keys
+    bool pending = c0 + STEP < nk;             // the next step's keys still have to be fetched
     float acc[kTailKB][16];
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b)
@@ -1122,12 +1138,12 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
 #pragma unroll
         for (int b = 0; b < kTailKB; ++b) {
           const int bk0 = wc0 + b * 32;
-          if (bk0 + 31 > rr0) {  // block touches the diagonal: keys above the row contribute 0
+          if (bk0 + 31 > off + rr0) {  // block touches the diagonal: keys above the row contribute 0
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               const int key = bk0 + 8 * (i >> 2) + 4 * h + (i & 3);
               const float p = fast_exp2(fmaf(sacc[b][i], scale_log2e, -bias[rb]));
-              acc[b][i] += key > r ? 0.f : p;
+              acc[b][i] += key > off + r ? 0.f : p;
             }
           } else {
 #pragma unroll
@@ -1146,7 +1162,8 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int key = wc0 + b * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-          if (key < n) Sg[key] = acc[b][i];
+          // `accumulate`: on top of `decay` times the older score (a chunk: alpha^n)
+          if (key < nk) Sg[key] = accumulate ? fmaf(decay, Sg[key], acc[b][i]) : acc[b][i];
         }
       }
     }
@@ -1322,6 +1339,15 @@ void launch_cols_rect(const void* q, const void* k, const float* lse2, int G, co
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   float l2a;
   const int first = first_contributing_row(rc.m, alpha, &l2a);
+  if constexpr (D == 128) {
+    // a row window of at most four tiles: staged once per head, every key streamed once
+    if (rc.kv_group == 1 && rc.m - (first / kTile) * kTile <= kTailTiles * kTile) {
+      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
+                         (const bf16_t*)k, lse2, scores, rc, s_stride, accumulate, decay, first, l2a,
+                         alpha_heads, scale_log2e, 0.f);
+      return;
+    }
+  }
   const int ncb = (keys_per_head + kWaves * 32 - 1) / (kWaves * 32);
   const long long total = (long long)G * ncb;
   const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
@@ -1339,7 +1365,8 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
   if constexpr (D == 128) {
     if (n - (first / kTile) * kTile <= kTailTiles * kTile) {
       hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
-                         (const bf16_t*)k, lse2, scores, n, first, l2a, alpha_heads, scale_log2e, tol);
+                         (const bf16_t*)k, lse2, scores, AttnRect{n, n, nullptr}, n, false, 0.f, first, l2a,
+                         alpha_heads, scale_log2e, tol);
       return;
     }
     constexpr int BC = kWaves * 32 * kStreamKB;
