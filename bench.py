@@ -135,16 +135,28 @@ def chunked_prompt(w, alpha, m):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps
-    flops, cached = 0, 0
+    # Model flops, and the bytes a chunk cannot avoid: its Q, K, V rows read and its outputs written,
+    # the cached K/V rows read once, the rows the head keeps written once.  A chunk of a few hundred
+    # tokens against a budget of the same order has far fewer flops per byte than the machine
+    # (2500 TFLOP/s : 8 TB/s = 312): the bound that applies is reported first.
+    e = 4 if w.dtype == "f32" else 2
+    flops, nbytes, cached = 0, 0, 0
     for a, mm in chunks:
         flops += G * 2 * 2 * d * (mm * cached + mm * (mm + 1) // 2)
-        cached = min(cached + mm, w.budget)
+        kept = min(cached + mm, w.budget)
+        nbytes += G * d * e * (4 * mm + 2 * cached + 2 * kept)
+        cached = kept
     tf = flops / ms / 1e9
+    gbs = nbytes / ms / 1e6
+    mfma = {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": tf / MFMA_BF16_PEAK_TFLOPS}
+    hbm = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+    hbm_bound = flops / nbytes < MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS
     print(json.dumps({"kernel": "a2sf_prefill_chunk", "workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n,
                       "chunk": m, "budget": f"{w.select}+{w.recent}", "alpha": alpha, "dtype": w.dtype,
-                      "ms_per_prompt": ms, "flops_model": flops,
-                      "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                                   "frac": tf / MFMA_BF16_PEAK_TFLOPS}}), flush=True)
+                      "ms_per_prompt": ms, "flops_model": flops, "bytes_compulsory": nbytes,
+                      "flops_per_byte": flops / nbytes,
+                      "roofline": hbm if hbm_bound else mfma, "roofline_other": mfma if hbm_bound else hbm}), flush=True)
 
 
 def grouped_query_step(w, alpha, group, steps=60):

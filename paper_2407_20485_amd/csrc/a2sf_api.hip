@@ -240,10 +240,14 @@ a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int3
   int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
   int32_t* n_keep = (int32_t*)(ws + w.n_keep);
   const int G = cache->G, d = cache->d, C = cache->capacity;
-  const AttnRect rc{m, C, len_old};
+  AttnRect rc{m, C, len_old};
   const float decay = alpha > 0.f ? powf(alpha, (float)m) : 0.f;   // 0^m = 0 for m >= 1
+  // Where the kernels can read the chunk's K/V rows from the call's inputs, the rows are not
+  // copied behind the cached ones first: the compaction copies in those that are kept.
+  const bool two_source = cache->dtype == A2SF_BF16 && bf16_two_source_ok(d, rc, alpha);
+  if (two_source) { rc.k2 = k; rc.v2 = v; }
 
-  launch_chunk_append(k, v, m, pos0, *cache, len_old, st);
+  launch_chunk_append(k, v, m, pos0, *cache, len_old, !two_source, st);
   if (cache->dtype == A2SF_F32) {
     launch_attn_f32((const float*)q, (const float*)cache->k, (const float*)cache->v, G, rc, d,
                     (float*)o, lse2, st);
@@ -255,7 +259,10 @@ a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int3
   }
   launch_select(cache->scores, cache->pos, cache->len, G, C, C, budget.select, budget.recent,
                 keep_idx, n_keep, st);
-  launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
+  if (two_source)
+    launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st, k, v, m, len_old);
+  else
+    launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
   return launch_status();
 }
 

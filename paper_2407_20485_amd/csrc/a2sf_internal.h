@@ -13,8 +13,11 @@ namespace a2sf {
 void launch_select(const float* scores, const int32_t* pos, const int32_t* len, int G, int L,
                    int stride, int select, int recent, int32_t* keep_idx, int32_t* n_keep,
                    hipStream_t st);
+// k2 / v2 [G, m2, d] set: the rows of the slots from off_heads[g] on are taken from there
+// (a chunk whose rows were not copied into the cache)
 void launch_compact(const a2sf_cache& c, const int32_t* keep_idx, int keep_stride,
-                    const int32_t* n_keep, hipStream_t st);
+                    const int32_t* n_keep, hipStream_t st, const void* k2 = nullptr,
+                    const void* v2 = nullptr, int m2 = 0, const int32_t* off_heads = nullptr);
 // Out-of-place gather of the prompt's surviving rows into the cache.
 void launch_gather_prompt(const void* k, const void* v, const float* scores_full, int n,
                           const int32_t* keep_idx, int keep_stride, const int32_t* n_keep,
@@ -43,7 +46,7 @@ void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int 
 // chunk.hip: the chunk's K/V rows go behind each head's cached tokens (len grows by m, the old
 // lengths are left in len_old, -1 where the chunk does not fit)
 void launch_chunk_append(const void* k, const void* v, int m, int pos0, const a2sf_cache& c,
-                         int32_t* len_old, hipStream_t st);
+                         int32_t* len_old, bool copy_rows, hipStream_t st);
 
 // similarity.hip: cosine between the policy's attention row (cache positions + the new token)
 // and the Ideal row over the first L rows of k_all, per head.
@@ -65,7 +68,15 @@ struct AttnRect {
   int kv_stride;
   const int32_t* off_heads;  // [G] device, or null: 0 for every head
   int kv_group = 1;
+  // Second source of key / value rows (bf16, d = 128, kv_group = 1 only): when set, a head's
+  // keys 0 .. off-1 are rows of k / v and its keys off .. off+m-1 are the m rows [G, m, d] of
+  // k2 / v2 -- a chunk whose rows have not been copied behind the cached ones.
+  const void* k2 = nullptr;
+  const void* v2 = nullptr;
 };
+// true when launch_attn_bf16 / launch_colscores_bf16 serve these sizes with kernels that read a
+// second key / value source
+bool bf16_two_source_ok(int d, const AttnRect& rc, float alpha);
 
 // prefill_f32.hip / prefill_bf16.hip
 // lse2[g][i] = log2(sum_j exp(s_ij)) of the masked row i (s already scaled by 1/sqrt(d)).

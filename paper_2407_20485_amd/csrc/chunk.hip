@@ -13,7 +13,9 @@ namespace {
 // One workgroup per head: rows len .. len+m-1 of the cache receive the chunk's K/V rows, position
 // pos0 + i and score 0; len grows by m; len_old[g] keeps the old length for the kernels that
 // follow (-1 for a head without room for the chunk, which is left untouched).
-template <int ROW_UNITS>  // 16-byte units per K (or V) row
+// COPY_ROWS = false: positions, scores and lengths only; the kernels that follow read the
+// chunk's rows from the call's inputs, and the compaction copies those that are kept.
+template <int ROW_UNITS, bool COPY_ROWS>  // 16-byte units per K (or V) row
 __global__ __launch_bounds__(kThreads) void chunk_append_kernel(
     const uint4* __restrict__ kin, const uint4* __restrict__ vin, int m, int pos0,
     uint4* __restrict__ K, uint4* __restrict__ V, float* __restrict__ S, int32_t* __restrict__ P,
@@ -30,9 +32,11 @@ __global__ __launch_bounds__(kThreads) void chunk_append_kernel(
   const size_t src0 = (size_t)g * m * ROW_UNITS;
   const size_t dst0 = ((size_t)g * capacity + L) * ROW_UNITS;
   const int units = m * ROW_UNITS;
-  for (int u = tid; u < units; u += kThreads) {
-    K[dst0 + u] = kin[src0 + u];
-    V[dst0 + u] = vin[src0 + u];
+  if (COPY_ROWS) {
+    for (int u = tid; u < units; u += kThreads) {
+      K[dst0 + u] = kin[src0 + u];
+      V[dst0 + u] = vin[src0 + u];
+    }
   }
   for (int i = tid; i < m; i += kThreads) {
     S[(size_t)g * capacity + L + i] = 0.f;
@@ -43,16 +47,22 @@ __global__ __launch_bounds__(kThreads) void chunk_append_kernel(
 }  // namespace
 
 void launch_chunk_append(const void* k, const void* v, int m, int pos0, const a2sf_cache& c,
-                         int32_t* len_old, hipStream_t st) {
+                         int32_t* len_old, bool copy_rows, hipStream_t st) {
   const int ru = c.d * (c.dtype == A2SF_BF16 ? 2 : 4) / 16;
-#define A2SF_APPEND(RU)                                                                           \
-  hipLaunchKernelGGL(chunk_append_kernel<RU>, dim3(c.G), dim3(kThreads), 0, st, (const uint4*)k,  \
-                     (const uint4*)v, m, pos0, (uint4*)c.k, (uint4*)c.v, c.scores, c.pos, c.len,  \
-                     c.capacity, len_old)
+#define A2SF_APPEND_(RU, COPY)                                                                    \
+  hipLaunchKernelGGL((chunk_append_kernel<RU, COPY>), dim3(c.G), dim3(kThreads), 0, st,           \
+                     (const uint4*)k, (const uint4*)v, m, pos0, (uint4*)c.k, (uint4*)c.v,         \
+                     c.scores, c.pos, c.len, c.capacity, len_old)
+#define A2SF_APPEND(RU)                \
+  do {                                 \
+    if (copy_rows) A2SF_APPEND_(RU, true); \
+    else A2SF_APPEND_(RU, false);      \
+  } while (0)
   if (ru == 8) A2SF_APPEND(8);
   else if (ru == 16) A2SF_APPEND(16);
   else A2SF_APPEND(32);
 #undef A2SF_APPEND
+#undef A2SF_APPEND_
 }
 
 }  // namespace a2sf

@@ -398,6 +398,27 @@ __device__ __forceinline__ void dma_tile(const bf16_t* __restrict__ Mg, int row0
   }
 }
 
+// dma_tile for a tile that straddles two sources: rows below `off` are rows of A, rows from
+// `off` on are rows 0 .. of B (n rows in all).
+template <bool V_LAYOUT>
+__device__ __forceinline__ void dma_tile2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                          int off, int row0, int n, lds_char* tile) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int rr = lane >> 4, pc = lane & 15;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int lrow = (u * 4 + wave) * 4 + rr;
+    const int c = pc ^ (V_LAYOUT ? v_swizzle(lrow) : k_swizzle(lrow));
+    int r = row0 + lrow;
+    r = r < n ? r : n - 1;
+    const bf16_t* src = r < off ? A + (size_t)r * 128 : B + (size_t)(r - off) * 128;
+    __builtin_amdgcn_global_load_lds((const void*)(src + c * 8),
+                                     (__attribute__((address_space(3))) void*)(tile + (u * 4 + wave) * 1024),
+                                     16, 0, 0);
+  }
+}
+
 // Same as dma_tile for a tile that lies completely inside the matrix: the per-lane byte
 // offsets `loff` (row-in-tile and swizzled chunk) are loop invariants, the tile base is
 // wave-uniform, so a tile costs four load instructions and no address arithmetic per lane.
@@ -462,6 +483,9 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)gk * rc.kv_stride * D;
   const bf16_t* Vg = V + (size_t)gk * rc.kv_stride * D;
+  // second source (keys off .. off+n-1), or null
+  const bf16_t* K2g = rc.k2 ? (const bf16_t*)rc.k2 + (size_t)gk * n * D : nullptr;
+  const bf16_t* V2g = rc.k2 ? (const bf16_t*)rc.v2 + (size_t)gk * n * D : nullptr;
   const int wrow0 = row0 + wave * 32 * NB;  // first query row of this wave
 
   // Q fragments (B operand): lane (query l32, half h) holds Q[query][16kk + 8h .. +7]
@@ -504,6 +528,16 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
   dma_offsets<false>(k_loff);
   dma_offsets<true>(v_loff);
   auto fetch = [&](int t, lds_char* buf) {  // K tile t and V tile t into buf | buf + 16 KB
+    if (K2g && (t + 1) * kTile > off) {       // the tile holds rows of the second source
+      if (t * kTile >= off && (t + 1) * kTile <= nk) {
+        dma_full_tile(K2g, t * kTile - off, k_loff, buf);
+        if (WITH_O) dma_full_tile(V2g, t * kTile - off, v_loff, buf + kTileBytes);
+      } else {
+        dma_tile2<false>(Kg, K2g, off, t * kTile, nk, buf);
+        if (WITH_O) dma_tile2<true>(Vg, V2g, off, t * kTile, nk, buf + kTileBytes);
+      }
+      return;
+    }
     if ((t + 1) * kTile <= nk) {
       dma_full_tile(Kg, t * kTile, k_loff, buf);
       if (WITH_O) dma_full_tile(Vg, t * kTile, v_loff, buf + kTileBytes);
@@ -1049,6 +1083,7 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   const int nk = off + n;
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)g * rc.kv_stride * D;
+  const bf16_t* K2g = rc.k2 ? (const bf16_t*)rc.k2 + (size_t)g * n * D : nullptr;  // keys off .. from here
   const float* lse = LSE2 + (size_t)g * n;
   float* Sg = S + (size_t)g * s_stride;
 
@@ -1080,10 +1115,11 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     for (int b = 0; b < kTailKB; ++b) {
       int r = c0 + (wave * kTailKB + b) * 32 + l32;
       r = r < nk ? r : nk - 1;
+      const bf16_t* row = (K2g && r >= off) ? K2g + (size_t)(r - off) * D : Kg + (size_t)r * D;
 #pragma unroll
       // (plain loads: a lane takes 32 bytes of its key's row per instruction, so every 128-byte
       // line is shared by four instructions and has to stay in the cache between them)
-      for (int kk = 0; kk < KK; ++kk) kf[b][kk] = load16(Kg + (size_t)r * D + kk * 16 + h * 8);
+      for (int kk = 0; kk < KK; ++kk) kf[b][kk] = load16(row + kk * 16 + h * 8);
     }
   };
   uint4 kf[kTailKB][KK];
@@ -1341,7 +1377,7 @@ void launch_cols_rect(const void* q, const void* k, const float* lse2, int G, co
   const int first = first_contributing_row(rc.m, alpha, &l2a);
   if constexpr (D == 128) {
     // a row window of at most four tiles: staged once per head, every key streamed once
-    if (rc.kv_group == 1 && rc.m - (first / kTile) * kTile <= kTailTiles * kTile) {
+    if (bf16_two_source_ok(D, rc, alpha)) {  // (also the only score kernel that reads a second key source)
       hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
                          (const bf16_t*)k, lse2, scores, rc, s_stride, accumulate, decay, first, l2a,
                          alpha_heads, scale_log2e, 0.f);
@@ -1382,6 +1418,13 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
 }
 
 }  // namespace
+
+bool bf16_two_source_ok(int d, const AttnRect& rc, float alpha) {
+  if (d != 128 || rc.kv_group != 1) return false;
+  float l2a;
+  const int first = first_contributing_row(rc.m, alpha, &l2a);
+  return rc.m - (first / kTile) * kTile <= kTailTiles * kTile;  // the staged-window score kernel
+}
 
 void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const AttnRect& rc, int d,
                       void* o, float* lse2, hipStream_t st) {

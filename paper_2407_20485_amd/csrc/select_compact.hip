@@ -164,19 +164,28 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
 // keep[r].  Rows are processed in ascending chunks; inside a chunk every source row is in
 // registers before (barrier) any destination row is written.  A later chunk's sources lie
 // at or beyond its own destinations, i.e. beyond everything written so far.
+// Second source (kin != null): the K/V rows of the slots from off_heads[g] on have not been
+// stored in the cache yet; they are rows 0 .. m-1 of kin / vin [G, m, ...] (a chunk of a
+// prompt).  Kept rows among them are copied in; they follow every kept cached row, so no
+// cached row that is still to be moved lies at or behind their destinations.
 template <int ROW_UNITS>  // 16-byte units per K (or V) row
 __global__ __launch_bounds__(kThreads) void compact_kernel(
     uint4* __restrict__ K, uint4* __restrict__ V, float* __restrict__ S, int32_t* __restrict__ P,
     int32_t* __restrict__ len, int capacity, const int32_t* __restrict__ keep_idx, int keep_stride,
-    const int32_t* __restrict__ n_keep) {
+    const int32_t* __restrict__ n_keep, const uint4* __restrict__ kin, const uint4* __restrict__ vin,
+    int m, const int32_t* __restrict__ off_heads) {
   constexpr int U = 4;                                  // units per thread per chunk
   constexpr int CH = kThreads * U / ROW_UNITS;          // rows per chunk
   const int g = blockIdx.x, tid = threadIdx.x;
   int nk = n_keep[g];
   nk = nk < 0 ? 0 : (nk > capacity ? capacity : nk);
   nk = nk > keep_stride ? keep_stride : nk;
+  const int off = kin ? off_heads[g] : capacity;  // slots from here on live in the second source
+  if (off < 0) return;                            // a head the chunk did not fit into: untouched
   // as many strictly ascending indices of valid slots as there are valid slots: the identity
-  if (nk == len[g]) return;
+  if (!kin && nk == len[g]) return;
+  const uint4* king = kin ? kin + (size_t)g * m * ROW_UNITS : nullptr;
+  const uint4* ving = kin ? vin + (size_t)g * m * ROW_UNITS : nullptr;
   const int32_t* keep = keep_idx + (size_t)g * keep_stride;
   uint4* Kg = K + (size_t)g * capacity * ROW_UNITS;
   uint4* Vg = V + (size_t)g * capacity * ROW_UNITS;
@@ -196,7 +205,12 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(
       if (r < nk) {
         int src = keep[r];
         src = src < 0 ? 0 : (src >= capacity ? capacity - 1 : src);
-        if (src != r) {
+        if (src >= off) {
+          const int r2 = src - off < m ? src - off : m - 1;
+          mv[u] = true;
+          kr[u] = king[r2 * ROW_UNITS + c];
+          vr[u] = ving[r2 * ROW_UNITS + c];
+        } else if (src != r) {
           mv[u] = true;
           kr[u] = Kg[src * ROW_UNITS + c];
           vr[u] = Vg[src * ROW_UNITS + c];
@@ -257,12 +271,13 @@ void launch_select(const float* scores, const int32_t* pos, const int32_t* len, 
 }
 
 void launch_compact(const a2sf_cache& c, const int32_t* keep_idx, int keep_stride,
-                    const int32_t* n_keep, hipStream_t st) {
+                    const int32_t* n_keep, hipStream_t st, const void* k2, const void* v2, int m2,
+                    const int32_t* off_heads) {
   const int ru = row_units(c.d, c.dtype);
 #define A2SF_COMPACT(RU)                                                                        \
   hipLaunchKernelGGL(compact_kernel<RU>, dim3(c.G), dim3(kThreads), 0, st, (uint4*)c.k,         \
                      (uint4*)c.v, c.scores, c.pos, c.len, c.capacity, keep_idx, keep_stride,    \
-                     n_keep)
+                     n_keep, (const uint4*)k2, (const uint4*)v2, m2, off_heads)
   if (ru == 8) A2SF_COMPACT(8);
   else if (ru == 16) A2SF_COMPACT(16);
   else A2SF_COMPACT(32);
