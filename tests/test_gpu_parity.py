@@ -484,6 +484,8 @@ def test_strong_sink_stays_in_the_cache(say):
     (0, 128, 0, (48, 100, 1), (30, 30)),             # fp32 d=128, the first chunk goes into an empty cache
     (1, 128, 0, (256, 200), (100, 100)),             # bf16, empty cache, budget reached inside the second chunk
     (1, 128, 300, (20, 20), (400, 0)),               # budget never binds: the cache only grows
+    (1, 128, 100, (300, 40), (50, 50)),              # bf16 d=128, a chunk longer than the score pass's staged window
+                                                     # (alpha = 1: rows copied behind the cache first; else read in place)
 ])
 @pytest.mark.parametrize("alpha", [0.0, 0.4, 1.0])
 def test_prefill_chunks_match_oracle(base, d, n0, chunks, budget, alpha, say):
