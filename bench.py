@@ -194,10 +194,36 @@ def grouped_query_step(w, alpha, group, steps=60):
     us = e0.elapsed_time(e1) * 1e3 / steps
     L = B + 1
     nbytes = G * (2 * L * d * e + 8 * L + (2 * group + 2) * d * e)
+    # the prompt phase of the same grouping (random rows; model flops as for the plain prompt phase:
+    # every query head has its own QK^T and PV sweep)
+    n = w.n
+    del q, kn, vn, o
+    code = a2sf.A2SF_F32 if w.dtype == "f32" else a2sf.A2SF_BF16
+    qp = torch.randn(G, group, n, d, device="cuda").to(tdt)
+    kp, vp = (torch.randn(G, n, d, device="cuda").to(tdt) for _ in range(2))
+    op = torch.empty_like(qp)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, n, cap, d, code, w.select, w.recent), dtype=torch.uint8,
+                     device="cuda")
+
+    def prompt():
+        a2sf.a2sf_prefill_gqa(qp, kp, vp, n, group, alpha, w.select, w.recent, c, o=op, workspace=ws)
+    prompt()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(3):
+        prompt()
+    e1.record()
+    torch.cuda.synchronize()
+    pre_ms = e0.elapsed_time(e1) / 3
+    flops = prefill_model_flops(G * group, n, d, with_o=True)
     print(json.dumps({"kernel": "a2sf_decode_step_gqa", "kv_heads": G, "group": group, "slots": L, "head_dim": d,
                       "dtype": w.dtype, "us_per_step": us, "bytes_per_step": nbytes,
                       "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                   "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
+                                   "frac": nbytes / us / 1e3 / HBM_PEAK_GBS},
+                      "prefill_gqa_ms": pre_ms, "prompt": n,
+                      "roofline_prefill": {"kernel": "a2sf_prefill_gqa", "bound": "mfma", "achieved": flops / pre_ms / 1e9,
+                                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                           "frac": flops / pre_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS}}), flush=True)
 
 
 def cpu_baseline(w, alpha, budget_s=12.0):

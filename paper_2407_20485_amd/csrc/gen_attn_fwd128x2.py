@@ -568,7 +568,9 @@ def look_ahead():
             f"s_cselect_b32 s{HASNEXT}, 1, 0",
             f"s_cselect_b32 s{SGN}, s{PAIR}, s{SG}",
             f"s_cselect_b32 s{SQBN}, s{ST1}, s{SQB}",
-            f"s_mul_i32 s{SHEAD}, s{SGN}, %[n]"] + pointer(KPN, "k", SHEAD, 8) + pointer(VPN, "v", SHEAD, 8)
+            # K/V head = query head >> %[kvs] (grouped-query heads; 0 = one K/V head per query head)
+            f"s_lshr_b32 s{SHEAD}, s{SGN}, %[kvs]",
+            f"s_mul_i32 s{SHEAD}, s{SHEAD}, %[n]"] + pointer(KPN, "k", SHEAD, 8) + pointer(VPN, "v", SHEAD, 8)
 
 
 def next_block():
@@ -599,7 +601,8 @@ def setup(out):
     out.e(f"s_mov_b32 s{SG}, %[g0]")
     out.e(f"s_mov_b32 s{SQB}, %[qb0]")
     out.ext(q_pointers() + q_loads())
-    out.e(f"s_mul_i32 s{SHEAD}, s{SG}, %[n]")
+    out.e(f"s_lshr_b32 s{SHEAD}, s{SG}, %[kvs]")
+    out.e(f"s_mul_i32 s{SHEAD}, s{SHEAD}, %[n]")
     out.ext(pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8))
     out.ext(look_ahead())
     out.e(f"s_lshl_b32 s{NTMAX}, s{SQB}, 2")

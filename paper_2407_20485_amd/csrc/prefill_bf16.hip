@@ -773,7 +773,8 @@ constexpr int kX2Slots = 32;             // persistent launch: workgroups per XC
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int nqb, int id_base, int ids,
-    int rounds, float scale_log2e) {
+    int rounds, int kv_shift, float scale_log2e) {
+  // kv_shift: query head g reads the keys and values of K/V head g >> kv_shift (grouped-query heads)
   __shared__ __attribute__((aligned(1024))) char smem[kX2LdsBytes];
   // this launch covers the ids id_base .. id_base + ids - 1; id = head * nqb + block position
   int vid0;
@@ -834,7 +835,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
                  [llo] "s"((unsigned)la), [lhi] "s"((unsigned)(la >> 32)),
                  [n] "s"(n), [g0] "s"(g0), [qb0] "s"(qb0), [vid0] "s"(vid0), [rounds] "s"(rounds),
                  [lgnqb] "s"(lgnqb), [nqbm1] "s"(nqbm1), [w32a] "s"(w32a), [w32b] "s"(w32b),
-                 [wodd] "s"(wodd), [wave_lds] "s"(wave_lds), [scale] "s"(scale_log2e)
+                 [wodd] "s"(wodd), [wave_lds] "s"(wave_lds), [kvs] "s"(kv_shift),
+                 [scale] "s"(scale_log2e)
                : A2SF_FWD128X2_CLOBBERS);
 }
 
@@ -987,15 +989,19 @@ void launch_fwd_rect(const void* q, const void* k, const void* v, int G, const A
                        rc, GQ, nqb, scale_log2e);
 }
 
+// Square geometry (a whole prompt): G K/V heads, kv_group query heads each.
 template <int D>
-void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void* o, float* lse2,
-                hipStream_t st) {
+void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, void* o, float* lse2,
+                hipStream_t st, int kv_group = 1) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  const int G = G_kv * kv_group;  // query heads
+  int kv_shift = 0;
+  while ((1 << kv_shift) < kv_group) ++kv_shift;
   if constexpr (D == 128) {
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
     // the start and end of a row block: from n = 2048 with one workgroup per block, from
     // n = 512 in the persistent form, which overlaps them with the neighbouring blocks.
-    if (o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31)) {
+    if (o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31) && (1 << kv_shift) == kv_group) {
       const int nqb2 = n / kX2Rows;
       const long long items = (long long)G * nqb2;
       // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
@@ -1007,7 +1013,7 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
           const unsigned grid2 = rounds > 1 ? 8 * kX2Slots : (unsigned)(((ids + 7) / 8) * 8);
           hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st,
                              (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
-                             nqb2, id_base, ids, rounds, scale_log2e);
+                             nqb2, id_base, ids, rounds, kv_shift, scale_log2e);
         };
         // persistent part: an even number of full rounds; what is left over goes one workgroup
         // per row block
@@ -1022,9 +1028,9 @@ void launch_fwd(const void* q, const void* k, const void* v, int G, int n, void*
     // (fma + exp + add per logit against 1/16 matrix op): one 32-row block per wave at four
     // workgroups per compute unit overlaps the two better than two blocks per wave at two
     // (16384 heads of n = 2048: 11.1 ms against 12.75).
-    launch_fwd_rect<D>(q, k, v, G, AttnRect{n, n, nullptr}, o, lse2, st);
+    launch_fwd_rect<D>(q, k, v, G_kv, AttnRect{n, n, nullptr, kv_group}, o, lse2, st);
   } else {
-    launch_fwd_rect<D>(q, k, v, G, AttnRect{n, n, nullptr}, o, lse2, st);
+    launch_fwd_rect<D>(q, k, v, G_kv, AttnRect{n, n, nullptr, kv_group}, o, lse2, st);
   }
 }
 
@@ -1428,7 +1434,10 @@ bool bf16_two_source_ok(int d, const AttnRect& rc, float alpha) {
 
 void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const AttnRect& rc, int d,
                       void* o, float* lse2, hipStream_t st) {
+  // a whole prompt (every head's keys are its own rows): the kernels chosen for the prompt phase
+  const bool square = !rc.off_heads && !rc.k2 && rc.kv_stride == rc.m;
   if (d == 64) launch_fwd_rect<64>(q, k, v, G, rc, o, lse2, st);
+  else if (square) launch_fwd<128>(q, k, v, G, rc.m, o, lse2, st, rc.kv_group);
   else launch_fwd_rect<128>(q, k, v, G, rc, o, lse2, st);
 }
 

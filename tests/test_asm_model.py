@@ -236,7 +236,7 @@ class Wave:
     def ds_write_b64(self, a): pass
 
 
-def run_workgroup(program, n, G, rounds, block_x, seed=None):
+def run_workgroup(program, n, G, rounds, block_x, seed=None, kvs=0):
     """Runs one workgroup of a launch over G heads of n rows; returns its four waves."""
     prog, labels = program
     nqb = n // 256
@@ -253,7 +253,7 @@ def run_workgroup(program, n, G, rounds, block_x, seed=None):
         operands = dict(qlo=QBASE & M32, qhi=QBASE >> 32, klo=KBASE & M32, khi=KBASE >> 32,
                         vlo=VBASE & M32, vhi=VBASE >> 32, olo=OBASE & M32, ohi=OBASE >> 32,
                         llo=LBASE & M32, lhi=LBASE >> 32, n=n, g0=vid0 // nqb, qb0=nqb - 1 - vid0 % nqb,
-                        vid0=vid0, rounds=rounds, lgnqb=nqb.bit_length() - 1, nqbm1=nqb - 1,
+                        vid0=vid0, rounds=rounds, lgnqb=nqb.bit_length() - 1, nqbm1=nqb - 1, kvs=kvs,
                         w32a=32 * w, w32b=32 * (7 - w), wodd=w & 1, wave_lds=1024 * w, scale=0,
                         hx16=0, krow=0, clvs16=0, vrow=0, kl0=0, vl0=0, qoff=0, lv=0, l32x4=0,
                         lanex16=0, strip_w=0, x16=0, crr16=0, strip_r=0)
@@ -272,7 +272,7 @@ def block_of(vid0, j, nqb):
     return vid // nqb, (pos if j & 1 else nqb - 1 - pos)
 
 
-def check_workgroup(waves, vid0, n, G, rounds):
+def check_workgroup(waves, vid0, n, G, rounds, kvs=0):
     nqb = n // 256
     blocks = [block_of(vid0, j, nqb) for j in range(rounds)]
     assert len({wv.epoch for wv in waves}) == 1
@@ -281,11 +281,11 @@ def check_workgroup(waves, vid0, n, G, rounds):
     for wv in waves:
         for ev in wv.dma:
             for kind, base in (("K", KBASE), ("V", VBASE)):
-                if base <= ev["global"] < base + G * n * 256:
+                if base <= ev["global"] < base + (G >> kvs) * n * 256:
                     rel = ev["global"] - base
                     head, inside = divmod(rel, n * 256)
                     tile, within = divmod(inside, 16384)
-                    assert within % 4096 == 1024 * wv.wave and ev["global"] + 1024 <= base + G * n * 256
+                    assert within % 4096 == 1024 * wv.wave and ev["global"] + 1024 <= base + (G >> kvs) * n * 256
                     stage, slot = divmod(ev["lds"], 32768)
                     assert 0 <= ev["lds"] < RING, "direct-to-LDS load outside the stage ring"
                     assert (slot >= 16384) == (kind == "V") and slot % 16384 == within, (kind, slot, within)
@@ -318,7 +318,7 @@ def check_workgroup(waves, vid0, n, G, rounds):
                 last = mine[-1]
                 if want >= nt and rd["round"] + 1 >= rounds:
                     continue        # run-ahead fragments past the last block: never used
-                assert (last["head"], last["tile"]) == (head, tile), (rd, last)
+                assert (last["head"], last["tile"]) == (head >> kvs, tile), (rd, last)   # K/V head of the query head
                 assert last["retired"] is not None and last["retired"] < rd["epoch"], (rd, last)
     # ---- Q rows, O rows, log-sum-exp rows
     for wv in waves:
@@ -354,6 +354,21 @@ CASES = [  # n, G, rounds, workgroup
 def test_stream_model(program, n, G, rounds, block_x):
     waves, vid0 = run_workgroup(program, n, G, rounds, block_x)
     check_workgroup(waves, vid0, n, G, rounds)
+
+
+@pytest.mark.parametrize("n,G,rounds,block_x,kvs", [(1024, 256, 4, 37, 2), (2048, 8, 1, 13, 3), (512, 512, 4, 129, 1)])
+def test_stream_model_grouped_query_heads(program, n, G, rounds, block_x, kvs):
+    """2^kvs query heads share a K/V head: Q rows, outputs and log-sum-exp rows go by the query
+    head, every K/V tile by the K/V head query head >> kvs."""
+    waves, vid0 = run_workgroup(program, n, G, rounds, block_x, kvs=kvs)
+    check_workgroup(waves, vid0, n, G, rounds, kvs=kvs)
+
+
+def test_model_catches_a_wrong_kv_head(program):
+    """Planted mistake: the K/V head is taken to be the query head although four of them share one."""
+    waves, vid0 = run_workgroup(program, 1024, 256, 4, 37, kvs=0)
+    with pytest.raises(AssertionError):
+        check_workgroup(waves, vid0, 1024, 256, 4, kvs=2)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])

@@ -839,12 +839,12 @@ def test_cfg2_grouped_query_full_size_sampled(cfg2_inputs, say):
     """The benchmark's grouped-query leg (bench.py --group 4) on the config's inputs: 4096 K/V
     heads (keys and values of every fourth head) with the four heads from there on as their query
     heads.  a2sf_prefill_gqa and 16 generation steps (one wave per K/V head) on all of them; 24
-    seeded K/V heads are replayed by the oracle: the last 64 prompt rows of every query head, the
+    seeded K/V heads are replayed by the oracle: every prompt row of every query head, the
     prompt scores, then outputs, scores and retained set of every step."""
     import oracle_replay
     w = CFG[2]
     p = cfg2_inputs(say)
-    R, T, rows = 4, 16, 64
+    R, T, rows = 4, 16, w.n
     Gk = w.G // R
     rng = np.random.default_rng(23)
     sample = sorted(rng.choice(Gk, 24, replace=False).tolist())
