@@ -298,16 +298,41 @@ a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_
   int32_t* n_keep = (int32_t*)(ws + w.n_keep);
   AttnRect rc{n, n, nullptr};
   rc.kv_group = group;
-  if (cache->dtype == A2SF_F32) {
-    launch_attn_f32((const float*)q, (const float*)k, (const float*)v, G, rc, d, (float*)o, lse2, st);
-    launch_colscores_f32((const float*)q, (const float*)k, lse2, G, rc, n, d, alpha, nullptr, s_full, n,
-                         false, 0.f, st);
-  } else {
-    launch_attn_bf16(q, k, v, G, rc, d, o, lse2, st);
-    launch_colscores_bf16(q, k, lse2, G, rc, n, d, alpha, s_full, n, false, 0.f, st);
+  // in parts of kPrefillPartHeads query heads, as the plain prompt phase and for the same reason
+  const size_t e = cache->dtype == A2SF_F32 ? 4 : 2;
+  const int B = budget.select + budget.recent;
+  const int part_kv = kPrefillPartHeads / group;   // K/V heads per part (group is 1, 2, 4 or 8)
+  const int part = (cache->dtype == A2SF_BF16 && G >= 2 * part_kv) ? part_kv : G;
+  for (int g0 = 0; g0 < G; g0 += part) {
+    const int Gp = G - g0 < part ? G - g0 : part;
+    const size_t kv0 = (size_t)g0 * n;          // first K/V row of the part
+    const size_t q0 = kv0 * group;              // first query / output / log-sum-exp row
+    const char* qp = (const char*)q + q0 * d * e;
+    const char* kp = (const char*)k + kv0 * d * e;
+    const char* vp = (const char*)v + kv0 * d * e;
+    void* op = o ? (char*)o + q0 * d * e : nullptr;
+    float* lp = lse2 + q0;
+    float* sp = s_full + kv0;
+    int32_t* kip = keep_idx + (size_t)g0 * B;
+    int32_t* nkp = n_keep + g0;
+    a2sf_cache cp = *cache;
+    cp.G = Gp;
+    cp.k = (char*)cache->k + (size_t)g0 * cache->capacity * d * e;
+    cp.v = (char*)cache->v + (size_t)g0 * cache->capacity * d * e;
+    cp.scores = cache->scores + (size_t)g0 * cache->capacity;
+    cp.pos = cache->pos + (size_t)g0 * cache->capacity;
+    cp.len = cache->len + g0;
+    if (cache->dtype == A2SF_F32) {
+      launch_attn_f32((const float*)qp, (const float*)kp, (const float*)vp, Gp, rc, d, (float*)op, lp, st);
+      launch_colscores_f32((const float*)qp, (const float*)kp, lp, Gp, rc, n, d, alpha, nullptr, sp, n,
+                           false, 0.f, st);
+    } else {
+      launch_attn_bf16(qp, kp, vp, Gp, rc, d, op, lp, st);
+      launch_colscores_bf16(qp, kp, lp, Gp, rc, n, d, alpha, sp, n, false, 0.f, st);
+    }
+    launch_select(sp, nullptr, nullptr, Gp, n, n, budget.select, budget.recent, kip, nkp, st);
+    launch_gather_prompt(kp, vp, sp, n, kip, B, nkp, cp, st);
   }
-  launch_select(s_full, nullptr, nullptr, G, n, n, budget.select, budget.recent, keep_idx, n_keep, st);
-  launch_gather_prompt(k, v, s_full, n, keep_idx, budget.select + budget.recent, n_keep, *cache, st);
   return launch_status();
 }
 
