@@ -126,6 +126,59 @@ __global__ __launch_bounds__(256) void sweep_heads(uint4* __restrict__ A, uint4*
   }
 }
 
+// The same traffic with the K and the V rows of the same slots requested together (what a
+// single-pass form of the step with a running softmax would do): twice the loads in flight per
+// wave, no gap between a K phase and a V phase.
+template <int U, bool SMALL>
+__global__ __launch_bounds__(256) void sweep_heads_together(uint4* __restrict__ A, uint4* __restrict__ B,
+                                                            int units, int heads, float* __restrict__ S,
+                                                            int slots, uint4* __restrict__ O, int launch,
+                                                            float* out) {
+  const int g = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (g >= heads) return;
+  const uint4* a = A + (size_t)g * units;
+  const uint4* b = B + (size_t)g * units;
+  float sv[4] = {0.f, 0.f, 0.f, 0.f};
+  if (SMALL) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = lane + 64 * k;
+      if (j < slots) sv[k] = S[(size_t)g * slots + j];
+    }
+  }
+  float acc = 0.f, acc2 = 0.f;
+  for (int i = lane; i < units; i += 64 * U) {
+    uint4 x[U], y[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = i + u * 64;
+      x[u] = ld16<true>(a + (j < units ? j : 0));
+      y[u] = ld16<true>(b + (j < units ? j : 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      acc += sum4(x[u]);
+      acc2 += acc * sum4(y[u]);
+    }
+  }
+  if (SMALL) {
+    for (int o = 32; o > 0; o >>= 1) acc2 += __shfl_xor(acc2, o, 64);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = lane + 64 * k;
+      if (j < slots - 1) S[(size_t)g * slots + j] = 0.5f * sv[k] + 1e-30f * acc2;
+    }
+    const int rows = units / 16;
+    const int v = (int)(((unsigned)g * 7u + (unsigned)launch * 13u) % (unsigned)rows);
+    const uint4 w = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, __float_as_uint(acc2) & 0x3f803f80u);
+    if (lane < 16) A[(size_t)g * units + v * 16 + lane] = w;
+    else if (lane < 32) B[(size_t)g * units + v * 16 + lane - 16] = w;
+    else if (lane < 48) O[(size_t)g * 16 + lane - 32] = w;
+  } else if (acc2 == 12345.678f) {
+    out[g] = acc2;
+  }
+}
+
 static void run_hbm() {
   const int heads = 16384, rows = 201, units = rows * 16;       // 16-byte units per head and region
   const size_t bytes = (size_t)heads * units * 16;              // one region set (K or V): 843 MB
@@ -147,9 +200,11 @@ static void run_hbm() {
   CK(hipEventCreate(&e1));
   const char* names[] = {"linear sweep", "linear sweep, non-temporal", "one wave per head (K then V)",
                          "one wave per head, non-temporal", "one wave per head + the step's small accesses",
-                         "one wave per head, non-temporal + the step's small accesses"};
+                         "one wave per head, non-temporal + the step's small accesses",
+                         "one wave per head, K and V rows together, non-temporal",
+                         "one wave per head, K and V rows together, non-temporal + the step's small accesses"};
   const double small_bytes = (double)heads * (8.0 * rows + 3 * 256.0);
-  for (int variant = 0; variant < 6; ++variant) {
+  for (int variant = 0; variant < 8; ++variant) {
     float best = 1e30f;
     const int launches = 10;
     for (int rep = 0; rep < 3; ++rep) {
@@ -171,6 +226,8 @@ static void run_hbm() {
           case 3: hipLaunchKernelGGL((sweep_heads<8, true, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
           case 4: hipLaunchKernelGGL((sweep_heads<8, false, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
           case 5: hipLaunchKernelGGL((sweep_heads<8, true, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 6: hipLaunchKernelGGL((sweep_heads_together<8, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 7: hipLaunchKernelGGL((sweep_heads_together<8, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
         }
       }
       CK(hipEventRecord(e1));
@@ -181,7 +238,7 @@ static void run_hbm() {
     }
     const double us = best * 1e3 / launches;
     const double kv = 2.0 * bytes;
-    const double total = kv + (variant >= 4 ? small_bytes : 0.0);
+    const double total = kv + ((variant == 4 || variant == 5 || variant == 7) ? small_bytes : 0.0);
     printf("{\"probe\": \"hbm\", \"pattern\": \"%s\", \"bytes\": %.0f, \"us\": %.1f, \"GBps\": %.0f, "
            "\"frac_of_8TBps\": %.3f}\n", names[variant], total, us, total / us / 1e3, total / us / 1e3 / 8000.0);
     fflush(stdout);
