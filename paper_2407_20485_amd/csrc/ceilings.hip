@@ -6,7 +6,10 @@
 //                      of 256 bytes, K then V) in the step's own access pattern (one wave per
 //                      head) and as a plain linear sweep, with and without the non-temporal
 //                      hint; then the same reads plus the step's small per-head accesses (score
-//                      row read and written, two 256-byte row writes, one 256-byte output row)
+//                      row read and written, two 256-byte row writes, one 256-byte output row),
+//                      all of them and one kind at a time, with plain and with non-temporal
+//                      stores, and with all small writes held back in LDS until a persistent
+//                      workgroup has finished reading
 //     ceilings mfma    sustained rate of v_mfma_f32_32x32x16_bf16 from registers, for operands
 //                      that are all zero, N(0,1)-like, and probability-like (in [0,1)): the chip
 //                      lowers its clock with the switching activity of the operands, so the
@@ -46,6 +49,21 @@ __device__ __forceinline__ float sum4(uint4 x) {
   return __uint_as_float(x.x) + __uint_as_float(x.y) + __uint_as_float(x.z) + __uint_as_float(x.w);
 }
 
+template <bool NT>
+__device__ __forceinline__ void st16(uint4* p, uint4 w) {
+  if (NT) {
+    const u32x4 t = {w.x, w.y, w.z, w.w};
+    __builtin_nontemporal_store(t, (u32x4*)p);
+  } else {
+    *p = w;
+  }
+}
+template <bool NT>
+__device__ __forceinline__ void st4(float* p, float w) {
+  if (NT) __builtin_nontemporal_store(w, p);
+  else *p = w;
+}
+
 // ---- HBM ------------------------------------------------------------------------------
 // linear sweep over n 16-byte units, U loads in flight per lane
 template <int U, bool NT>
@@ -66,10 +84,12 @@ __global__ __launch_bounds__(256) void sweep_linear(const uint4* __restrict__ A,
 }
 
 // One wave per head: the head's K region (units x 16 bytes), a wave reduction, then its V region.
-// SMALL adds the generation step's other per-head traffic: a score row of `slots` floats read
-// up front and written at the end, one 256-byte row written into each of the two regions at a
-// slot that changes from launch to launch, and a 256-byte output row.
-template <int U, bool NT, bool SMALL>
+// MODE adds the generation step's other per-head traffic, one bit per kind: 1 = a score row of
+// `slots` floats read up front, 2 = that row written at the end, 4 = one 256-byte row written
+// into each of the two regions at a slot that changes from launch to launch, 8 = a 256-byte
+// output row.  NTS: these writes carry the non-temporal hint.
+constexpr int kSmallAll = 15;
+template <int U, bool NT, int MODE, bool NTS = false>
 __global__ __launch_bounds__(256) void sweep_heads(uint4* __restrict__ A, uint4* __restrict__ B, int units,
                                                    int heads, float* __restrict__ S, int slots,
                                                    uint4* __restrict__ O, int launch, float* out) {
@@ -78,7 +98,7 @@ __global__ __launch_bounds__(256) void sweep_heads(uint4* __restrict__ A, uint4*
   const uint4* a = A + (size_t)g * units;
   const uint4* b = B + (size_t)g * units;
   float sv[4] = {0.f, 0.f, 0.f, 0.f};
-  if (SMALL) {
+  if (MODE & 1) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int j = lane + 64 * k;
@@ -108,21 +128,93 @@ __global__ __launch_bounds__(256) void sweep_heads(uint4* __restrict__ A, uint4*
 #pragma unroll
     for (int u = 0; u < U; ++u) acc2 += acc * sum4(x[u]);
   }
-  if (SMALL) {
+  if (MODE) {
     for (int o = 32; o > 0; o >>= 1) acc2 += __shfl_xor(acc2, o, 64);
+    acc2 += 1e-30f * (sv[0] + sv[1] + sv[2] + sv[3]);   // keeps the score row's loads alive
+    if (MODE & 2) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int j = lane + 64 * k;
+        if (j < slots - 1) st4<NTS>(&S[(size_t)g * slots + j], 0.5f * sv[k] + 1e-30f * acc2);
+      }
+    }
+    const int rows = units / 16;                                // 256-byte rows of a region
+    const int v = (int)(((unsigned)g * 7u + (unsigned)launch * 13u) % (unsigned)rows);
+    const uint4 w = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, __float_as_uint(acc2) & 0x3f803f80u);
+    if ((MODE & 4) && lane < 16) st16<NTS>(&A[(size_t)g * units + v * 16 + lane], w);
+    else if ((MODE & 4) && lane < 32) st16<NTS>(&B[(size_t)g * units + v * 16 + lane - 16], w);
+    else if ((MODE & 8) && lane >= 32 && lane < 48) st16<NTS>(&O[(size_t)g * 16 + lane - 32], w);
+    if (!(MODE & 14) && acc2 == 12345.678f) out[g] = acc2;     // no write requested: never true
+  } else if (acc2 == 12345.678f) {
+    out[g] = acc2;
+  }
+}
+
+// The same traffic (all small accesses) from persistent workgroups: 256 workgroups of 16 waves,
+// a wave works through HP heads and keeps what it would write in LDS; nothing is written before
+// the wave has read all its heads' rows.
+template <int U, int HP>
+__global__ __launch_bounds__(1024) void sweep_heads_stash(uint4* __restrict__ A, uint4* __restrict__ B,
+                                                          int units, int heads, float* __restrict__ S,
+                                                          int slots, uint4* __restrict__ O, int launch) {
+  extern __shared__ float stash[];   // [16 waves][HP][256 scores + 8]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nw = gridDim.x * 16;
+  float* mine = stash + (size_t)wave * HP * 264;
+  int cnt = 0;
+  for (int g = blockIdx.x * 16 + wave; g < heads && cnt < HP; g += nw, ++cnt) {
+    const uint4* a = A + (size_t)g * units;
+    const uint4* b = B + (size_t)g * units;
+    float sv[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int j = lane + 64 * k;
-      if (j < slots - 1) S[(size_t)g * slots + j] = 0.5f * sv[k] + 1e-30f * acc2;
+      sv[k] = j < slots ? S[(size_t)g * slots + j] : 0.f;
     }
-    const int rows = units / 16;                                // 256-byte rows of a region
+    float acc = 0.f;
+    for (int i = lane; i < units; i += 64 * U) {
+      uint4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = i + u * 64;
+        x[u] = ld16<true>(a + (j < units ? j : 0));
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc += sum4(x[u]);
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    float acc2 = 0.f;
+    for (int i = lane; i < units; i += 64 * U) {
+      uint4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = i + u * 64;
+        x[u] = ld16<true>(b + (j < units ? j : 0));
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc2 += acc * sum4(x[u]);
+    }
+    for (int o = 32; o > 0; o >>= 1) acc2 += __shfl_xor(acc2, o, 64);
+    float* st = mine + cnt * 264;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) st[lane + 64 * k] = 0.5f * sv[k] + 1e-30f * acc2;
+    if (lane == 0) st[256] = acc2;
+  }
+  int c2 = 0;
+  for (int g = blockIdx.x * 16 + wave; g < heads && c2 < HP; g += nw, ++c2) {
+    const float* st = mine + c2 * 264;
+    const float acc2 = st[256];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int j = lane + 64 * k;
+      if (j < slots - 1) S[(size_t)g * slots + j] = st[j];
+    }
+    const int rows = units / 16;
     const int v = (int)(((unsigned)g * 7u + (unsigned)launch * 13u) % (unsigned)rows);
     const uint4 w = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, __float_as_uint(acc2) & 0x3f803f80u);
     if (lane < 16) A[(size_t)g * units + v * 16 + lane] = w;
     else if (lane < 32) B[(size_t)g * units + v * 16 + lane - 16] = w;
     else if (lane < 48) O[(size_t)g * 16 + lane - 32] = w;
-  } else if (acc2 == 12345.678f) {
-    out[g] = acc2;
   }
 }
 
@@ -202,9 +294,20 @@ static void run_hbm() {
                          "one wave per head, non-temporal", "one wave per head + the step's small accesses",
                          "one wave per head, non-temporal + the step's small accesses",
                          "one wave per head, K and V rows together, non-temporal",
-                         "one wave per head, K and V rows together, non-temporal + the step's small accesses"};
+                         "one wave per head, K and V rows together, non-temporal + the step's small accesses",
+                         "one wave per head, non-temporal + only the score row read",
+                         "one wave per head, non-temporal + only the score row written",
+                         "one wave per head, non-temporal + only the two row writes",
+                         "one wave per head, non-temporal + only the output row",
+                         "one wave per head, non-temporal + the small accesses, their writes non-temporal too",
+                         "persistent workgroups, non-temporal + the small accesses, writes held in LDS until all rows are read"};
+  const double small_part[] = {0, 0, 0, 0, 1, 1, 0, 1, 0, 0, 0, 0, 1, 1};   // counts the small accesses' bytes
   const double small_bytes = (double)heads * (8.0 * rows + 3 * 256.0);
-  for (int variant = 0; variant < 8; ++variant) {
+  constexpr int kStashHeads = 4;   // 16384 heads / (256 workgroups x 16 waves)
+  const size_t stash_lds = (size_t)16 * kStashHeads * 264 * sizeof(float);
+  CK(hipFuncSetAttribute((const void*)sweep_heads_stash<8, kStashHeads>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                         (int)stash_lds));
+  for (int variant = 0; variant < 14; ++variant) {
     float best = 1e30f;
     const int launches = 10;
     for (int rep = 0; rep < 3; ++rep) {
@@ -213,6 +316,8 @@ static void run_hbm() {
         uint4* a = A[it & 1];
         uint4* b = B[it & 1];
         const dim3 gh(heads / 4), bl(256);
+#define SWEEP(NT, MODE, NTS) \
+  hipLaunchKernelGGL((sweep_heads<8, NT, MODE, NTS>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out)
         switch (variant) {
           case 0:
             hipLaunchKernelGGL((sweep_linear<8, false>), dim3(2048), bl, 0, 0, a, n, out);
@@ -222,13 +327,23 @@ static void run_hbm() {
             hipLaunchKernelGGL((sweep_linear<8, true>), dim3(2048), bl, 0, 0, a, n, out);
             hipLaunchKernelGGL((sweep_linear<8, true>), dim3(2048), bl, 0, 0, b, n, out);
             break;
-          case 2: hipLaunchKernelGGL((sweep_heads<8, false, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
-          case 3: hipLaunchKernelGGL((sweep_heads<8, true, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
-          case 4: hipLaunchKernelGGL((sweep_heads<8, false, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
-          case 5: hipLaunchKernelGGL((sweep_heads<8, true, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 2: SWEEP(false, 0, false); break;
+          case 3: SWEEP(true, 0, false); break;
+          case 4: SWEEP(false, kSmallAll, false); break;
+          case 5: SWEEP(true, kSmallAll, false); break;
           case 6: hipLaunchKernelGGL((sweep_heads_together<8, false>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
           case 7: hipLaunchKernelGGL((sweep_heads_together<8, true>), gh, bl, 0, 0, a, b, units, heads, S, rows, O, it, out); break;
+          case 8: SWEEP(true, 1, false); break;
+          case 9: SWEEP(true, 2, false); break;
+          case 10: SWEEP(true, 4, false); break;
+          case 11: SWEEP(true, 8, false); break;
+          case 12: SWEEP(true, kSmallAll, true); break;
+          case 13:
+            hipLaunchKernelGGL((sweep_heads_stash<8, kStashHeads>), dim3(256), dim3(1024), stash_lds, 0, a, b, units,
+                               heads, S, rows, O, it);
+            break;
         }
+#undef SWEEP
       }
       CK(hipEventRecord(e1));
       CK(hipEventSynchronize(e1));
@@ -236,9 +351,10 @@ static void run_hbm() {
       CK(hipEventElapsedTime(&ms, e0, e1));
       if (ms < best) best = ms;
     }
+    CK(hipGetLastError());
     const double us = best * 1e3 / launches;
     const double kv = 2.0 * bytes;
-    const double total = kv + ((variant == 4 || variant == 5 || variant == 7) ? small_bytes : 0.0);
+    const double total = kv + small_part[variant] * small_bytes;
     printf("{\"probe\": \"hbm\", \"pattern\": \"%s\", \"bytes\": %.0f, \"us\": %.1f, \"GBps\": %.0f, "
            "\"frac_of_8TBps\": %.3f}\n", names[variant], total, us, total / us / 1e3, total / us / 1e3 / 8000.0);
     fflush(stdout);

@@ -557,21 +557,40 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
 // Tail of a one-wave-per-head step: S <- alpha*S + prob on the head's slots held in registers
 // (slot j = lane + 64k; slot n_old is the new token), then the eviction.  z = the wave's LDS
 // strip of at least n_old + 1 floats (used by the rare general path).
-template <typename T, int D, int NJ>
+// What a head's step has to write, held back in LDS (decode_wave_loop_kernel): the score row, the
+// output row, and where the new token's rows go.
+struct HeldStep {
+  static constexpr int kOutFloats = 128;  // room for an output row of up to 512 bytes
+  static constexpr int kMeta = 4;         // head, slot of the new token's rows (-1: none), scores to write, new length (-1: unchanged)
+  template <int NJ>
+  static constexpr int floats() { return NJ * 64 + kOutFloats + kMeta; }
+};
+
+template <typename T, int D, int NJ, bool HOLD = false>
 __device__ __forceinline__ void wave_update_and_evict(const float (&s_old)[NJ], const float (&prob)[NJ],
                                                       const int (&pos)[NJ], float* z, int n_old, T* Kg,
                                                       T* Vg, float* Sg, int32_t* Pg, int32_t* len_g,
                                                       const T* knew, const T* vnew, int t_pos,
                                                       float alpha, int select, int recent,
-                                                      bool evict_here, StepSmem& sm) {
+                                                      bool evict_here, StepSmem& sm,
+                                                      float* held = nullptr) {
   using Grp = WaveGroup;
   const int lane = threadIdx.x & 63;
   const int L = n_old + 1;
+  // HOLD: the score row goes to held[0 .. ), the rest of the step's writes are described by
+  // held[NJ*64 + kOutFloats + 1 ..] = (slot of the new rows, scores to write, new length)
+  int* meta = HOLD ? reinterpret_cast<int*>(held + NJ * 64 + HeldStep::kOutFloats) : nullptr;
   float s_new[NJ];
 #pragma unroll
   for (int k = 0; k < NJ; ++k) s_new[k] = fmaf(alpha, s_old[k], prob[k]);
   const int excess = evict_here ? L - (select + recent) : 0;
   if (excess <= 0) {  // room left: the new token takes slot n_old, nothing leaves
+    if constexpr (HOLD) {
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) held[lane + 64 * k] = s_new[k];
+      if (lane == 0) { meta[1] = n_old; meta[2] = L; meta[3] = L; }
+      return;
+    }
 #pragma unroll
     for (int k = 0; k < NJ; ++k) {
       const int j = lane + 64 * k;
@@ -614,6 +633,15 @@ __device__ __forceinline__ void wave_update_and_evict(const float (&s_old)[NJ], 
     for (int k = 0; k < NJ; ++k)
       if (k == n_old / 64) s_tok = s_new[k];
     s_tok = __shfl(s_tok, n_old & 63, 64);
+    if constexpr (HOLD) {
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        held[j] = (j == v) ? s_tok : s_new[k];
+      }
+      if (lane == 0) { meta[1] = v != n_old ? v : -1; meta[2] = n_old; meta[3] = -1; }
+      return;
+    }
     // one contiguous store of the scores; the victim's slot receives the new token's
 #pragma unroll
     for (int k = 0; k < NJ; ++k) {
@@ -627,7 +655,10 @@ __device__ __forceinline__ void wave_update_and_evict(const float (&s_old)[NJ], 
     // len stays n_old (= select + recent): nothing to write
     return;
   }
-  // rare: several evictions or gaps in the newest positions
+  // rare: several evictions or gaps in the newest positions (written at once, also under HOLD)
+  if constexpr (HOLD) {
+    if (lane == 0) { meta[1] = -1; meta[2] = 0; meta[3] = -1; }
+  }
 #pragma unroll
   for (int k = 0; k < NJ; ++k) {
     const int j = lane + 64 * k;
@@ -824,6 +855,133 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
 
   wave_update_and_evict<T, D, NJ>(s_old, zr, pos, z, n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos,
                                   alpha, select, recent, evict_here != kEvictNone, sm);
+}
+
+// ---- one wave per head, several heads per wave ----------------------------------------------
+// The fast-mode step of decode_wave_kernel for launches with several times more heads than the
+// chip holds waves.  The few small writes of a step (score row, output row, the new token's two
+// rows) cost far more than their bytes when they trickle into the K/V read stream.  Here 256
+// persistent workgroups of 16 waves each work through the heads; a wave holds what its heads'
+// steps write in LDS and writes it out every HP heads and at the end, in bursts.  (Measured with
+// the stand-alone probe of the step's memory traffic: 284 us per step with the writes in place,
+// 274 us held back like this.)
+constexpr int kLoopWaves = 16;
+constexpr int kLoopGrid = 256;        // one workgroup per compute unit
+constexpr int kLoopMinHeads = 8192;   // at least two heads per wave
+template <typename T, int D, int NJ, int HP>
+__global__ __launch_bounds__(kLoopWaves * 64) void decode_wave_loop_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
+    T* K, T* V, float* S, int32_t* P, int32_t* len, int G, int capacity, float alpha,
+    const float* __restrict__ alpha_heads, int select, int recent, T* __restrict__ o,
+    float scale_log2e) {
+  using Gm = RowGeom<T, D>;
+  using Grp = WaveGroup;
+  constexpr int NS = NJ * 64, REC = HeldStep::floats<NJ>();
+  extern __shared__ __attribute__((aligned(16))) float lds[];  // [16][NS] logits | [16][HP][REC] held steps
+  __shared__ StepSmem sms[kLoopWaves];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* z = lds + wave * NS;
+  float* held0 = lds + kLoopWaves * NS + wave * HP * REC;
+  StepSmem& sm = sms[wave];
+  const int sub = lane % Gm::LPR, rgrp = lane / Gm::LPR;
+  const int stride = gridDim.x * kLoopWaves;
+
+  // writes out the first `cnt` held steps of this wave
+  auto flush = [&](int cnt) {
+    Grp::sync();
+    for (int r = 0; r < cnt; ++r) {
+      const float* rec = held0 + r * REC;
+      const int* meta = reinterpret_cast<const int*>(rec + NS + HeldStep::kOutFloats);
+      const int g = meta[0], slot = meta[1], nscores = meta[2], new_len = meta[3];
+      float* Sg = S + (size_t)g * capacity;
+#pragma unroll
+      for (int k = 0; k < NJ; ++k) {
+        const int j = lane + 64 * k;
+        if (j < nscores) Sg[j] = rec[j];
+      }
+      if (lane < Gm::LPR)
+        store16(o + (size_t)g * D + lane * Gm::EPL, *reinterpret_cast<const uint4*>(rec + NS + 4 * lane));
+      if (slot >= 0) {
+        T* Kg = K + (size_t)g * capacity * D;
+        T* Vg = V + (size_t)g * capacity * D;
+        copy_kv_row<Grp, T, D>(Kg + (size_t)slot * D, k_new + (size_t)g * D, Vg + (size_t)slot * D,
+                               v_new + (size_t)g * D);
+        if (lane == 63) P[(size_t)g * capacity + slot] = t_pos;
+      }
+      if (new_len >= 0 && lane == 0) len[g] = new_len;
+    }
+    Grp::sync();
+  };
+
+  int cnt = 0;
+  for (int g = blockIdx.x * kLoopWaves + wave; g < G; g += stride) {
+    const int n_old = len[g];
+    if (n_old < 0 || n_old >= capacity) {
+      flag_bad_head<T, D>(o + (size_t)g * D, lane, kWave);
+      continue;
+    }
+    const int L = n_old + 1;
+    const float alpha_g = alpha_heads ? alpha_heads[g] : alpha;
+    T* Kg = K + (size_t)g * capacity * D;
+    T* Vg = V + (size_t)g * capacity * D;
+    float* Sg = S + (size_t)g * capacity;
+    int32_t* Pg = P + (size_t)g * capacity;
+    const T* knew = k_new + (size_t)g * D;
+    const T* vnew = v_new + (size_t)g * D;
+
+    float s_old[NJ];
+    int pos[NJ];
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      s_old[k] = j < n_old ? Sg[j] : 0.f;
+      pos[k] = j < n_old ? Pg[j] : t_pos;
+    }
+    float qv[Gm::EPL];
+    load_query<T, D>(q + (size_t)g * D, scale_log2e, qv);
+    sweep_k<Grp, kWaveUnroll, true, T, D>(Kg, knew, n_old, 0, L, qv, z, 0);
+    Grp::sync();
+
+    float zr[NJ];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      zr[k] = j < L ? z[j] : -INFINITY;
+      mx = fmaxf(mx, zr[k]);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      zr[k] = exp2f(zr[k] - mx);  // 0 for j >= L
+      sum += zr[k];
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      zr[k] *= inv;
+      const int j = lane + 64 * k;
+      if (j < L) z[j] = zr[k];
+    }
+    Grp::sync();
+
+    float acc[Gm::EPL];
+    sweep_v<Grp, kWaveUnroll, true, T, D>(Vg, vnew, n_old, 0, L, z, 0, acc);
+    float* rec = held0 + cnt * REC;
+    if (rgrp == 0) *reinterpret_cast<uint4*>(rec + NS + 4 * sub) = pack16(acc, T());
+    if (lane == 0) reinterpret_cast<int*>(rec + NS + HeldStep::kOutFloats)[0] = g;
+
+    wave_update_and_evict<T, D, NJ, true>(s_old, zr, pos, z, n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew, t_pos,
+                                          alpha_g, select, recent, true, sm, rec);
+    if (++cnt == HP) {
+      flush(cnt);
+      cnt = 0;
+    }
+  }
+  flush(cnt);
 }
 
 // ---- grouped-query heads, one wave per K/V head ------------------------------------------
@@ -1075,6 +1233,26 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                   int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
                   hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
+  if (plan.nsplit <= 1 && plan.wave_slots > 0 && plan.wave_slots <= 4 && evict_here && c.G >= kLoopMinHeads) {
+    // several heads per wave, their small writes held back in LDS (up to 256 slots: with 512 the
+    // kernel no longer fits the 128 registers that 16 waves per compute unit leave a lane)
+#define A2SF_LOOP(NJ, HP)                                                                              \
+  do {                                                                                                 \
+    constexpr int kLds = kLoopWaves * (NJ * 64 + HP * HeldStep::floats<NJ>()) * (int)sizeof(float);    \
+    static const hipError_t raised = hipFuncSetAttribute(                                              \
+        (const void*)decode_wave_loop_kernel<T, D, NJ, HP>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+        kLds);                                                                                         \
+    (void)raised;                                                                                      \
+    hipLaunchKernelGGL((decode_wave_loop_kernel<T, D, NJ, HP>), dim3(kLoopGrid), dim3(kLoopWaves * 64), \
+                       kLds, st, (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k,        \
+                       (T*)c.v, c.scores, c.pos, c.len, c.G, c.capacity, alpha, alpha_heads, select,   \
+                       recent, (T*)o, scale_log2e);                                                    \
+  } while (0)
+    if (plan.wave_slots == 2) A2SF_LOOP(2, 4);
+    else A2SF_LOOP(4, 4);
+#undef A2SF_LOOP
+    return;
+  }
   if (plan.nsplit <= 1 && plan.wave_slots > 0) {
     const dim3 grid((c.G + kWaves - 1) / kWaves);
 #define A2SF_WAVE_(NJ, STABLE)                                                                        \

@@ -271,24 +271,34 @@ def test_small_fp32(d, say):
     run_lockstep(w, 0.5, mode=a2sf.A2SF_EVICT_STABLE, say=say)
 
 
-@pytest.mark.parametrize("G", [1100, 4200])
+@pytest.mark.parametrize("G", [1100, 4200, 8300])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_many_heads_decode(dtype, G, say):
     """G >= 1024 heads: one workgroup per head (no token split); G >= 4096 heads with a short
-    cache: one wave per head."""
+    cache: one wave per head; G >= 8192 in the fast mode: several heads per wave, their writes
+    held back in LDS."""
     w = variant(1, heads=G, d=128 if dtype == "bf16" else 64, dtype=dtype, n=96, T=12,
                 select=12, recent=12, name=f"{G} heads {dtype}")
     run_lockstep(w, 0.3, sample=list(range(0, G, G // 20)), say=say)
     run_lockstep(w, 0.3, sample=list(range(7, G, G // 5)), mode=a2sf.A2SF_EVICT_STABLE, say=say)
 
 
+@pytest.mark.parametrize("G", [4100, 8200])
 @pytest.mark.parametrize("select,recent,d,dtype", [(150, 151, 128, "bf16"), (100, 100, 64, "bf16"),
                                                    (90, 90, 128, "f32"), (20, 20, 128, "bf16")])
-def test_wave_per_head_slot_counts(select, recent, d, dtype, say):
-    """The wave-per-head decode kernel holds 128 / 256 / 512 slots per head in registers."""
-    w = variant(1, heads=4100, d=d, dtype=dtype, n=select + recent + 30, T=5, select=select,
-                recent=recent, name=f"wave slots B={select + recent} d{d} {dtype}")
-    run_lockstep(w, 0.5, sample=[0, 1, 2, 3, 2049, 4099], say=say)
+def test_wave_per_head_slot_counts(select, recent, d, dtype, G, say):
+    """The wave-per-head decode kernels hold 128 / 256 / 512 slots per head in registers."""
+    w = variant(1, heads=G, d=d, dtype=dtype, n=select + recent + 30, T=5, select=select,
+                recent=recent, name=f"wave slots B={select + recent} d{d} {dtype} G={G}")
+    run_lockstep(w, 0.5, sample=sorted({0, 1, 2, 3, 2049, 4099, G - 1}), say=say)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_many_heads_cache_still_filling(dtype, d, say):
+    """8300 heads whose prompt is shorter than the budget: the first steps only append (the length
+    grows), the later ones evict; several heads per wave, the writes of a step held back in LDS."""
+    w = variant(1, heads=8300, d=d, dtype=dtype, n=20, T=16, select=14, recent=14, name=f"filling 8300 heads {dtype}")
+    run_lockstep(w, 0.6, sample=[0, 15, 16, 4095, 4096, 4111, 8191, 8192, 8299], say=say)
 
 
 @pytest.mark.parametrize("G,budget,mode", [(3, 26214, "fast"), (3, 26214, "stable"), (650, 16384, "fast"),
@@ -365,7 +375,7 @@ def test_budget_shapes(select, recent, say):
         run_lockstep(w2, 0.3, sample=[0, 500, G - 1], say=say)
 
 
-@pytest.mark.parametrize("G", [3, 1040, 4100])
+@pytest.mark.parametrize("G", [3, 1040, 4100, 8200])
 def test_budget_lowered_between_steps(G, say):
     """A step that must evict several tokens at once, and a recent window larger than the one
     the cache was built with (its newest positions then have gaps)."""
@@ -387,7 +397,7 @@ def test_budget_lowered_between_steps(G, say):
 
 
 @pytest.mark.parametrize("base,G,d,n", [(1, 7, 128, 300), (1, 4200, 128, 150), (0, 5, 64, 140),
-                                         (1, 6, 64, 260), (1, 3, 128, 2100)])
+                                         (1, 6, 64, 260), (1, 3, 128, 2100), (1, 8200, 128, 100)])
 def test_alpha_per_head(base, G, d, n, say):
     """A distinct forgetting factor per head (Section 6 of the paper), both ends included."""
     w = variant(base, heads=G, d=d, n=n, T=6, select=10, recent=10, name=f"per-head alpha G={G} d={d}")
@@ -424,7 +434,7 @@ def test_alpha_above_the_bound_is_computed_as_the_bound(say):
     say(f"  [alpha above bound] factors {alphas.tolist()} under bound {bound}: max score rel={worst:.2e}")
 
 
-@pytest.mark.parametrize("G,cap", [(6, 40), (4200, 40), (5, 700)])
+@pytest.mark.parametrize("G,cap", [(6, 40), (4200, 40), (5, 700), (8200, 40)])
 def test_decode_flags_heads_with_an_invalid_length(G, cap, say):
     """len[g] + 1 <= capacity is a precondition the host cannot check (the lengths live on the
     device).  A head that breaks it is left untouched and its output row is NaN; every other
@@ -941,14 +951,14 @@ def test_cfg4_long_context(say):
 
 # ---------------------------------------------------------------- HIP graph capture
 @pytest.mark.parametrize("G,mode,select", [(48, "fast", 300), (48, "stable", 300), (48, "fast", 10),
-                                           (1100, "fast", 10), (4200, "fast", 10)])
+                                           (1100, "fast", 10), (4200, "fast", 10), (8200, "fast", 10)])
 def test_decode_steps_replay_from_a_hip_graph(G, mode, select, say):
     """The calls only enqueue kernels on the caller's stream (no allocation, no
     synchronisation, no memset), so a run of generation steps can be captured in a HIP graph.
     Every replay -- with eager work and synchronisations in between -- must leave exactly
     what the eager run left: outputs and the whole cache, bit for bit.  (Each launch path:
-    token-split -- few heads with more than 256 slots --, workgroup per head, wave per head;
-    fast and stable eviction.)"""
+    token-split -- few heads with more than 256 slots --, workgroup per head, wave per head,
+    several heads per wave; fast and stable eviction.)"""
     d, n, T, recent, alpha = 128, 96, 6, select, 0.4
     evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
     gen = torch.Generator(device="cuda").manual_seed(G)
