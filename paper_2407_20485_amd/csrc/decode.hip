@@ -14,7 +14,10 @@
 //
 // With few heads (G small) the tokens of a head are split over several workgroups
 // (partial kernel writes logits, per-split max / sum / unnormalised output) and a combine
-// kernel per head finishes the softmax, the score update and the eviction.
+// kernel per head finishes the softmax, the score update and the eviction.  With many heads and
+// short caches a single wave works on a head (decode_wave_kernel), and with several times more
+// heads than the chip holds waves a wave works through several heads and holds their small
+// writes back in LDS (decode_wave_loop_kernel).
 #include <math.h>
 
 #include "a2sf_dev.h"
