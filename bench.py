@@ -433,9 +433,11 @@ def main():
     flops = prefill_model_flops(G, n, d, with_o=not args.no_o)
     dec_gbs = dbytes / dec_s_per_step / 1e9
     pre_tflops = flops / pre_s / 1e12
-    nsplit, rows_per_split, wave_slots = a2sf.a2sf_decode_plan(G, capacity, d)   # the library's launch plan
+    nsplit, rows_per_split, wave_slots, wave_heads = a2sf.a2sf_decode_plan(G, capacity, d)   # the library's launch plan
     if nsplit > 1:
         nsplit_note = f"tokens of a head split over {nsplit} workgroups + combine kernel"
+    elif wave_slots and wave_heads > 1 and args.mode != "stable":
+        nsplit_note = f"one fused kernel, persistent workgroups, {wave_heads} heads per wave, small writes held in LDS"
     else:
         nsplit_note = "one fused kernel, " + ("one wave per head" if wave_slots else "one workgroup per head")
     if args.mode == "stable":

@@ -282,11 +282,12 @@ a2sf_status a2sf_similarity_mean(const float* cos, int32_t steps, int32_t G, int
  *   nsplit          workgroups per head; 1 = one fused kernel, > 1 = the tokens of a head are
  *                   split over that many workgroups and a second kernel combines them.
  *   rows_per_split  cached tokens per workgroup when nsplit > 1.
- *   wave_slots      > 0: a wave works on a whole head (64 * wave_slots slots in registers); in
- *                   the fast eviction mode from 8192 heads on, with up to 256 slots, persistent
- *                   workgroups in which a wave works through several heads. */
+ *   wave_slots      > 0: a wave works on a whole head (64 * wave_slots slots in registers).
+ *   wave_heads      heads a wave works through in the fast eviction mode: 1, or more in the
+ *                   form for launches with several times more heads than the chip holds waves
+ *                   (persistent workgroups; a step's small writes are held back in LDS). */
 a2sf_status a2sf_decode_plan(int32_t G, int32_t capacity, int32_t d, int32_t* nsplit,
-                             int32_t* rows_per_split, int32_t* wave_slots);
+                             int32_t* rows_per_split, int32_t* wave_slots, int32_t* wave_heads);
 
 const char* a2sf_status_string(int32_t status);
 

@@ -90,7 +90,7 @@ def lib() -> ctypes.CDLL:
         L.a2sf_similarity_mean.argtypes = [vp, i32, i32, i32, vp, vp]
         L.a2sf_decode_plan.restype = i32
         L.a2sf_decode_plan.argtypes = [i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32),
-                                       ctypes.POINTER(i32)]
+                                       ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.a2sf_status_string.restype = ctypes.c_char_p
         L.a2sf_status_string.argtypes = [i32]
         _lib = L
@@ -275,10 +275,11 @@ def a2sf_similarity_mean(cos, steps, G, first_step, mean_out, stream=None):
 
 
 def a2sf_decode_plan(G, capacity, d):
-    """(nsplit, rows_per_split, wave_slots) of a2sf_decode_step for these sizes."""
-    a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
-    _check(lib().a2sf_decode_plan(G, capacity, d, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
-    return a.value, b.value, c.value
+    """(nsplit, rows_per_split, wave_slots, wave_heads) of a2sf_decode_step for these sizes."""
+    a, b, c, h = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().a2sf_decode_plan(G, capacity, d, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                  ctypes.byref(h)))
+    return a.value, b.value, c.value, h.value
 
 
 def a2sf_compact(cache, keep_idx, keep_stride, n_keep, stream=None):

@@ -470,13 +470,14 @@ a2sf_status a2sf_similarity_mean(const float* cos, int32_t steps, int32_t G, int
 }
 
 a2sf_status a2sf_decode_plan(int32_t G, int32_t capacity, int32_t d, int32_t* nsplit,
-                             int32_t* rows_per_split, int32_t* wave_slots) {
+                             int32_t* rows_per_split, int32_t* wave_slots, int32_t* wave_heads) {
   if (G < 1 || (d != 64 && d != 128)) return A2SF_ESHAPE;
   if (capacity < 1 || capacity > A2SF_MAX_CAPACITY) return A2SF_ECAPACITY;
   const DecodePlan p = plan_decode(G, capacity, d);
   if (nsplit) *nsplit = p.nsplit;
   if (rows_per_split) *rows_per_split = p.rows_per_split;
   if (wave_slots) *wave_slots = p.wave_slots;
+  if (wave_heads) *wave_heads = p.wave_heads;
   return A2SF_OK;
 }
 

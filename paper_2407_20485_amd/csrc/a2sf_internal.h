@@ -28,6 +28,8 @@ struct DecodePlan {
   int nsplit;          // workgroups per head (1 = single fused kernel)
   int rows_per_split;  // multiple of 64
   int wave_slots;      // > 0: wave-per-head kernel holding 64*wave_slots slots in registers
+  bool loop;           // wave-per-head path, fast mode: persistent workgroups, a wave works through several heads
+  int wave_heads;      // ... that many (1 otherwise)
   bool stream;         // single-kernel paths: load the cache rows with the non-temporal hint
   size_t ws_bytes;     // split-K scratch
 };

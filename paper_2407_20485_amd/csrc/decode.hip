@@ -1236,7 +1236,7 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                   int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
                   hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
-  if (plan.nsplit <= 1 && plan.wave_slots > 0 && plan.wave_slots <= 4 && evict_here && c.G >= kLoopMinHeads) {
+  if (plan.nsplit <= 1 && plan.loop && evict_here) {
     // several heads per wave, their small writes held back in LDS (up to 256 slots: with 512 the
     // kernel no longer fits the 128 registers that 16 waves per compute unit leave a lane)
 #define A2SF_LOOP(NJ, HP)                                                                              \
@@ -1403,6 +1403,8 @@ DecodePlan plan_decode(int G, int capacity, int d) {
   // Many heads with short caches: one wave per head (slots held as 64 * wave_slots registers).
   p.wave_slots = 0;
   if (ns == 1 && G >= 4096 && capacity <= 512) p.wave_slots = capacity <= 128 ? 2 : (capacity <= 256 ? 4 : 8);
+  p.loop = p.wave_slots > 0 && p.wave_slots <= 4 && G >= kLoopMinHeads;
+  p.wave_heads = p.loop ? (G + kLoopGrid * kLoopWaves - 1) / (kLoopGrid * kLoopWaves) : 1;
   // Cache rows carry the non-temporal hint when the K/V working set cannot stay in the 256 MB
   // last-level cache from one step to the next anyway (320 heads x 410 slots, 69 MB, resident:
   // 17.2 us per step without the hint, 20.8 with it; 16384 x 201, 1.7 GB: 317 without, 291 with).

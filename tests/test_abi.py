@@ -171,15 +171,17 @@ def test_grouped_query_argument_errors():
 
 
 def test_decode_plan_is_a_host_query():
-    assert B.a2sf_decode_plan(16384, 201, 128) == (1, 256, 4)        # one wave per head, 256 slots in registers
-    nsplit, rows, wave = B.a2sf_decode_plan(32, 3277, 128)           # few heads, long cache: tokens are split
-    assert nsplit > 1 and rows % 64 == 0 and nsplit * rows >= 3277 and wave == 0
+    assert B.a2sf_decode_plan(16384, 201, 128) == (1, 256, 4, 4)     # a wave per head, 256 slots in registers, four heads per wave
+    assert B.a2sf_decode_plan(4200, 201, 128) == (1, 256, 4, 1)      # fewer heads: one head per wave
+    assert B.a2sf_decode_plan(16384, 500, 128)[2:] == (8, 1)         # 512 slots: one head per wave
+    nsplit, rows, wave, heads = B.a2sf_decode_plan(32, 3277, 128)     # few heads, long cache: tokens are split
+    assert nsplit > 1 and rows % 64 == 0 and nsplit * rows >= 3277 and wave == 0 and heads == 1
     assert B.a2sf_decode_plan(320, 410, 128)[0] == 1
     lib = B.lib()
-    assert lib.a2sf_decode_plan(0, 10, 128, None, None, None) == B.A2SF_ESHAPE
-    assert lib.a2sf_decode_plan(4, 10, 100, None, None, None) == B.A2SF_ESHAPE
-    assert lib.a2sf_decode_plan(4, B.A2SF_MAX_CAPACITY + 1, 128, None, None, None) == B.A2SF_ECAPACITY
-    assert lib.a2sf_decode_plan(4, 10, 128, None, None, None) == B.A2SF_OK      # out pointers are optional
+    assert lib.a2sf_decode_plan(0, 10, 128, None, None, None, None) == B.A2SF_ESHAPE
+    assert lib.a2sf_decode_plan(4, 10, 100, None, None, None, None) == B.A2SF_ESHAPE
+    assert lib.a2sf_decode_plan(4, B.A2SF_MAX_CAPACITY + 1, 128, None, None, None, None) == B.A2SF_ECAPACITY
+    assert lib.a2sf_decode_plan(4, 10, 128, None, None, None, None) == B.A2SF_OK      # out pointers are optional
 
 
 def test_similarity_mean_argument_errors():
