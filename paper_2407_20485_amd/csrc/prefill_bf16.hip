@@ -1075,6 +1075,7 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     float log2_alpha, const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
   __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
+  __shared__ __attribute__((aligned(16))) float strip[kWaves][32 * kTailKB];   // a wave's scores of one step
   lds_char* const qs = (lds_char*)smem;
 
   const int g = blockIdx.x;
@@ -1195,20 +1196,43 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
       }
     }
     if (pending) load_keys(c0 + STEP, kf);
-    // sum over the 32 rows held by the lanes of one half
+    // sum over the 32 rows held by the lanes of one half; the wave's 32 * kTailKB scores go
+    // through its LDS strip so that they leave as whole 16-byte pieces of one contiguous run
+    // (two lanes hold them all, four consecutive keys per register quad)
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[b][i] = group_sum<32>(acc[b][i]);
       if (l32 == 0) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = wc0 + b * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-          // `accumulate`: on top of `decay` times the older score (a chunk: alpha^n)
-          if (key < nk) Sg[key] = accumulate ? fmaf(decay, Sg[key], acc[b][i]) : acc[b][i];
-        }
+        for (int i4 = 0; i4 < 4; ++i4)   // keys b*32 + 8*i4 + 4h .. +3
+          *reinterpret_cast<float4*>(&strip[wave][b * 32 + 8 * i4 + 4 * h]) =
+              make_float4(acc[b][4 * i4], acc[b][4 * i4 + 1], acc[b][4 * i4 + 2], acc[b][4 * i4 + 3]);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    if (lane < 8 * kTailKB) {
+      const int key = wc0 + 4 * lane;
+      float4 v = *reinterpret_cast<const float4*>(&strip[wave][4 * lane]);
+      float* out = Sg + key;
+      // `accumulate`: on top of `decay` times the older score (a chunk: alpha^n)
+      if (key + 3 < nk && (reinterpret_cast<size_t>(out) & 15) == 0) {
+        if (accumulate) {
+          const float4 old = *reinterpret_cast<const float4*>(out);
+          v = make_float4(fmaf(decay, old.x, v.x), fmaf(decay, old.y, v.y), fmaf(decay, old.z, v.z),
+                          fmaf(decay, old.w, v.w));
+        }
+        *reinterpret_cast<float4*>(out) = v;
+      } else {
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (key + e < nk) out[e] = accumulate ? fmaf(decay, out[e], vv[e]) : vv[e];
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();   // the strip is rewritten in the next step
   }
 }
 
