@@ -57,24 +57,56 @@ __device__ __forceinline__ uint4 pack16(const float* f, bf16_t) {
   return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
 }
 
-// Sum over aligned groups of N consecutive lanes (N = 8, 16, 32 or 64); every lane of a
-// group gets the group's total.  The first four halvings are DPP lane permutations folded
-// into the adds (quad swaps, then mirrors inside half rows and rows of 16 lanes: a mirror
-// pairs each lane with one holding the other half's partial sum); only the steps across
-// rows of 16 go through the LDS crossbar.
+// ---- lane exchanges ---------------------------------------------------------------------
+// Reductions over the wave stay in the vector pipe: inside a row of 16 lanes DPP lane
+// permutations folded into the operation (quad swaps, then mirrors inside half rows and rows:
+// a mirror pairs each lane with one holding the other half's partial result), across rows the
+// two swap instructions of gfx950 (odd with even rows of 16 lanes, upper with lower half of
+// the wave).  A butterfly through the LDS crossbar (ds_bpermute) costs ~100 cycles of latency
+// per step instead of a handful.
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+// the value of lane l ^ 16 / l ^ 32
+__device__ __forceinline__ uint32_t lane_xor16_u32(uint32_t v) {
+  const u32x2_t r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return ((threadIdx.x >> 4) & 1) ? r[0] : r[1];   // r[0] = rows (0,0,2,2), r[1] = rows (1,1,3,3)
+}
+__device__ __forceinline__ uint32_t lane_xor32_u32(uint32_t v) {
+  const u32x2_t r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return ((threadIdx.x >> 5) & 1) ? r[0] : r[1];   // r[0] = halves (lo, lo), r[1] = (hi, hi)
+}
+// op(v of this lane, v of the partner lane) for commutative op, both steps across rows
+template <typename Op>
+__device__ __forceinline__ float across_rows(float v, Op op, bool rows16, bool halves) {
+  if (rows16) {
+    const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  }
+  if (halves) {
+    const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = op(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  }
+  return v;
+}
+struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
+
+// Sum over aligned groups of N consecutive lanes (N = 8, 16, 32 or 64); every lane of a
+// group gets the group's total.
 template <int N>
 __device__ __forceinline__ float group_sum(float v) {
   v += dpp_move<0xB1>(v);                  // quad_perm [1,0,3,2]
   v += dpp_move<0x4E>(v);                  // quad_perm [2,3,0,1]
   if (N >= 8) v += dpp_move<0x141>(v);     // row_half_mirror
   if (N >= 16) v += dpp_move<0x140>(v);    // row_mirror
-  if (N >= 32) v += __shfl_xor(v, 16, 64);
-  if (N >= 64) v += __shfl_xor(v, 32, 64);
-  return v;
+  return across_rows(v, OpAdd(), N >= 32, N >= 64);
 }
 
 // ---- ordering ---------------------------------------------------------------------------
@@ -86,27 +118,52 @@ __device__ __forceinline__ uint32_t ordered_key(float s) {
 
 // ---- wave / block reductions ------------------------------------------------------------
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  return across_rows(v, OpMax(), true, true);
 }
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
+__device__ __forceinline__ float wave_sum(float v) { return group_sum<64>(v); }
 __device__ __forceinline__ int wave_sum_i(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  uint32_t u = (uint32_t)v;
+  u += dpp_move_u32<0xB1>(u);
+  u += dpp_move_u32<0x4E>(u);
+  u += dpp_move_u32<0x141>(u);
+  u += dpp_move_u32<0x140>(u);
+  u32x2_t r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  u = r[0] + r[1];
+  r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return (int)(r[0] + r[1]);
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+  v = ::max(v, (int)dpp_move_u32<0xB1>((uint32_t)v));
+  v = ::max(v, (int)dpp_move_u32<0x4E>((uint32_t)v));
+  v = ::max(v, (int)dpp_move_u32<0x141>((uint32_t)v));
+  v = ::max(v, (int)dpp_move_u32<0x140>((uint32_t)v));
+  u32x2_t r = __builtin_amdgcn_permlane16_swap((uint32_t)v, (uint32_t)v, false, false);
+  v = ::max((int)r[0], (int)r[1]);
+  r = __builtin_amdgcn_permlane32_swap((uint32_t)v, (uint32_t)v, false, false);
+  return ::max((int)r[0], (int)r[1]);
+}
+// lane `src` (the same for the whole wave) hands its value to every lane
+__device__ __forceinline__ float wave_broadcast(float v, int src) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), __builtin_amdgcn_readfirstlane(src)));
 }
 __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    unsigned long long other = __shfl_xor(v, o, 64);
-    v = other < v ? other : v;
-  }
-  return v;
+  uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+  const auto take = [&](uint32_t olo, uint32_t ohi) {
+    const unsigned long long other = ((unsigned long long)ohi << 32) | olo;
+    const unsigned long long mine = ((unsigned long long)hi << 32) | lo;
+    if (other < mine) { lo = olo; hi = ohi; }
+  };
+  take(dpp_move_u32<0xB1>(lo), dpp_move_u32<0xB1>(hi));
+  take(dpp_move_u32<0x4E>(lo), dpp_move_u32<0x4E>(hi));
+  take(dpp_move_u32<0x141>(lo), dpp_move_u32<0x141>(hi));
+  take(dpp_move_u32<0x140>(lo), dpp_move_u32<0x140>(hi));
+  take(lane_xor16_u32(lo), lane_xor16_u32(hi));
+  take(lane_xor32_u32(lo), lane_xor32_u32(hi));
+  return ((unsigned long long)hi << 32) | lo;
 }
 
 // Block-wide reductions over 4 waves; `red` is a shared array of >= 8 floats / u64.

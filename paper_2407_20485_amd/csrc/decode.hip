@@ -20,6 +20,8 @@
 // writes back in LDS (decode_wave_loop_kernel).
 #include <math.h>
 
+#include <type_traits>
+
 #include "a2sf_dev.h"
 #include "a2sf_internal.h"
 
@@ -108,8 +110,8 @@ __device__ __forceinline__ void v_fold_row_groups(float* acc) {
   using Gm = RowGeom<T, D>;
 #pragma unroll
   for (int e = 0; e < Gm::EPL; ++e) {
-#pragma unroll
-    for (int o = Gm::LPR; o < kWave; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+    if (Gm::LPR <= 8) acc[e] += dpp_move<0x128>(acc[e]);  // row_ror:8
+    acc[e] = across_rows(acc[e], OpAdd(), Gm::LPR <= 16, true);
   }
 }
 
@@ -627,15 +629,14 @@ __device__ __forceinline__ void wave_update_and_evict(const float (&s_old)[NJ], 
       const int j = lane + 64 * k;
       if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
+    v = wave_max_i(v);
     if (v < 0) v = n_old;  // cannot happen for valid input: drop the new token rather than write out of range
     // the new token's updated score (= its probability) sits with lane n_old%64, slot n_old/64
     float s_tok = 0.f;
 #pragma unroll
     for (int k = 0; k < NJ; ++k)
       if (k == n_old / 64) s_tok = s_new[k];
-    s_tok = __shfl(s_tok, n_old & 63, 64);
+    s_tok = wave_broadcast(s_tok, n_old & 63);
     if constexpr (HOLD) {
 #pragma unroll
       for (int k = 0; k < NJ; ++k) {
@@ -784,8 +785,7 @@ __global__ __launch_bounds__(kThreads) void decode_wave_kernel(
           const int j = lane + 64 * k;
           if (j < L && pos[k] <= thr && evict_key(s_new[k], pos[k]) == win) v = j;
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v = ::max(v, __shfl_xor(v, off, 64));
+        v = wave_max_i(v);
       }
     }
     if (v >= 0) {
@@ -994,7 +994,8 @@ __global__ __launch_bounds__(kLoopWaves * 64) void decode_wave_loop_kernel(
 // Registers: 160 (R = 2) and 200 (R = 4) per lane when the compiler is left alone; bounding
 // them to raise the occupancy spills into the sweeps and is slower (R = 4: 182 us per step
 // instead of 100 at 4096 K/V heads x 201 slots); R = 8 is held to 256, which two waves per SIMD
-// need, and is faster for it (76 us instead of 99 at 2048 K/V heads).
+// need, and is faster for it (76 us instead of 99 at 2048 K/V heads).  bf16 with d = 128 and
+// R = 4 or 8 runs decode_gqa_mfma_kernel below instead.
 template <typename T, int D, int NJ, int R, bool STREAM>
 __global__ __launch_bounds__(kThreads, R <= 4 ? 1 : 2) void decode_gqa_wave_kernel(
     const T* __restrict__ q, const T* __restrict__ k_new, const T* __restrict__ v_new, int t_pos,
@@ -1126,6 +1127,228 @@ __global__ __launch_bounds__(kThreads, R <= 4 ? 1 : 2) void decode_gqa_wave_kern
     v_fold_row_groups<T, D>(acc[r]);
     if (rgrp == 0) store16(o + ((size_t)g * R + r) * D + sub * Gm::EPL, pack16(acc[r], T()));
   }
+  Grp::sync();  // the strip's first row is reused by the rare general eviction
+
+  wave_update_and_evict<T, D, NJ>(s_old, psum, pos, z[0], n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew,
+                                  t_pos, alpha, select, recent, evict_here != 0, sms[wave]);
+}
+
+// ---- grouped-query heads on the 4x4 matrix instructions --------------------------------
+// bf16, d = 128, R = 4 or 8 query heads per K/V head.  The wave-per-head kernel above spends
+// ~20 vector instructions per row and query head on the logits (eight multiply-adds, a lane
+// reduction, a masked LDS write) and eight per row and head on the output; with R >= 4 that
+// arithmetic, not the row stream, sets its time.  Here both products go to the matrix pipe as
+// sixteen independent 4x4 blocks per instruction, which fits four query heads exactly:
+//   logits   v_mfma_f32_4x4x4_16B_bf16: block b = lane / 4 takes the 8 elements 8b .. 8b+7 of
+//            4 K rows (lane 4b+i: row i, one 16-byte load = two k-steps) against the same
+//            elements of the 4 queries (lane 4b+j: head j); register v of lane 4b+j then holds
+//            the partial dot product of row v with head j over chunk b, and the 16 chunks are
+//            summed across lanes: two halving steps that swap lane halves / odd and even rows
+//            of 16 lanes between two registers (so the register count halves with each add),
+//            then two rotations inside the rows of 16 lanes;
+//   outputs  v_mfma_f32_4x4x1_16B_f32, an outer product per block: lane 4b+i brings the
+//            probability of head i for the V row of its row group, lane 4b+j element e of its 16
+//            bytes of that row; register i of lane 4b+j accumulates o[head i][8*(lane%16)+e] --
+//            the layout the vector form ends in, so the fold over row groups is shared.
+// Lane layouts of both instructions and of the two swaps were checked on the device against
+// a host computation before this was written.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x4_t as_bf16x4(uint32_t lo, uint32_t hi) {
+  const u32x2_t t = {lo, hi};
+  return __builtin_bit_cast(bf16x4_t, t);
+}
+// a, b -> sum over the lane pairs (l, l ^ 32): lanes < 32 get a's, lanes >= 32 get b's
+__device__ __forceinline__ float fold_halves(float a, float b) {
+  const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// a, b -> sum over the lane pairs (l, l ^ 16): even rows of 16 lanes get a's, odd rows b's
+// (of the half of the wave they are in)
+__device__ __forceinline__ float fold_rows(float a, float b) {
+  const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Waves per SIMD the registers are held to: four (128 registers) where that needs no spill, else
+// three (two for the one form that would still spill).  Four loads of 16 bytes in flight per lane: with eight the kernel needs 136 registers
+// and up, and at 16 384 query heads x 201 slots a step took 101 us (R = 4) / 50 us (R = 8)
+// instead of 92 / 47.  The vector form above takes 91 / 72 us there; at four times the heads
+// 348 / 301 us against 300 / 173 us here.
+template <int NJ, int R, bool STREAM>
+__global__ __launch_bounds__(kThreads, (R == 4 && NJ <= 4) ? 4 : ((R == 8 && NJ == 4 && !STREAM) ? 2 : 3))
+void decode_gqa_mfma_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+    int t_pos, bf16_t* K, bf16_t* V, float* S, int32_t* P, int32_t* len, int G, int capacity,
+    float alpha, int select, int recent, int evict_here, bf16_t* __restrict__ o, float scale_log2e) {
+  using T = bf16_t;
+  // U = loads of 16 bytes in flight per lane = row groups of four rows per round of a sweep
+  constexpr int D = 128, U = 4, ROWS = 4 * U, NS = NJ * 64, ZS = NS + 4, HB = R / 4;
+  static_assert(R == 4 || R == 8, "four query heads per matrix block");
+  static_assert(U % 4 == 0, "the block sum halves the registers twice");
+  using Grp = WaveGroup;
+  __shared__ __align__(16) float zs[kWaves][R][ZS];
+  __shared__ StepSmem sms[kWaves];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.x * kWaves + wave;
+  if (g >= G) return;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) {
+    for (int r = 0; r < R; ++r) flag_bad_head<T, D>(o + ((size_t)g * R + r) * D, lane, kWave);
+    return;
+  }
+  const int L = n_old + 1;
+  float (*z)[ZS] = zs[wave];
+  T* Kg = K + (size_t)g * capacity * D;
+  T* Vg = V + (size_t)g * capacity * D;
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+  const int blk = lane >> 2, jl = lane & 3;     // matrix block, row / head inside it
+  const int sub = lane & 15, rgrp = lane >> 4;  // V sweep: 16-byte piece of a row, row group
+
+  float s_old[NJ];
+  int pos[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) {
+    const int j = lane + 64 * k;
+    s_old[k] = j < n_old ? Sg[j] : 0.f;
+    pos[k] = j < n_old ? Pg[j] : t_pos;
+  }
+  uint4 qb[HB];  // elements 8*blk .. 8*blk+7 of query head 4h + jl
+#pragma unroll
+  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+
+  // One round of a sweep: load u of this lane is 16 bytes (`piece`) of row base + 4u + row0.
+  // Rounds that end before the newest row take the plain addresses; the last ones redirect the
+  // newest row to the call's input and the rows past it to row 0 (loaded, never used).
+  const auto request = [&](const T* rows, const T* newest, int base, int row0, int piece, uint4 (&x)[U]) {
+    if (base + ROWS <= n_old) {
+      const T* p = rows + (size_t)(base + row0) * D + piece;
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = load16_as<STREAM>(p + (size_t)u * 4 * D);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int row = base + 4 * u + row0;
+        const T* p = (row == n_old) ? newest : rows + (size_t)(row < n_old ? row : 0) * D;
+        x[u] = load16_as<STREAM>(p + piece);
+      }
+    }
+  };
+
+  // ---- K sweep
+  for (int base = 0; base < L; base += ROWS) {
+    uint4 x[U];
+    request(Kg, knew, base, jl, 8 * blk, x);
+#pragma unroll
+    for (int h = 0; h < HB; ++h) {
+      f32x4_t dot[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+        dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].x, x[u].y),
+                                                        as_bf16x4(qb[h].x, qb[h].y), zero, 0, 0, 0);
+        dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].z, x[u].w),
+                                                        as_bf16x4(qb[h].z, qb[h].w), dot[u], 0, 0, 0);
+      }
+      // Sum over the 16 blocks.  The first two steps take two registers each and leave one: the
+      // row of 16 lanes rho then holds, in register (c, v), K row v of row group c + (U/4) * rho,
+      // c < U/4: the U rows of a lane are consecutive.
+      constexpr int C = U / 4;
+      float w[C][4];
+#pragma unroll
+      for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float a = fold_halves(dot[c][v], dot[c + 2 * C][v]);
+          const float b = fold_halves(dot[c + C][v], dot[c + 3 * C][v]);
+          float t = fold_rows(a, b);
+          t += dpp_move<0x124>(t);  // row_ror:4
+          t += dpp_move<0x128>(t);  // row_ror:8
+          w[c][v] = t * scale_log2e;
+        }
+      // rows past L hold row 0's logits; the strip has room (base + ROWS <= NS), nobody reads them
+      if (sub < 4) {
+        float* zp = &z[4 * h + jl][base + 4 * C * rgrp];
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+          *reinterpret_cast<float4*>(zp + 4 * c) = make_float4(w[c][0], w[c][1], w[c][2], w[c][3]);
+      }
+    }
+  }
+  Grp::sync();
+
+  // ---- R softmaxes; psum = the group's probability of each slot.  The strip gets a 0 for
+  // every slot from L on, so that the V sweep reads it without a bound.
+  float psum[NJ];
+#pragma unroll
+  for (int k = 0; k < NJ; ++k) psum[k] = 0.f;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    float zr[NJ];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const int j = lane + 64 * k;
+      zr[k] = j < L ? z[r][j] : -INFINITY;
+      mx = fmaxf(mx, zr[k]);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      zr[k] = exp2f(zr[k] - mx);  // 0 for j >= L
+      sum += zr[k];
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      zr[k] *= inv;
+      psum[k] += zr[k];
+      z[r][lane + 64 * k] = zr[k];
+    }
+  }
+  Grp::sync();
+
+  // ---- V sweep: acc[h][e][i] = o[head 4h+i][8*sub + e], partial over this lane's row group
+  f32x4_t acc[HB][8];
+#pragma unroll
+  for (int h = 0; h < HB; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int base = 0; base < L; base += ROWS) {
+    uint4 x[U];
+    request(Vg, vnew, base, rgrp, 8 * sub, x);
+    float pa[U][HB];  // probability of head 4h + jl for the row of load u
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int h = 0; h < HB; ++h) pa[u][h] = z[4 * h + jl][base + 4 * u + rgrp];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float f[8];
+      Elem<T>::unpack(x[u], f);
+#pragma unroll
+      for (int h = 0; h < HB; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          acc[h][e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pa[u][h], f[e], acc[h][e], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int h = 0; h < HB; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float out[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = acc[h][e][i];
+      v_fold_row_groups<T, D>(out);
+      if (rgrp == 0) store16(o + ((size_t)g * R + 4 * h + i) * D + 8 * sub, pack16(out, T()));
+    }
   Grp::sync();  // the strip's first row is reused by the rare general eviction
 
   wave_update_and_evict<T, D, NJ>(s_old, psum, pos, z[0], n_old, Kg, Vg, Sg, Pg, len + g, knew, vnew,
@@ -1340,6 +1563,31 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
     else if (nj == 4) A2SF_GQAW_(4, R);     \
     else A2SF_GQAW_(8, R);                  \
   } while (0)
+    if constexpr (std::is_same<T, bf16_t>::value && D == 128) {
+      if (group >= 4) {  // both products on the matrix pipe
+#define A2SF_GQAM__(NJ, R, STREAM)                                                                   \
+  hipLaunchKernelGGL((decode_gqa_mfma_kernel<NJ, R, STREAM>), grid, dim3(kThreads), 0, st,           \
+                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,         \
+                     c.scores, c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, \
+                     (T*)o, scale_log2e)
+#define A2SF_GQAM_(NJ, R)                   \
+  do {                                      \
+    if (stream) A2SF_GQAM__(NJ, R, true);   \
+    else A2SF_GQAM__(NJ, R, false);         \
+  } while (0)
+        if (group == 4) {
+          if (nj == 2) A2SF_GQAM_(2, 4);
+          else if (nj == 4) A2SF_GQAM_(4, 4);
+          else A2SF_GQAM_(8, 4);
+        } else {
+          if (nj == 2) A2SF_GQAM_(2, 8);   // group 8: 64*NJ <= 256 slots
+          else A2SF_GQAM_(4, 8);
+        }
+#undef A2SF_GQAM_
+#undef A2SF_GQAM__
+        return;
+      }
+    }
     if (group == 2) A2SF_GQAW(2);
     else if (group == 4) A2SF_GQAW(4);
     else if (nj == 2) A2SF_GQAW_(2, 8);   // group 8: 64*NJ <= 256 slots

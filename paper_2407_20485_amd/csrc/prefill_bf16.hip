@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = across_rows(mx, OpMax(), false, true);
         // The running maximum only has to bound the exponents, not equal the true maximum:
         // it is raised (and the accumulators rescaled) only when some row of the wave
         // exceeds it by more than 2^kLazyRescale, so probabilities stay below that factor
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(kThreads, kFwdOcc) void attn_fwd_bf16_kernel(
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int qrow = wrow0 + nb * 32 + l32;
-    const float l = lsum[nb] + __shfl_xor(lsum[nb], 32, 64);
+    const float l = across_rows(lsum[nb], OpAdd(), false, true);
     if (qrow < n) {
       if (h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
       if (WITH_O) {
@@ -620,7 +620,7 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          mx = across_rows(mx, OpMax(), false, true);
           const float m_new = fmaxf(m[nb], fmaxf(mx * scale_log2e, -1e30f));
           lsum[nb] *= fast_exp2(m[nb] - m_new);  // 0 on the first tile
           m[nb] = m_new;
@@ -638,7 +638,7 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][kb][i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = across_rows(mx, OpMax(), false, true);
       const float mxs = fmaxf(mx * scale_log2e, -1e30f);
       if (__any(mxs > m[nb] + kLazyRescale)) {  // see attn_fwd_bf16_kernel
         const float m_new = fmaxf(m[nb], mxs);
@@ -719,7 +719,7 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
     const int qrow = wrow0 + nb * 32 + l32;
-    const float l = lsum[nb] + __shfl_xor(lsum[nb], 32, 64);
+    const float l = across_rows(lsum[nb], OpAdd(), false, true);
     if (qrow < n && h == 0) LSE2[(size_t)g * n + qrow] = m[nb] + log2f(l);
     if (WITH_O) {
       const float inv = 1.0f / l;
@@ -937,8 +937,7 @@ __global__ __launch_bounds__(kThreads) void col_scores_bf16_kernel(
   // sum over the 32 queries (lanes with the same half)
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) acc[i] += __shfl_xor(acc[i], o, 64);
+    acc[i] = group_sum<32>(acc[i]);
   }
   if (l32 == 0) {
 #pragma unroll

@@ -619,11 +619,56 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
                                                            ("bf16", 128, 8, 160, 80, 70),   # 64*4 slots, 8 query heads
                                                            ("f32", 64, 2, 310, 150, 150),   # 64*8 slots
                                                            ("bf16", 64, 4, 200, 0, 190),    # recent tokens only
-                                                           ("bf16", 128, 2, 140, 129, 0)])  # scores only
+                                                           ("bf16", 128, 2, 140, 129, 0),   # scores only
+                                                           ("bf16", 128, 4, 300, 150, 150), # matrix form, 64*8 slots
+                                                           ("bf16", 128, 4, 100, 70, 80),   # ... cache still filling
+                                                           ("bf16", 128, 8, 40, 30, 30)])   # ... 8 heads, 64*2 slots, filling
 def test_grouped_query_heads_many_kv_heads(dtype, d, group, n, select, recent, say):
     """The same with 1024 K/V heads and short caches: the generation step runs one wave per
-    K/V head."""
+    K/V head (bf16 with d = 128 and four or eight query heads: on the 4x4 matrix instructions)."""
     grouped_query_case(dtype, d, group, n, 0.5, 1024, 4, select, recent, say)
+
+
+@pytest.mark.parametrize("G,cap,group,dtype", [(1024, 40, 4, torch.bfloat16), (1030, 200, 8, torch.bfloat16),
+                                               (1024, 40, 2, torch.bfloat16), (1024, 40, 4, torch.float32),
+                                               (6, 40, 4, torch.bfloat16)])
+def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dtype, say):
+    """As for a2sf_decode_step: a K/V head whose length leaves no free slot (or is negative) is
+    left untouched, the output rows of its query heads are NaN, every other head is computed as
+    if the bad ones were not there.  One case per launch path of a2sf_decode_step_gqa."""
+    d, select = 128, (cap - 1) // 2
+    recent = cap - 1 - select
+    gen = torch.Generator(device="cuda").manual_seed(G + group)
+    c = a2sf.Cache(G, cap, d, dtype)
+    c.k.copy_(torch.randn((G, cap, d), device="cuda", generator=gen))
+    c.v.copy_(torch.randn((G, cap, d), device="cuda", generator=gen))
+    c.scores.copy_(torch.rand((G, cap), device="cuda", generator=gen))
+    c.pos.copy_(torch.arange(cap, dtype=torch.int32, device="cuda").repeat(G, 1))
+    c.len.fill_(cap - 1)
+    q = torch.randn((G, group, d), device="cuda", generator=gen).to(dtype)
+    k, v = (torch.randn((G, d), device="cuda", generator=gen).to(dtype) for _ in range(2))
+    start = c.snapshot()
+    o_good = torch.zeros((G, group, d), dtype=dtype, device="cuda")
+    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o_good)
+    torch.cuda.synchronize()
+    good = c.snapshot()
+    assert bool((c.len == cap - 1).all()) and not torch.isnan(o_good.float()).any()
+    c.restore(start)
+    bad = [1, G - 2]
+    c.len[bad[0]] = cap           # no free slot
+    c.len[bad[1]] = -1
+    start_bad = c.snapshot()
+    o = torch.zeros_like(o_good)
+    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o)
+    torch.cuda.synchronize()
+    ok = torch.ones(G, dtype=torch.bool, device="cuda")
+    ok[bad] = False
+    assert torch.isnan(o[bad].float()).all(), "the bad heads' output rows must be NaN"
+    assert torch.equal(o[ok], o_good[ok])
+    for now, before, clean in zip(c.tensors(), start_bad, good):
+        assert torch.equal(now[bad], before[bad]), "a bad head's cache was touched"
+        assert torch.equal(now[ok], clean[ok])
+    say(f"  [grouped-query invalid length G={G} capacity={cap} group={group}] bad heads flagged with NaN, the others unchanged")
 
 
 def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say):
