@@ -19,6 +19,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -479,6 +480,25 @@ def main():
                              "traffic": read_traffic(f"prefill_cfg{w.cfg_id}" + ("_no_o" if args.no_o else "")),
                              "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"},
     }
+    if args.no_o:
+        # Without outputs the call computes the log-sum-exp of the rows that can still contribute in
+        # fp32 (Section 3.3: the forgetting factor takes older rows to 0) and nothing for the others,
+        # so a full QK^T sweep is no measure of its work any more: the leg is priced by the bytes it
+        # cannot avoid -- every key once, the query rows of that window, the kept rows gathered.
+        rows = n if alpha >= 1.0 else (1 if alpha <= 0.0 else min(n, int(160.0 / -math.log2(alpha)) + 1))
+        B = min(n, w.budget)
+        pbytes = G * (n * d * e + rows * d * e + 2 * n * 4 + 2 * 2 * B * d * e)
+        out["prefill_tflops_model_note"] = ("dense-equivalent: one full causal QK^T sweep over the time of a call "
+                                            "that skips the rows whose weight is exactly 0 in fp32")
+        out["roofline_prefill"] = {
+            "kernel": "a2sf_prefill without outputs (log-sum-exp of the contributing rows + column scores + select + gather)",
+            "bound": "hbm", "achieved": pbytes / pre_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": pbytes / pre_s / 1e9 / HBM_PEAK_GBS, "bytes_per_launch": pbytes, "avg_launch_ms": pre_s * 1e3,
+            "bytes_convention": f"K read once, the {rows} query rows per head of nonzero fp32 weight, scores written and read, "
+                                "kept K/V rows read and written",
+            "dense_equivalent_tflops": pre_tflops,
+            "traffic": read_traffic(f"prefill_cfg{w.cfg_id}_no_o"),
+            "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"}
     if not args.no_cpu_baseline:
         log("[bench] timing the float64 oracle on the host cores ...")
         out["cpu_baseline"] = cpu_baseline(w, alpha)

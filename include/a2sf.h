@@ -104,8 +104,9 @@ size_t a2sf_workspace_bytes(int32_t G, int32_t n_max, int32_t capacity, int32_t 
  *                position: K, V rows, their Eq.5 score, their position; len = min(n, B).
  *                Survivors: the `recent` last positions, plus of the others the `select`
  *                with the largest score (tie -> lower position).
- *   o            out [G, n, d] dtype: attention output rows; may be NULL (then no P*V
- *                work is done).
+ *   o            out [G, n, d] dtype: attention output rows; may be NULL: then no P*V
+ *                work is done, and (bf16, d = 128) rows whose weight alpha^(n-1-i) is
+ *                exactly 0 in fp32 are not visited at all where the scores do not need them.
  *   scores_full  out [G, n] fp32: the Eq.5 score of every prompt token; may be NULL.
  * The n x n probability matrix is never written to memory. */
 a2sf_status a2sf_prefill(const void* q, const void* k, const void* v, int32_t n, float alpha,

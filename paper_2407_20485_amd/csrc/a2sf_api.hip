@@ -147,7 +147,8 @@ a2sf_status prefill_impl(const void* q, const void* k, const void* v, int32_t n,
       launch_prefill_f32((const float*)qp, (const float*)kp, (const float*)vp, Gp, n, d, (float*)op, lp, st);
       launch_scores_f32((const float*)qp, (const float*)kp, lp, Gp, n, d, alpha, ap, sp, st);
     } else {
-      launch_prefill_bf16(qp, kp, vp, Gp, n, d, op, lp, st);
+      // without outputs only the rows the score kernel will read need their log-sum-exp
+      launch_prefill_bf16(qp, kp, vp, Gp, n, d, op, lp, st, op ? 0 : bf16_first_lse_row(n, d, alpha));
       launch_scores_bf16(qp, kp, lp, Gp, n, d, alpha, ap, tol, sp, st);
     }
     launch_select(sp, nullptr, nullptr, Gp, n, n, budget.select, budget.recent, kip, nkp, st);

@@ -75,6 +75,9 @@ struct AttnRect {
   // k2 / v2 -- a chunk whose rows have not been copied behind the cached ones.
   const void* k2 = nullptr;
   const void* v2 = nullptr;
+  // Calls without outputs (bf16, d = 128): the log-sum-exp of the rows before first_row is not
+  // needed (the score kernel that follows skips them), so their row blocks are not computed.
+  int first_row = 0;
 };
 // true when launch_attn_bf16 / launch_colscores_bf16 serve these sizes with kernels that read a
 // second key / value source
@@ -102,8 +105,12 @@ void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const 
 void launch_colscores_bf16(const void* q, const void* k, const float* lse2, int G,
                            const AttnRect& rc, int keys_per_head, int d, float alpha, float* scores,
                            int s_stride, bool accumulate, float decay, hipStream_t st);
+// first_row > 0 (only with o == null): rows before it need no log-sum-exp
 void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
-                         void* o, float* lse2, hipStream_t st);
+                         void* o, float* lse2, hipStream_t st, int first_row = 0);
+// First prompt row whose log-sum-exp launch_scores_bf16 reads for these sizes (Section 3.3: the
+// forgetting factor takes older rows' contributions to 0; exactly 0 in fp32 before that row).
+int bf16_first_lse_row(int n, int d, float alpha_max);
 // tol > 0 (d = 128 only): rows whose whole remaining contribution is provably below tol * S_j
 // are skipped (see RowWindow in prefill_bf16.hip); tol = 0 computes every row of nonzero weight.
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,

@@ -464,7 +464,9 @@ __global__ __launch_bounds__(kThreads, !WITH_O ? kScoreOnlyOcc : (NB == 1 ? 2 : 
   const long long vid = xcd_contiguous_id(total);
   if (vid >= total) return;
   const int g = (int)(vid / nqb);
-  const int qb = nqb - 1 - (int)(vid % nqb);  // longest rows first
+  // longest rows first; without outputs the launch covers only the nqb row blocks from the one
+  // that holds rc.first_row on
+  const int qb = (WITH_O ? 0 : rc.first_row / BM) + nqb - 1 - (int)(vid % nqb);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
@@ -960,7 +962,8 @@ void launch_fwd_rect(const void* q, const void* k, const void* v, int G, const A
   if constexpr (D == 128) {
     // direct-to-LDS tiles and transposing LDS reads; without outputs one row block per wave
     const int nb = o ? 1 : kScoreOnlyNB;
-    const int nqb = (rc.m + kWaves * 32 * nb - 1) / (kWaves * 32 * nb);
+    const int bm = kWaves * 32 * nb;
+    const int nqb = (rc.m + bm - 1) / bm - (o ? 0 : rc.first_row / bm);  // row blocks to compute
     const long long total = (long long)GQ * nqb;
     const unsigned grid = (unsigned)(((total + 7) / 8) * 8);
     if (o)
@@ -991,7 +994,7 @@ void launch_fwd_rect(const void* q, const void* k, const void* v, int G, const A
 // Square geometry (a whole prompt): G K/V heads, kv_group query heads each.
 template <int D>
 void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, void* o, float* lse2,
-                hipStream_t st, int kv_group = 1) {
+                hipStream_t st, int kv_group = 1, int first_row = 0) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const int G = G_kv * kv_group;  // query heads
   int kv_shift = 0;
@@ -1027,7 +1030,9 @@ void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, vo
     // (fma + exp + add per logit against 1/16 matrix op): one 32-row block per wave at four
     // workgroups per compute unit overlaps the two better than two blocks per wave at two
     // (16384 heads of n = 2048: 11.1 ms against 12.75).
-    launch_fwd_rect<D>(q, k, v, G_kv, AttnRect{n, n, nullptr, kv_group}, o, lse2, st);
+    AttnRect rc{n, n, nullptr, kv_group};
+    rc.first_row = o ? 0 : first_row;
+    launch_fwd_rect<D>(q, k, v, G_kv, rc, o, lse2, st);
   } else {
     launch_fwd_rect<D>(q, k, v, G_kv, AttnRect{n, n, nullptr, kv_group}, o, lse2, st);
   }
@@ -1474,9 +1479,18 @@ void launch_colscores_bf16(const void* q, const void* k, const float* lse2, int 
 }
 
 void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int n, int d,
-                         void* o, float* lse2, hipStream_t st) {
+                         void* o, float* lse2, hipStream_t st, int first_row) {
   if (d == 64) launch_fwd<64>(q, k, v, G, n, o, lse2, st);
-  else launch_fwd<128>(q, k, v, G, n, o, lse2, st);
+  else launch_fwd<128>(q, k, v, G, n, o, lse2, st, 1, first_row);
+}
+
+int bf16_first_lse_row(int n, int d, float alpha_max) {
+  if (d != 128) return 0;
+  float l2a;
+  const int r_lo = (first_contributing_row(n, alpha_max, &l2a) / kTile) * kTile;
+  // col_scores_tail128_kernel reads the rows it stages, from r_lo on; the other score kernels
+  // are given every row
+  return n - r_lo <= kTailTiles * kTile ? r_lo : 0;
 }
 
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,
