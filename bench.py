@@ -497,6 +497,10 @@ def main():
             "bytes_convention": f"K read once, the {rows} query rows per head of nonzero fp32 weight, scores written and read, "
                                 "kept K/V rows read and written",
             "dense_equivalent_tflops": pre_tflops,
+            # flops of the rows that are processed: the log-sum-exp pass over the 128-row blocks from the
+            # one holding row n - rows on, the score pass over the rows themselves (2 flop per MAC)
+            "flops_of_rows_processed": G * 2 * d * (sum(i + 1 for i in range(((n - rows) // 128) * 128, n))
+                                                    + sum(i + 1 for i in range(n - rows, n))),
             "traffic": read_traffic(f"prefill_cfg{w.cfg_id}_no_o"),
             "traffic_source": f"{TRAFFIC_FILE} (earlier rocprofv3 --pmc runs of this command; not measured in this run)"}
     if not args.no_cpu_baseline:

@@ -1487,10 +1487,10 @@ void launch_prefill_bf16(const void* q, const void* k, const void* v, int G, int
 int bf16_first_lse_row(int n, int d, float alpha_max) {
   if (d != 128) return 0;
   float l2a;
-  const int r_lo = (first_contributing_row(n, alpha_max, &l2a) / kTile) * kTile;
-  // col_scores_tail128_kernel reads the rows it stages, from r_lo on; the other score kernels
-  // are given every row
-  return n - r_lo <= kTailTiles * kTile ? r_lo : 0;
+  // every score kernel walks the row tiles from the one that holds the first contributing row
+  // on (col_scores_tail128_kernel stages them, the others start their tile loop there; a tile
+  // they fetch below it is never used)
+  return (first_contributing_row(n, alpha_max, &l2a) / kTile) * kTile;
 }
 
 void launch_scores_bf16(const void* q, const void* k, const float* lse2, int G, int n, int d,

@@ -129,22 +129,24 @@ def test_small_bf16_ragged(alpha, d, n, say):
     run_lockstep(w, alpha, say=say)
 
 
-@pytest.mark.parametrize("base,d,n", [(1, 128, 300), (1, 64, 200), (0, 64, 130), (1, 128, 1100)])
-def test_prefill_optional_outputs(base, d, n):
+@pytest.mark.parametrize("base,d,n,alpha", [(1, 128, 300, 0.4), (1, 64, 200, 0.4), (0, 64, 130, 0.4), (1, 128, 1100, 0.4),
+                                            (1, 128, 1500, 0.9)])
+def test_prefill_optional_outputs(base, d, n, alpha):
     """o = NULL (no P*V work) and scores_full = NULL (scores kept in the workspace) must leave
     the same cache as the call that returns both: the same tokens, rows and positions bit for
     bit, the same scores (without outputs: to fp32 rounding).  Without outputs the bf16 path of
     d = 128 also leaves out the row blocks whose log-sum-exp the score pass never reads (at
-    n = 1100 seven of nine)."""
+    n = 1100 seven of nine; at n = 1500 with alpha = 0.9, where the streaming score kernel
+    runs, three of twelve)."""
     w = variant(base, heads=6, d=d, n=n, T=1, select=11, recent=9, name="optional outputs")
     p = parity.Problem(w)
-    p.gpu_prefill(0.4)
+    p.gpu_prefill(alpha)
     torch.cuda.synchronize()
     full = p.cache.snapshot()
     for want_o, want_s in ((False, True), (True, False), (False, False)):
         for t in p.cache.tensors():
             t.zero_()
-        p.gpu_prefill(0.4, want_o=want_o, want_scores=want_s)
+        p.gpu_prefill(alpha, want_o=want_o, want_scores=want_s)
         torch.cuda.synchronize()
         for name, a, b in zip(("k", "v", "scores", "pos", "len"), full, p.cache.tensors()):
             if name == "scores" and not want_o:
