@@ -1041,11 +1041,12 @@ void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, vo
 // ---------------------------------------------------------------------------------------
 // col_scores for a short row window (alpha well below 1), d = 128.  Only rows >= first_row
 // contribute (see first_contributing_row), at most kTailTiles tiles of 64 rows.  One
-// workgroup per head stages those Q rows in LDS once (direct global-to-LDS loads) and then
-// walks over all key blocks of the head: a wave keeps 32 keys as A fragments in registers
-// (the next block's fragments are fetched while the current block is computed), recomputes
-// the logit tiles against the staged Q rows, applies exp2(s - lse_i + (n-1-i) log2 alpha) and
-// sums down the rows.  K is read exactly once, Q's window once per head.
+// workgroup per head (with few heads: per share of a head's keys) stages those Q rows in LDS
+// once (direct global-to-LDS loads) and then walks over its key blocks: a wave keeps 32 keys
+// as A fragments in registers (the next block's fragments are fetched while the current block
+// is computed), recomputes the logit tiles against the staged Q rows, applies
+// exp2(s - lse_i + (n-1-i) log2 alpha) and sums down the rows.  K is read exactly once, Q's
+// window once per workgroup.
 constexpr int kTailTiles = 4;
 constexpr int kTailKB = 2;  // 32-key blocks per wave and step
 
@@ -1076,13 +1077,15 @@ struct RowWindow {
 __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const float* __restrict__ LSE2,
     float* __restrict__ S, AttnRect rc, int s_stride, bool accumulate, float decay, int first_row,
-    float log2_alpha, const float* __restrict__ alpha_heads, float scale_log2e, float tol) {
+    float log2_alpha, const float* __restrict__ alpha_heads, float scale_log2e, float tol, int ksplit) {
   constexpr int D = 128, KK = D / 16, BC = kWaves * 32;
   __shared__ __attribute__((aligned(1024))) char smem[kTailTiles * kTileBytes];
   __shared__ __attribute__((aligned(16))) float strip[kWaves][32 * kTailKB];   // a wave's scores of one step
   lds_char* const qs = (lds_char*)smem;
 
-  const int g = blockIdx.x;
+  // ksplit workgroups share a head's keys (few heads with long prompts: one workgroup per head
+  // would leave most of the chip idle); each stages the row window for itself
+  const int g = blockIdx.x / ksplit, kpart = blockIdx.x % ksplit;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: branches on it are scalar
   const int l32 = lane & 31, h = lane >> 5;
@@ -1092,6 +1095,10 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
   const int off = rc.off_heads ? rc.off_heads[g] : 0;
   if (off < 0) return;  // a head the caller's precondition excludes
   const int nk = off + n;
+  constexpr int STEP = BC * kTailKB;  // keys per workgroup step
+  const int kspan = ((nk + ksplit * STEP - 1) / (ksplit * STEP)) * STEP;  // keys per workgroup
+  const int c_begin = kpart * kspan, c_end = min(nk, c_begin + kspan);
+  if (c_begin >= nk) return;
   const bf16_t* Qg = Q + (size_t)g * n * D;
   const bf16_t* Kg = K + (size_t)g * rc.kv_stride * D;
   const bf16_t* K2g = rc.k2 ? (const bf16_t*)rc.k2 + (size_t)g * n * D : nullptr;  // keys off .. from here
@@ -1134,18 +1141,17 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_tail128_kernel(
     }
   };
   uint4 kf[kTailKB][KK];
-  load_keys(0, kf);
+  load_keys(c_begin, kf);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   const RowWindow win(tol, log2_alpha);
   const int rb_last = (n - 1 - r_lo) >> 5;   // the row block that holds the newest row
   const int lane_last = (n - 1 - r_lo) & 31;
-  constexpr int STEP = BC * kTailKB;  // keys per workgroup step
-  for (int c0 = 0; c0 < nk; c0 += STEP) {
+  for (int c0 = c_begin; c0 < c_end; c0 += STEP) {
     const int wc0 = c0 + wave * kTailKB * 32;  // first key of this wave in this step
     int lim = max(wc0 - off, first_row);       // rows before `lim` add nothing to this wave's keys
-    bool pending = c0 + STEP < nk;             // the next step's keys still have to be fetched
+    bool pending = c0 + STEP < c_end;          // the next step's keys still have to be fetched
     float acc[kTailKB][16];
 #pragma unroll
     for (int b = 0; b < kTailKB; ++b)
@@ -1401,6 +1407,14 @@ __global__ __launch_bounds__(kThreads, 2) void col_scores_stream128_kernel(
   }
 }
 
+// Workgroups per head of col_scores_tail128_kernel: with fewer heads than the chip takes
+// workgroups (two per compute unit), a head's keys are shared out, in steps of 256 keys.
+inline int tail_key_split(int G, int keys_per_head) {
+  const int steps = (keys_per_head + kWaves * 32 * kTailKB - 1) / (kWaves * 32 * kTailKB);
+  const int want = (512 + G - 1) / G;
+  return want < 1 ? 1 : (want > steps ? steps : want);
+}
+
 // col_scores_bf16_kernel for any head size and geometry
 template <int D>
 void launch_cols_rect(const void* q, const void* k, const float* lse2, int G, const AttnRect& rc,
@@ -1412,9 +1426,10 @@ void launch_cols_rect(const void* q, const void* k, const float* lse2, int G, co
   if constexpr (D == 128) {
     // a row window of at most four tiles: staged once per head, every key streamed once
     if (bf16_two_source_ok(D, rc, alpha)) {  // (also the only score kernel that reads a second key source)
-      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
+      const int ks = tail_key_split(G, keys_per_head);
+      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G * ks), dim3(kThreads), 0, st, (const bf16_t*)q,
                          (const bf16_t*)k, lse2, scores, rc, s_stride, accumulate, decay, first, l2a,
-                         alpha_heads, scale_log2e, 0.f);
+                         alpha_heads, scale_log2e, 0.f, ks);
       return;
     }
   }
@@ -1434,9 +1449,10 @@ void launch_cols(const void* q, const void* k, const float* lse2, int G, int n, 
   const int first = first_contributing_row(n, alpha, &l2a);
   if constexpr (D == 128) {
     if (n - (first / kTile) * kTile <= kTailTiles * kTile) {
-      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G), dim3(kThreads), 0, st, (const bf16_t*)q,
+      const int ks = tail_key_split(G, n);
+      hipLaunchKernelGGL(col_scores_tail128_kernel, dim3(G * ks), dim3(kThreads), 0, st, (const bf16_t*)q,
                          (const bf16_t*)k, lse2, scores, AttnRect{n, n, nullptr}, n, false, 0.f, first, l2a,
-                         alpha_heads, scale_log2e, tol);
+                         alpha_heads, scale_log2e, tol, ks);
       return;
     }
     constexpr int BC = kWaves * 32 * kStreamKB;
