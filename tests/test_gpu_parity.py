@@ -1246,3 +1246,63 @@ def test_similarity_protocol_module(say):
     assert abs(float(mean.item()) - got[first:].mean()) <= 1e-6
     a2sf.a2sf_similarity_mean(cos, n, G, n, mean)        # nothing left to average
     assert float(mean.item()) == 1.0
+
+
+# ------------------------------------------------------------------------------ seeded random shapes
+def test_random_shapes_lockstep(say):
+    """Prompt phase and generation steps in lock-step with the oracle on 40 seeded random
+    shapes: 1 to 40 heads (one case in five: 960 to 8960 heads with short prompts, a seeded
+    sample of them followed by the oracle), both head sizes and dtypes, prompts of 1 to 700
+    tokens, budgets from 1 to 1500 tokens split at random (also larger than the prompt: the
+    cache still filling), capacities with and without spare slots, six forgetting factors,
+    both eviction modes."""
+    rng = np.random.default_rng(20485)
+    for c in range(40):
+        big = rng.random() < 0.2
+        base = int(rng.integers(0, 2))
+        d = int(rng.choice([64, 128]))
+        if big:
+            heads, layers = 32, int(rng.integers(30, 280))
+            n, B = int(rng.integers(1, 120)), int(rng.integers(2, 500))
+        else:
+            heads, layers = int(rng.integers(1, 41)), 1
+            n = int(rng.integers(1, 700))
+            B = int(rng.choice([rng.integers(1, 40), rng.integers(40, 600), rng.integers(600, 1500)]))
+        select = int(rng.integers(0, B + 1))
+        alpha = float(rng.choice([0.0, 0.1, 0.3, 0.5, 0.9, 1.0]))
+        mode = int(rng.choice([a2sf.A2SF_EVICT_FAST, a2sf.A2SF_EVICT_STABLE]))
+        cap = B + 1 + int(rng.choice([0, 0, 3, 64]))
+        w = variant(base, heads=heads, layers=layers, batch=1, d=d, n=n, T=int(rng.integers(1, 7)), select=select,
+                    recent=B - select, name=f"random shape {c}: G={heads * layers} d={d} n={n} budget={select}+{B - select} capacity={cap}")
+        sample = None if w.G <= 40 else sorted(set(rng.choice(w.G, 24, replace=False).tolist()) | {0, w.G - 1})
+        run_lockstep(w, alpha, mode=mode, sample=sample, capacity=cap, say=say)
+
+
+def test_random_shapes_grouped_query(say):
+    """The grouped-query prompt phase and generation steps on 16 seeded random shapes (group
+    sizes 2, 4, 8; a handful or more than a thousand K/V heads; both dtypes and head sizes)."""
+    rng = np.random.default_rng(20486)
+    for c in range(16):
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        d, group = int(rng.choice([64, 128])), int(rng.choice([2, 4, 8]))
+        big = rng.random() < 0.5
+        G = int(rng.integers(1024, 1400)) if big else int(rng.integers(1, 12))
+        n = int(rng.integers(1, 200)) if big else int(rng.integers(1, 500))
+        B = int(rng.integers(2, min(500, 16384 // group - 1)))
+        select = int(rng.integers(0, B + 1))
+        alpha = float(rng.choice([0.0, 0.3, 0.5, 0.9, 1.0]))
+        grouped_query_case(dtype, d, group, n, alpha, G, int(rng.integers(1, 5)), select, B - select, say)
+
+
+def test_random_chunkings(say):
+    """a2sf_prefill_chunk on 40 seeded random chunkings (with and without a prompt phase before
+    them, chunks of 1 to 300 rows, budgets of 1 to 300 tokens)."""
+    rng = np.random.default_rng(20487)
+    body = getattr(test_prefill_chunks_match_oracle, "__wrapped__", test_prefill_chunks_match_oracle)
+    for c in range(40):
+        base, d = int(rng.integers(0, 2)), int(rng.choice([64, 128]))
+        n0 = int(rng.choice([0, rng.integers(1, 300)]))
+        chunks = tuple(int(x) for x in rng.integers(1, int(rng.choice([8, 70, 300])) + 1, size=int(rng.integers(1, 4))))
+        B = int(rng.integers(1, 300))
+        select = int(rng.integers(0, B + 1))
+        body(base, d, n0, chunks, (select, B - select), float(rng.choice([0.0, 0.2, 0.4, 0.9, 1.0])), say)
