@@ -426,6 +426,105 @@ __global__ __launch_bounds__(kThreads) void decode_fused_kernel(
                                sm);
 }
 
+// ---- grouped-query heads on the 4x4 matrix instructions --------------------------------
+// bf16, d = 128, R = 4 or 8 query heads per K/V head.  The wave-per-head kernel above spends
+// ~20 vector instructions per row and query head on the logits (eight multiply-adds, a lane
+// reduction, a masked LDS write) and eight per row and head on the output; with R >= 4 that
+// arithmetic, not the row stream, sets its time.  Here both products go to the matrix pipe as
+// sixteen independent 4x4 blocks per instruction, which fits four query heads exactly:
+//   logits   v_mfma_f32_4x4x4_16B_bf16: block b = lane / 4 takes the 8 elements 8b .. 8b+7 of
+//            4 K rows (lane 4b+i: row i, one 16-byte load = two k-steps) against the same
+//            elements of the 4 queries (lane 4b+j: head j); register v of lane 4b+j then holds
+//            the partial dot product of row v with head j over chunk b, and the 16 chunks are
+//            summed across lanes: two halving steps that swap lane halves / odd and even rows
+//            of 16 lanes between two registers (so the register count halves with each add),
+//            then two rotations inside the rows of 16 lanes;
+//   outputs  v_mfma_f32_4x4x1_16B_f32, an outer product per block: lane 4b+i brings the
+//            probability of head i for the V row of its row group, lane 4b+j element e of its 16
+//            bytes of that row; register i of lane 4b+j accumulates o[head i][8*(lane%16)+e] --
+//            the layout the vector form ends in, so the fold over row groups is shared.
+// Lane layouts of both instructions and of the two swaps were checked on the device against
+// a host computation before this was written.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x4_t as_bf16x4(uint32_t lo, uint32_t hi) {
+  const u32x2_t t = {lo, hi};
+  return __builtin_bit_cast(bf16x4_t, t);
+}
+// a, b -> sum over the lane pairs (l, l ^ 32): lanes < 32 get a's, lanes >= 32 get b's
+__device__ __forceinline__ float fold_halves(float a, float b) {
+  const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+// a, b -> sum over the lane pairs (l, l ^ 16): even rows of 16 lanes get a's, odd rows b's
+// (of the half of the wave they are in)
+__device__ __forceinline__ float fold_rows(float a, float b) {
+  const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// One round of a sweep in the matrix forms: load u of a lane is 16 bytes (`piece`) of row
+// base + 4u + row0.  Rounds that end before the newest row take the plain addresses; the
+// last ones redirect the newest row to the call's input and the rows past it to row 0
+// (loaded, never used).
+template <int U, bool STREAM>
+__device__ __forceinline__ void gqa_request_rows(const bf16_t* rows, const bf16_t* newest, int base,
+                                                 int row0, int piece, int n_old, uint4 (&x)[U]) {
+  constexpr int D = 128;
+  if (base + 4 * U <= n_old) {
+    const bf16_t* p = rows + (size_t)(base + row0) * D + piece;
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = load16_as<STREAM>(p + (size_t)u * 4 * D);
+  } else {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = base + 4 * u + row0;
+      const bf16_t* p = (row == n_old) ? newest : rows + (size_t)(row < n_old ? row : 0) * D;
+      x[u] = load16_as<STREAM>(p + piece);
+    }
+  }
+}
+
+// Logits of the 4U K rows of a round (x as requested with row0 = lane % 4, piece = 8 * (lane / 4))
+// against four query heads (qb: elements 8 * (lane / 4) .. + 7 of head lane % 4).  The sum over
+// the 16 blocks takes two registers and leaves one in its first two steps: the row of 16 lanes
+// rho then holds, in w[c][v], K row 4 * (c + (U / 4) * rho) + v of the round, for head lane % 4
+// (the same value in the four lanes of the row that share lane % 4).
+template <int U>
+__device__ __forceinline__ void gqa_block_logits(const uint4 (&x)[U], const uint4& qb, float scale,
+                                                 float (&w)[U / 4][4]) {
+  static_assert(U % 4 == 0, "the block sum halves the registers twice");
+  constexpr int C = U / 4;
+  f32x4_t dot[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].x, x[u].y), as_bf16x4(qb.x, qb.y), zero, 0, 0, 0);
+    dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].z, x[u].w), as_bf16x4(qb.z, qb.w), dot[u], 0, 0, 0);
+  }
+#pragma unroll
+  for (int c = 0; c < C; ++c)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float a = fold_halves(dot[c][v], dot[c + 2 * C][v]);
+      const float b = fold_halves(dot[c + C][v], dot[c + 3 * C][v]);
+      float t = fold_rows(a, b);
+      t += dpp_move<0x124>(t);  // row_ror:4
+      t += dpp_move<0x128>(t);  // row_ror:8
+      w[c][v] = t * scale;
+    }
+}
+
+// acc[e][i] += pa * (element e of this lane's 16 bytes of a V row): lane 4b+i brings head i's
+// probability of the row, register i of lane 4b+j gets o[head i][8 * (lane % 16) + e]
+__device__ __forceinline__ void gqa_outer_products(const uint4& xu, float pa, f32x4_t (&acc)[8]) {
+  float f[8];
+  Elem<bf16_t>::unpack(xu, f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pa, f[e], acc[e], 0, 0, 0);
+}
+
 // ---- grouped-query heads: one workgroup per K/V head, R query heads ---------------------
 // The K and V rows of the head are streamed once and serve all R queries (R logits per row in
 // the K sweep, R output accumulators in the V sweep); every query head has its own softmax.
@@ -463,31 +562,65 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
   SlotBatch first;
   load_slot_batch(first, no_aux, Sg, Pg, tid, n_old, t_pos);
 
-  float qv[R][Gm::EPL];
-#pragma unroll
-  for (int r = 0; r < R; ++r) load_query<T, D>(q + ((size_t)g * R + r) * D, scale_log2e, qv[r]);
+  // bf16, d = 128, four or eight query heads: both products on the 4x4 matrix instructions (see
+  // above; with R >= 4 the vector form is bound by its arithmetic: 640 K/V heads x 2001 slots,
+  // R = 8: 228 us per step against 107 us of the same cache with ungrouped heads).  A wave takes
+  // 4 * UM consecutive rows of every round of 4 * UM * kWaves.
+  constexpr bool kMatrix = std::is_same<T, bf16_t>::value && D == 128 && (R == 4 || R == 8);
+  constexpr int UM = 8, HB = R / 4, MROWS = 4 * UM;
+  const int blk = lane >> 2, jl = lane & 3;  // matrix block, row / head inside it
 
-  // ---- K sweep: R logits per row
-  for (int base = 0; base < L; base += ROWS_PER_ITER) {
-    uint4 x[U];
+  if constexpr (kMatrix) {
+    uint4 qb[HB > 0 ? HB : 1];  // elements 8*blk .. 8*blk+7 of query head 4h + jl
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
-      const T* p = (row == n_old) ? knew : Kg + (size_t)(row < L ? row : 0) * D;
-      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+    for (int h = 0; h < HB; ++h)
+      qb[h] = load16(reinterpret_cast<const bf16_t*>(q) + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+    for (int base = wave * MROWS; base < L; base += kWaves * MROWS) {
+      uint4 x[UM];
+      gqa_request_rows<UM, STREAM>(reinterpret_cast<const bf16_t*>(Kg), reinterpret_cast<const bf16_t*>(knew),
+                                   base, jl, 8 * blk, n_old, x);
+#pragma unroll
+      for (int h = 0; h < HB; ++h) {
+        float w[UM / 4][4];
+        gqa_block_logits<UM>(x, qb[h], scale_log2e, w);
+        if (sub < 4) {
+#pragma unroll
+          for (int c = 0; c < UM / 4; ++c)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const int row = base + UM * rgrp + 4 * c + v;
+              if (row < L) a[(4 * h + jl) * capacity + row] = w[c][v];
+            }
+        }
+      }
     }
+  } else {
+    float qv[R][Gm::EPL];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
-      float f[Gm::EPL];
-      Elem<T>::unpack(x[u], f);
+    for (int r = 0; r < R; ++r) load_query<T, D>(q + ((size_t)g * R + r) * D, scale_log2e, qv[r]);
+
+    // ---- K sweep: R logits per row
+    for (int base = 0; base < L; base += ROWS_PER_ITER) {
+      uint4 x[U];
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        float dot = 0.f;
+      for (int u = 0; u < U; ++u) {
+        const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+        const T* p = (row == n_old) ? knew : Kg + (size_t)(row < L ? row : 0) * D;
+        x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+      }
 #pragma unroll
-        for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[r][e], f[e], dot);
-        dot = group_sum<Gm::LPR>(dot);
-        if (sub == 0 && row < L) a[r * capacity + row] = dot;
+      for (int u = 0; u < U; ++u) {
+        const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+        float f[Gm::EPL];
+        Elem<T>::unpack(x[u], f);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < Gm::EPL; ++e) dot = fmaf(qv[r][e], f[e], dot);
+          dot = group_sum<Gm::LPR>(dot);
+          if (sub == 0 && row < L) a[r * capacity + row] = dot;
+        }
       }
     }
   }
@@ -513,37 +646,72 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
   __syncthreads();
 
   // ---- V sweep: R output rows
-  float acc[R][Gm::EPL];
+  if constexpr (kMatrix) {
+    f32x4_t macc[HB > 0 ? HB : 1][8];  // macc[h][e][i] = o[head 4h+i][8*sub + e], this lane's row group
 #pragma unroll
-  for (int r = 0; r < R; ++r)
+    for (int h = 0; h < HB; ++h)
 #pragma unroll
-    for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = 0.f;
-  for (int base = 0; base < L; base += ROWS_PER_ITER) {
-    uint4 x[U];
+      for (int e = 0; e < 8; ++e) macc[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int base = wave * MROWS; base < L; base += kWaves * MROWS) {
+      uint4 x[UM];
+      gqa_request_rows<UM, STREAM>(reinterpret_cast<const bf16_t*>(Vg), reinterpret_cast<const bf16_t*>(vnew),
+                                   base, rgrp, 8 * sub, n_old, x);
+      float pa[UM][HB > 0 ? HB : 1];  // probability of head 4h + jl for the row of load u
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
-      const T* p = (row == n_old) ? vnew : Vg + (size_t)(row < L ? row : 0) * D;
-      x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+      for (int u = 0; u < UM; ++u) {
+        const int row = base + 4 * u + rgrp;
+#pragma unroll
+        for (int h = 0; h < HB; ++h) pa[u][h] = row < L ? a[(4 * h + jl) * capacity + row] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < UM; ++u)
+#pragma unroll
+        for (int h = 0; h < HB; ++h) gqa_outer_products(x[u], pa[u][h], macc[h]);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
-      float f[Gm::EPL];
-      Elem<T>::unpack(x[u], f);
+    for (int h = 0; h < HB; ++h)
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        const float wr = row < L ? a[r * capacity + row] : 0.f;
+      for (int i = 0; i < 4; ++i) {
+        float out[Gm::EPL];
 #pragma unroll
-        for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = fmaf(wr, f[e], acc[r][e]);
+        for (int e = 0; e < Gm::EPL; ++e) out[e] = macc[h][e < 8 ? e : 0][i];
+        v_fold_row_groups<T, D>(out);
+        reduce_output<T, D>(out, part);
+        if (tid < D) Elem<T>::store(o + ((size_t)g * R + 4 * h + i) * D + tid, part[0][tid]);
+      }
+  } else {
+    float acc[R][Gm::EPL];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = 0.f;
+    for (int base = 0; base < L; base += ROWS_PER_ITER) {
+      uint4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+        const T* p = (row == n_old) ? vnew : Vg + (size_t)(row < L ? row : 0) * D;
+        x[u] = load16_as<STREAM>(p + sub * Gm::EPL);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int row = base + (u * kWaves + wave) * Gm::RPW + rgrp;
+        float f[Gm::EPL];
+        Elem<T>::unpack(x[u], f);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+          const float wr = row < L ? a[r * capacity + row] : 0.f;
+#pragma unroll
+          for (int e = 0; e < Gm::EPL; ++e) acc[r][e] = fmaf(wr, f[e], acc[r][e]);
+        }
       }
     }
-  }
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    v_fold_row_groups<T, D>(acc[r]);
-    reduce_output<T, D>(acc[r], part);
-    if (tid < D) Elem<T>::store(o + ((size_t)g * R + r) * D + tid, part[0][tid]);
+    for (int r = 0; r < R; ++r) {
+      v_fold_row_groups<T, D>(acc[r]);
+      reduce_output<T, D>(acc[r], part);
+      if (tid < D) Elem<T>::store(o + ((size_t)g * R + r) * D + tid, part[0][tid]);
+    }
   }
 
   // ---- S <- alpha*S + sum of the R probability rows, eviction as for a single head
@@ -1133,44 +1301,6 @@ __global__ __launch_bounds__(kThreads, R <= 4 ? 1 : 2) void decode_gqa_wave_kern
                                   t_pos, alpha, select, recent, evict_here != 0, sms[wave]);
 }
 
-// ---- grouped-query heads on the 4x4 matrix instructions --------------------------------
-// bf16, d = 128, R = 4 or 8 query heads per K/V head.  The wave-per-head kernel above spends
-// ~20 vector instructions per row and query head on the logits (eight multiply-adds, a lane
-// reduction, a masked LDS write) and eight per row and head on the output; with R >= 4 that
-// arithmetic, not the row stream, sets its time.  Here both products go to the matrix pipe as
-// sixteen independent 4x4 blocks per instruction, which fits four query heads exactly:
-//   logits   v_mfma_f32_4x4x4_16B_bf16: block b = lane / 4 takes the 8 elements 8b .. 8b+7 of
-//            4 K rows (lane 4b+i: row i, one 16-byte load = two k-steps) against the same
-//            elements of the 4 queries (lane 4b+j: head j); register v of lane 4b+j then holds
-//            the partial dot product of row v with head j over chunk b, and the 16 chunks are
-//            summed across lanes: two halving steps that swap lane halves / odd and even rows
-//            of 16 lanes between two registers (so the register count halves with each add),
-//            then two rotations inside the rows of 16 lanes;
-//   outputs  v_mfma_f32_4x4x1_16B_f32, an outer product per block: lane 4b+i brings the
-//            probability of head i for the V row of its row group, lane 4b+j element e of its 16
-//            bytes of that row; register i of lane 4b+j accumulates o[head i][8*(lane%16)+e] --
-//            the layout the vector form ends in, so the fold over row groups is shared.
-// Lane layouts of both instructions and of the two swaps were checked on the device against
-// a host computation before this was written.
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-typedef short bf16x4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ bf16x4_t as_bf16x4(uint32_t lo, uint32_t hi) {
-  const u32x2_t t = {lo, hi};
-  return __builtin_bit_cast(bf16x4_t, t);
-}
-// a, b -> sum over the lane pairs (l, l ^ 32): lanes < 32 get a's, lanes >= 32 get b's
-__device__ __forceinline__ float fold_halves(float a, float b) {
-  const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// a, b -> sum over the lane pairs (l, l ^ 16): even rows of 16 lanes get a's, odd rows b's
-// (of the half of the wave they are in)
-__device__ __forceinline__ float fold_rows(float a, float b) {
-  const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
 // Waves per SIMD the registers are held to: four (128 registers) where that needs no spill, else
 // three (two for the one form that would still spill).  Four loads of 16 bytes in flight per lane: with eight the kernel needs 136 registers
 // and up, and at 16 384 query heads x 201 slots a step took 101 us (R = 4) / 50 us (R = 8)
@@ -1221,60 +1351,19 @@ void decode_gqa_mfma_kernel(
 #pragma unroll
   for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
 
-  // One round of a sweep: load u of this lane is 16 bytes (`piece`) of row base + 4u + row0.
-  // Rounds that end before the newest row take the plain addresses; the last ones redirect the
-  // newest row to the call's input and the rows past it to row 0 (loaded, never used).
-  const auto request = [&](const T* rows, const T* newest, int base, int row0, int piece, uint4 (&x)[U]) {
-    if (base + ROWS <= n_old) {
-      const T* p = rows + (size_t)(base + row0) * D + piece;
-#pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = load16_as<STREAM>(p + (size_t)u * 4 * D);
-    } else {
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int row = base + 4 * u + row0;
-        const T* p = (row == n_old) ? newest : rows + (size_t)(row < n_old ? row : 0) * D;
-        x[u] = load16_as<STREAM>(p + piece);
-      }
-    }
-  };
-
   // ---- K sweep
   for (int base = 0; base < L; base += ROWS) {
     uint4 x[U];
-    request(Kg, knew, base, jl, 8 * blk, x);
+    gqa_request_rows<U, STREAM>(Kg, knew, base, jl, 8 * blk, n_old, x);
 #pragma unroll
     for (int h = 0; h < HB; ++h) {
-      f32x4_t dot[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
-        dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].x, x[u].y),
-                                                        as_bf16x4(qb[h].x, qb[h].y), zero, 0, 0, 0);
-        dot[u] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(as_bf16x4(x[u].z, x[u].w),
-                                                        as_bf16x4(qb[h].z, qb[h].w), dot[u], 0, 0, 0);
-      }
-      // Sum over the 16 blocks.  The first two steps take two registers each and leave one: the
-      // row of 16 lanes rho then holds, in register (c, v), K row v of row group c + (U/4) * rho,
-      // c < U/4: the U rows of a lane are consecutive.
-      constexpr int C = U / 4;
-      float w[C][4];
-#pragma unroll
-      for (int c = 0; c < C; ++c)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const float a = fold_halves(dot[c][v], dot[c + 2 * C][v]);
-          const float b = fold_halves(dot[c + C][v], dot[c + 3 * C][v]);
-          float t = fold_rows(a, b);
-          t += dpp_move<0x124>(t);  // row_ror:4
-          t += dpp_move<0x128>(t);  // row_ror:8
-          w[c][v] = t * scale_log2e;
-        }
+      float w[U / 4][4];
+      gqa_block_logits<U>(x, qb[h], scale_log2e, w);
       // rows past L hold row 0's logits; the strip has room (base + ROWS <= NS), nobody reads them
       if (sub < 4) {
-        float* zp = &z[4 * h + jl][base + 4 * C * rgrp];
+        float* zp = &z[4 * h + jl][base + U * rgrp];
 #pragma unroll
-        for (int c = 0; c < C; ++c)
+        for (int c = 0; c < U / 4; ++c)
           *reinterpret_cast<float4*>(zp + 4 * c) = make_float4(w[c][0], w[c][1], w[c][2], w[c][3]);
       }
     }
@@ -1322,22 +1411,16 @@ void decode_gqa_mfma_kernel(
     for (int e = 0; e < 8; ++e) acc[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   for (int base = 0; base < L; base += ROWS) {
     uint4 x[U];
-    request(Vg, vnew, base, rgrp, 8 * sub, x);
+    gqa_request_rows<U, STREAM>(Vg, vnew, base, rgrp, 8 * sub, n_old, x);
     float pa[U][HB];  // probability of head 4h + jl for the row of load u
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int h = 0; h < HB; ++h) pa[u][h] = z[4 * h + jl][base + 4 * u + rgrp];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float f[8];
-      Elem<T>::unpack(x[u], f);
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int h = 0; h < HB; ++h)
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          acc[h][e] = __builtin_amdgcn_mfma_f32_4x4x1f32(pa[u][h], f[e], acc[h][e], 0, 0, 0);
-    }
+      for (int h = 0; h < HB; ++h) gqa_outer_products(x[u], pa[u][h], acc[h]);
   }
 #pragma unroll
   for (int h = 0; h < HB; ++h)

@@ -619,6 +619,17 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
     grouped_query_case(dtype, d, group, n, alpha, 3, 6, 14, 10, say)
 
 
+@pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 8, 700, 300, 300),
+                                                           ("bf16", 128, 4, 900, 500, 390),
+                                                           ("bf16", 128, 8, 300, 1000, 1000),   # cache still filling
+                                                           ("f32", 128, 4, 400, 150, 150)])
+def test_grouped_query_heads_long_caches(dtype, d, group, n, select, recent, say):
+    """Few K/V heads with caches of hundreds of slots: the generation step runs one workgroup
+    per K/V head (bf16 with d = 128 and four or eight query heads: on the 4x4 matrix
+    instructions, every wave 32 consecutive rows of a round of 128)."""
+    grouped_query_case(dtype, d, group, n, 0.5, 3, 3, select, recent, say)
+
+
 @pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 4, 30, 14, 10),    # 64*2 slots per wave
                                                            ("bf16", 128, 8, 160, 80, 70),   # 64*4 slots, 8 query heads
                                                            ("f32", 64, 2, 310, 150, 150),   # 64*8 slots
