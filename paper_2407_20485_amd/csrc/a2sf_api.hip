@@ -360,8 +360,11 @@ a2sf_status a2sf_decode_step_gqa(const void* q, const void* k_new, const void* v
 
   hipStream_t st = (hipStream_t)hip_stream;
   clear_stale_error();
+  // the split region of the workspace, as far as the caller's buffer reaches into it
+  const bool has_split = workspace && !misaligned(workspace) && workspace_bytes > w.split;
   launch_decode_gqa(q, k_new, v_new, t_pos, *cache, group, alpha, budget.select, budget.recent,
-                    mode == A2SF_EVICT_FAST, o, st);
+                    mode == A2SF_EVICT_FAST, o, has_split ? (char*)workspace + w.split : nullptr,
+                    has_split ? workspace_bytes - w.split : 0, st);
   if (mode == A2SF_EVICT_STABLE) {
     char* ws = (char*)workspace;
     int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);

@@ -40,10 +40,11 @@ void launch_decode(const void* q, const void* k_new, const void* v_new, int t_po
                    hipStream_t st);
 
 // Generation step of G K/V heads with `group` (2, 4 or 8) query heads each: q, o are
-// [G, group, d]; group * capacity floats of LDS per workgroup.
+// [G, group, d]; group * capacity floats of LDS per workgroup.  ws (may be null) / ws_bytes:
+// scratch memory for the token-split form that few K/V heads with long caches take.
 void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int t_pos,
                        const a2sf_cache& c, int group, float alpha, int select, int recent,
-                       bool evict_here, void* o, hipStream_t st);
+                       bool evict_here, void* o, void* ws, size_t ws_bytes, hipStream_t st);
 
 // chunk.hip: the chunk's K/V rows go behind each head's cached tokens (len grows by m, the old
 // lengths are left in len_old, -1 where the chunk does not fit)

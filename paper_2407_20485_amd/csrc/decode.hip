@@ -20,6 +20,7 @@
 // writes back in LDS (decode_wave_loop_kernel).
 #include <math.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "a2sf_dev.h"
@@ -1618,13 +1619,241 @@ void launch_typed(const void* q, const void* k_new, const void* v_new, int t_pos
                      zbuf, ml, po, alpha, alpha_heads, select, recent, (int)evict_here, (T*)o);
 }
 
+// ---- grouped-query heads, tokens of a K/V head split over workgroups -------------------
+// Few K/V heads with long caches (a layer of a grouped-query model at batch 1 has 8 of them):
+// one workgroup per head leaves the chip idle, as in the ungrouped case.  bf16, d = 128, R = 4 or
+// 8: workgroup (g, c) runs the matrix-instruction rounds over rows [c * rows_per_split, ...) for
+// all R query heads, leaves their logits, per-split (max, sum) and unnormalised outputs in the
+// workspace; one combine workgroup per K/V head merges the R softmaxes, writes the R outputs,
+// sums the R probability rows per slot and runs the usual score update and eviction.
+// workspace (floats): z[G*R][capacity] | ml[G*R][nsplit][2] | po[G*R][nsplit][128]
+template <int R>
+__global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+    const bf16_t* __restrict__ K, const bf16_t* __restrict__ V, const int32_t* __restrict__ len,
+    int capacity, int nsplit, int rows_per_split, float* __restrict__ zbuf, float* __restrict__ ml,
+    float* __restrict__ po, float scale_log2e) {
+  using T = bf16_t;
+  // a wave takes 16 consecutive rows of a round of 64 (the smallest split), and the workgroup
+  // meets at three barriers only: a split is too short to pay for more
+  constexpr int D = 128, UM = 4, HB = R / 4, MROWS = 4 * UM;
+  static_assert(R == 4 || R == 8, "four query heads per matrix block");
+  extern __shared__ float z[];  // [R][rows_per_split]
+  __shared__ float part[kWaves][R][D];
+  const int g = blockIdx.x / nsplit, c = blockIdx.x % nsplit, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int blk = lane >> 2, jl = lane & 3, sub = lane & 15, rgrp = lane >> 4;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) return;
+  const int L = n_old + 1;
+  const int r0 = c * rows_per_split;
+  const int r1 = min(L, r0 + rows_per_split);
+  if (r0 >= r1) {
+    for (int r = 0; r < R; ++r) {
+      float* mlo = ml + (((size_t)g * R + r) * nsplit + c) * 2;
+      if (tid == 0) { mlo[0] = -INFINITY; mlo[1] = 0.f; }
+      if (tid < D) po[(((size_t)g * R + r) * nsplit + c) * D + tid] = 0.f;
+    }
+    return;
+  }
+  const T* Kg = K + (size_t)g * capacity * D;
+  const T* Vg = V + (size_t)g * capacity * D;
+  const T* knew = k_new + (size_t)g * D;
+  const T* vnew = v_new + (size_t)g * D;
+  uint4 qb[HB];
+#pragma unroll
+  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+
+  for (int base = r0 + wave * MROWS; base < r1; base += kWaves * MROWS) {
+    uint4 x[UM];
+    gqa_request_rows<UM, true>(Kg, knew, base, jl, 8 * blk, n_old, x);
+#pragma unroll
+    for (int h = 0; h < HB; ++h) {
+      float w[UM / 4][4];
+      gqa_block_logits<UM>(x, qb[h], scale_log2e, w);
+      if (sub < 4) {
+#pragma unroll
+        for (int cc = 0; cc < UM / 4; ++cc)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int row = base + UM * rgrp + 4 * cc + v;
+            if (row < r1) z[(4 * h + jl) * rows_per_split + row - r0] = w[cc][v];
+          }
+      }
+    }
+  }
+  __syncthreads();
+  // a query head's softmax over the split is one wave's work
+  for (int r = wave; r < R; r += kWaves) {
+    float* zr = z + r * rows_per_split;
+    float* zg = zbuf + ((size_t)g * R + r) * capacity;
+    float mx = -INFINITY;
+    for (int j = r0 + lane; j < r1; j += kWave) {
+      const float zz = zr[j - r0];
+      zg[j] = zz;
+      mx = fmaxf(mx, zz);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int j = r0 + lane; j < r1; j += kWave) {
+      const float pr = exp2f(zr[j - r0] - mx);
+      zr[j - r0] = pr;
+      sum += pr;
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) {
+      float* mlo = ml + (((size_t)g * R + r) * nsplit + c) * 2;
+      mlo[0] = mx;
+      mlo[1] = sum;
+    }
+  }
+  __syncthreads();
+
+  f32x4_t macc[HB][8];
+#pragma unroll
+  for (int h = 0; h < HB; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) macc[h][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int base = r0 + wave * MROWS; base < r1; base += kWaves * MROWS) {
+    uint4 x[UM];
+    gqa_request_rows<UM, true>(Vg, vnew, base, rgrp, 8 * sub, n_old, x);
+    float pa[UM][HB];
+#pragma unroll
+    for (int u = 0; u < UM; ++u) {
+      const int row = base + 4 * u + rgrp;
+#pragma unroll
+      for (int h = 0; h < HB; ++h) pa[u][h] = row < r1 ? z[(4 * h + jl) * rows_per_split + row - r0] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < UM; ++u)
+#pragma unroll
+      for (int h = 0; h < HB; ++h) gqa_outer_products(x[u], pa[u][h], macc[h]);
+  }
+  // every wave's partial outputs of all R heads side by side, then one sum over the waves
+#pragma unroll
+  for (int h = 0; h < HB; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float out[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = macc[h][e][i];
+      v_fold_row_groups<T, D>(out);
+      if (rgrp == 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[wave][4 * h + i][8 * sub + e] = out[e];
+      }
+    }
+  __syncthreads();
+  for (int idx = tid; idx < R * D; idx += kThreads) {
+    const int r = idx / D, col = idx % D;
+    po[(((size_t)g * R + r) * nsplit + c) * D + col] =
+        (part[0][r][col] + part[1][r][col]) + (part[2][r][col] + part[3][r][col]);
+  }
+}
+
+template <int R>
+__global__ __launch_bounds__(kThreads) void decode_gqa_combine_kernel(
+    const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new, int t_pos, bf16_t* K, bf16_t* V,
+    float* S, int32_t* P, int32_t* len, int capacity, int nsplit, const float* __restrict__ zbuf,
+    const float* __restrict__ ml, const float* __restrict__ po, float alpha, int select, int recent,
+    int evict_here, bf16_t* __restrict__ o) {
+  using T = bf16_t;
+  constexpr int D = 128;
+  extern __shared__ float a[];  // [capacity]: the group's summed probability of each slot
+  __shared__ StepSmem sm;
+  __shared__ float wsplit[R][kWave];
+  __shared__ float mx_s[R], inv_s[R];
+  const int g = blockIdx.x, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int n_old = len[g];
+  if (n_old < 0 || n_old >= capacity) {
+    for (int r = 0; r < R; ++r) flag_bad_head<T, D>(o + ((size_t)g * R + r) * D, tid, kThreads);
+    return;
+  }
+  const int L = n_old + 1;
+  float* Sg = S + (size_t)g * capacity;
+  int32_t* Pg = P + (size_t)g * capacity;
+  const auto no_aux = [](int) { return 0.f; };
+  SlotBatch first;
+  load_slot_batch(first, no_aux, Sg, Pg, tid, n_old, t_pos);
+  // per query head: the splits' (max, sum) merged by one wave, one lane per split (nsplit <= 64)
+  for (int r = wave; r < R; r += kWaves) {
+    const float* mlg = ml + ((size_t)g * R + r) * nsplit * 2;
+    const float mc = lane < nsplit ? mlg[2 * lane] : -INFINITY;
+    const float lc = lane < nsplit ? mlg[2 * lane + 1] : 0.f;
+    const float mw = wave_max(mc);
+    const float w = exp2f(mc - mw);  // 0 for empty splits
+    const float sw = wave_sum(lc * w);
+    wsplit[r][lane] = w;
+    if (lane == 0) { mx_s[r] = mw; inv_s[r] = 1.0f / sw; }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < R * D; idx += kThreads) {
+    const int r = idx / D, col = idx % D;
+    const float* por = po + ((size_t)g * R + r) * nsplit * D + col;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int c = 0; c < nsplit; ++c) acc = fmaf(por[(size_t)c * D], wsplit[r][c], acc);
+    Elem<T>::store(o + ((size_t)g * R + r) * D + col, acc * inv_s[r]);
+  }
+  for (int j = tid; j < L; j += kThreads) {
+    float p = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) p += exp2f(zbuf[((size_t)g * R + r) * capacity + j] - mx_s[r]) * inv_s[r];
+    a[j] = p;
+  }
+  __syncthreads();
+  update_and_evict<T, D, true>(no_aux, [&](int j, float) { return a[j]; }, first, a, n_old,
+                               K + (size_t)g * capacity * D, V + (size_t)g * capacity * D, Sg, Pg,
+                               len + g, k_new + (size_t)g * D, v_new + (size_t)g * D, t_pos, alpha,
+                               select, recent, evict_here != 0, sm);
+}
+
 template <typename T, int D>
 void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t_pos,
                       const a2sf_cache& c, int group, float alpha, int select, int recent,
-                      bool evict_here, void* o, hipStream_t st) {
+                      bool evict_here, void* o, void* ws, size_t ws_bytes, hipStream_t st) {
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const size_t lds = (size_t)group * c.capacity * sizeof(float);
   const bool stream = 4.0 * c.G * c.capacity * D > 512e6;   // as in plan_decode
+  // Few K/V heads with long caches: tokens split over workgroups where plan_decode would split
+  // the same cache with ungrouped heads, as far as the scratch memory the caller gave allows.
+  if constexpr (std::is_same<T, bf16_t>::value && D == 128) {
+    const DecodePlan kv = plan_decode(c.G, c.capacity, D);
+    if (group >= 4 && kv.nsplit > 1 && ws) {
+      const size_t heads = (size_t)c.G * group;
+      const size_t fixed = heads * c.capacity * sizeof(float);              // the logits
+      const size_t per_split = heads * (2 + D) * sizeof(float);             // (max, sum) and output
+      int ns = ws_bytes > fixed ? (int)std::min<size_t>((ws_bytes - fixed) / per_split, (size_t)kv.nsplit) : 0;
+      if (ns >= 2) {
+        int rows = (c.capacity + ns - 1) / ns;
+        rows = (rows + 63) / 64 * 64;
+        ns = (c.capacity + rows - 1) / rows;
+        float* zbuf = (float*)ws;
+        float* ml = zbuf + heads * c.capacity;
+        float* po = ml + heads * ns * 2;
+        const size_t lds_p = (size_t)group * rows * sizeof(float);
+        const size_t lds_c = (size_t)c.capacity * sizeof(float);
+        constexpr int kMaxLds = A2SF_MAX_CAPACITY * (int)sizeof(float);
+#define A2SF_GQAS(R)                                                                                      \
+  do {                                                                                                    \
+    static const hipError_t raised = hipFuncSetAttribute(                                                 \
+        (const void*)decode_gqa_combine_kernel<R>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);  \
+    (void)raised;                                                                                         \
+    hipLaunchKernelGGL((decode_gqa_partial_kernel<R>), dim3((unsigned)c.G * ns), dim3(kThreads), lds_p,   \
+                       st, (const T*)q, (const T*)k_new, (const T*)v_new, (const T*)c.k, (const T*)c.v,   \
+                       c.len, c.capacity, ns, rows, zbuf, ml, po, scale_log2e);                           \
+    hipLaunchKernelGGL((decode_gqa_combine_kernel<R>), dim3(c.G), dim3(kThreads), lds_c, st,              \
+                       (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len, \
+                       c.capacity, ns, zbuf, ml, po, alpha, select, recent, (int)evict_here, (T*)o);      \
+  } while (0)
+        if (group == 4) A2SF_GQAS(4);
+        else A2SF_GQAS(8);
+#undef A2SF_GQAS
+        return;
+      }
+    }
+  }
   // Many K/V heads with short caches: one wave per K/V head (its strip of R probability rows
   // must fit: 4 waves x R x 64*NJ floats <= 32 KB)
   const int nj = c.capacity <= 128 ? 2 : (c.capacity <= 256 ? 4 : 8);
@@ -1701,13 +1930,13 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
 
 void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int t_pos,
                        const a2sf_cache& c, int group, float alpha, int select, int recent,
-                       bool evict_here, void* o, hipStream_t st) {
+                       bool evict_here, void* o, void* ws, size_t ws_bytes, hipStream_t st) {
   if (c.dtype == A2SF_F32) {
-    if (c.d == 64) launch_gqa_typed<float, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
-    else launch_gqa_typed<float, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+    if (c.d == 64) launch_gqa_typed<float, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, ws, ws_bytes, st);
+    else launch_gqa_typed<float, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, ws, ws_bytes, st);
   } else {
-    if (c.d == 64) launch_gqa_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
-    else launch_gqa_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, st);
+    if (c.d == 64) launch_gqa_typed<bf16_t, 64>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, ws, ws_bytes, st);
+    else launch_gqa_typed<bf16_t, 128>(q, k_new, v_new, t_pos, c, group, alpha, select, recent, evict_here, o, ws, ws_bytes, st);
   }
 }
 

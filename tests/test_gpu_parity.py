@@ -623,11 +623,14 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
                                                            ("bf16", 128, 4, 900, 500, 390),
                                                            ("bf16", 128, 8, 300, 1000, 1000),   # cache still filling
                                                            ("f32", 128, 4, 400, 150, 150)])
-def test_grouped_query_heads_long_caches(dtype, d, group, n, select, recent, say):
-    """Few K/V heads with caches of hundreds of slots: the generation step runs one workgroup
-    per K/V head (bf16 with d = 128 and four or eight query heads: on the 4x4 matrix
-    instructions, every wave 32 consecutive rows of a round of 128)."""
-    grouped_query_case(dtype, d, group, n, 0.5, 3, 3, select, recent, say)
+@pytest.mark.parametrize("split", [False, True])
+def test_grouped_query_heads_long_caches(dtype, d, group, n, select, recent, split, say):
+    """Few K/V heads with caches of hundreds of slots.  Without room for it in the workspace the
+    generation step runs one workgroup per K/V head (bf16 with d = 128 and four or eight query
+    heads: on the 4x4 matrix instructions, every wave 32 consecutive rows of a round of 128);
+    with the workspace of the prompt phase those forms split a head's tokens over workgroups
+    and merge them in a second kernel."""
+    grouped_query_case(dtype, d, group, n, 0.5, 3, 3, select, recent, say, small_decode_ws=not split)
 
 
 @pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 4, 30, 14, 10),    # 64*2 slots per wave
@@ -646,7 +649,7 @@ def test_grouped_query_heads_many_kv_heads(dtype, d, group, n, select, recent, s
 
 @pytest.mark.parametrize("G,cap,group,dtype", [(1024, 40, 4, torch.bfloat16), (1030, 200, 8, torch.bfloat16),
                                                (1024, 40, 2, torch.bfloat16), (1024, 40, 4, torch.float32),
-                                               (6, 40, 4, torch.bfloat16)])
+                                               (6, 40, 4, torch.bfloat16), (6, 1000, 8, torch.bfloat16)])
 def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dtype, say):
     """As for a2sf_decode_step: a K/V head whose length leaves no free slot (or is negative) is
     left untouched, the output rows of its query heads are NaN, every other head is computed as
@@ -662,9 +665,12 @@ def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dt
     c.len.fill_(cap - 1)
     q = torch.randn((G, group, d), device="cuda", generator=gen).to(dtype)
     k, v = (torch.randn((G, d), device="cuda", generator=gen).to(dtype) for _ in range(2))
+    # with this workspace the long-cache case takes the token-split form
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, 64, cap, d, a2sf.A2SF_F32 if dtype == torch.float32 else a2sf.A2SF_BF16,
+                                               select, recent), dtype=torch.uint8, device="cuda")
     start = c.snapshot()
     o_good = torch.zeros((G, group, d), dtype=dtype, device="cuda")
-    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o_good)
+    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o_good, workspace=ws)
     torch.cuda.synchronize()
     good = c.snapshot()
     assert bool((c.len == cap - 1).all()) and not torch.isnan(o_good.float()).any()
@@ -674,7 +680,7 @@ def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dt
     c.len[bad[1]] = -1
     start_bad = c.snapshot()
     o = torch.zeros_like(o_good)
-    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o)
+    a2sf.a2sf_decode_step_gqa(q, k, v, cap, c, group, 0.5, select, recent, o, workspace=ws)
     torch.cuda.synchronize()
     ok = torch.ones(G, dtype=torch.bool, device="cuda")
     ok[bad] = False
@@ -686,7 +692,7 @@ def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dt
     say(f"  [grouped-query invalid length G={G} capacity={cap} group={group}] bad heads flagged with NaN, the others unchanged")
 
 
-def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say):
+def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say, small_decode_ws=False):
     rng = np.random.Generator(np.random.Philox(key=[n, d * 16 + group]))
     # heads the oracle follows: all of them, or the first and last workgroups plus a seeded sample
     heads = list(range(G)) if G <= 16 else sorted(set(range(8)) | set(range(G - 8, G)) |
@@ -733,10 +739,13 @@ def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say):
             assert np.array_equal(parity.to_f64(cache.k[g, :lens[g]]), c.K)
         assert o_err <= parity.O_TOL[dtype]
         od = torch.empty((G, group, d), dtype=tdt, device="cuda")
+        # small_decode_ws: only what the stable mode needs, which leaves no room for the token-split form
+        ws_dec = ws if not small_decode_ws else torch.empty(
+            a2sf.a2sf_workspace_bytes(G, 0, B + 1, d, code, select, recent), dtype=torch.uint8, device="cuda")
         for t in range(T):
             r = n + t
             a2sf.a2sf_decode_step_gqa(dev[0][:, :, r].contiguous(), dev[1][:, r].contiguous(), dev[2][:, r].contiguous(),
-                                      r, cache, group, alpha, select, recent, od, mode=mode, workspace=ws)
+                                      r, cache, group, alpha, select, recent, od, mode=mode, workspace=ws_dec)
             torch.cuda.synchronize()
             pos = cache.pos.cpu().numpy()
             lens = cache.len.cpu().numpy()
