@@ -1299,16 +1299,17 @@ def test_random_shapes_lockstep(say):
 
 
 def test_random_shapes_grouped_query(say):
-    """The grouped-query prompt phase and generation steps on 16 seeded random shapes (group
-    sizes 2, 4, 8; a handful or more than a thousand K/V heads; both dtypes and head sizes)."""
+    """The grouped-query prompt phase and generation steps on 20 seeded random shapes (group
+    sizes 2, 4, 8; a handful of K/V heads with budgets up to 2040 tokens, or more than a
+    thousand with short caches; both dtypes and head sizes)."""
     rng = np.random.default_rng(20486)
-    for c in range(16):
+    for c in range(20):
         dtype = str(rng.choice(["bf16", "bf16", "f32"]))
         d, group = int(rng.choice([64, 128])), int(rng.choice([2, 4, 8]))
         big = rng.random() < 0.5
         G = int(rng.integers(1024, 1400)) if big else int(rng.integers(1, 12))
         n = int(rng.integers(1, 200)) if big else int(rng.integers(1, 500))
-        B = int(rng.integers(2, min(500, 16384 // group - 1)))
+        B = int(rng.integers(2, min(500 if big else 2040, 16384 // group - 1)))   # long caches of few heads: token split
         select = int(rng.integers(0, B + 1))
         alpha = float(rng.choice([0.0, 0.3, 0.5, 0.9, 1.0]))
         grouped_query_case(dtype, d, group, n, alpha, G, int(rng.integers(1, 5)), select, B - select, say)
