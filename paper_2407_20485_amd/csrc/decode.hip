@@ -1788,13 +1788,25 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_combine_kernel(
     if (lane == 0) { mx_s[r] = mw; inv_s[r] = 1.0f / sw; }
   }
   __syncthreads();
-  for (int idx = tid; idx < R * D; idx += kThreads) {
-    const int r = idx / D, col = idx % D;
-    const float* por = po + ((size_t)g * R + r) * nsplit * D + col;
-    float acc = 0.f;
-#pragma unroll 4
-    for (int c = 0; c < nsplit; ++c) acc = fmaf(por[(size_t)c * D], wsplit[r][c], acc);
-    Elem<T>::store(o + ((size_t)g * R + r) * D + col, acc * inv_s[r]);
+  {
+    // a thread's R * D / kThreads outputs side by side, so that their loads are in flight together
+    constexpr int PER = R * D / kThreads;
+    float acc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+#pragma unroll 8
+    for (int c = 0; c < nsplit; ++c) {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int idx = tid + i * kThreads, r = idx / D, col = idx % D;
+        acc[i] = fmaf(po[(((size_t)g * R + r) * nsplit + c) * D + col], wsplit[r][c], acc[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int idx = tid + i * kThreads, r = idx / D, col = idx % D;
+      Elem<T>::store(o + ((size_t)g * R + r) * D + col, acc[i] * inv_s[r]);
+    }
   }
   for (int j = tid; j < L; j += kThreads) {
     float p = 0.f;
