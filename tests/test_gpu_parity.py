@@ -1067,6 +1067,55 @@ def test_decode_steps_replay_from_a_hip_graph(G, mode, select, say):
     say(f"  [graph replay G={G} {mode} budget={select + recent}] {T} steps captured, 3 replays identical to the eager run")
 
 
+@pytest.mark.parametrize("G,group,select,mode", [(6, 8, 500, "fast"),      # token split over workgroups
+                                                 (6, 4, 500, "stable"),
+                                                 (1100, 4, 60, "fast"),    # one wave per K/V head, matrix form
+                                                 (1100, 2, 60, "stable"),  # ... vector form
+                                                 (5, 8, 100, "fast")])     # one workgroup per K/V head
+def test_grouped_query_steps_replay_from_a_hip_graph(G, group, select, mode, say):
+    """The same for a2sf_decode_step_gqa, one case per launch path (the first two with caches
+    still filling, so that some splits are empty; the others evicting)."""
+    d, n, T, recent, alpha = 128, 300, 5, select, 0.4
+    evict = a2sf.A2SF_EVICT_FAST if mode == "fast" else a2sf.A2SF_EVICT_STABLE
+    gen = torch.Generator(device="cuda").manual_seed(G + group)
+    q = torch.randn((G, group, n + T, d), device="cuda", generator=gen).bfloat16()
+    k, v = (torch.randn((G, n + T, d), device="cuda", generator=gen).bfloat16() for _ in range(2))
+    cap = select + recent + 1
+    cache = a2sf.Cache(G, cap, d, torch.bfloat16)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, n, cap, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    a2sf.a2sf_prefill_gqa(q[:, :, :n].contiguous(), k[:, :n].contiguous(), v[:, :n].contiguous(), n, group, alpha,
+                          select, recent, cache, workspace=ws)
+    start = cache.snapshot()
+    steps = [(q[:, :, n + t].contiguous(), k[:, n + t].contiguous(), v[:, n + t].contiguous()) for t in range(T)]
+    outs = torch.zeros((T, G, group, d), dtype=torch.bfloat16, device="cuda")
+
+    def run_steps():
+        for t, (qt, kt, vt) in enumerate(steps):
+            a2sf.a2sf_decode_step_gqa(qt, kt, vt, n + t, cache, group, alpha, select, recent, outs[t], mode=evict,
+                                      workspace=ws)
+
+    run_steps()
+    torch.cuda.synchronize()
+    want_o, want_cache = outs.clone(), cache.snapshot()
+    assert not torch.isnan(want_o.float()).any()
+    graph = torch.cuda.CUDAGraph()
+    cache.restore(start)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        run_steps()
+    for replay in range(3):
+        cache.restore(start)
+        outs.zero_()
+        (k[:, 0] * 2).sum().item()          # unrelated eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, want_o), f"replay {replay}: outputs differ"
+        for a, b in zip(cache.tensors(), want_cache):
+            assert torch.equal(a, b), f"replay {replay}: cache differs"
+    say(f"  [graph replay grouped-query G={G} x {group} {mode} budget={select + recent}] {T} steps captured, 3 replays identical to the eager run")
+
+
 @pytest.mark.parametrize("n,G,d", [(512, 256, 128), (300, 5, 128), (200, 6, 64)])
 def test_prompt_phase_replays_from_a_hip_graph(n, G, d, say):
     """The prompt phase (attention, column scores, selection, gather: up to five launches,
