@@ -176,7 +176,7 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
  * group.  The group's score of a token is the SUM of its query heads' accumulated scores -- as
  * the paper's Eq.1 sums over the heads that one pruning decision serves.  Every query head has
  * its own softmax and its own output.
- *   group        1, 2, 4 or 8 (1 = the plain calls).
+ *   group        1 .. 8 (1 = the plain calls).
  *   q            prefill: [G, group, n, d]; decode: [G, group, d].
  *   k, v / k_new, v_new   as in the plain calls: one row per K/V head.
  *   o            prefill: [G, group, n, d] (may be NULL); decode: [G, group, d].

@@ -270,7 +270,7 @@ a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int3
 }
 
 namespace {
-inline bool bad_group(int32_t group) { return group != 1 && group != 2 && group != 4 && group != 8; }
+inline bool bad_group(int32_t group) { return group < 1 || group > 8; }
 }  // namespace
 
 a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_t n, int32_t group,
@@ -302,7 +302,7 @@ a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_
   // in parts of kPrefillPartHeads query heads, as the plain prompt phase and for the same reason
   const size_t e = cache->dtype == A2SF_F32 ? 4 : 2;
   const int B = budget.select + budget.recent;
-  const int part_kv = kPrefillPartHeads / group;   // K/V heads per part (group is 1, 2, 4 or 8)
+  const int part_kv = kPrefillPartHeads / group;   // K/V heads per part
   const int part = (cache->dtype == A2SF_BF16 && G >= 2 * part_kv) ? part_kv : G;
   for (int g0 = 0; g0 < G; g0 += part) {
     const int Gp = G - g0 < part ? G - g0 : part;

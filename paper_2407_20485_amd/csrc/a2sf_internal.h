@@ -39,7 +39,7 @@ void launch_decode(const void* q, const void* k_new, const void* v_new, int t_po
                    int recent, bool evict_here, void* o, void* ws, const DecodePlan& plan,
                    hipStream_t st);
 
-// Generation step of G K/V heads with `group` (2, 4 or 8) query heads each: q, o are
+// Generation step of G K/V heads with `group` (2 .. 8) query heads each: q, o are
 // [G, group, d]; group * capacity floats of LDS per workgroup.  ws (may be null) / ws_bytes:
 // scratch memory for the token-split form that few K/V heads with long caches take.
 void launch_decode_gqa(const void* q, const void* k_new, const void* v_new, int t_pos,

@@ -567,15 +567,15 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
   // above; with R >= 4 the vector form is bound by its arithmetic: 640 K/V heads x 2001 slots,
   // R = 8: 228 us per step against 107 us of the same cache with ungrouped heads).  A wave takes
   // 4 * UM consecutive rows of every round of 4 * UM * kWaves.
-  constexpr bool kMatrix = std::is_same<T, bf16_t>::value && D == 128 && (R == 4 || R == 8);
-  constexpr int UM = 8, HB = R / 4, MROWS = 4 * UM;
+  constexpr bool kMatrix = std::is_same<T, bf16_t>::value && D == 128 && R >= 3;
+  constexpr int UM = 8, HB = (R + 3) / 4, MROWS = 4 * UM;   // a last block of fewer than four heads idles its other columns
   const int blk = lane >> 2, jl = lane & 3;  // matrix block, row / head inside it
 
   if constexpr (kMatrix) {
     uint4 qb[HB > 0 ? HB : 1];  // elements 8*blk .. 8*blk+7 of query head 4h + jl
 #pragma unroll
     for (int h = 0; h < HB; ++h)
-      qb[h] = load16(reinterpret_cast<const bf16_t*>(q) + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+      qb[h] = load16(reinterpret_cast<const bf16_t*>(q) + ((size_t)g * R + min(4 * h + jl, R - 1)) * D + 8 * blk);
     for (int base = wave * MROWS; base < L; base += kWaves * MROWS) {
       uint4 x[UM];
       gqa_request_rows<UM, STREAM>(reinterpret_cast<const bf16_t*>(Kg), reinterpret_cast<const bf16_t*>(knew),
@@ -590,7 +590,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
               const int row = base + UM * rgrp + 4 * c + v;
-              if (row < L) a[(4 * h + jl) * capacity + row] = w[c][v];
+              if (row < L && 4 * h + jl < R) a[(4 * h + jl) * capacity + row] = w[c][v];
             }
         }
       }
@@ -662,7 +662,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
       for (int u = 0; u < UM; ++u) {
         const int row = base + 4 * u + rgrp;
 #pragma unroll
-        for (int h = 0; h < HB; ++h) pa[u][h] = row < L ? a[(4 * h + jl) * capacity + row] : 0.f;
+        for (int h = 0; h < HB; ++h) pa[u][h] = (row < L && 4 * h + jl < R) ? a[(4 * h + jl) * capacity + row] : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < UM; ++u)
@@ -673,6 +673,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_kernel(
     for (int h = 0; h < HB; ++h)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        if (4 * h + i >= R) continue;
         float out[Gm::EPL];
 #pragma unroll
         for (int e = 0; e < Gm::EPL; ++e) out[e] = macc[h][e < 8 ? e : 0][i];
@@ -1308,15 +1309,15 @@ __global__ __launch_bounds__(kThreads, R <= 4 ? 1 : 2) void decode_gqa_wave_kern
 // instead of 92 / 47.  The vector form above takes 91 / 72 us there; at four times the heads
 // 348 / 301 us against 300 / 173 us here.
 template <int NJ, int R, bool STREAM>
-__global__ __launch_bounds__(kThreads, (R == 4 && NJ <= 4) ? 4 : ((R == 8 && NJ == 4 && !STREAM) ? 2 : 3))
+__global__ __launch_bounds__(kThreads, (R <= 4 && NJ <= 4) ? 4 : ((R > 4 && NJ == 4 && !STREAM) ? 2 : 3))
 void decode_gqa_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
     int t_pos, bf16_t* K, bf16_t* V, float* S, int32_t* P, int32_t* len, int G, int capacity,
     float alpha, int select, int recent, int evict_here, bf16_t* __restrict__ o, float scale_log2e) {
   using T = bf16_t;
   // U = loads of 16 bytes in flight per lane = row groups of four rows per round of a sweep
-  constexpr int D = 128, U = 4, ROWS = 4 * U, NS = NJ * 64, ZS = NS + 4, HB = R / 4;
-  static_assert(R == 4 || R == 8, "four query heads per matrix block");
+  constexpr int D = 128, U = 4, ROWS = 4 * U, NS = NJ * 64, ZS = NS + 4, HB = (R + 3) / 4;
+  static_assert(R >= 3 && R <= 8, "one or two matrix blocks of four query heads (the last one may be partly idle)");
   static_assert(U % 4 == 0, "the block sum halves the registers twice");
   using Grp = WaveGroup;
   __shared__ __align__(16) float zs[kWaves][R][ZS];
@@ -1350,7 +1351,7 @@ void decode_gqa_mfma_kernel(
   }
   uint4 qb[HB];  // elements 8*blk .. 8*blk+7 of query head 4h + jl
 #pragma unroll
-  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + min(4 * h + jl, R - 1)) * D + 8 * blk);
 
   // ---- K sweep
   for (int base = 0; base < L; base += ROWS) {
@@ -1361,7 +1362,7 @@ void decode_gqa_mfma_kernel(
       float w[U / 4][4];
       gqa_block_logits<U>(x, qb[h], scale_log2e, w);
       // rows past L hold row 0's logits; the strip has room (base + ROWS <= NS), nobody reads them
-      if (sub < 4) {
+      if (sub < 4 && 4 * h + jl < R) {
         float* zp = &z[4 * h + jl][base + U * rgrp];
 #pragma unroll
         for (int c = 0; c < U / 4; ++c)
@@ -1417,7 +1418,7 @@ void decode_gqa_mfma_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int h = 0; h < HB; ++h) pa[u][h] = z[4 * h + jl][base + 4 * u + rgrp];
+      for (int h = 0; h < HB; ++h) pa[u][h] = 4 * h + jl < R ? z[4 * h + jl][base + 4 * u + rgrp] : 0.f;
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -1427,6 +1428,7 @@ void decode_gqa_mfma_kernel(
   for (int h = 0; h < HB; ++h)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      if (4 * h + i >= R) continue;
       float out[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = acc[h][e][i];
@@ -1636,8 +1638,8 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
   using T = bf16_t;
   // a wave takes 16 consecutive rows of a round of 64 (the smallest split), and the workgroup
   // meets at three barriers only: a split is too short to pay for more
-  constexpr int D = 128, UM = 4, HB = R / 4, MROWS = 4 * UM;
-  static_assert(R == 4 || R == 8, "four query heads per matrix block");
+  constexpr int D = 128, UM = 4, HB = (R + 3) / 4, MROWS = 4 * UM;
+  static_assert(R >= 3 && R <= 8, "one or two matrix blocks of four query heads");
   extern __shared__ float z[];  // [R][rows_per_split]
   __shared__ float part[kWaves][R][D];
   const int g = blockIdx.x / nsplit, c = blockIdx.x % nsplit, tid = threadIdx.x;
@@ -1662,7 +1664,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
   const T* vnew = v_new + (size_t)g * D;
   uint4 qb[HB];
 #pragma unroll
-  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + 4 * h + jl) * D + 8 * blk);
+  for (int h = 0; h < HB; ++h) qb[h] = load16(q + ((size_t)g * R + min(4 * h + jl, R - 1)) * D + 8 * blk);
 
   for (int base = r0 + wave * MROWS; base < r1; base += kWaves * MROWS) {
     uint4 x[UM];
@@ -1677,7 +1679,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             const int row = base + UM * rgrp + 4 * cc + v;
-            if (row < r1) z[(4 * h + jl) * rows_per_split + row - r0] = w[cc][v];
+            if (row < r1 && 4 * h + jl < R) z[(4 * h + jl) * rows_per_split + row - r0] = w[cc][v];
           }
       }
     }
@@ -1722,7 +1724,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
     for (int u = 0; u < UM; ++u) {
       const int row = base + 4 * u + rgrp;
 #pragma unroll
-      for (int h = 0; h < HB; ++h) pa[u][h] = row < r1 ? z[(4 * h + jl) * rows_per_split + row - r0] : 0.f;
+      for (int h = 0; h < HB; ++h) pa[u][h] = (row < r1 && 4 * h + jl < R) ? z[(4 * h + jl) * rows_per_split + row - r0] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < UM; ++u)
@@ -1734,6 +1736,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_partial_kernel(
   for (int h = 0; h < HB; ++h)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      if (4 * h + i >= R) continue;
       float out[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) out[e] = macc[h][e][i];
@@ -1790,7 +1793,7 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_combine_kernel(
   __syncthreads();
   {
     // a thread's R * D / kThreads outputs side by side, so that their loads are in flight together
-    constexpr int PER = R * D / kThreads;
+    constexpr int PER = (R * D + kThreads - 1) / kThreads;
     float acc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.f;
@@ -1798,14 +1801,14 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_combine_kernel(
     for (int c = 0; c < nsplit; ++c) {
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        const int idx = tid + i * kThreads, r = idx / D, col = idx % D;
+        const int idx = min(tid + i * kThreads, R * D - 1), r = idx / D, col = idx % D;
         acc[i] = fmaf(po[(((size_t)g * R + r) * nsplit + c) * D + col], wsplit[r][c], acc[i]);
       }
     }
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int idx = tid + i * kThreads, r = idx / D, col = idx % D;
-      Elem<T>::store(o + ((size_t)g * R + r) * D + col, acc[i] * inv_s[r]);
+      if (idx < R * D) Elem<T>::store(o + ((size_t)g * R + r) * D + col, acc[i] * inv_s[r]);
     }
   }
   for (int j = tid; j < L; j += kThreads) {
@@ -1821,6 +1824,20 @@ __global__ __launch_bounds__(kThreads) void decode_gqa_combine_kernel(
                                select, recent, evict_here != 0, sm);
 }
 
+// f(std::integral_constant<int, R>) for the run-time group size R = 2 .. 8
+template <typename F>
+void with_group(int group, F f) {
+  switch (group) {
+    case 2: f(std::integral_constant<int, 2>()); break;
+    case 3: f(std::integral_constant<int, 3>()); break;
+    case 4: f(std::integral_constant<int, 4>()); break;
+    case 5: f(std::integral_constant<int, 5>()); break;
+    case 6: f(std::integral_constant<int, 6>()); break;
+    case 7: f(std::integral_constant<int, 7>()); break;
+    default: f(std::integral_constant<int, 8>()); break;
+  }
+}
+
 template <typename T, int D>
 void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t_pos,
                       const a2sf_cache& c, int group, float alpha, int select, int recent,
@@ -1828,11 +1845,12 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const size_t lds = (size_t)group * c.capacity * sizeof(float);
   const bool stream = 4.0 * c.G * c.capacity * D > 512e6;   // as in plan_decode
+  constexpr bool kMatrixType = std::is_same<T, bf16_t>::value && D == 128;   // the forms on the 4x4 matrix instructions
   // Few K/V heads with long caches: tokens split over workgroups where plan_decode would split
   // the same cache with ungrouped heads, as far as the scratch memory the caller gave allows.
-  if constexpr (std::is_same<T, bf16_t>::value && D == 128) {
+  if constexpr (kMatrixType) {
     const DecodePlan kv = plan_decode(c.G, c.capacity, D);
-    if (group >= 4 && kv.nsplit > 1 && ws) {
+    if (group >= 3 && kv.nsplit > 1 && ws) {
       const size_t heads = (size_t)c.G * group;
       const size_t fixed = heads * c.capacity * sizeof(float);              // the logits
       const size_t per_split = heads * (2 + D) * sizeof(float);             // (max, sum) and output
@@ -1847,21 +1865,20 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
         const size_t lds_p = (size_t)group * rows * sizeof(float);
         const size_t lds_c = (size_t)c.capacity * sizeof(float);
         constexpr int kMaxLds = A2SF_MAX_CAPACITY * (int)sizeof(float);
-#define A2SF_GQAS(R)                                                                                      \
-  do {                                                                                                    \
-    static const hipError_t raised = hipFuncSetAttribute(                                                 \
-        (const void*)decode_gqa_combine_kernel<R>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);  \
-    (void)raised;                                                                                         \
-    hipLaunchKernelGGL((decode_gqa_partial_kernel<R>), dim3((unsigned)c.G * ns), dim3(kThreads), lds_p,   \
-                       st, (const T*)q, (const T*)k_new, (const T*)v_new, (const T*)c.k, (const T*)c.v,   \
-                       c.len, c.capacity, ns, rows, zbuf, ml, po, scale_log2e);                           \
-    hipLaunchKernelGGL((decode_gqa_combine_kernel<R>), dim3(c.G), dim3(kThreads), lds_c, st,              \
-                       (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len, \
-                       c.capacity, ns, zbuf, ml, po, alpha, select, recent, (int)evict_here, (T*)o);      \
-  } while (0)
-        if (group == 4) A2SF_GQAS(4);
-        else A2SF_GQAS(8);
-#undef A2SF_GQAS
+        with_group(group, [&](auto rc) {
+          constexpr int R = decltype(rc)::value;
+          if constexpr (R >= 3) {
+            static const hipError_t raised = hipFuncSetAttribute(
+                (const void*)decode_gqa_combine_kernel<R>, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
+            (void)raised;
+            hipLaunchKernelGGL((decode_gqa_partial_kernel<R>), dim3((unsigned)c.G * ns), dim3(kThreads), lds_p,
+                               st, (const T*)q, (const T*)k_new, (const T*)v_new, (const T*)c.k, (const T*)c.v,
+                               c.len, c.capacity, ns, rows, zbuf, ml, po, scale_log2e);
+            hipLaunchKernelGGL((decode_gqa_combine_kernel<R>), dim3(c.G), dim3(kThreads), lds_c, st,
+                               (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                               c.capacity, ns, zbuf, ml, po, alpha, select, recent, (int)evict_here, (T*)o);
+          }
+        });
         return;
       }
     }
@@ -1871,71 +1888,57 @@ void launch_gqa_typed(const void* q, const void* k_new, const void* v_new, int t
   const int nj = c.capacity <= 128 ? 2 : (c.capacity <= 256 ? 4 : 8);
   if (c.G >= 1024 && c.capacity <= 512 && group * nj <= 32) {
     const dim3 grid((c.G + kWaves - 1) / kWaves);
-#define A2SF_GQAW__(NJ, R, STREAM)                                                                   \
-  hipLaunchKernelGGL((decode_gqa_wave_kernel<T, D, NJ, R, STREAM>), grid, dim3(kThreads), 0, st,     \
-                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,         \
-                     c.scores, c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, \
-                     (T*)o, scale_log2e)
-#define A2SF_GQAW_(NJ, R)                   \
-  do {                                      \
-    if (stream) A2SF_GQAW__(NJ, R, true);   \
-    else A2SF_GQAW__(NJ, R, false);         \
-  } while (0)
-#define A2SF_GQAW(R)                        \
-  do {                                      \
-    if (nj == 2) A2SF_GQAW_(2, R);          \
-    else if (nj == 4) A2SF_GQAW_(4, R);     \
-    else A2SF_GQAW_(8, R);                  \
-  } while (0)
-    if constexpr (std::is_same<T, bf16_t>::value && D == 128) {
-      if (group >= 4) {  // both products on the matrix pipe
-#define A2SF_GQAM__(NJ, R, STREAM)                                                                   \
-  hipLaunchKernelGGL((decode_gqa_mfma_kernel<NJ, R, STREAM>), grid, dim3(kThreads), 0, st,           \
-                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,         \
-                     c.scores, c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, \
-                     (T*)o, scale_log2e)
-#define A2SF_GQAM_(NJ, R)                   \
-  do {                                      \
-    if (stream) A2SF_GQAM__(NJ, R, true);   \
-    else A2SF_GQAM__(NJ, R, false);         \
-  } while (0)
-        if (group == 4) {
-          if (nj == 2) A2SF_GQAM_(2, 4);
-          else if (nj == 4) A2SF_GQAM_(4, 4);
-          else A2SF_GQAM_(8, 4);
-        } else {
-          if (nj == 2) A2SF_GQAM_(2, 8);   // group 8: 64*NJ <= 256 slots
-          else A2SF_GQAM_(4, 8);
-        }
-#undef A2SF_GQAM_
-#undef A2SF_GQAM__
-        return;
+    bool launched = false;
+    with_group(group, [&](auto rc) {
+      constexpr int R = decltype(rc)::value;
+      auto with_nj = [&](auto f) {   // f(std::integral_constant<int, NJ>) for the forms that exist (R * NJ <= 32)
+        if (nj == 2) f(std::integral_constant<int, 2>());
+        else if (nj == 4) f(std::integral_constant<int, 4>());
+        else if constexpr (R <= 4) f(std::integral_constant<int, 8>());
+      };
+      if constexpr (kMatrixType && R >= 3) {   // both products on the matrix pipe
+        with_nj([&](auto njc) {
+          constexpr int NJ = decltype(njc)::value;
+          if (stream)
+            hipLaunchKernelGGL((decode_gqa_mfma_kernel<NJ, R, true>), grid, dim3(kThreads), 0, st, (const T*)q,
+                               (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                               c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+          else
+            hipLaunchKernelGGL((decode_gqa_mfma_kernel<NJ, R, false>), grid, dim3(kThreads), 0, st, (const T*)q,
+                               (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                               c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+          launched = true;
+        });
+      } else if constexpr (R == 2 || R == 4 || R == 8) {   // the vector form exists for these group sizes
+        with_nj([&](auto njc) {
+          constexpr int NJ = decltype(njc)::value;
+          if (stream)
+            hipLaunchKernelGGL((decode_gqa_wave_kernel<T, D, NJ, R, true>), grid, dim3(kThreads), 0, st,
+                               (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores,
+                               c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o,
+                               scale_log2e);
+          else
+            hipLaunchKernelGGL((decode_gqa_wave_kernel<T, D, NJ, R, false>), grid, dim3(kThreads), 0, st,
+                               (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores,
+                               c.pos, c.len, c.G, c.capacity, alpha, select, recent, (int)evict_here, (T*)o,
+                               scale_log2e);
+          launched = true;
+        });
       }
-    }
-    if (group == 2) A2SF_GQAW(2);
-    else if (group == 4) A2SF_GQAW(4);
-    else if (nj == 2) A2SF_GQAW_(2, 8);   // group 8: 64*NJ <= 256 slots
-    else A2SF_GQAW_(4, 8);
-#undef A2SF_GQAW
-#undef A2SF_GQAW_
-#undef A2SF_GQAW__
-    return;
+    });
+    if (launched) return;   // other group sizes of other types take the workgroup kernel
   }
-#define A2SF_GQA_(R, STREAM)                                                                      \
-  hipLaunchKernelGGL((decode_gqa_kernel<T, D, R, STREAM>), dim3(c.G), dim3(kThreads), lds, st,    \
-                     (const T*)q, (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v,      \
-                     c.scores, c.pos, c.len, c.capacity, alpha, select, recent, (int)evict_here,  \
-                     (T*)o, scale_log2e)
-#define A2SF_GQA(R)              \
-  do {                           \
-    if (stream) A2SF_GQA_(R, true); \
-    else A2SF_GQA_(R, false);    \
-  } while (0)
-  if (group == 2) A2SF_GQA(2);
-  else if (group == 4) A2SF_GQA(4);
-  else A2SF_GQA(8);
-#undef A2SF_GQA
-#undef A2SF_GQA_
+  with_group(group, [&](auto rc) {
+    constexpr int R = decltype(rc)::value;
+    if (stream)
+      hipLaunchKernelGGL((decode_gqa_kernel<T, D, R, true>), dim3(c.G), dim3(kThreads), lds, st, (const T*)q,
+                         (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                         c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+    else
+      hipLaunchKernelGGL((decode_gqa_kernel<T, D, R, false>), dim3(c.G), dim3(kThreads), lds, st, (const T*)q,
+                         (const T*)k_new, (const T*)v_new, t_pos, (T*)c.k, (T*)c.v, c.scores, c.pos, c.len,
+                         c.capacity, alpha, select, recent, (int)evict_here, (T*)o, scale_log2e);
+  });
 }
 
 }  // namespace

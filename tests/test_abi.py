@@ -153,13 +153,15 @@ def test_grouped_query_argument_errors():
     lib = B.lib()
     c = fake_cache(capacity=40)
     b = B.Budget(4, 4)
-    assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 3, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
-                                None) == B.A2SF_ESHAPE                                   # group of 3
+    assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 9, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
+                                None) == B.A2SF_ESHAPE                                   # group of 9
+    assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 0, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
+                                None) == B.A2SF_ESHAPE
     assert lib.a2sf_prefill_gqa(FAKE, FAKE, FAKE, 16, 4, 0.3, b, ctypes.byref(c), None, None, FAKE, 64,
                                 None) == B.A2SF_EWORKSPACE
     assert lib.a2sf_prefill_gqa(None, FAKE, FAKE, 16, 4, 0.3, b, ctypes.byref(c), None, None, FAKE, 1 << 30,
                                 None) == B.A2SF_EINVAL
-    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 5, 0.3, b, 0, FAKE, None, 0,
+    assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 9, 0.3, b, 0, FAKE, None, 0,
                                     None) == B.A2SF_ESHAPE
     big = fake_cache(capacity=4096)
     assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(big), 8, 0.3, b, 0, FAKE, None, 0,

@@ -610,7 +610,9 @@ def test_chunk_without_room_is_flagged():
 
 
 @pytest.mark.parametrize("dtype,d,group,n", [("bf16", 128, 4, 300), ("bf16", 64, 8, 200), ("f32", 64, 2, 130),
-                                             ("f32", 128, 4, 70), ("bf16", 128, 2, 64), ("bf16", 128, 8, 257)])
+                                             ("f32", 128, 4, 70), ("bf16", 128, 2, 64), ("bf16", 128, 8, 257),
+                                             ("bf16", 128, 7, 300), ("bf16", 128, 3, 2048), ("f32", 64, 5, 90),
+                                             ("bf16", 64, 6, 130)])
 @pytest.mark.parametrize("alpha", [0.0, 0.5, 1.0])
 def test_grouped_query_heads(dtype, d, group, n, alpha, say):
     """a2sf_prefill_gqa / a2sf_decode_step_gqa: `group` query heads per K/V head; own softmax and
@@ -621,6 +623,9 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
 
 @pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 8, 700, 300, 300),
                                                            ("bf16", 128, 4, 900, 500, 390),
+                                                           ("bf16", 128, 7, 700, 300, 300),
+                                                           ("bf16", 128, 3, 500, 300, 300),
+                                                           ("bf16", 64, 5, 400, 150, 150),
                                                            ("bf16", 128, 8, 300, 1000, 1000),   # cache still filling
                                                            ("f32", 128, 4, 400, 150, 150)])
 @pytest.mark.parametrize("split", [False, True])
@@ -640,7 +645,12 @@ def test_grouped_query_heads_long_caches(dtype, d, group, n, select, recent, spl
                                                            ("bf16", 128, 2, 140, 129, 0),   # scores only
                                                            ("bf16", 128, 4, 300, 150, 150), # matrix form, 64*8 slots
                                                            ("bf16", 128, 4, 100, 70, 80),   # ... cache still filling
-                                                           ("bf16", 128, 8, 40, 30, 30)])   # ... 8 heads, 64*2 slots, filling
+                                                           ("bf16", 128, 8, 40, 30, 30),    # ... 8 heads, 64*2 slots, filling
+                                                           ("bf16", 128, 7, 160, 80, 70),   # ... 7 heads: a block of 4 and one of 3
+                                                           ("bf16", 128, 3, 300, 150, 150), # ... 3 heads, 64*8 slots
+                                                           ("bf16", 128, 5, 100, 70, 80),   # ... 5 heads, cache still filling
+                                                           ("f32", 128, 3, 60, 20, 20),     # other group sizes of other types: workgroup kernel
+                                                           ("bf16", 64, 6, 60, 20, 20)])
 def test_grouped_query_heads_many_kv_heads(dtype, d, group, n, select, recent, say):
     """The same with 1024 K/V heads and short caches: the generation step runs one wave per
     K/V head (bf16 with d = 128 and four or eight query heads: on the 4x4 matrix instructions)."""
@@ -649,7 +659,8 @@ def test_grouped_query_heads_many_kv_heads(dtype, d, group, n, select, recent, s
 
 @pytest.mark.parametrize("G,cap,group,dtype", [(1024, 40, 4, torch.bfloat16), (1030, 200, 8, torch.bfloat16),
                                                (1024, 40, 2, torch.bfloat16), (1024, 40, 4, torch.float32),
-                                               (6, 40, 4, torch.bfloat16), (6, 1000, 8, torch.bfloat16)])
+                                               (6, 40, 4, torch.bfloat16), (6, 1000, 8, torch.bfloat16),
+                                               (1024, 40, 7, torch.bfloat16), (6, 1000, 5, torch.bfloat16)])
 def test_grouped_query_step_flags_heads_with_an_invalid_length(G, cap, group, dtype, say):
     """As for a2sf_decode_step: a K/V head whose length leaves no free slot (or is negative) is
     left untouched, the output rows of its query heads are NaN, every other head is computed as
@@ -1071,7 +1082,8 @@ def test_decode_steps_replay_from_a_hip_graph(G, mode, select, say):
                                                  (6, 4, 500, "stable"),
                                                  (1100, 4, 60, "fast"),    # one wave per K/V head, matrix form
                                                  (1100, 2, 60, "stable"),  # ... vector form
-                                                 (5, 8, 100, "fast")])     # one workgroup per K/V head
+                                                 (5, 8, 100, "fast"),      # one workgroup per K/V head
+                                                 (1100, 7, 60, "fast"), (6, 6, 500, "fast")])
 def test_grouped_query_steps_replay_from_a_hip_graph(G, group, select, mode, say):
     """The same for a2sf_decode_step_gqa, one case per launch path (the first two with caches
     still filling, so that some splits are empty; the others evicting)."""
@@ -1349,12 +1361,12 @@ def test_random_shapes_lockstep(say):
 
 def test_random_shapes_grouped_query(say):
     """The grouped-query prompt phase and generation steps on 20 seeded random shapes (group
-    sizes 2, 4, 8; a handful of K/V heads with budgets up to 2040 tokens, or more than a
+    sizes 2 to 8; a handful of K/V heads with budgets up to 2040 tokens, or more than a
     thousand with short caches; both dtypes and head sizes)."""
     rng = np.random.default_rng(20486)
     for c in range(20):
         dtype = str(rng.choice(["bf16", "bf16", "f32"]))
-        d, group = int(rng.choice([64, 128])), int(rng.choice([2, 4, 8]))
+        d, group = int(rng.choice([64, 128])), int(rng.integers(2, 9))
         big = rng.random() < 0.5
         G = int(rng.integers(1024, 1400)) if big else int(rng.integers(1, 12))
         n = int(rng.integers(1, 200)) if big else int(rng.integers(1, 500))
