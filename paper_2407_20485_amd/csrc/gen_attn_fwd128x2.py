@@ -568,9 +568,18 @@ def look_ahead():
             f"s_cselect_b32 s{HASNEXT}, 1, 0",
             f"s_cselect_b32 s{SGN}, s{PAIR}, s{SG}",
             f"s_cselect_b32 s{SQBN}, s{ST1}, s{SQB}",
-            # K/V head = query head >> %[kvs] (grouped-query heads; 0 = one K/V head per query head)
-            f"s_lshr_b32 s{SHEAD}, s{SGN}, %[kvs]",
+            ] + kv_head(SGN) + [
             f"s_mul_i32 s{SHEAD}, s{SHEAD}, %[n]"] + pointer(KPN, "k", SHEAD, 8) + pointer(VPN, "v", SHEAD, 8)
+
+
+def kv_head(head):
+    """s[SHEAD] = K/V head of query head s[head] = head / r for r query heads per K/V head
+    (grouped-query heads): for r a power of two %[kvm] = 0 and %[kvs] = log2 r; otherwise
+    %[kvs] = 31 (the shift gives 0) and %[kvm] = floor(2^32 / r) + 1, whose high product with the
+    head is the quotient for every head below 2^32 / r.  s[OB] is scratch."""
+    return [f"s_mul_hi_u32 s{SHEAD}, s{head}, %[kvm]",
+            f"s_lshr_b32 s{OB}, s{head}, %[kvs]",
+            f"s_add_u32 s{SHEAD}, s{SHEAD}, s{OB}"]
 
 
 def next_block():
@@ -601,7 +610,7 @@ def setup(out):
     out.e(f"s_mov_b32 s{SG}, %[g0]")
     out.e(f"s_mov_b32 s{SQB}, %[qb0]")
     out.ext(q_pointers() + q_loads())
-    out.e(f"s_lshr_b32 s{SHEAD}, s{SG}, %[kvs]")
+    out.ext(kv_head(SG))
     out.e(f"s_mul_i32 s{SHEAD}, s{SHEAD}, %[n]")
     out.ext(pointer(KP, "k", SHEAD, 8) + pointer(VP, "v", SHEAD, 8))
     out.ext(look_ahead())

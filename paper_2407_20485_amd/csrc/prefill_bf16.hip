@@ -775,8 +775,10 @@ constexpr int kX2Slots = 32;             // persistent launch: workgroups per XC
 __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
     const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
     bf16_t* __restrict__ O, float* __restrict__ LSE2, int n, int nqb, int id_base, int ids,
-    int rounds, int kv_shift, float scale_log2e) {
-  // kv_shift: query head g reads the keys and values of K/V head g >> kv_shift (grouped-query heads)
+    int rounds, int kv_shift, unsigned kv_magic, float scale_log2e) {
+  // query head g reads the keys and values of K/V head g / r (grouped-query heads) =
+  // mulhi(g, kv_magic) + (g >> kv_shift): r a power of two: kv_magic = 0, kv_shift = log2 r;
+  // otherwise kv_shift = 31 and kv_magic = floor(2^32 / r) + 1
   __shared__ __attribute__((aligned(1024))) char smem[kX2LdsBytes];
   // this launch covers the ids id_base .. id_base + ids - 1; id = head * nqb + block position
   int vid0;
@@ -837,7 +839,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_fwd128x2_kernel(
                  [llo] "s"((unsigned)la), [lhi] "s"((unsigned)(la >> 32)),
                  [n] "s"(n), [g0] "s"(g0), [qb0] "s"(qb0), [vid0] "s"(vid0), [rounds] "s"(rounds),
                  [lgnqb] "s"(lgnqb), [nqbm1] "s"(nqbm1), [w32a] "s"(w32a), [w32b] "s"(w32b),
-                 [wodd] "s"(wodd), [wave_lds] "s"(wave_lds), [kvs] "s"(kv_shift),
+                 [wodd] "s"(wodd), [wave_lds] "s"(wave_lds), [kvs] "s"(kv_shift), [kvm] "s"(kv_magic),
                  [scale] "s"(scale_log2e)
                : A2SF_FWD128X2_CLOBBERS);
 }
@@ -998,12 +1000,17 @@ void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, vo
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)D);
   const int G = G_kv * kv_group;  // query heads
   int kv_shift = 0;
+  unsigned kv_magic = 0;
   while ((1 << kv_shift) < kv_group) ++kv_shift;
+  if ((1 << kv_shift) != kv_group) {   // not a power of two: divide by multiplication
+    kv_shift = 31;
+    kv_magic = (unsigned)((1ull << 32) / (unsigned)kv_group) + 1u;
+  }
   if constexpr (D == 128) {
     // Two query blocks per wave pay off once a workgroup streams enough key tiles to amortise
     // the start and end of a row block: from n = 2048 with one workgroup per block, from
     // n = 512 in the persistent form, which overlaps them with the neighbouring blocks.
-    if (o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31) && (1 << kv_shift) == kv_group) {
+    if (o && n % kX2Rows == 0 && (long long)G * n < (1ll << 31)) {
       const int nqb2 = n / kX2Rows;
       const long long items = (long long)G * nqb2;
       // persistent form: needs the id arithmetic of its later rounds to be shifts and an even
@@ -1015,7 +1022,7 @@ void launch_fwd(const void* q, const void* k, const void* v, int G_kv, int n, vo
           const unsigned grid2 = rounds > 1 ? 8 * kX2Slots : (unsigned)(((ids + 7) / 8) * 8);
           hipLaunchKernelGGL(attn_fwd128x2_kernel, dim3(grid2), dim3(kThreads), 0, st,
                              (const bf16_t*)q, (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)o, lse2, n,
-                             nqb2, id_base, ids, rounds, kv_shift, scale_log2e);
+                             nqb2, id_base, ids, rounds, kv_shift, kv_magic, scale_log2e);
         };
         // persistent part: an even number of full rounds; what is left over goes one workgroup
         // per row block

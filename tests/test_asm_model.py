@@ -147,6 +147,7 @@ class Wave:
         self.put(a[0], (x - y) & M32)
 
     def s_mul_i32(self, a): self.put(a[0], (self.val(a[1]) * self.val(a[2])) & M32)
+    def s_mul_hi_u32(self, a): self.put(a[0], ((self.val(a[1]) & M32) * (self.val(a[2]) & M32)) >> 32)
 
     def _logic(self, a, f, mask):
         r = f(self.val(a[1]), self.val(a[2])) & mask
@@ -236,7 +237,14 @@ class Wave:
     def ds_write_b64(self, a): pass
 
 
-def run_workgroup(program, n, G, rounds, block_x, seed=None, kvs=0):
+def kv_division(r):
+    """(kvs, kvm) operands for r query heads per K/V head, as the launcher forms them."""
+    if r & (r - 1) == 0:
+        return r.bit_length() - 1, 0
+    return 31, (1 << 32) // r + 1
+
+
+def run_workgroup(program, n, G, rounds, block_x, seed=None, kvr=1):
     """Runs one workgroup of a launch over G heads of n rows; returns its four waves."""
     prog, labels = program
     nqb = n // 256
@@ -253,7 +261,8 @@ def run_workgroup(program, n, G, rounds, block_x, seed=None, kvs=0):
         operands = dict(qlo=QBASE & M32, qhi=QBASE >> 32, klo=KBASE & M32, khi=KBASE >> 32,
                         vlo=VBASE & M32, vhi=VBASE >> 32, olo=OBASE & M32, ohi=OBASE >> 32,
                         llo=LBASE & M32, lhi=LBASE >> 32, n=n, g0=vid0 // nqb, qb0=nqb - 1 - vid0 % nqb,
-                        vid0=vid0, rounds=rounds, lgnqb=nqb.bit_length() - 1, nqbm1=nqb - 1, kvs=kvs,
+                        vid0=vid0, rounds=rounds, lgnqb=nqb.bit_length() - 1, nqbm1=nqb - 1,
+                        kvs=kv_division(kvr)[0], kvm=kv_division(kvr)[1],
                         w32a=32 * w, w32b=32 * (7 - w), wodd=w & 1, wave_lds=1024 * w, scale=0,
                         hx16=0, krow=0, clvs16=0, vrow=0, kl0=0, vl0=0, qoff=0, lv=0, l32x4=0,
                         lanex16=0, strip_w=0, x16=0, crr16=0, strip_r=0)
@@ -272,7 +281,7 @@ def block_of(vid0, j, nqb):
     return vid // nqb, (pos if j & 1 else nqb - 1 - pos)
 
 
-def check_workgroup(waves, vid0, n, G, rounds, kvs=0):
+def check_workgroup(waves, vid0, n, G, rounds, kvr=1):
     nqb = n // 256
     blocks = [block_of(vid0, j, nqb) for j in range(rounds)]
     assert len({wv.epoch for wv in waves}) == 1
@@ -281,11 +290,11 @@ def check_workgroup(waves, vid0, n, G, rounds, kvs=0):
     for wv in waves:
         for ev in wv.dma:
             for kind, base in (("K", KBASE), ("V", VBASE)):
-                if base <= ev["global"] < base + (G >> kvs) * n * 256:
+                if base <= ev["global"] < base + -(-G // kvr) * n * 256:
                     rel = ev["global"] - base
                     head, inside = divmod(rel, n * 256)
                     tile, within = divmod(inside, 16384)
-                    assert within % 4096 == 1024 * wv.wave and ev["global"] + 1024 <= base + (G >> kvs) * n * 256
+                    assert within % 4096 == 1024 * wv.wave and ev["global"] + 1024 <= base + -(-G // kvr) * n * 256
                     stage, slot = divmod(ev["lds"], 32768)
                     assert 0 <= ev["lds"] < RING, "direct-to-LDS load outside the stage ring"
                     assert (slot >= 16384) == (kind == "V") and slot % 16384 == within, (kind, slot, within)
@@ -318,7 +327,7 @@ def check_workgroup(waves, vid0, n, G, rounds, kvs=0):
                 last = mine[-1]
                 if want >= nt and rd["round"] + 1 >= rounds:
                     continue        # run-ahead fragments past the last block: never used
-                assert (last["head"], last["tile"]) == (head >> kvs, tile), (rd, last)   # K/V head of the query head
+                assert (last["head"], last["tile"]) == (head // kvr, tile), (rd, last)   # K/V head of the query head
                 assert last["retired"] is not None and last["retired"] < rd["epoch"], (rd, last)
     # ---- Q rows, O rows, log-sum-exp rows
     for wv in waves:
@@ -356,19 +365,31 @@ def test_stream_model(program, n, G, rounds, block_x):
     check_workgroup(waves, vid0, n, G, rounds)
 
 
-@pytest.mark.parametrize("n,G,rounds,block_x,kvs", [(1024, 256, 4, 37, 2), (2048, 8, 1, 13, 3), (512, 512, 4, 129, 1)])
-def test_stream_model_grouped_query_heads(program, n, G, rounds, block_x, kvs):
-    """2^kvs query heads share a K/V head: Q rows, outputs and log-sum-exp rows go by the query
-    head, every K/V tile by the K/V head query head >> kvs."""
-    waves, vid0 = run_workgroup(program, n, G, rounds, block_x, kvs=kvs)
-    check_workgroup(waves, vid0, n, G, rounds, kvs=kvs)
+@pytest.mark.parametrize("n,G,rounds,block_x,kvr", [(1024, 256, 4, 37, 4), (2048, 8, 1, 13, 8), (512, 512, 4, 129, 2),
+                                                    (1024, 256, 4, 37, 7), (2048, 8, 1, 6, 3), (512, 512, 4, 250, 5),
+                                                    (512, 512, 4, 129, 6)])
+def test_stream_model_grouped_query_heads(program, n, G, rounds, block_x, kvr):
+    """kvr query heads share a K/V head: Q rows, outputs and log-sum-exp rows go by the query
+    head, every K/V tile by the K/V head query head / kvr (a shift for powers of two, a
+    multiplication by the reciprocal otherwise)."""
+    waves, vid0 = run_workgroup(program, n, G, rounds, block_x, kvr=kvr)
+    check_workgroup(waves, vid0, n, G, rounds, kvr=kvr)
+
+
+def test_reciprocal_division_is_exact():
+    """mulhi(head, floor(2^32 / r) + 1) = head // r for every head a launch can have."""
+    for r in (3, 5, 6, 7):
+        kvs, kvm = kv_division(r)
+        assert kvs == 31
+        for head in list(range(0, 70000)) + [2 ** 24 - 1, 2 ** 24, 2 ** 27 + 12345, 2 ** 28 - 1]:
+            assert ((head * kvm) >> 32) + (head >> kvs) == head // r, (r, head)
 
 
 def test_model_catches_a_wrong_kv_head(program):
     """Planted mistake: the K/V head is taken to be the query head although four of them share one."""
-    waves, vid0 = run_workgroup(program, 1024, 256, 4, 37, kvs=0)
+    waves, vid0 = run_workgroup(program, 1024, 256, 4, 37, kvr=1)
     with pytest.raises(AssertionError):
-        check_workgroup(waves, vid0, 1024, 256, 4, kvs=2)
+        check_workgroup(waves, vid0, 1024, 256, 4, kvr=4)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])

@@ -621,6 +621,14 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
     grouped_query_case(dtype, d, group, n, alpha, 3, 6, 14, 10, say)
 
 
+@pytest.mark.parametrize("group,G", [(7, 22), (5, 26), (3, 43)])
+def test_grouped_query_prompt_in_the_persistent_launch(group, G, say):
+    """Group sizes that are no power of two in the generated attention stream (the K/V head of a
+    query head by multiplication with the reciprocal): enough row blocks for two rounds of the
+    persistent launch plus a remainder launch."""
+    grouped_query_case("bf16", 128, group, 1024, 0.5, G, 2, 100, 100, say)
+
+
 @pytest.mark.parametrize("dtype,d,group,n,select,recent", [("bf16", 128, 8, 700, 300, 300),
                                                            ("bf16", 128, 4, 900, 500, 390),
                                                            ("bf16", 128, 7, 700, 300, 300),
@@ -707,7 +715,7 @@ def grouped_query_case(dtype, d, group, n, alpha, G, T, select, recent, say, sma
     rng = np.random.Generator(np.random.Philox(key=[n, d * 16 + group]))
     # heads the oracle follows: all of them, or the first and last workgroups plus a seeded sample
     heads = list(range(G)) if G <= 16 else sorted(set(range(8)) | set(range(G - 8, G)) |
-                                                  set(rng.choice(G, 80, replace=False).tolist()))
+                                                  set(rng.choice(G, min(80, G), replace=False).tolist()))
     total = n + T
     u = rng.standard_normal(d)
     u /= np.linalg.norm(u)
