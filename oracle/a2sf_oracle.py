@@ -59,7 +59,7 @@ __all__ = [
     "HeadCache", "prefill", "attend_and_update", "evict", "decode_step",
     "pruned_row", "ideal_row", "cosine_similarity", "similarity_to_ideal",
     "chunk_attend_and_update", "prefill_chunk", "gqa_prefill", "gqa_attend_and_update",
-    "gqa_decode_step",
+    "gqa_decode_step", "gqa_chunk_attend_and_update", "gqa_prefill_chunk",
 ]
 
 
@@ -375,6 +375,48 @@ def gqa_decode_step(cache: HeadCache, qs, k_new, v_new, t_pos: int, alpha: float
     o, a = gqa_attend_and_update(cache, qs, k_new, v_new, t_pos, alpha)
     gone, swaps = evict(cache, select, recent, forced_retained, margin)
     return o, a, gone, swaps
+
+
+def gqa_chunk_attend_and_update(cache: HeadCache, Qcs, Kc, Vc, pos0: int, alpha: float):
+    """A chunk of m new tokens of one K/V head with r query heads (Qcs: [r, m, d]; Kc, Vc: [m, d])
+    against a cache of L earlier tokens, in place, no eviction yet.  Every query head attends as
+    a single head's chunk does (``chunk_attend_and_update``: the cached tokens and the chunk's
+    tokens up to its own), with its own softmax and output; the scores take the recurrence
+    S <- alpha*S + (sum of the r heads' probability rows) once per chunk row, i.e. a cached
+    token ends with alpha^m S_j + sum_h sum_i alpha^(m-1-i) P_h[i, j].
+    Returns (O[r, m, d], P[r, m, L+m])."""
+    Qcs = np.asarray(Qcs, dtype=np.float64)
+    Kc, Vc = (np.asarray(x, dtype=np.float64) for x in (Kc, Vc))
+    r, m, d = Qcs.shape
+    L = len(cache)
+    K_all = np.vstack([cache.K.reshape(L, d), Kc])
+    V_all = np.vstack([cache.V.reshape(L, d), Vc])
+    rows = np.arange(m)[:, None]
+    cols = np.arange(L + m)[None, :]
+    O = np.zeros((r, m, d), dtype=np.float64)
+    P = np.zeros((r, m, L + m), dtype=np.float64)
+    S_new = (float(alpha) ** m) * np.concatenate([cache.S, np.zeros(m, dtype=np.float64)])
+    for h in range(r):
+        s = (Qcs[h] @ K_all.T) / np.sqrt(float(d))
+        s[np.broadcast_to(cols > L + rows, s.shape)] = -np.inf
+        s -= s.max(axis=1, keepdims=True)
+        e = np.exp(s)
+        P[h] = e / e.sum(axis=1, keepdims=True)
+        O[h] = P[h] @ V_all
+        S_new += _weights(m, alpha) @ P[h]
+    cache.S = S_new
+    cache.K, cache.V = K_all, V_all
+    cache.pos = np.concatenate([cache.pos, np.arange(pos0, pos0 + m, dtype=np.int64)])
+    return O, P
+
+
+def gqa_prefill_chunk(cache: HeadCache, Qcs, Kc, Vc, pos0: int, alpha: float, select: int, recent: int,
+                      forced_retained=None, margin: float = 1e-6):
+    """gqa_chunk_attend_and_update, then one eviction down to the budget (``evict``).
+    Returns (O[r, m, d], evicted_positions, n_swapped)."""
+    O, _ = gqa_chunk_attend_and_update(cache, Qcs, Kc, Vc, pos0, alpha)
+    gone, swaps = evict(cache, select, recent, forced_retained, margin)
+    return O, gone, swaps
 
 
 # --------------------------------------------------------------------------- similarity to Ideal

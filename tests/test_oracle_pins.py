@@ -528,6 +528,89 @@ class TestGroupedQueryHeads:
         orc.gqa_attend_and_update(c, Qs[:, n], K[n], V[n], n, alpha)
         assert math.isclose(c.S.sum(), alpha * before + r, rel_tol=1e-13)
 
+    @pytest.mark.parametrize("alpha", [0.0, 0.4, 1.0])
+    def test_grouped_chunk_is_grouped_steps_then_one_eviction(self, alpha):
+        """A chunk of a grouped head against m calls of gqa_attend_and_update with no eviction in
+        between, then evict: same outputs, scores and survivors."""
+        rng = np.random.default_rng(21)
+        r, L, m, d, sel, rec = 3, 18, 7, 8, 7, 5
+        c1 = orc.HeadCache(rng.standard_normal((L, d)), rng.standard_normal((L, d)), rng.random(L),
+                           np.sort(rng.choice(60, L, replace=False)))
+        c2 = c1.copy()
+        Qcs = rng.standard_normal((r, m, d))
+        Kc, Vc = rng.standard_normal((m, d)), rng.standard_normal((m, d))
+        first = int(c1.pos.max()) + 1
+        O, gone, _ = orc.gqa_prefill_chunk(c1, Qcs, Kc, Vc, first, alpha, sel, rec)
+        for i in range(m):
+            o, _ = orc.gqa_attend_and_update(c2, Qcs[:, i], Kc[i], Vc[i], first + i, alpha)
+            assert np.abs(o - O[:, i]).max() < 1e-13
+        gone2, _ = orc.evict(c2, sel, rec)
+        assert gone == gone2 and len(gone) == L + m - (sel + rec)
+        assert list(c1.pos) == list(c2.pos) and np.abs(c1.S - c2.S).max() < 1e-13
+        assert np.array_equal(c1.K, c2.K) and np.array_equal(c1.V, c2.V)
+
+    def test_grouped_chunk_of_one_group_member_is_the_plain_chunk(self):
+        rng = np.random.default_rng(22)
+        L, m, d = 12, 9, 8
+        c1 = orc.HeadCache(rng.standard_normal((L, d)), rng.standard_normal((L, d)), rng.random(L), np.arange(L))
+        c2 = c1.copy()
+        Qc, Kc, Vc = (rng.standard_normal((m, d)) for _ in range(3))
+        O1, g1, _ = orc.prefill_chunk(c1, Qc, Kc, Vc, L, 0.35, 6, 5)
+        O2, g2, _ = orc.gqa_prefill_chunk(c2, Qc[None], Kc, Vc, L, 0.35, 6, 5)
+        assert np.abs(O1 - O2[0]).max() < 1e-15 and g1 == g2
+        assert list(c1.pos) == list(c2.pos) and np.abs(c1.S - c2.S).max() < 1e-15
+
+    def test_grouped_chunk_by_brute_force(self):
+        """Python loops over heads, rows and keys against the matrix form: softmax over the cached
+        tokens and the chunk's tokens up to the row's own, weights alpha^(m-1-i), old scores
+        times alpha^m, all r heads added."""
+        rng = np.random.default_rng(23)
+        r, L, m, d, alpha = 2, 5, 4, 3, 0.6
+        c = orc.HeadCache(rng.standard_normal((L, d)), rng.standard_normal((L, d)), rng.random(L), np.arange(L))
+        S0, K0, V0 = c.S.copy(), c.K.copy(), c.V.copy()
+        Qcs = rng.standard_normal((r, m, d))
+        Kc, Vc = rng.standard_normal((m, d)), rng.standard_normal((m, d))
+        O, P = orc.gqa_chunk_attend_and_update(c, Qcs, Kc, Vc, L, alpha)
+        keys = [list(K0[j]) for j in range(L)] + [list(Kc[j]) for j in range(m)]
+        vals = [list(V0[j]) for j in range(L)] + [list(Vc[j]) for j in range(m)]
+        S_ref = [alpha ** m * S0[j] for j in range(L)] + [0.0] * m
+        for h in range(r):
+            for i in range(m):
+                vis = L + i + 1
+                z = [sum(Qcs[h, i, e] * keys[j][e] for e in range(d)) / math.sqrt(d) for j in range(vis)]
+                mx = max(z)
+                ex = [math.exp(x - mx) for x in z]
+                tot = sum(ex)
+                for j in range(vis):
+                    pj = ex[j] / tot
+                    assert abs(P[h, i, j] - pj) < 1e-14
+                    S_ref[j] += alpha ** (m - 1 - i) * pj
+                for e in range(d):
+                    assert abs(O[h, i, e] - sum(ex[j] / tot * vals[j][e] for j in range(vis))) < 1e-13
+                assert np.all(P[h, i, vis:] == 0.0)
+        assert np.abs(c.S - np.array(S_ref)).max() < 1e-13
+
+    def test_grouped_chunk_score_total(self):
+        """r probability rows per chunk row: total_after = alpha^m total_before + r (1 - alpha^m)/(1 - alpha)."""
+        rng = np.random.default_rng(24)
+        r, L, m, d, alpha = 5, 14, 11, 8, 0.3
+        c = orc.HeadCache(rng.standard_normal((L, d)), rng.standard_normal((L, d)), rng.random(L), np.arange(L))
+        before = c.S.sum()
+        orc.gqa_chunk_attend_and_update(c, rng.standard_normal((r, m, d)), rng.standard_normal((m, d)),
+                                        rng.standard_normal((m, d)), L, alpha)
+        assert math.isclose(c.S.sum(), alpha ** m * before + r * (1 - alpha ** m) / (1 - alpha), rel_tol=1e-13)
+
+    def test_one_grouped_chunk_on_an_empty_cache_is_the_grouped_prompt_phase(self):
+        rng = np.random.default_rng(25)
+        r, n, d, alpha, sel, rec = 3, 40, 8, 0.45, 6, 5
+        Qs = rng.standard_normal((r, n, d))
+        K, V = rng.standard_normal((n, d)), rng.standard_normal((n, d))
+        O_ref, S_full, c_ref = orc.gqa_prefill(Qs, K, V, alpha, sel, rec)
+        c = orc.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64))
+        O, _, _ = orc.gqa_prefill_chunk(c, Qs, K, V, 0, alpha, sel, rec)
+        assert np.abs(O - O_ref).max() < 1e-13
+        assert list(c.pos) == list(c_ref.pos) and np.abs(c.S - c_ref.S).max() < 1e-13
+
     def test_one_eviction_serves_the_group(self):
         """The token with the smallest SUMMED score leaves, even where a single query head
         would have evicted another one."""
@@ -673,6 +756,9 @@ class TestPinsCatchMistakes:
         (TestGroupedQueryHeads, "test_group_score_is_the_sum_over_its_query_heads", ()),
         (TestGroupedQueryHeads, "test_group_totals", ()),
         (TestGroupedQueryHeads, "test_one_eviction_serves_the_group", ()),
+        (TestGroupedQueryHeads, "test_grouped_chunk_is_grouped_steps_then_one_eviction", (0.4,)),
+        (TestGroupedQueryHeads, "test_grouped_chunk_by_brute_force", ()),
+        (TestGroupedQueryHeads, "test_grouped_chunk_score_total", ()),
     ]
 
     def _some_pin_fails(self):
@@ -817,6 +903,30 @@ class TestPinsCatchMistakes:
             cache.pos = np.concatenate([cache.pos, np.arange(pos0, pos0 + m)])
             return P @ V_all, P
         monkeypatch.setattr(orc, "chunk_attend_and_update", bad)
+        assert self._some_pin_fails()
+
+    def test_grouped_chunk_decay_forgotten(self, monkeypatch):
+        real = orc.gqa_chunk_attend_and_update
+
+        def bad(cache, Qcs, Kc, Vc, pos0, alpha):
+            old = np.concatenate([cache.S, np.zeros(len(Kc))])
+            m = len(Kc)
+            O, P = real(cache, Qcs, Kc, Vc, pos0, alpha)
+            cache.S = cache.S - float(alpha) ** m * old + old      # older scores not decayed
+            return O, P
+        monkeypatch.setattr(orc, "gqa_chunk_attend_and_update", bad)
+        assert self._some_pin_fails()
+
+    def test_grouped_chunk_counts_one_head_only(self, monkeypatch):
+        real = orc.gqa_chunk_attend_and_update
+
+        def bad(cache, Qcs, Kc, Vc, pos0, alpha):
+            c0 = cache.copy()
+            O, P = real(cache, Qcs, Kc, Vc, pos0, alpha)
+            real(c0, np.asarray(Qcs)[:1], Kc, Vc, pos0, alpha)
+            cache.S = c0.S                                          # the other heads' rows dropped
+            return O, P
+        monkeypatch.setattr(orc, "gqa_chunk_attend_and_update", bad)
         assert self._some_pin_fails()
 
     def test_group_score_averaged_instead_of_summed(self, monkeypatch):
