@@ -199,6 +199,19 @@ a2sf_status a2sf_decode_step_gqa(const void* q, const void* k_new, const void* v
                                  a2sf_budget budget, int32_t mode, void* o, void* workspace,
                                  size_t workspace_bytes, void* hip_stream);
 
+/* a2sf_prefill_chunk for grouped-query heads (the two extensions above together): a chunk of m
+ * tokens of G K/V heads with `group` query heads each.  Every query head attends as a plain
+ * head's chunk does, with its own softmax and output; a cached token's score becomes
+ * alpha^m * S + the sum over the group's heads of sum_i alpha^(m-1-i) P_h[i, .]; one eviction
+ * per K/V head.
+ *   q, o      [G, group, m, d] (o may be NULL);  k, v  [G, m, d].
+ * Everything else as in a2sf_prefill_chunk.
+ * Workspace: a2sf_workspace_bytes(G * group, m, capacity, d, dtype, budget). */
+a2sf_status a2sf_prefill_chunk_gqa(const void* q, const void* k, const void* v, int32_t m,
+                                   int32_t pos0, int32_t group, float alpha, a2sf_budget budget,
+                                   const a2sf_cache* cache, void* o, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream);
+
 /* a2sf_decode_step for callers that cannot provide or allocate a workspace: code under HIP
  * graph capture, tight serving loops, harnesses that forbid allocation.  Identical in every
  * other respect (same kernels, same results); the scratch memory that a2sf_decode_step takes

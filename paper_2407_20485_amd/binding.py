@@ -25,7 +25,7 @@ EXPORTS = ("a2sf_workspace_bytes", "a2sf_prefill", "a2sf_decode_step", "a2sf_sel
            "a2sf_compact", "a2sf_status_string", "a2sf_prefill_alpha_per_head",
            "a2sf_decode_step_alpha_per_head", "a2sf_ideal_similarity", "a2sf_decode_step_static_ws",
            "a2sf_similarity_mean", "a2sf_decode_plan", "a2sf_prefill_windowed",
-           "a2sf_prefill_chunk", "a2sf_prefill_gqa", "a2sf_decode_step_gqa")
+           "a2sf_prefill_chunk", "a2sf_prefill_gqa", "a2sf_decode_step_gqa", "a2sf_prefill_chunk_gqa")
 
 
 class Budget(ctypes.Structure):
@@ -62,6 +62,9 @@ def lib() -> ctypes.CDLL:
         L.a2sf_prefill_chunk.restype = i32
         L.a2sf_prefill_chunk.argtypes = [vp, vp, vp, i32, i32, f32, Budget, ctypes.POINTER(CacheStruct), vp,
                                          vp, sz, vp]
+        L.a2sf_prefill_chunk_gqa.restype = i32
+        L.a2sf_prefill_chunk_gqa.argtypes = [vp, vp, vp, i32, i32, i32, f32, Budget, ctypes.POINTER(CacheStruct),
+                                             vp, vp, sz, vp]
         L.a2sf_prefill_gqa.restype = i32
         L.a2sf_prefill_gqa.argtypes = [vp, vp, vp, i32, i32, f32, Budget, ctypes.POINTER(CacheStruct), vp, vp,
                                        vp, sz, vp]
@@ -197,6 +200,16 @@ def a2sf_prefill_chunk(q, k, v, m, pos0, alpha, select, recent, cache, o=None, w
     _check(lib().a2sf_prefill_chunk(_ptr(q), _ptr(k), _ptr(v), m, pos0, alpha, Budget(select, recent),
                                     ctypes.byref(cs), _ptr(o), _ptr(workspace), workspace_bytes,
                                     _stream(stream)))
+
+
+def a2sf_prefill_chunk_gqa(q, k, v, m, pos0, group, alpha, select, recent, cache, o=None, workspace=None,
+                           workspace_bytes=None, stream=None):
+    cs = _cache_struct(cache)
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().a2sf_prefill_chunk_gqa(_ptr(q), _ptr(k), _ptr(v), m, pos0, group, alpha, Budget(select, recent),
+                                        ctypes.byref(cs), _ptr(o), _ptr(workspace), workspace_bytes,
+                                        _stream(stream)))
 
 
 def a2sf_prefill_gqa(q, k, v, n, group, alpha, select, recent, cache, o=None, scores_full=None,

@@ -220,30 +220,36 @@ a2sf_status a2sf_prefill_windowed(const void* q, const void* k, const void* v, i
                       workspace, workspace_bytes, hip_stream);
 }
 
-a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int32_t m, int32_t pos0,
-                               float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
-                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+inline bool bad_group(int32_t group) { return group < 1 || group > 8; }
+
+// A chunk of a prompt for G K/V heads with `group` query heads each (1 = plain heads).
+a2sf_status chunk_impl(const void* q, const void* k, const void* v, int32_t m, int32_t pos0, int32_t group,
+                       float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
   a2sf_status s;
   if ((s = check_budget(budget)) != A2SF_OK) return s;
   if ((s = check_alpha(alpha)) != A2SF_OK) return s;
   if ((s = check_cache(cache, budget)) != A2SF_OK) return s;
   if (!q || !k || !v) return A2SF_EINVAL;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o)) return A2SF_EINVAL;
+  if (bad_group(group)) return A2SF_ESHAPE;
   if (m < 1 || pos0 < 0 || (long long)pos0 + m > 0x7FFFFFFFLL) return A2SF_ESHAPE;
   if (m >= cache->capacity) return A2SF_ECAPACITY;   // a chunk needs room beside at least one slot
-  if ((long long)cache->G * m > 0x7FFFFFFFLL) return A2SF_ESHAPE;
-  const WsLayout w = ws_layout(cache->G, m, 0, cache->d, budget);
+  if ((long long)cache->G * group * m > 0x7FFFFFFFLL) return A2SF_ESHAPE;
+  const WsLayout w = ws_layout(cache->G * group, m, 0, cache->d, budget);   // one log-sum-exp row per QUERY head
   if (!workspace || misaligned(workspace) || workspace_bytes < w.total) return A2SF_EWORKSPACE;
 
   hipStream_t st = (hipStream_t)hip_stream;
   clear_stale_error();
   char* ws = (char*)workspace;
   float* lse2 = (float*)(ws + w.lse2);
-  int32_t* len_old = (int32_t*)(ws + w.s_full);   // G ints fit where G * m floats would go
+  int32_t* len_old = (int32_t*)(ws + w.s_full);   // G ints fit where G * group * m floats would go
   int32_t* keep_idx = (int32_t*)(ws + w.keep_idx);
   int32_t* n_keep = (int32_t*)(ws + w.n_keep);
   const int G = cache->G, d = cache->d, C = cache->capacity;
   AttnRect rc{m, C, len_old};
+  rc.kv_group = group;
   const float decay = alpha > 0.f ? powf(alpha, (float)m) : 0.f;   // 0^m = 0 for m >= 1
   // Where the kernels can read the chunk's K/V rows from the call's inputs, the rows are not
   // copied behind the cached ones first: the compaction copies in those that are kept.
@@ -268,10 +274,19 @@ a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int3
     launch_compact(*cache, keep_idx, budget.select + budget.recent, n_keep, st);
   return launch_status();
 }
-
-namespace {
-inline bool bad_group(int32_t group) { return group < 1 || group > 8; }
 }  // namespace
+
+a2sf_status a2sf_prefill_chunk(const void* q, const void* k, const void* v, int32_t m, int32_t pos0,
+                               float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return chunk_impl(q, k, v, m, pos0, 1, alpha, budget, cache, o, workspace, workspace_bytes, hip_stream);
+}
+
+a2sf_status a2sf_prefill_chunk_gqa(const void* q, const void* k, const void* v, int32_t m, int32_t pos0,
+                                   int32_t group, float alpha, a2sf_budget budget, const a2sf_cache* cache,
+                                   void* o, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return chunk_impl(q, k, v, m, pos0, group, alpha, budget, cache, o, workspace, workspace_bytes, hip_stream);
+}
 
 a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_t n, int32_t group,
                              float alpha, a2sf_budget budget, const a2sf_cache* cache, void* o,

@@ -163,6 +163,11 @@ def test_grouped_query_argument_errors():
                                 None) == B.A2SF_EINVAL
     assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(c), 9, 0.3, b, 0, FAKE, None, 0,
                                     None) == B.A2SF_ESHAPE
+    g = lib.a2sf_prefill_chunk_gqa
+    assert g(FAKE, FAKE, FAKE, 8, 0, 9, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_ESHAPE      # group of 9
+    assert g(FAKE, FAKE, FAKE, 40, 0, 4, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_ECAPACITY  # no room beside the chunk
+    assert g(FAKE, FAKE, FAKE, 8, 0, 4, 0.3, b, ctypes.byref(c), None, FAKE, 64, None) == B.A2SF_EWORKSPACE
+    assert g(FAKE, None, FAKE, 8, 0, 4, 0.3, b, ctypes.byref(c), None, FAKE, 1 << 30, None) == B.A2SF_EINVAL
     big = fake_cache(capacity=4096)
     assert lib.a2sf_decode_step_gqa(FAKE, FAKE, FAKE, 5, ctypes.byref(big), 8, 0.3, b, 0, FAKE, None, 0,
                                     None) == B.A2SF_ECAPACITY                            # 8 * 4096 logits

@@ -1396,3 +1396,118 @@ def test_random_chunkings(say):
         B = int(rng.integers(1, 300))
         select = int(rng.integers(0, B + 1))
         body(base, d, n0, chunks, (select, B - select), float(rng.choice([0.0, 0.2, 0.4, 0.9, 1.0])), say)
+
+
+# ------------------------------------------------------------------------------ chunks of grouped-query heads
+def grouped_chunks_case(dtype, d, group, G, n0, chunks, select, recent, alpha, say):
+    """a2sf_prefill_gqa on the first n0 tokens (n0 = 0: an empty cache), then a2sf_prefill_chunk_gqa
+    chunk by chunk, then two generation steps; every chunk's output rows, the scores, the retained
+    sets and the cached rows against the oracle's gqa_prefill_chunk."""
+    rng = np.random.Generator(np.random.Philox(key=[n0 + 7 * sum(chunks), d * 16 + group]))
+    total = n0 + sum(chunks) + 2
+    u = rng.standard_normal(d)
+    u /= np.linalg.norm(u)
+    q = rng.standard_normal((G, group, total, d)) + u
+    k = rng.standard_normal((G, total, d))
+    k[:, ::13] += 3.0 * u
+    v = rng.standard_normal((G, total, d))
+    if dtype == "bf16":
+        bits = [synth.round_to_bf16_bits(x.astype(np.float32)) for x in (q, k, v)]
+        host = [synth.bf16_bits_to_f32(b).astype(np.float64) for b in bits]
+        dev = [parity.to_device(b, "bf16") for b in bits]
+    else:
+        host = [x.astype(np.float32).astype(np.float64) for x in (q, k, v)]
+        dev = [parity.to_device(x.astype(np.float32), "f32") for x in (q, k, v)]
+    tdt = parity.torch_dtype(dtype)
+    code = a2sf.A2SF_F32 if dtype == "f32" else a2sf.A2SF_BF16
+    B = select + recent
+    cap = B + max(chunks) + 1
+    alpha32 = float(np.float32(alpha))
+    cache = a2sf.Cache(G, cap, d, tdt)
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, max(max(chunks), n0, 1), cap, d, code, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    oc = {}
+    at = n0
+    o_err = s_rel = 0.0
+
+    def compare(g, what):
+        nonlocal s_rel
+        L = int(cache.len[g])
+        pos = cache.pos[g, :L].cpu().numpy()
+        assert np.all(np.diff(pos) > 0), what            # chunks keep the slots in ascending position
+        assert np.array_equal(pos, oc[g].pos), f"{what}: retained sets differ"
+        s_rel = max(s_rel, parity.compare_scores(cache.scores[g, :L].cpu().numpy(), oc[g].S, what))
+        assert np.array_equal(parity.to_f64(cache.k[g, :L]), oc[g].K) and np.array_equal(parity.to_f64(cache.v[g, :L]), oc[g].V)
+
+    if n0 > 0:
+        a2sf.a2sf_prefill_gqa(dev[0][:, :, :n0].contiguous(), dev[1][:, :n0].contiguous(), dev[2][:, :n0].contiguous(),
+                              n0, group, alpha, select, recent, cache, workspace=ws)
+        torch.cuda.synchronize()
+        for g in range(G):
+            L = int(cache.len[g])
+            _, _, oc[g] = orc.gqa_prefill(host[0][g, :, :n0], host[1][g, :n0], host[2][g, :n0], alpha32, select, recent,
+                                          forced_retained=cache.pos[g, :L].cpu().tolist(), margin=parity.MARGIN)
+            compare(g, f"kv head {g} after the prompt phase")
+    else:
+        for t in cache.tensors():
+            t.zero_()
+        for g in range(G):
+            oc[g] = orc.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64))
+    for m in chunks:
+        qc = dev[0][:, :, at:at + m].contiguous()
+        kc, vc = dev[1][:, at:at + m].contiguous(), dev[2][:, at:at + m].contiguous()
+        o = torch.full((G, group, m, d), float("nan"), dtype=tdt, device="cuda")
+        a2sf.a2sf_prefill_chunk_gqa(qc, kc, vc, m, at, group, alpha, select, recent, cache, o=o, workspace=ws)
+        torch.cuda.synchronize()
+        og = parity.to_f64(o)
+        for g in range(G):
+            L = int(cache.len[g])
+            O, _, _ = orc.gqa_prefill_chunk(oc[g], host[0][g, :, at:at + m], host[1][g, at:at + m], host[2][g, at:at + m],
+                                            at, alpha32, select, recent,
+                                            forced_retained=cache.pos[g, :L].cpu().tolist(), margin=parity.MARGIN)
+            err = float(np.abs(og[g] - O).max())
+            o_err = max(o_err, err)
+            assert err <= parity.O_TOL[dtype], f"kv head {g} chunk at {at}: output max-abs {err:.3e}"
+            compare(g, f"kv head {g} after the chunk at {at}")
+        at += m
+    od = torch.empty((G, group, d), dtype=tdt, device="cuda")
+    for t in range(2):
+        r = at + t
+        a2sf.a2sf_decode_step_gqa(dev[0][:, :, r].contiguous(), dev[1][:, r].contiguous(), dev[2][:, r].contiguous(),
+                                  r, cache, group, alpha, select, recent, od, mode=a2sf.A2SF_EVICT_STABLE, workspace=ws)
+        torch.cuda.synchronize()
+        for g in range(G):
+            L = int(cache.len[g])
+            o_ref, _, _, _ = orc.gqa_decode_step(oc[g], host[0][g, :, r], host[1][g, r], host[2][g, r], r, alpha32, select,
+                                                 recent, forced_retained=cache.pos[g, :L].cpu().tolist(), margin=parity.MARGIN)
+            assert float(np.abs(parity.to_f64(od[g]) - o_ref).max()) <= parity.O_TOL[dtype]
+            compare(g, f"kv head {g} step {t} after the chunks")
+    say(f"  [grouped chunks {dtype} d={d} group={group} kv heads={G} prompt {n0} + {chunks} budget={select}+{recent} alpha={alpha}] "
+        f"max|o err|={o_err:.2e} max score rel={s_rel:.2e}")
+
+
+@pytest.mark.parametrize("dtype,d,group,n0,chunks,budget", [
+    ("bf16", 128, 4, 200, (64, 64), (20, 20)),
+    ("bf16", 128, 7, 0, (100, 37, 5), (30, 25)),       # from an empty cache; a group size that is no power of two
+    ("bf16", 64, 8, 150, (130, 1), (0, 40)),           # recent tokens only
+    ("f32", 64, 2, 90, (33, 70), (25, 0)),             # scores only
+    ("f32", 128, 3, 40, (20, 20, 20), (200, 200)),     # the budget never binds: the cache only grows
+    ("bf16", 128, 5, 100, (300,), (60, 60)),           # a chunk longer than the budget
+])
+@pytest.mark.parametrize("alpha", [0.0, 0.4, 1.0])
+def test_grouped_query_chunks_match_oracle(dtype, d, group, n0, chunks, budget, alpha, say):
+    grouped_chunks_case(dtype, d, group, 4, n0, chunks, budget[0], budget[1], alpha, say)
+
+
+def test_random_grouped_chunkings(say):
+    """a2sf_prefill_chunk_gqa on 24 seeded random shapes and chunkings."""
+    rng = np.random.default_rng(20488)
+    for c in range(24):
+        dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+        d, group = int(rng.choice([64, 128])), int(rng.integers(2, 9))
+        n0 = int(rng.choice([0, rng.integers(1, 250)]))
+        chunks = tuple(int(x) for x in rng.integers(1, int(rng.choice([8, 70, 260])) + 1, size=int(rng.integers(1, 4))))
+        B = int(rng.integers(1, 260))
+        select = int(rng.integers(0, B + 1))
+        grouped_chunks_case(dtype, d, group, int(rng.integers(1, 7)), n0, chunks, select, B - select,
+                            float(rng.choice([0.0, 0.2, 0.4, 0.9, 1.0])), say)
