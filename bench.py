@@ -98,10 +98,12 @@ def similarity_kernel(spec):
                                    "unit": "GB/s", "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
 
 
-def chunked_prompt(w, alpha, m):
+def chunked_prompt(w, alpha, m, group=1):
     """`--chunked M`: the workload's prompt processed as n / M chunks with a2sf_prefill_chunk (the
     first into an empty cache), one eviction per chunk.  Model flops: a chunk row attends the
-    tokens cached before the chunk and the chunk's tokens up to itself (QK^T + PV)."""
+    tokens cached before the chunk and the chunk's tokens up to itself (QK^T + PV).  With
+    `--group R` the workload's heads are R query heads per K/V head (G / R K/V heads, random
+    K/V rows) and the call is a2sf_prefill_chunk_gqa."""
     import torch
 
     import paper_2407_20485_amd as a2sf
@@ -115,17 +117,26 @@ def chunked_prompt(w, alpha, m):
         q, k, v = (t.view(torch.int16).view(torch.bfloat16) for t in (q, k, v))
     q, k, v = q.cuda(), k.cuda(), v.cuda()
     del data
+    GQ = G                       # query heads
+    if group > 1:                # the first G / group heads' K/V rows serve a group each
+        G = G // group
+        GQ = G * group
+        q = q[:GQ].view(G, group, n, d)
+        k, v = k[:G].contiguous(), v[:G].contiguous()
     cap = w.budget + m + 1
     cache = a2sf.Cache(G, cap, d, tdt)
-    ws = torch.empty(a2sf.a2sf_workspace_bytes(G, m, cap, d, code, w.select, w.recent), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(GQ, m, cap, d, code, w.select, w.recent), dtype=torch.uint8, device="cuda")
     chunks = [(a, min(m, n - a)) for a in range(0, n, m)]
-    parts = [tuple(x[:, a:a + mm].contiguous() for x in (q, k, v)) for a, mm in chunks]
-    o = torch.empty((G, m, d), dtype=tdt, device="cuda")
+    parts = [(q[..., a:a + mm, :].contiguous(), k[:, a:a + mm].contiguous(), v[:, a:a + mm].contiguous()) for a, mm in chunks]
+    o = torch.empty((GQ, m, d), dtype=tdt, device="cuda")
 
     def run():
         cache.len.zero_()
         for (a, mm), (qc, kc, vc) in zip(chunks, parts):
-            a2sf.a2sf_prefill_chunk(qc, kc, vc, mm, a, alpha, w.select, w.recent, cache, o=o, workspace=ws)
+            if group > 1:
+                a2sf.a2sf_prefill_chunk_gqa(qc, kc, vc, mm, a, group, alpha, w.select, w.recent, cache, o=o, workspace=ws)
+            else:
+                a2sf.a2sf_prefill_chunk(qc, kc, vc, mm, a, alpha, w.select, w.recent, cache, o=o, workspace=ws)
     run()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -143,9 +154,9 @@ def chunked_prompt(w, alpha, m):
     e = 4 if w.dtype == "f32" else 2
     flops, nbytes, cached = 0, 0, 0
     for a, mm in chunks:
-        flops += G * 2 * 2 * d * (mm * cached + mm * (mm + 1) // 2)
+        flops += GQ * 2 * 2 * d * (mm * cached + mm * (mm + 1) // 2)
         kept = min(cached + mm, w.budget)
-        nbytes += G * d * e * (4 * mm + 2 * cached + 2 * kept)
+        nbytes += d * e * (GQ * 2 * mm + G * (2 * mm + 2 * cached + 2 * kept))   # Q in and O out per query head, the rest per K/V head
         cached = kept
     tf = flops / ms / 1e9
     gbs = nbytes / ms / 1e6
@@ -153,7 +164,8 @@ def chunked_prompt(w, alpha, m):
             "frac": tf / MFMA_BF16_PEAK_TFLOPS}
     hbm = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
     hbm_bound = flops / nbytes < MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS
-    print(json.dumps({"kernel": "a2sf_prefill_chunk", "workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "prompt": n,
+    print(json.dumps({"kernel": "a2sf_prefill_chunk_gqa" if group > 1 else "a2sf_prefill_chunk",
+                      "workload": f"configs[{w.cfg_id}] {w.name}", "G": G, "group": group, "prompt": n,
                       "chunk": m, "budget": f"{w.select}+{w.recent}", "alpha": alpha, "dtype": w.dtype,
                       "ms_per_prompt": ms, "flops_model": flops, "bytes_compulsory": nbytes,
                       "flops_per_byte": flops / nbytes,
@@ -338,7 +350,7 @@ def main():
     w = synth.CONFIGS[args.config]
     alpha = w.alpha if args.alpha is None else args.alpha
     if args.chunked:
-        return chunked_prompt(w, alpha, args.chunked)
+        return chunked_prompt(w, alpha, args.chunked, args.group or 1)
     if args.group:
         return grouped_query_step(w, alpha, args.group)
     G, n, d, T = w.G, w.n, w.d, w.T
