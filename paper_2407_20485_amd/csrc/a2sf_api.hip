@@ -314,6 +314,8 @@ a2sf_status a2sf_prefill_gqa(const void* q, const void* k, const void* v, int32_
   int32_t* n_keep = (int32_t*)(ws + w.n_keep);
   AttnRect rc{n, n, nullptr};
   rc.kv_group = group;
+  // without outputs only the rows the score kernel will read need their log-sum-exp
+  if (!o && cache->dtype == A2SF_BF16) rc.first_row = bf16_first_lse_row(n, cache->d, alpha);
   // in parts of kPrefillPartHeads query heads, as the plain prompt phase and for the same reason
   const size_t e = cache->dtype == A2SF_F32 ? 4 : 2;
   const int B = budget.select + budget.recent;

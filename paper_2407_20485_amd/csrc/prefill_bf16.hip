@@ -1488,7 +1488,7 @@ void launch_attn_bf16(const void* q, const void* k, const void* v, int G, const 
   // a whole prompt (every head's keys are its own rows): the kernels chosen for the prompt phase
   const bool square = !rc.off_heads && !rc.k2 && rc.kv_stride == rc.m;
   if (d == 64) launch_fwd_rect<64>(q, k, v, G, rc, o, lse2, st);
-  else if (square) launch_fwd<128>(q, k, v, G, rc.m, o, lse2, st, rc.kv_group);
+  else if (square) launch_fwd<128>(q, k, v, G, rc.m, o, lse2, st, rc.kv_group, rc.first_row);
   else launch_fwd_rect<128>(q, k, v, G, rc, o, lse2, st);
 }
 

@@ -621,6 +621,35 @@ def test_grouped_query_heads(dtype, d, group, n, alpha, say):
     grouped_query_case(dtype, d, group, n, alpha, 3, 6, 14, 10, say)
 
 
+@pytest.mark.parametrize("group,n,alpha", [(4, 1100, 0.4), (7, 700, 0.1), (2, 1500, 0.9), (8, 300, 1.0)])
+def test_grouped_query_prompt_without_outputs(group, n, alpha):
+    """a2sf_prefill_gqa with o = NULL leaves the cache of the call with outputs: the same tokens,
+    rows and positions bit for bit, the scores to fp32 rounding (the statistics-only attention
+    pass, which also leaves out the row blocks the score pass never reads)."""
+    G, d, select, recent = 5, 128, 11, 9
+    gen = torch.Generator(device="cuda").manual_seed(n + group)
+    q = torch.randn((G, group, n, d), device="cuda", generator=gen).bfloat16()
+    k, v = (torch.randn((G, n, d), device="cuda", generator=gen).bfloat16() for _ in range(2))
+    ws = torch.empty(a2sf.a2sf_workspace_bytes(G * group, n, select + recent + 1, d, a2sf.A2SF_BF16, select, recent),
+                     dtype=torch.uint8, device="cuda")
+    caches, scores = [], []
+    for with_o in (True, False):
+        c = a2sf.Cache(G, select + recent + 1, d, torch.bfloat16)
+        o = torch.empty((G, group, n, d), dtype=torch.bfloat16, device="cuda") if with_o else None
+        sf = torch.empty((G, n), dtype=torch.float32, device="cuda")
+        ws.zero_()
+        a2sf.a2sf_prefill_gqa(q, k, v, n, group, alpha, select, recent, c, o=o, scores_full=sf, workspace=ws)
+        torch.cuda.synchronize()
+        caches.append(c.snapshot())
+        scores.append(sf)
+    assert torch.allclose(scores[0], scores[1], rtol=1e-5, atol=0.0)
+    for name, a, b in zip(("k", "v", "scores", "pos", "len"), caches[0], caches[1]):
+        if name == "scores":
+            assert torch.allclose(a, b, rtol=1e-5, atol=0.0)
+        else:
+            assert torch.equal(a, b), name
+
+
 @pytest.mark.parametrize("group,G", [(7, 22), (5, 26), (3, 43)])
 def test_grouped_query_prompt_in_the_persistent_launch(group, G, say):
     """Group sizes that are no power of two in the generated attention stream (the K/V head of a
