@@ -172,15 +172,22 @@ def chunked_prompt(w, alpha, m, group=1):
                       "roofline": hbm if hbm_bound else mfma, "roofline_other": mfma if hbm_bound else hbm}), flush=True)
 
 
-def grouped_query_step(w, alpha, group, steps=60):
+def grouped_query_step(w, alpha, group, steps=60, kv_shape=None, graph=False):
     """`--group R`: generation steps of the workload's shape with R query heads per K/V head (G / R
     K/V heads; random rows).  Algorithmic bytes: K and V rows once per K/V head, scores read and
-    written, R query and output rows, the new K/V rows."""
+    written, R query and output rows, the new K/V rows.  `--kv-shape HEADSxSLOTS` replaces the
+    workload's K/V heads and cache slots (the generation step only, with the workspace that lets
+    few heads split their tokens over workgroups); `--graph` replays the steps from a HIP graph."""
     import torch
 
     import paper_2407_20485_amd as a2sf
     d, B = w.d, w.budget
     G = max(1, w.G // group)
+    select, recent = w.select, w.recent
+    if kv_shape:
+        G, slots = (int(x) for x in kv_shape.lower().split("x"))
+        B = slots - 1
+        select, recent = B // 2, B - B // 2
     e = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     cap = B + 1
@@ -193,25 +200,49 @@ def grouped_query_step(w, alpha, group, steps=60):
     q = torch.randn(G, group, d, device="cuda").to(tdt)
     kn, vn = (torch.randn(G, d, device="cuda").to(tdt) for _ in range(2))
     o = torch.empty((G, group, d), dtype=tdt, device="cuda")
+    code = a2sf.A2SF_F32 if w.dtype == "f32" else a2sf.A2SF_BF16
+    ws_step = None
+    if kv_shape:   # room for the token-split form: the logits of every query head + 64 splits of (max, sum, output)
+        ws_step = torch.empty(a2sf.a2sf_workspace_bytes(G * group, 0, cap, d, code, select, recent)
+                              + 4 * G * group * (cap + 64 * (d + 2)), dtype=torch.uint8, device="cuda")
 
     def run(t0, cnt):
         for t in range(t0, t0 + cnt):
-            a2sf.a2sf_decode_step_gqa(q, kn, vn, B + t, c, group, alpha, w.select, w.recent, o)
+            a2sf.a2sf_decode_step_gqa(q, kn, vn, B + t, c, group, alpha, select, recent, o, workspace=ws_step)
     run(0, 5)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    run(5, steps)
-    e1.record()
+    if graph:
+        snap = c.snapshot()          # every replay starts from the same cache: positions must not repeat
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run(5, steps)
+        c.restore(snap)
+        g.replay()
+        c.restore(snap)
+        torch.cuda.synchronize()
+        e0.record()
+        g.replay()
+        e1.record()
+    else:
+        e0.record()
+        run(5, steps)
+        e1.record()
     torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / steps
     L = B + 1
     nbytes = G * (2 * L * d * e + 8 * L + (2 * group + 2) * d * e)
+    if kv_shape:
+        print(json.dumps({"kernel": "a2sf_decode_step_gqa", "kv_heads": G, "group": group, "slots": L, "head_dim": d,
+                          "dtype": w.dtype, "launch": "hip graph" if graph else "one launch per kernel",
+                          "us_per_step": us, "bytes_per_step": nbytes,
+                          "roofline": {"bound": "hbm", "achieved": nbytes / us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": nbytes / us / 1e3 / HBM_PEAK_GBS}}), flush=True)
+        return
     # the prompt phase of the same grouping (random rows; model flops as for the plain prompt phase:
     # every query head has its own QK^T and PV sweep)
     n = w.n
     del q, kn, vn, o
-    code = a2sf.A2SF_F32 if w.dtype == "f32" else a2sf.A2SF_BF16
     qp = torch.randn(G, group, n, d, device="cuda").to(tdt)
     kp, vp = (torch.randn(G, n, d, device="cuda").to(tdt) for _ in range(2))
     op = torch.empty_like(qp)
@@ -317,6 +348,8 @@ def main():
                     help="instead of the pass: the prompt phase as chunks of M tokens (a2sf_prefill_chunk)")
     ap.add_argument("--group", type=int, metavar="R", default=None,
                     help="instead of the pass: generation steps with R query heads per K/V head (a2sf_decode_step_gqa)")
+    ap.add_argument("--kv-shape", metavar="HEADSxSLOTS", default=None,
+                    help="with --group: time the generation step alone on this many K/V heads and cache slots")
     ap.add_argument("--ceilings", choices=["hbm", "mfma", "all"], default=None,
                     help="instead of the pass: run the stand-alone probe of the machine's ceilings "
                          "(streaming reads in the generation step's access pattern; sustained matrix-core rate)")
@@ -352,7 +385,7 @@ def main():
     if args.chunked:
         return chunked_prompt(w, alpha, args.chunked, args.group or 1)
     if args.group:
-        return grouped_query_step(w, alpha, args.group)
+        return grouped_query_step(w, alpha, args.group, kv_shape=args.kv_shape, graph=args.graph)
     G, n, d, T = w.G, w.n, w.d, w.T
     e = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
