@@ -18,6 +18,11 @@
 // short caches a single wave works on a head (decode_wave_kernel), and with several times more
 // heads than the chip holds waves a wave works through several heads and holds their small
 // writes back in LDS (decode_wave_loop_kernel).
+//
+// Grouped-query heads (R query heads share a K/V head, beyond the paper) have the same three
+// forms; there a loaded row serves R logits or R output rows, the arithmetic per byte grows
+// with R, and for bf16 rows of 128 elements with R >= 3 both products go to the 4x4 matrix
+// instructions, whose blocks four query heads fill exactly (decode_gqa_*).
 #include <math.h>
 
 #include <algorithm>
