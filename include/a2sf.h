@@ -186,7 +186,7 @@ a2sf_status a2sf_decode_step(const void* q, const void* k_new, const void* v_new
  * (a2sf_workspace_bytes(G, 0, capacity, ...) is enough for that).  Given a larger one -- the
  * prefill's, or a2sf_workspace_bytes(G * group, 0, capacity, ...) plus
  * 4 * G * group * 64 * (d + 2) bytes -- a step over few K/V heads with long caches (bf16,
- * d = 128, group 4 or 8) splits each head's tokens over as many workgroups as its scratch
+ * d = 128) splits each head's tokens over as many workgroups as its scratch
  * memory allows; results do not depend on that beyond fp32 summation order.  The decode step
  * holds group * capacity logits in LDS: group * capacity <= A2SF_GQA_MAX_LOGITS. */
 #define A2SF_GQA_MAX_LOGITS 16384
